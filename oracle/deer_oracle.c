@@ -1,0 +1,606 @@
+/*
+ * deer_oracle.c -- plain CPU fp64 oracle for the DEER hot path (arxiv 2309.12252).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  It exists so that the GPU
+ * library can be checked against something slow and obviously right.  Only
+ * tests, the smoke check and the benchmark's cpu_baseline leg may call it.
+ * It shares no code, header, table or helper with the HIP path.
+ *
+ * Everything is fp64, row-major, host memory, one loop per mathematical index.
+ * No blocking, fusion or reordering beyond what the paper's equations state.
+ *
+ * What follows the paper and where:
+ *   - sequential evaluation y_i = f(y_{i-1}, x_i)            Sec. 3.4
+ *   - DEER iteration y <- L_G^{-1}[ f(y_shift) + G y_shift ],
+ *     G = -df/dy, err = max|y_next - y|, loop while
+ *     err > tol and iter < max_iter, err starts at 1e10      Sec. 3.1 eq. 3, 5; App. B.1
+ *   - RNN inverse operator  y_i + G_i y_{i-1} = z_i           Sec. 3.4 eq. 11
+ *   - ODE inverse operator  y_{i+1} = Gbar_i y_i + zbar_i,
+ *     Gbar = exp(-G dt), zbar = G^{-1}(I - Gbar) z,
+ *     midpoint values of G and z                              Sec. 3.3 eq. 8, 9; Table 3
+ *   - associative operator on pairs (Gbar | zbar)             Sec. 3.3 eq. 10
+ *   - backward derivative through the dual operator           Sec. 3.1.1 eq. 7
+ *
+ * Readings where the paper is silent (all listed in the design notes):
+ *   - GRU cell: gates r, z, candidate c with the reset gate applied after the
+ *     hidden projection; biases on the three input projections and on the
+ *     candidate's hidden projection:
+ *         r = sig(W_r x + b_r + U_r h)      z = sig(W_z x + b_z + U_z h)
+ *         q = U_c h + b_hc                  c = tanh(W_c x + b_c + r*q)
+ *         h' = (1 - z)*c + z*h
+ *     theta = W[3n,d] (rows r|z|c), U[3n,n] (rows r|z|c), b[3n], b_hc[n].
+ *   - MLP field: f(y) = W_out tanh(... tanh(W_1 y + b_1) ...) + b_out with
+ *     nhid hidden layers of equal width; theta = W_1[w,n], b_1[w],
+ *     (W_k[w,w], b_k[w]) for k = 2..nhid, W_out[n,w], b_out[n]; nhid = 0 is
+ *     the linear field W_out[n,n] y + b_out.
+ *   - affine RNN cell (a test hook, used to pin "Newton is exact for linear
+ *     f"): f(h, x) = A h + Bm x + c, theta = A[n,n], Bm[n,d], c[n].
+ *   - one global convergence test over batch, time and state; the returned
+ *     iteration count is the number of linear solves performed.
+ *   - ODE: the first grid point is pinned to y0 in every iterate, so err runs
+ *     over grid points 1..T-1; G^{-1}(I - exp(-G dt)) is evaluated as
+ *     dt * phi1(-G dt), phi1(A) = sum_k A^k/(k+1)!, which is the same matrix
+ *     when G is invertible and stays defined when it is not.
+ *
+ * Parity pins live in tests/ (library GRU cell and autograd, finite
+ * differences, closed forms, SciPy expm, RK4, brute force).
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_CELL_GRU 0
+#define ORACLE_CELL_MLP 1
+#define ORACLE_CELL_AFFINE 2
+
+typedef struct {
+    int cell;   /* ORACLE_CELL_* */
+    int n;      /* state size */
+    int d;      /* input size (GRU, AFFINE); ignored for MLP */
+    int width;  /* MLP hidden width */
+    int nhid;   /* MLP number of hidden layers */
+} oracle_cell;
+
+static double sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
+
+long oracle_theta_count(const oracle_cell* c) {
+    long n = c->n, d = c->d, w = c->width;
+    if (c->cell == ORACLE_CELL_GRU) return 3 * n * d + 3 * n * n + 3 * n + n;
+    if (c->cell == ORACLE_CELL_AFFINE) return n * n + n * d + n;
+    if (c->nhid == 0) return n * n + n;
+    return (w * n + w) + (long)(c->nhid - 1) * (w * w + w) + (n * w + n);
+}
+
+/* ------------------------------------------------------------------ GRU -- */
+
+/* gate values of the GRU cell at (h, x); each output has n entries */
+static void gru_gates(int n, int d, const double* th, const double* h, const double* x,
+                      double* r, double* z, double* q, double* c) {
+    const double* W = th;                 /* [3n, d] */
+    const double* U = W + 3 * n * d;      /* [3n, n] */
+    const double* b = U + 3 * n * n;      /* [3n]    */
+    const double* bhc = b + 3 * n;        /* [n]     */
+    for (int i = 0; i < n; i++) {
+        double ar = b[i], az = b[n + i], ac = b[2 * n + i], qi = bhc[i];
+        for (int k = 0; k < d; k++) {
+            ar += W[(i)*d + k] * x[k];
+            az += W[(n + i) * d + k] * x[k];
+            ac += W[(2 * n + i) * d + k] * x[k];
+        }
+        for (int j = 0; j < n; j++) {
+            ar += U[(i)*n + j] * h[j];
+            az += U[(n + i) * n + j] * h[j];
+            qi += U[(2 * n + i) * n + j] * h[j];
+        }
+        r[i] = sigmoid(ar);
+        z[i] = sigmoid(az);
+        q[i] = qi;
+        c[i] = tanh(ac + r[i] * qi);
+    }
+}
+
+static void gru_f(int n, int d, const double* th, const double* h, const double* x, double* out) {
+    double* r = malloc(4 * n * sizeof(double));
+    double *z = r + n, *q = z + n, *c = q + n;
+    gru_gates(n, d, th, h, x, r, z, q, c);
+    for (int i = 0; i < n; i++) out[i] = (1.0 - z[i]) * c[i] + z[i] * h[i];
+    free(r);
+}
+
+/* J[i][j] = d h'_i / d h_j */
+static void gru_jac(int n, int d, const double* th, const double* h, const double* x, double* J) {
+    const double* U = th + 3 * n * d;
+    const double *Ur = U, *Uz = U + n * n, *Uc = U + 2 * n * n;
+    double* r = malloc(4 * n * sizeof(double));
+    double *z = r + n, *q = z + n, *c = q + n;
+    gru_gates(n, d, th, h, x, r, z, q, c);
+    for (int i = 0; i < n; i++) {
+        double dz = z[i] * (1.0 - z[i]);   /* sigmoid' at the z gate */
+        double dr = r[i] * (1.0 - r[i]);   /* sigmoid' at the r gate */
+        double dc = 1.0 - c[i] * c[i];     /* tanh' at the candidate */
+        for (int j = 0; j < n; j++) {
+            double dzi = dz * Uz[i * n + j];                              /* dz_i/dh_j */
+            double dci = dc * (dr * Ur[i * n + j] * q[i] + r[i] * Uc[i * n + j]); /* dc_i/dh_j */
+            J[i * n + j] = (h[i] - c[i]) * dzi + (1.0 - z[i]) * dci + (i == j ? z[i] : 0.0);
+        }
+    }
+    free(r);
+}
+
+/* vector-Jacobian products of the GRU cell for an output cotangent lam:
+ * dtheta += lam^T df/dtheta, dx = lam^T df/dx, dh = lam^T df/dh. */
+static void gru_vjp(int n, int d, const double* th, const double* h, const double* x,
+                    const double* lam, double* dtheta, double* dx, double* dh) {
+    const double* W = th;
+    const double* U = W + 3 * n * d;
+    double* dW = dtheta;
+    double* dU = dW + 3 * n * d;
+    double* db = dU + 3 * n * n;
+    double* dbhc = db + 3 * n;
+    double* r = malloc(4 * n * sizeof(double));
+    double *z = r + n, *q = z + n, *c = q + n;
+    gru_gates(n, d, th, h, x, r, z, q, c);
+    for (int k = 0; k < d; k++) dx[k] = 0.0;
+    for (int j = 0; j < n; j++) dh[j] = z[j] * lam[j];   /* direct path h -> h' */
+    for (int i = 0; i < n; i++) {
+        double dcand = lam[i] * (1.0 - z[i]);                 /* dL/dc_i          */
+        double dac = dcand * (1.0 - c[i] * c[i]);             /* pre-tanh         */
+        double daz = lam[i] * (h[i] - c[i]) * z[i] * (1.0 - z[i]); /* pre-sigmoid z */
+        double dq = dac * r[i];                               /* dL/dq_i          */
+        double dar = dac * q[i] * r[i] * (1.0 - r[i]);        /* pre-sigmoid r    */
+        for (int k = 0; k < d; k++) {
+            dW[(i)*d + k] += dar * x[k];
+            dW[(n + i) * d + k] += daz * x[k];
+            dW[(2 * n + i) * d + k] += dac * x[k];
+            dx[k] += W[(i)*d + k] * dar + W[(n + i) * d + k] * daz + W[(2 * n + i) * d + k] * dac;
+        }
+        for (int j = 0; j < n; j++) {
+            dU[(i)*n + j] += dar * h[j];
+            dU[(n + i) * n + j] += daz * h[j];
+            dU[(2 * n + i) * n + j] += dq * h[j];
+            dh[j] += U[(i)*n + j] * dar + U[(n + i) * n + j] * daz + U[(2 * n + i) * n + j] * dq;
+        }
+        db[i] += dar;
+        db[n + i] += daz;
+        db[2 * n + i] += dac;
+        dbhc[i] += dq;
+    }
+    free(r);
+}
+
+/* ------------------------------------------------------------------ MLP -- */
+
+/* forward pass keeping every layer's activations: act[l] (l = 0..nhid-1), width w */
+static void mlp_forward(const oracle_cell* c, const double* th, const double* y, double* act, double* out) {
+    int n = c->n, w = c->width, L = c->nhid;
+    const double* p = th;
+    const double* in = y;
+    int nin = n;
+    for (int l = 0; l < L; l++) {
+        const double* Wl = p;
+        const double* bl = p + w * nin;
+        for (int i = 0; i < w; i++) {
+            double a = bl[i];
+            for (int j = 0; j < nin; j++) a += Wl[i * nin + j] * in[j];
+            act[l * w + i] = tanh(a);
+        }
+        p += w * nin + w;
+        in = act + l * w;
+        nin = w;
+    }
+    const double* Wo = p;
+    const double* bo = p + n * nin;
+    for (int i = 0; i < n; i++) {
+        double a = bo[i];
+        for (int j = 0; j < nin; j++) a += Wo[i * nin + j] * in[j];
+        out[i] = a;
+    }
+}
+
+static void mlp_f(const oracle_cell* c, const double* th, const double* y, double* out) {
+    double* act = malloc((size_t)(c->nhid * c->width + 1) * sizeof(double));
+    mlp_forward(c, th, y, act, out);
+    free(act);
+}
+
+/* J = W_out D_L W_L ... D_1 W_1, D_l = diag(1 - act_l^2): propagate the n
+ * columns of the identity through the layers (forward mode). */
+static void mlp_jac(const oracle_cell* c, const double* th, const double* y, double* J) {
+    int n = c->n, w = c->width, L = c->nhid;
+    int big = (w > n ? w : n);
+    double* act = malloc((size_t)(L * w + 1) * sizeof(double));
+    double* out = malloc((size_t)n * sizeof(double));
+    double* S = malloc((size_t)big * n * sizeof(double));   /* d(layer input)/dy, [nin, n] */
+    double* S2 = malloc((size_t)big * n * sizeof(double));
+    mlp_forward(c, th, y, act, out);
+    for (int i = 0; i < n; i++)
+        for (int j = 0; j < n; j++) S[i * n + j] = (i == j ? 1.0 : 0.0);
+    const double* p = th;
+    int nin = n;
+    for (int l = 0; l < L; l++) {
+        const double* Wl = p;
+        for (int i = 0; i < w; i++) {
+            double dact = 1.0 - act[l * w + i] * act[l * w + i];
+            for (int j = 0; j < n; j++) {
+                double s = 0.0;
+                for (int k = 0; k < nin; k++) s += Wl[i * nin + k] * S[k * n + j];
+                S2[i * n + j] = dact * s;
+            }
+        }
+        memcpy(S, S2, (size_t)w * n * sizeof(double));
+        p += w * nin + w;
+        nin = w;
+    }
+    const double* Wo = p;
+    for (int i = 0; i < n; i++)
+        for (int j = 0; j < n; j++) {
+            double s = 0.0;
+            for (int k = 0; k < nin; k++) s += Wo[i * nin + k] * S[k * n + j];
+            J[i * n + j] = s;
+        }
+    free(act); free(out); free(S); free(S2);
+}
+
+/* --------------------------------------------------------------- affine -- */
+
+static void affine_f(int n, int d, const double* th, const double* h, const double* x, double* out) {
+    const double* A = th;
+    const double* Bm = A + n * n;
+    const double* cc = Bm + n * d;
+    for (int i = 0; i < n; i++) {
+        double a = cc[i];
+        for (int j = 0; j < n; j++) a += A[i * n + j] * h[j];
+        for (int k = 0; k < d; k++) a += Bm[i * d + k] * x[k];
+        out[i] = a;
+    }
+}
+
+/* ------------------------------------------------------ cell dispatchers -- */
+
+void oracle_cell_f(const oracle_cell* c, const double* th, const double* h, const double* x, double* out) {
+    if (c->cell == ORACLE_CELL_GRU) gru_f(c->n, c->d, th, h, x, out);
+    else if (c->cell == ORACLE_CELL_MLP) mlp_f(c, th, h, out);
+    else affine_f(c->n, c->d, th, h, x, out);
+}
+
+void oracle_cell_jac(const oracle_cell* c, const double* th, const double* h, const double* x, double* J) {
+    if (c->cell == ORACLE_CELL_GRU) gru_jac(c->n, c->d, th, h, x, J);
+    else if (c->cell == ORACLE_CELL_MLP) mlp_jac(c, th, h, J);
+    else memcpy(J, th, (size_t)c->n * c->n * sizeof(double));
+}
+
+/* GRU only. dtheta is accumulated into; dx and dh are overwritten. */
+void oracle_gru_vjp(int n, int d, const double* th, const double* h, const double* x,
+                    const double* lam, double* dtheta, double* dx, double* dh) {
+    gru_vjp(n, d, th, h, x, lam, dtheta, dx, dh);
+}
+
+/* --------------------------------------------- affine pairs and the scan -- */
+
+/* Sec. 3.3 eq. 10: (Gi | zi) is the earlier element, (Gj | zj) the later one;
+ * result = (Gj Gi | Gj zi + zj).  Outputs must not alias the inputs. */
+void oracle_affine_combine(int n, const double* Gi, const double* zi, const double* Gj, const double* zj,
+                           double* Gout, double* zout) {
+    for (int r = 0; r < n; r++) {
+        for (int c = 0; c < n; c++) {
+            double s = 0.0;
+            for (int k = 0; k < n; k++) s += Gj[r * n + k] * Gi[k * n + c];
+            Gout[r * n + c] = s;
+        }
+        double s = zj[r];
+        for (int k = 0; k < n; k++) s += Gj[r * n + k] * zi[k];
+        zout[r] = s;
+    }
+}
+
+/* Sec. 3.3 eq. 9 / Sec. 3.4 eq. 11 solved one step after the other:
+ * y_i = Gbar_i y_{i-1} + zbar_i, i = 1..T, y_0 given; y holds y_1..y_T. */
+void oracle_linrec_serial(int n, long T, const double* Gbar, const double* zbar, const double* y0, double* y) {
+    const double* prev = y0;
+    for (long i = 0; i < T; i++) {
+        const double* G = Gbar + i * n * n;
+        for (int r = 0; r < n; r++) {
+            double s = zbar[i * n + r];
+            for (int k = 0; k < n; k++) s += G[r * n + k] * prev[k];
+            y[i * n + r] = s;
+        }
+        prev = y + i * n;
+    }
+}
+
+/* The same result through the definition with the associative operator:
+ * running value c <- c . element_i, started at c_0 = (I | y0); y_i is the
+ * vector part of the running value (Sec. 3.3, text after eq. 10). */
+void oracle_affine_scan(int n, long T, const double* Gbar, const double* zbar, const double* y0, double* y) {
+    double* G = malloc((size_t)n * n * sizeof(double));
+    double* z = malloc((size_t)n * sizeof(double));
+    double* G2 = malloc((size_t)n * n * sizeof(double));
+    double* z2 = malloc((size_t)n * sizeof(double));
+    for (int r = 0; r < n; r++) {
+        for (int c = 0; c < n; c++) G[r * n + c] = (r == c ? 1.0 : 0.0);
+        z[r] = y0[r];
+    }
+    for (long i = 0; i < T; i++) {
+        oracle_affine_combine(n, G, z, Gbar + i * n * n, zbar + i * n, G2, z2);
+        memcpy(G, G2, (size_t)n * n * sizeof(double));
+        memcpy(z, z2, (size_t)n * sizeof(double));
+        memcpy(y + i * n, z, (size_t)n * sizeof(double));
+    }
+    free(G); free(z); free(G2); free(z2);
+}
+
+/* ------------------------------------------------ sequential evaluation -- */
+
+/* y[b, i-1] = y_i = f(y_{i-1}, x_i), i = 1..T (Sec. 3.4). x is [B,T,d], y0 [B,n], y [B,T,n]. */
+void oracle_seq_eval(const oracle_cell* c, const double* th, long B, long T, const double* x,
+                     const double* y0, double* y, int nthreads) {
+    int n = c->n, d = c->d;
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for num_threads(nthreads) schedule(static)
+    for (long b = 0; b < B; b++) {
+        const double* h = y0 + b * n;
+        for (long i = 0; i < T; i++) {
+            double* out = y + (b * T + i) * n;
+            oracle_cell_f(c, th, h, x ? x + (b * T + i) * d : NULL, out);
+            h = out;
+        }
+    }
+}
+
+/* ------------------------------------------------------- DEER for an RNN -- */
+
+/* DEER iteration for y_i = f(y_{i-1}, x_i) (Sec. 3.1 eq. 3 and 5, Sec. 3.4 eq. 11, App. B.1).
+ * guess may be NULL (zeros). err_hist (may be NULL) receives err after every iteration
+ * (max_iter entries at most). Returns the number of iterations (linear solves) done. */
+int oracle_deer_eval(const oracle_cell* c, const double* th, long B, long T, const double* x,
+                     const double* y0, const double* guess, double tol, int max_iter,
+                     double* y, double* final_err, double* err_hist, int nthreads) {
+    int n = c->n, d = c->d;
+    size_t total = (size_t)B * T * n;
+    double* ynew = malloc(total * sizeof(double));
+    if (guess) memcpy(y, guess, total * sizeof(double));
+    else memset(y, 0, total * sizeof(double));
+    if (nthreads < 1) nthreads = 1;
+    double err = 1e10;
+    int iter = 0;
+    while (err > tol && iter < max_iter) {
+        double errmax = 0.0;
+        int bad = 0;
+#pragma omp parallel for num_threads(nthreads) schedule(static) reduction(max : errmax) reduction(| : bad)
+        for (long b = 0; b < B; b++) {
+            double* f = malloc((size_t)(3 * n + n * n) * sizeof(double));
+            double *zv = f + n, *G = zv + n;
+            for (long i = 0; i < T; i++) {
+                /* shifter: the argument of f at position i is the previous iterate at i-1 */
+                const double* hs = (i == 0 ? y0 + b * n : y + (b * T + i - 1) * n);
+                const double* xi = x ? x + (b * T + i) * d : NULL;
+                oracle_cell_f(c, th, hs, xi, f);
+                oracle_cell_jac(c, th, hs, xi, G);
+                for (int k = 0; k < n * n; k++) G[k] = -G[k];               /* G = -df/dy  */
+                for (int r = 0; r < n; r++) {                                /* z = f + G y */
+                    double s = f[r];
+                    for (int k = 0; k < n; k++) s += G[r * n + k] * hs[k];
+                    zv[r] = s;
+                }
+                /* inverse operator: y_i + G_i y_{i-1} = z_i with the new y_{i-1} */
+                const double* hp = (i == 0 ? y0 + b * n : ynew + (b * T + i - 1) * n);
+                for (int r = 0; r < n; r++) {
+                    double s = zv[r];
+                    for (int k = 0; k < n; k++) s -= G[r * n + k] * hp[k];
+                    ynew[(b * T + i) * n + r] = s;
+                    double dlt = fabs(s - y[(b * T + i) * n + r]);
+                    if (dlt > errmax) errmax = dlt;
+                    if (!(dlt == dlt) || isinf(dlt)) bad = 1;
+                }
+            }
+            free(f);
+        }
+        err = bad ? NAN : errmax;
+        memcpy(y, ynew, total * sizeof(double));
+        if (err_hist) err_hist[iter] = err;
+        iter++;
+    }
+    if (final_err) *final_err = err;
+    free(ynew);
+    return iter;
+}
+
+/* ---------------------------------------------- backward derivative, GRU -- */
+
+/* Sec. 3.1.1 eq. 7 for the RNN operator (L y)_i = y_i + G_i y_{i-1}, G_i = -J_i:
+ * first lam = (dL/dy) L_G^{-1}, i.e. lam_T = g_T, lam_i = g_i - G_{i+1}^T lam_{i+1};
+ * then the vector-Jacobian product of f with lam at every position.
+ * J_i is evaluated at the given trajectory y (h = y_{i-1}, y_0 for i = 1).
+ * g, y: [B,T,n]; outputs dtheta [theta_count] (overwritten), dx [B,T,d], dy0 [B,n]. */
+void oracle_gru_grad(int n, int d, const double* th, long B, long T, const double* x,
+                     const double* y0, const double* y, const double* g,
+                     double* dtheta, double* dx, double* dy0) {
+    long P = 3L * n * d + 3L * n * n + 4L * n;
+    memset(dtheta, 0, (size_t)P * sizeof(double));
+    double* lam = malloc((size_t)T * n * sizeof(double));
+    double* G = malloc((size_t)n * n * sizeof(double));
+    double* dh = malloc((size_t)n * sizeof(double));
+    for (long b = 0; b < B; b++) {
+        for (long i = T - 1; i >= 0; i--) {
+            for (int r = 0; r < n; r++) lam[i * n + r] = g[(b * T + i) * n + r];
+            if (i < T - 1) {
+                /* G_{i+1} uses h = y_i and x_{i+1} */
+                gru_jac(n, d, th, y + (b * T + i) * n, x + (b * T + i + 1) * d, G);
+                for (int k = 0; k < n * n; k++) G[k] = -G[k];
+                for (int r = 0; r < n; r++) {
+                    double s = 0.0;
+                    for (int k = 0; k < n; k++) s += G[k * n + r] * lam[(i + 1) * n + k];
+                    lam[i * n + r] -= s;
+                }
+            }
+        }
+        for (long i = 0; i < T; i++) {
+            const double* h = (i == 0 ? y0 + b * n : y + (b * T + i - 1) * n);
+            gru_vjp(n, d, th, h, x + (b * T + i) * d, lam + i * n, dtheta, dx + (b * T + i) * d, dh);
+            if (i == 0) memcpy(dy0 + b * n, dh, (size_t)n * sizeof(double));
+        }
+    }
+    free(lam); free(G); free(dh);
+}
+
+/* ------------------------------------------- matrix exponential and phi1 -- */
+
+static void matmul(int n, const double* A, const double* Bm, double* C) {
+    for (int r = 0; r < n; r++)
+        for (int c = 0; c < n; c++) {
+            double s = 0.0;
+            for (int k = 0; k < n; k++) s += A[r * n + k] * Bm[k * n + c];
+            C[r * n + c] = s;
+        }
+}
+
+/* E = exp(A) and P = phi1(A) = sum_{k>=0} A^k/(k+1)!  (so that A P = E - I).
+ * Taylor series on A/2^s with the max-row-sum norm of A/2^s at most 1/2, summed
+ * until a term no longer changes the sum, then s doublings:
+ * exp(2X) = exp(X)^2, phi1(2X) = (exp(X) + I) phi1(X) / 2. */
+void oracle_expm_phi1(int n, const double* A, double* E, double* P) {
+    size_t nn = (size_t)n * n;
+    double* X = malloc(4 * nn * sizeof(double));
+    double *term = X + nn, *tmp = term + nn, *tmp2 = tmp + nn;
+    double norm = 0.0;
+    for (int r = 0; r < n; r++) {
+        double s = 0.0;
+        for (int c = 0; c < n; c++) s += fabs(A[r * n + c]);
+        if (s > norm) norm = s;
+    }
+    int s = 0;
+    while (norm > 0.5 && s < 60) { norm *= 0.5; s++; }
+    double scale = ldexp(1.0, -s);
+    for (size_t k = 0; k < nn; k++) X[k] = A[k] * scale;
+    for (int r = 0; r < n; r++)
+        for (int c = 0; c < n; c++) {
+            double id = (r == c ? 1.0 : 0.0);
+            term[r * n + c] = id;   /* X^0/0! */
+            E[r * n + c] = id;
+            P[r * n + c] = id;      /* X^0/1! */
+        }
+    for (int k = 1; k <= 40; k++) {
+        matmul(n, term, X, tmp);
+        double tmax = 0.0;
+        for (size_t q = 0; q < nn; q++) {
+            term[q] = tmp[q] / k;                 /* X^k/k!      */
+            E[q] += term[q];
+            P[q] += term[q] / (k + 1);            /* X^k/(k+1)!  */
+            if (fabs(term[q]) > tmax) tmax = fabs(term[q]);
+        }
+        if (tmax < 1e-30) break;
+    }
+    for (int j = 0; j < s; j++) {
+        for (int r = 0; r < n; r++)
+            for (int c = 0; c < n; c++) tmp[r * n + c] = 0.5 * (E[r * n + c] + (r == c ? 1.0 : 0.0));
+        matmul(n, tmp, P, tmp2);
+        memcpy(P, tmp2, nn * sizeof(double));
+        matmul(n, E, E, tmp);
+        memcpy(E, tmp, nn * sizeof(double));
+    }
+    free(X);
+}
+
+/* One interval of the ODE inverse operator (Sec. 3.3 eq. 9 with midpoint values):
+ * Gc = (G0 + G1)/2, zc = (z0 + z1)/2, Gbar = exp(-Gc dt), zbar = Gc^{-1}(I - Gbar) zc
+ * computed as dt * phi1(-Gc dt) zc. */
+void oracle_ode_discretise(int n, const double* G0, const double* z0, const double* G1, const double* z1,
+                           double dt, double* Gbar, double* zbar) {
+    size_t nn = (size_t)n * n;
+    double* M = malloc((2 * nn + n) * sizeof(double));
+    double *Ph = M + nn, *zc = Ph + nn;
+    for (size_t k = 0; k < nn; k++) M[k] = -0.5 * (G0[k] + G1[k]) * dt;
+    for (int r = 0; r < n; r++) zc[r] = 0.5 * (z0[r] + z1[r]);
+    oracle_expm_phi1(n, M, Gbar, Ph);
+    for (int r = 0; r < n; r++) {
+        double s = 0.0;
+        for (int k = 0; k < n; k++) s += Ph[r * n + k] * zc[k];
+        zbar[r] = dt * s;
+    }
+    free(M);
+}
+
+/* -------------------------------------------------------- DEER for an ODE -- */
+
+/* dy/dt = f(y) on the uniform grid t_j = t0 + j dt, dt = (t1 - t0)/(T - 1), j = 0..T-1
+ * (Sec. 3.3).  Each iteration: G_j = -df/dy(y_j), z_j = f(y_j) + G_j y_j at every grid
+ * point of the previous iterate; then y_{i+1} = Gbar_i y_i + zbar_i from y_0 = y0.
+ * y: [B,T,n] with y[:,0] = y0.  guess may be NULL (zeros); its first point is replaced by y0. */
+int oracle_ode_deer_eval(const oracle_cell* c, const double* th, long B, long T, double t0, double t1,
+                         const double* y0, const double* guess, double tol, int max_iter,
+                         double* y, double* final_err, double* err_hist, int nthreads) {
+    int n = c->n;
+    size_t nn = (size_t)n * n;
+    size_t total = (size_t)B * T * n;
+    double dt = (t1 - t0) / (double)(T - 1);
+    double* ynew = malloc(total * sizeof(double));
+    if (guess) memcpy(y, guess, total * sizeof(double));
+    else memset(y, 0, total * sizeof(double));
+    for (long b = 0; b < B; b++) memcpy(y + b * T * n, y0 + b * n, (size_t)n * sizeof(double));
+    if (nthreads < 1) nthreads = 1;
+    double err = 1e10;
+    int iter = 0;
+    while (err > tol && iter < max_iter) {
+        double errmax = 0.0;
+        int bad = 0;
+#pragma omp parallel for num_threads(nthreads) schedule(static) reduction(max : errmax) reduction(| : bad)
+        for (long b = 0; b < B; b++) {
+            double* buf = malloc((3 * nn + 5 * n) * sizeof(double));
+            double *Ga = buf, *Gb = Ga + nn, *Gbar = Gb + nn;
+            double *za = Gbar + nn, *zb = za + n, *zbar = zb + n, *f = zbar + n;
+            const double* yb = y + b * T * n;
+            double* ynb = ynew + b * T * n;
+            memcpy(ynb, y0 + b * n, (size_t)n * sizeof(double));
+            /* G and z at grid point 0 */
+            mlp_f(c, th, yb, f);
+            mlp_jac(c, th, yb, Ga);
+            for (size_t k = 0; k < nn; k++) Ga[k] = -Ga[k];
+            for (int r = 0; r < n; r++) {
+                double s = f[r];
+                for (int k = 0; k < n; k++) s += Ga[r * n + k] * yb[k];
+                za[r] = s;
+            }
+            for (long i = 0; i + 1 < T; i++) {
+                const double* y1 = yb + (i + 1) * n;
+                mlp_f(c, th, y1, f);
+                mlp_jac(c, th, y1, Gb);
+                for (size_t k = 0; k < nn; k++) Gb[k] = -Gb[k];
+                for (int r = 0; r < n; r++) {
+                    double s = f[r];
+                    for (int k = 0; k < n; k++) s += Gb[r * n + k] * y1[k];
+                    zb[r] = s;
+                }
+                oracle_ode_discretise(n, Ga, za, Gb, zb, dt, Gbar, zbar);
+                for (int r = 0; r < n; r++) {
+                    double s = zbar[r];
+                    for (int k = 0; k < n; k++) s += Gbar[r * n + k] * ynb[i * n + k];
+                    ynb[(i + 1) * n + r] = s;
+                    double dlt = fabs(s - yb[(i + 1) * n + r]);
+                    if (dlt > errmax) errmax = dlt;
+                    if (!(dlt == dlt) || isinf(dlt)) bad = 1;
+                }
+                memcpy(Ga, Gb, nn * sizeof(double));
+                memcpy(za, zb, (size_t)n * sizeof(double));
+            }
+            free(buf);
+        }
+        err = bad ? NAN : errmax;
+        memcpy(y, ynew, total * sizeof(double));
+        if (err_hist) err_hist[iter] = err;
+        iter++;
+    }
+    if (final_err) *final_err = err;
+    free(ynew);
+    return iter;
+}
+
+int oracle_max_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

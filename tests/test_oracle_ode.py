@@ -1,0 +1,154 @@
+"""Pins of the oracle's matrix exponential, phi1, the midpoint discretisation and the ODE DEER
+iteration against SciPy, closed forms and a Runge-Kutta reference.  CPU only."""
+import numpy as np
+import pytest
+import scipy.linalg
+from scipy.integrate import solve_ivp
+
+import oracle
+from paper_2309_12252_amd import inputs
+from conftest import read_golden
+
+GOLD = read_golden("paper_values.txt")
+
+
+@pytest.mark.parametrize("n,scale", [(1, 0.3), (2, 1e-4), (4, 0.7), (8, 3.0), (8, 25.0), (5, 0.0)])
+def test_expm_and_phi1_match_scipy(n, scale):
+    rng = np.random.default_rng(n)
+    A = rng.standard_normal((n, n)) * scale
+    E, P = oracle.expm_phi1(A)
+    Es = scipy.linalg.expm(A)
+    np.testing.assert_allclose(E, Es, rtol=1e-11, atol=1e-13 * max(1.0, np.abs(Es).max()))
+    # exp([[A, I], [0, 0]]) = [[exp(A), phi1(A)], [0, I]]
+    aug = np.zeros((2 * n, 2 * n)); aug[:n, :n] = A; aug[:n, n:] = np.eye(n)
+    Ps = scipy.linalg.expm(aug)[:n, n:]
+    np.testing.assert_allclose(P, Ps, rtol=1e-11, atol=1e-13 * max(1.0, np.abs(Ps).max()))
+    if scale > 0:
+        np.testing.assert_allclose(P, np.linalg.solve(A, E - np.eye(n)), rtol=1e-7, atol=1e-9)
+
+
+def test_phi1_of_a_singular_matrix():
+    A = np.array([[0.0, 1.0], [0.0, 0.0]])            # nilpotent: exp = I + A, phi1 = I + A/2
+    E, P = oracle.expm_phi1(A)
+    np.testing.assert_allclose(E, np.eye(2) + A, atol=1e-15)
+    np.testing.assert_allclose(P, np.eye(2) + A / 2, atol=1e-15)
+
+
+def test_discretise_matches_the_printed_formula():
+    # Sec. 3.3 eq. 9: Gbar = exp(-G dt), zbar = G^{-1}(I - Gbar) z with midpoint G and z
+    n, dt = 4, 0.05
+    rng = np.random.default_rng(1)
+    G0, G1 = rng.standard_normal((n, n)), rng.standard_normal((n, n))
+    z0, z1 = rng.standard_normal(n), rng.standard_normal(n)
+    Gbar, zbar = oracle.ode_discretise(G0, z0, G1, z1, dt)
+    Gc, zc = 0.5 * (G0 + G1), 0.5 * (z0 + z1)
+    want_G = scipy.linalg.expm(-Gc * dt)
+    np.testing.assert_allclose(Gbar, want_G, atol=1e-13)
+    np.testing.assert_allclose(zbar, np.linalg.solve(Gc, (np.eye(n) - want_G) @ zc), atol=1e-11)
+
+
+def linear_field_theta(A, c):
+    """MLP with no hidden layer: f(y) = W y + b with W = -A, b = c."""
+    return np.concatenate([(-A).ravel(), c])
+
+
+def test_linear_field_is_integrated_exactly_in_two_iterations():
+    # constant G, z: the piecewise-constant assumption of eq. 9 holds exactly
+    n, T, B = 3, 50, 2
+    rng = np.random.default_rng(7)
+    A = rng.standard_normal((n, n)) + 2 * np.eye(n)
+    c = rng.standard_normal(n)
+    y0 = rng.standard_normal((B, n))
+    cell = oracle.make_cell(oracle.CELL_MLP, n, 0, 0, 0)
+    y, it, err, hist = oracle.ode_deer_eval(cell, linear_field_theta(A, c), y0, T, 0.0, 2.0, tol=1e-10,
+                                            max_iter=50)
+    assert it == 2 and hist[1] < 1e-12
+    t = np.linspace(0.0, 2.0, T)
+    for b in range(B):
+        for j in range(T):
+            Et = scipy.linalg.expm(-A * t[j])
+            want = Et @ y0[b] + np.linalg.solve(A, (np.eye(n) - Et) @ c)
+            np.testing.assert_allclose(y[b, j], want, atol=1e-11)
+
+
+def mlp_numpy(n, width, nhid, theta):
+    o, nin, mats = 0, n, []
+    for _ in range(nhid):
+        W = theta[o:o + width * nin].reshape(width, nin); o += width * nin
+        b = theta[o:o + width]; o += width
+        mats.append((W, b)); nin = width
+    Wo = theta[o:o + n * nin].reshape(n, nin); o += n * nin
+    bo = theta[o:o + n]
+
+    def f(y):
+        a = y
+        for W, b in mats:
+            a = np.tanh(W @ a + b)
+        return Wo @ a + bo
+    return f
+
+
+def small_ode(seed=3, n=3, width=6, nhid=2, B=2):
+    w = inputs.mlp_ode_workload("t", seed, B=B, T=2, n=n, width=width, nhid=nhid, t0=0.0, t1=1.5)
+    return w, oracle.make_cell(oracle.CELL_MLP, n, 0, width, nhid)
+
+
+def test_converged_iterate_satisfies_the_discretised_equation():
+    # at the fixed point, y_{i+1} = Gbar_i y_i + zbar_i with G = -df/dy and z = f + G y taken at
+    # the iterate itself; rebuilt here with SciPy's expm, a linear solve and a finite-difference Jacobian
+    w, cell = small_ode()
+    T = 40
+    y, it, err, _ = oracle.ode_deer_eval(cell, w.theta, w.y0, T, w.t0, w.t1, tol=1e-12, max_iter=50)
+    assert it < 50
+    f = mlp_numpy(w.n, w.mlp_width, w.mlp_hidden_layers, w.theta.astype(np.float64))
+    dt = (w.t1 - w.t0) / (T - 1)
+    n = w.n
+
+    def Gz(yy):
+        J = np.empty((n, n))
+        for j in range(n):
+            e = np.zeros(n); e[j] = 1e-6
+            J[:, j] = (f(yy + e) - f(yy - e)) / 2e-6
+        return -J, f(yy) - J @ yy
+
+    for b in range(w.B):
+        np.testing.assert_allclose(y[b, 0], w.y0[b], atol=0)
+        for i in range(T - 1):
+            G0, z0 = Gz(y[b, i]); G1, z1 = Gz(y[b, i + 1])
+            Gc, zc = 0.5 * (G0 + G1), 0.5 * (z0 + z1)
+            Gbar = scipy.linalg.expm(-Gc * dt)
+            zbar = np.linalg.solve(Gc, (np.eye(n) - Gbar) @ zc)
+            np.testing.assert_allclose(y[b, i + 1], Gbar @ y[b, i] + zbar, atol=1e-8)
+
+
+def test_global_error_is_second_order_in_dt():
+    # local truncation error O(dt^3) with midpoint values (Sec. 3.3, App. A.5) => global error O(dt^2)
+    assert GOLD["midpoint_lte_order"] == 3
+    w, cell = small_ode(seed=11)
+    f = mlp_numpy(w.n, w.mlp_width, w.mlp_hidden_layers, w.theta.astype(np.float64))
+    errs = []
+    for T in (21, 41, 81, 161):
+        y, it, _, _ = oracle.ode_deer_eval(cell, w.theta, w.y0, T, w.t0, w.t1, tol=1e-13, max_iter=60)
+        assert it < 60
+        e = 0.0
+        for b in range(w.B):
+            ref = solve_ivp(lambda t, yy: f(yy), (w.t0, w.t1), w.y0[b].astype(np.float64), method="DOP853",
+                            rtol=1e-13, atol=1e-13, t_eval=np.linspace(w.t0, w.t1, T))
+            e = max(e, np.abs(ref.y.T - y[b]).max())
+        errs.append(e)
+    ratios = [errs[k] / errs[k + 1] for k in range(3)]
+    assert all(3.3 < r < 4.7 for r in ratios), (errs, ratios)
+    assert errs[-1] < 1e-4
+
+
+def test_ode_deer_options():
+    w, cell = small_ode(seed=5)
+    T = 30
+    y, it, err, hist = oracle.ode_deer_eval(cell, w.theta, w.y0, T, w.t0, w.t1, tol=1e-9, max_iter=50)
+    assert err <= 1e-9 and len(hist) == it
+    y2, it2, _, _ = oracle.ode_deer_eval(cell, w.theta, w.y0, T, w.t0, w.t1, guess=y, tol=1e-9, max_iter=50,
+                                         nthreads=2)
+    assert it2 == 1
+    np.testing.assert_allclose(y2, y, atol=1e-10)
+    _, it3, _, _ = oracle.ode_deer_eval(cell, w.theta, w.y0, T, w.t0, w.t1, tol=1e-9, max_iter=2)
+    assert it3 == 2
