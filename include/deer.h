@@ -1,0 +1,151 @@
+/*
+ * deer.h -- C ABI of the DEER hot path for one AMD MI355X (gfx950).
+ *
+ * DEER (arxiv 2309.12252) evaluates a non-linear recurrence y_i = f(y_{i-1}, x_i)
+ * (Sec. 3.4) or an ODE dy/dt = f(y) on a time grid (Sec. 3.3) by the fixed-point
+ * iteration  y <- L_G^{-1}[ f(y_shifted) + G y_shifted ],  G = -df/dy  (Sec. 3.1
+ * eq. 3 and 5), where L_G^{-1} solves a linear recurrence with an associative scan
+ * over affine pairs (Sec. 3.3 eq. 9-10, Sec. 3.4 eq. 11).  Gradients take one
+ * application of the transposed, reversed operator followed by the vector-Jacobian
+ * product of f (Sec. 3.1.1 eq. 7).
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; all other
+ *     pointers are HOST pointers owned by the caller.  The library allocates no
+ *     device memory: the caller hands in a workspace of deer_workspace_bytes().
+ *   - Arrays are dense, row-major, in the dtype of the configuration (fp32 or
+ *     fp64).  d_* arrays must be 16-byte aligned.
+ *   - Work is enqueued on the HIP stream given to deer_create().  deer_eval()
+ *     synchronises that stream (it reads the convergence error back) and returns
+ *     with its outputs complete; deer_grad() and deer_linrec_solve() synchronise
+ *     before returning as well.
+ *   - Every call returns a deer_status; nothing throws or aborts across the ABI.
+ *     After a non-OK status deer_last_error() describes what went wrong.
+ *   - Calls on one context must not overlap in time.
+ *
+ * The model
+ *   GRU cell (the paper names the cell but prints no equations; this is the
+ *   reading used, gates r, z and candidate c, reset applied after the hidden
+ *   projection):
+ *       r = sigmoid(W_r x + b_r + U_r h)     z = sigmoid(W_z x + b_z + U_z h)
+ *       q = U_c h + b_hc                     c = tanh(W_c x + b_c + r * q)
+ *       f(h, x) = (1 - z) * c + z * h
+ *     theta (flat): W[3n,d] (rows r|z|c), U[3n,n] (rows r|z|c), b[3n] (r|z|c), b_hc[n].
+ *   MLP vector field (autonomous):
+ *       f(y) = W_3 tanh(W_2 tanh(W_1 y + b_1) + b_2) + b_3
+ *     theta (flat): W_1[w,n], b_1[w], W_2[w,w], b_2[w], W_3[n,w], b_3[n].
+ */
+#ifndef DEER_H
+#define DEER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DEER_OK = 0,
+    DEER_ERR_INVALID_ARG = 1,  /* NULL where a pointer is required, non-positive size, bad enum          */
+    DEER_ERR_UNSUPPORTED = 2,  /* a shape or mode this build has no kernel for                           */
+    DEER_ERR_WORKSPACE = 3,    /* workspace NULL, misaligned or smaller than deer_workspace_bytes()      */
+    DEER_ERR_HIP = 4,          /* a HIP runtime call failed, or a kernel reported an internal time-out   */
+    DEER_ERR_NONFINITE = 5     /* the iteration produced a NaN/Inf; outputs hold the last iterate        */
+} deer_status;
+
+typedef enum { DEER_CELL_GRU = 0, DEER_CELL_MLP_ODE = 1 } deer_cell;
+typedef enum { DEER_F32 = 0, DEER_F64 = 1 } deer_dtype;
+
+typedef struct {
+    int32_t cell;               /* deer_cell                                                             */
+    int32_t dtype;              /* deer_dtype                                                            */
+    int32_t B;                  /* batch: independent sequences                                          */
+    int32_t T;                  /* GRU: number of steps; MLP_ODE: number of grid points (>= 2)           */
+    int32_t n;                  /* state size: 1, 2, 4, 8, 16 or 32                                      */
+    int32_t d;                  /* GRU input size (1..16); ignored for MLP_ODE                           */
+    int32_t mlp_width;          /* MLP_ODE hidden width (multiple of 4, <= 64); ignored for GRU          */
+    int32_t mlp_hidden_layers;  /* MLP_ODE: must be 2                                                    */
+    double t0, t1;              /* MLP_ODE: uniform grid t_j = t0 + j (t1 - t0)/(T - 1)                  */
+} deer_config;
+
+typedef struct deer_ctx deer_ctx; /* opaque, host memory owned by the library */
+
+/* Accumulated per-kernel device time, filled while profiling is on (see deer_set_profiling). */
+typedef struct {
+    double funceval_ms;   int64_t funceval_launches;   /* f, Jacobian and right-hand side            */
+    double discretise_ms; int64_t discretise_launches; /* ODE only: exp(-G dt), phi1                 */
+    double scan_ms;       int64_t scan_launches;       /* inverse linear operator (+ fused max|dy|)  */
+    double vjp_ms;        int64_t vjp_launches;        /* GRU VJP + parameter-gradient reduction     */
+} deer_profile;
+
+/* Number of parameters in the flat theta of this configuration (layouts above); 0 if invalid. */
+size_t deer_theta_count(const deer_config* cfg);
+
+/* Bytes of device workspace deer_create() needs for cfg (Jacobian stream [B,T,n,n], right-hand
+ * side, second trajectory buffer, scan tile descriptors, counters; Sec. 3.5: O(n^2 T) memory). */
+deer_status deer_workspace_bytes(const deer_config* cfg, size_t* bytes);
+
+/* Create a context.  d_workspace (device, 256-byte aligned, >= deer_workspace_bytes) stays owned by
+ * the caller and must outlive the context; the library may overwrite all of it in any call.
+ * hip_stream is a hipStream_t (NULL = the default stream).  On failure *out is NULL. */
+deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t workspace_bytes,
+                        void* hip_stream, deer_ctx** out);
+
+/* Forward evaluation by DEER (Sec. 3.1 eq. 3 with eq. 5; iteration control as in App. B.1).
+ *   d_theta   in  parameters, deer_theta_count() entries
+ *   d_x       in  GRU: inputs [B,T,d]; MLP_ODE: ignored (may be NULL)
+ *   d_y0      in  initial state [B,n]
+ *   d_y_guess in  initial guess [B,T,n], or NULL for all zeros (the paper's benchmarks start from
+ *                 zeros; a previous solution can be passed as a warm start, Sec. 3.1)
+ *   tol       in  stop when err = max|y_next - y| <= tol (paper: 1e-4 fp32, 1e-7 fp64)
+ *   max_iter  in  at most this many iterations (>= 0)
+ *   d_y       out GRU: y[b,i-1,:] = y_i for i = 1..T.  MLP_ODE: y[b,j,:] = y(t_j), y[b,0,:] = y0;
+ *                 the first grid point is pinned to y0 in every iterate, so err runs over j >= 1
+ *   iters     out number of iterations (linear solves) performed, including the one whose err met tol
+ *   final_err out err of the last iteration (1e10 if max_iter == 0)
+ *   converged out 1 if final_err <= tol else 0.  Not converging is not an error: DEER_OK is returned
+ *                 with iters == max_iter (Newton's method may diverge far from the solution, Sec. 3.5).
+ * The convergence test is global over batch, time and state.  DEER_ERR_NONFINITE if err is NaN/Inf. */
+deer_status deer_eval(deer_ctx* ctx, const void* d_theta, const void* d_x, const void* d_y0,
+                      const void* d_y_guess, double tol, int32_t max_iter, void* d_y,
+                      int32_t* iters, double* final_err, int32_t* converged);
+
+/* Backward derivative for the GRU recurrence (Sec. 3.1.1 eq. 7): one reverse scan with the
+ * transposed Jacobians, lam_T = g_T, lam_i = g_i + J_{i+1}^T lam_{i+1}, then the VJP of f.
+ * The Jacobians are recomputed at the trajectory d_y that is passed in, so the trajectory may
+ * come from deer_eval() or from a sequential evaluation (Sec. 3.1.1, last paragraph).
+ *   d_y        in  trajectory [B,T,n]          d_dLdy   in  g = dL/dy [B,T,n]
+ *   d_dLdx     out [B,T,d], or NULL to skip    d_dLdtheta out [theta_count] (overwritten, not accumulated)
+ *   d_dLdy0    out [B,n], or NULL to skip
+ * DEER_ERR_UNSUPPORTED for MLP_ODE configurations. */
+deer_status deer_grad(deer_ctx* ctx, const void* d_theta, const void* d_x, const void* d_y0,
+                      const void* d_y, const void* d_dLdy, void* d_dLdx, void* d_dLdtheta,
+                      void* d_dLdy0);
+
+/* The inverse linear operator alone (Sec. 3.3 eq. 9-10, Sec. 3.4 eq. 11):
+ * y_i = A_i y_{i-1} + b_i for i = 1..T from y_0, for B independent sequences, by the blocked
+ * associative scan.  Shapes come from the context (B, T, n, dtype).
+ *   d_A [B,T,n,n]   d_b [B,T,n]   d_y0 [B,n] (NULL = zeros)   d_y out [B,T,n]
+ *   reverse != 0 applies the dual (transposed, time-reversed) operator of Sec. 3.1.1 eq. 7 instead:
+ *   y_T = b_T, y_i = b_i + A_{i+1}^T y_{i+1}; d_y0 is ignored.  A is read as stored and transposed
+ *   on the fly. */
+deer_status deer_linrec_solve(deer_ctx* ctx, const void* d_A, const void* d_b, const void* d_y0,
+                              void* d_y, int32_t reverse);
+
+/* Switch per-kernel timing with HIP events on the context's stream on or off (off by default;
+ * turning it on resets the accumulated numbers), and read the numbers accumulated so far. */
+deer_status deer_set_profiling(deer_ctx* ctx, int32_t on);
+deer_status deer_get_profile(deer_ctx* ctx, deer_profile* out);
+
+/* Text of the last error on this context (never NULL; valid until the next call on ctx).
+ * With ctx == NULL: the last error of a failed deer_create()/deer_workspace_bytes() on this thread. */
+const char* deer_last_error(const deer_ctx* ctx);
+
+/* Free the context (host memory and HIP events only; the workspace stays with the caller). */
+void deer_destroy(deer_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEER_H */

@@ -1,0 +1,452 @@
+// Host driver and C ABI of the DEER library (see include/deer.h for the contract).
+// The driver owns no device memory: it carves the caller's workspace into the Jacobian stream,
+// the right-hand side, a second trajectory buffer, scan tile descriptors and a few counters.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/deer.h"
+#include "deer_common.h"
+
+using namespace deer;
+
+namespace {
+
+constexpr int kSlots = 256;          // ticket / error slots, one per scan launch between refills
+constexpr size_t kAlign = 256;
+
+thread_local std::string g_last_error;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+    size_t esz;          // bytes per scalar
+    int scan_T;          // scan positions per sequence
+    int tile;            // scan positions per tile
+    int tiles;           // tiles per sequence
+    int L;               // positions per lane (VALU scan)
+    bool mfma;
+    int vjp_blocks;
+    // byte offsets into the workspace
+    size_t off_J, off_rhs, off_ybuf, off_Gbar, off_zbar, off_flags, off_aggM, off_aggv, off_incl,
+        off_ctl, off_partial, total;
+};
+
+size_t theta_count(const deer_config* c) {
+    const size_t n = (size_t)c->n;
+    if (c->cell == DEER_CELL_GRU) return 3 * n * (size_t)c->d + 3 * n * n + 4 * n;
+    const size_t w = (size_t)c->mlp_width;
+    return (w * n + w) + (w * w + w) + (n * w + n);
+}
+
+bool validate(const deer_config* c, std::string& why) {
+    if (!c) { why = "config is NULL"; return false; }
+    if (c->cell != DEER_CELL_GRU && c->cell != DEER_CELL_MLP_ODE) { why = "unknown cell"; return false; }
+    if (c->dtype != DEER_F32 && c->dtype != DEER_F64) { why = "unknown dtype"; return false; }
+    if (c->B < 1 || c->T < 1 || c->n < 1) { why = "B, T and n must be positive"; return false; }
+    if ((long long)c->B * c->T > (1LL << 31) - 1) { why = "B*T must fit 31 bits"; return false; }
+    return true;
+}
+
+bool supported(const deer_config* c, std::string& why) {
+    const int n = c->n;
+    if (c->cell == DEER_CELL_GRU) {
+        if (!(n == 1 || n == 2 || n == 4 || n == 8 || n == 16 || n == 32)) {
+            why = "GRU state size must be 1, 2, 4, 8, 16 or 32";
+            return false;
+        }
+        if (c->d < 1 || c->d > 16) { why = "GRU input size must be 1..16"; return false; }
+    } else {
+        if (!(n == 2 || n == 4 || n == 8)) { why = "MLP_ODE state size must be 2, 4 or 8"; return false; }
+        if (c->mlp_hidden_layers != 2) { why = "MLP_ODE needs exactly 2 hidden layers"; return false; }
+        const int w = c->mlp_width;
+        if (!(w == 16 || w == 32 || w == 64) || w % n != 0) {
+            why = "MLP_ODE hidden width must be 16, 32 or 64 and a multiple of n";
+            return false;
+        }
+        if (c->T < 2) { why = "MLP_ODE needs at least 2 grid points"; return false; }
+        if (!(c->t1 > c->t0)) { why = "MLP_ODE needs t1 > t0"; return false; }
+    }
+    return true;
+}
+
+int env_int(const char* name, int dflt) {
+    const char* s = std::getenv(name);
+    if (!s || !*s) return dflt;
+    return std::atoi(s);
+}
+
+Plan make_plan(const deer_config* c) {
+    Plan p{};
+    p.esz = c->dtype == DEER_F32 ? 4 : 8;
+    const size_t n = (size_t)c->n, B = (size_t)c->B, T = (size_t)c->T;
+    const bool ode = c->cell == DEER_CELL_MLP_ODE;
+    p.scan_T = ode ? c->T - 1 : c->T;
+    p.mfma = c->n >= 16;
+    if (p.mfma) {
+        p.L = 0;
+        p.tile = scan_mfma_tile(c->dtype, c->n);
+    } else {
+        // positions per lane: enough tiles to fill the chip, long enough serial runs to amortise
+        // the log-step scan across lanes
+        const long long S = (long long)B * p.scan_T;
+        long long L = (S + 256LL * 1024 - 1) / (256LL * 1024);
+        if (L < 2) L = 2;
+        if (L > 16) L = 16;
+        L = env_int("DEER_SCAN_L", (int)L);
+        if (L < 1) L = 1;
+        if (L > 64) L = 64;
+        p.L = (int)L;
+        p.tile = scan_valu_tile(c->n, p.L);
+    }
+    p.tiles = (p.scan_T + p.tile - 1) / p.tile;
+    if (p.tiles < 1) p.tiles = 1;
+    p.vjp_blocks = c->cell == DEER_CELL_GRU ? gru_vjp_blocks(c->n, (long long)B * T) : 0;
+
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    p.off_J = take(B * T * n * n * p.esz);
+    p.off_rhs = take(B * T * n * p.esz);
+    p.off_ybuf = take(B * T * n * p.esz);
+    p.off_Gbar = take(ode ? B * (T - 1) * n * n * p.esz : 0);
+    p.off_zbar = take(ode ? B * (T - 1) * n * p.esz : 0);
+    const size_t nt = B * (size_t)p.tiles;
+    p.off_flags = take(nt * 4);
+    p.off_aggM = take(nt * n * n * p.esz);
+    p.off_aggv = take(nt * n * p.esz);
+    p.off_incl = take(nt * n * p.esz);
+    p.off_ctl = take((size_t)kSlots * 4 + (size_t)kSlots * 8 + 16);   // tickets, err bits, status
+    p.off_partial = take((size_t)p.vjp_blocks * 4 * theta_count(c) * p.esz);
+    p.total = off;
+    return p;
+}
+
+}  // namespace
+
+struct deer_ctx {
+    deer_config cfg;
+    Plan plan;
+    hipStream_t stream;
+    char* ws;
+    unsigned epoch;
+    void* h_err;            // pinned, 16 bytes
+    bool profiling;
+    deer_profile prof;
+    hipEvent_t ev[16];
+    int ev_kind[8];
+    int ev_used;
+    std::string last_error;
+};
+
+namespace {
+
+enum { KIND_FUNCEVAL = 0, KIND_DISC = 1, KIND_SCAN = 2, KIND_VJP = 3 };
+
+deer_status fail(deer_ctx* ctx, deer_status st, const std::string& msg) {
+    if (ctx) ctx->last_error = msg;
+    g_last_error = msg;
+    return st;
+}
+
+#define HIPCHK(ctx, expr)                                                                       \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess)                                                                   \
+            return fail(ctx, DEER_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));  \
+    } while (0)
+
+unsigned* ctl_ticket(deer_ctx* c, int slot) { return reinterpret_cast<unsigned*>(c->ws + c->plan.off_ctl) + slot; }
+void* ctl_err(deer_ctx* c, int slot) { return c->ws + c->plan.off_ctl + (size_t)kSlots * 4 + (size_t)slot * 8; }
+unsigned* ctl_status(deer_ctx* c) {
+    return reinterpret_cast<unsigned*>(c->ws + c->plan.off_ctl + (size_t)kSlots * 4 + (size_t)kSlots * 8);
+}
+size_t ctl_bytes() { return align_up((size_t)kSlots * 4 + (size_t)kSlots * 8 + 16); }
+
+void prof_begin(deer_ctx* c, int kind) {
+    if (!c->profiling || c->ev_used >= 8) return;
+    c->ev_kind[c->ev_used] = kind;
+    (void)hipEventRecord(c->ev[2 * c->ev_used], c->stream);
+}
+void prof_end(deer_ctx* c) {
+    if (!c->profiling || c->ev_used >= 8) return;
+    (void)hipEventRecord(c->ev[2 * c->ev_used + 1], c->stream);
+    c->ev_used++;
+}
+// call after the stream has been synchronised
+void prof_collect(deer_ctx* c) {
+    for (int i = 0; i < c->ev_used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->ev[2 * i], c->ev[2 * i + 1]) != hipSuccess) continue;
+        switch (c->ev_kind[i]) {
+            case KIND_FUNCEVAL: c->prof.funceval_ms += ms; c->prof.funceval_launches++; break;
+            case KIND_DISC: c->prof.discretise_ms += ms; c->prof.discretise_launches++; break;
+            case KIND_SCAN: c->prof.scan_ms += ms; c->prof.scan_launches++; break;
+            default: c->prof.vjp_ms += ms; c->prof.vjp_launches++; break;
+        }
+    }
+    c->ev_used = 0;
+}
+
+// One scan launch over the context's shapes.
+hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, void* out, const void* yold,
+                    long long strideA, long long strideb, long long strideOut, int reverse, int slot, bool want_err) {
+    const deer_config& g = c->cfg;
+    ScanParams p{};
+    p.A = A; p.bv = bv; p.y0 = y0; p.out = out; p.yold = yold;
+    p.strideA = strideA; p.strideb = strideb; p.strideOut = strideOut; p.strideOld = strideOut;
+    p.B = g.B; p.T = c->plan.scan_T; p.L = c->plan.L; p.tiles = c->plan.tiles; p.reverse = reverse;
+    p.epoch = ++c->epoch;
+    if (c->epoch >= (1u << 30)) c->epoch = 0;   // flags are re-zeroed by the caller path below when this wraps
+    p.flags = reinterpret_cast<unsigned*>(c->ws + c->plan.off_flags);
+    p.aggM = c->ws + c->plan.off_aggM;
+    p.aggv = c->ws + c->plan.off_aggv;
+    p.incl = c->ws + c->plan.off_incl;
+    p.ticket = ctl_ticket(c, slot);
+    p.err = want_err ? ctl_err(c, slot) : nullptr;
+    p.status = ctl_status(c);
+    prof_begin(c, KIND_SCAN);
+    hipError_t e = c->plan.mfma ? launch_scan_mfma(g.dtype, g.n, p, c->stream)
+                                : launch_scan_valu(g.dtype, g.n, p, c->stream);
+    prof_end(c);
+    return e;
+}
+
+deer_status zero_ctl(deer_ctx* c) {
+    HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_ctl, ctl_bytes(), c->stream));
+    if (c->epoch == 0) {
+        const size_t fb = align_up((size_t)c->cfg.B * c->plan.tiles * 4);
+        HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_flags, fb, c->stream));
+    }
+    return DEER_OK;
+}
+
+deer_status check_status(deer_ctx* c) {
+    unsigned st = 0;
+    HIPCHK(c, hipMemcpyAsync(c->h_err, ctl_status(c), 4, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    std::memcpy(&st, c->h_err, 4);
+    if (st != 0) return fail(c, DEER_ERR_HIP, "scan kernel: a tile waited too long for its predecessors");
+    return DEER_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t deer_theta_count(const deer_config* cfg) {
+    std::string why;
+    if (!validate(cfg, why)) return 0;
+    return theta_count(cfg);
+}
+
+deer_status deer_workspace_bytes(const deer_config* cfg, size_t* bytes) {
+    std::string why;
+    if (!bytes) return fail(nullptr, DEER_ERR_INVALID_ARG, "bytes is NULL");
+    if (!validate(cfg, why)) return fail(nullptr, DEER_ERR_INVALID_ARG, why);
+    if (!supported(cfg, why)) return fail(nullptr, DEER_ERR_UNSUPPORTED, why);
+    *bytes = make_plan(cfg).total;
+    return DEER_OK;
+}
+
+deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t workspace_bytes, void* hip_stream,
+                        deer_ctx** out) {
+    if (!out) return fail(nullptr, DEER_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    std::string why;
+    if (!validate(cfg, why)) return fail(nullptr, DEER_ERR_INVALID_ARG, why);
+    if (!supported(cfg, why)) return fail(nullptr, DEER_ERR_UNSUPPORTED, why);
+    Plan plan = make_plan(cfg);
+    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0 || workspace_bytes < plan.total)
+        return fail(nullptr, DEER_ERR_WORKSPACE, "workspace is NULL, misaligned or too small");
+    deer_ctx* c = new (std::nothrow) deer_ctx();
+    if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "out of host memory");
+    c->cfg = *cfg;
+    c->plan = plan;
+    c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    c->ws = reinterpret_cast<char*>(d_workspace);
+    c->epoch = 0;
+    c->h_err = nullptr;
+    c->profiling = false;
+    c->prof = deer_profile{};
+    c->ev_used = 0;
+    for (auto& e : c->ev) e = nullptr;
+    hipError_t e = hipHostMalloc(&c->h_err, 16, hipHostMallocDefault);
+    for (int i = 0; i < 16 && e == hipSuccess; ++i) e = hipEventCreate(&c->ev[i]);
+    if (e == hipSuccess) e = launch_fill_zero(c->ws + plan.off_flags, align_up((size_t)cfg->B * plan.tiles * 4), c->stream);
+    if (e == hipSuccess) e = launch_fill_zero(c->ws + plan.off_ctl, ctl_bytes(), c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) {
+        std::string msg = std::string("deer_create: ") + hipGetErrorString(e);
+        deer_destroy(c);
+        return fail(nullptr, DEER_ERR_HIP, msg);
+    }
+    c->epoch = 1;
+    *out = c;
+    return DEER_OK;
+}
+
+deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const void* d_y0, const void* d_y_guess,
+                      double tol, int32_t max_iter, void* d_y, int32_t* iters, double* final_err,
+                      int32_t* converged) {
+    if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
+    const deer_config& g = c->cfg;
+    const bool ode = g.cell == DEER_CELL_MLP_ODE;
+    if (!d_theta || !d_y0 || !d_y || (!ode && !d_x)) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
+    if (!iters || !final_err || !converged) return fail(c, DEER_ERR_INVALID_ARG, "an output pointer is NULL");
+    if (max_iter < 0 || !(tol >= 0.0)) return fail(c, DEER_ERR_INVALID_ARG, "max_iter and tol must be >= 0");
+
+    const size_t esz = c->plan.esz;
+    const size_t n = (size_t)g.n, B = (size_t)g.B, T = (size_t)g.T;
+    const size_t ybytes = B * T * n * esz;
+    char* J = c->ws + c->plan.off_J;
+    char* rhs = c->ws + c->plan.off_rhs;
+    char* cur = c->ws + c->plan.off_ybuf;   // current iterate
+    char* nxt = reinterpret_cast<char*>(d_y);
+
+    deer_status st = zero_ctl(c);
+    if (st != DEER_OK) return st;
+    if (d_y_guess) HIPCHK(c, hipMemcpyAsync(cur, d_y_guess, ybytes, hipMemcpyDeviceToDevice, c->stream));
+    else HIPCHK(c, launch_fill_zero(cur, align_up(ybytes), c->stream));
+    if (ode) {
+        HIPCHK(c, launch_pin_first(g.dtype, cur, d_y0, g.B, g.T, g.n, c->stream));
+        HIPCHK(c, launch_pin_first(g.dtype, nxt, d_y0, g.B, g.T, g.n, c->stream));
+    }
+
+    double err = 1e10;
+    int it = 0;
+    bool nonfinite = false;
+    while (err > tol && it < max_iter) {
+        const int slot = it % kSlots;
+        if (it > 0 && slot == 0) {
+            st = zero_ctl(c);
+            if (st != DEER_OK) return st;
+        }
+        if (!ode) {
+            GruParams gp{d_theta, d_x, d_y0, cur, J, rhs, g.B, g.T, g.n, g.d};
+            prof_begin(c, KIND_FUNCEVAL);
+            HIPCHK(c, launch_gru_funceval(g.dtype, gp, c->stream));
+            prof_end(c);
+            HIPCHK(c, run_scan(c, J, rhs, d_y0, nxt, cur, (long long)(T * n * n), (long long)(T * n),
+                               (long long)(T * n), 0, slot, true));
+        } else {
+            char* Gbar = c->ws + c->plan.off_Gbar;
+            char* zbar = c->ws + c->plan.off_zbar;
+            MlpParams mp{d_theta, cur, J, rhs, g.B, g.T, g.n, g.mlp_width};
+            prof_begin(c, KIND_FUNCEVAL);
+            HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
+            prof_end(c);
+            OdeDiscParams dp{J, rhs, Gbar, zbar, g.B, g.T, g.n, (g.t1 - g.t0) / (double)(g.T - 1)};
+            prof_begin(c, KIND_DISC);
+            HIPCHK(c, launch_ode_discretise(g.dtype, dp, c->stream));
+            prof_end(c);
+            // positions 1..T-1 of the trajectory; position 0 stays y0
+            HIPCHK(c, run_scan(c, Gbar, zbar, d_y0, nxt + n * esz, cur + n * esz, (long long)((T - 1) * n * n),
+                               (long long)((T - 1) * n), (long long)(T * n), 0, slot, true));
+        }
+        HIPCHK(c, hipMemcpyAsync(c->h_err, ctl_err(c, slot), 8, hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        prof_collect(c);
+        if (g.dtype == DEER_F32) {
+            float f;
+            std::memcpy(&f, c->h_err, 4);
+            err = (double)f;
+        } else {
+            std::memcpy(&err, c->h_err, 8);
+        }
+        char* tmp = cur; cur = nxt; nxt = tmp;
+        ++it;
+        if (!std::isfinite(err)) { nonfinite = true; break; }
+    }
+    st = check_status(c);
+    if (cur != reinterpret_cast<char*>(d_y)) {
+        HIPCHK(c, hipMemcpyAsync(d_y, cur, ybytes, hipMemcpyDeviceToDevice, c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+    }
+    *iters = it;
+    *final_err = err;
+    *converged = (err <= tol) ? 1 : 0;
+    if (st != DEER_OK) return st;
+    if (nonfinite) return fail(c, DEER_ERR_NONFINITE, "the iteration produced a non-finite value");
+    return DEER_OK;
+}
+
+deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const void* d_y0, const void* d_y,
+                      const void* d_dLdy, void* d_dLdx, void* d_dLdtheta, void* d_dLdy0) {
+    if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
+    const deer_config& g = c->cfg;
+    if (g.cell != DEER_CELL_GRU) return fail(c, DEER_ERR_UNSUPPORTED, "deer_grad supports the GRU cell only");
+    if (!d_theta || !d_x || !d_y0 || !d_y || !d_dLdy || !d_dLdtheta)
+        return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
+    const size_t n = (size_t)g.n, T = (size_t)g.T;
+    char* J = c->ws + c->plan.off_J;
+    char* rhs = c->ws + c->plan.off_rhs;
+    char* lam = c->ws + c->plan.off_ybuf;
+
+    deer_status st = zero_ctl(c);
+    if (st != DEER_OK) return st;
+    // Jacobians at the given trajectory (the right-hand side output is not used)
+    GruParams gp{d_theta, d_x, d_y0, d_y, J, rhs, g.B, g.T, g.n, g.d};
+    prof_begin(c, KIND_FUNCEVAL);
+    HIPCHK(c, launch_gru_funceval(g.dtype, gp, c->stream));
+    prof_end(c);
+    // lam = (dL/dy) L_G^{-1}: reverse scan with transposed Jacobians
+    HIPCHK(c, run_scan(c, J, d_dLdy, nullptr, lam, nullptr, (long long)(T * n * n), (long long)(T * n),
+                       (long long)(T * n), 1, 0, false));
+    GruVjpParams vp{d_theta, d_x, d_y0, d_y, lam, d_dLdx, d_dLdy0, c->ws + c->plan.off_partial, d_dLdtheta,
+                    g.B, g.T, g.n, g.d, c->plan.vjp_blocks};
+    prof_begin(c, KIND_VJP);
+    HIPCHK(c, launch_gru_vjp(g.dtype, vp, c->stream));
+    prof_end(c);
+    st = check_status(c);
+    prof_collect(c);
+    return st;
+}
+
+deer_status deer_linrec_solve(deer_ctx* c, const void* d_A, const void* d_b, const void* d_y0, void* d_y,
+                              int32_t reverse) {
+    if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
+    const deer_config& g = c->cfg;
+    if (!d_A || !d_b || !d_y) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
+    if (g.cell != DEER_CELL_GRU) return fail(c, DEER_ERR_UNSUPPORTED, "deer_linrec_solve needs a GRU-shaped context");
+    const size_t n = (size_t)g.n, T = (size_t)g.T;
+    deer_status st = zero_ctl(c);
+    if (st != DEER_OK) return st;
+    HIPCHK(c, run_scan(c, d_A, d_b, reverse ? nullptr : d_y0, d_y, nullptr, (long long)(T * n * n),
+                       (long long)(T * n), (long long)(T * n), reverse ? 1 : 0, 0, false));
+    st = check_status(c);
+    prof_collect(c);
+    return st;
+}
+
+deer_status deer_set_profiling(deer_ctx* c, int32_t on) {
+    if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
+    c->profiling = on != 0;
+    if (on) c->prof = deer_profile{};
+    c->ev_used = 0;
+    return DEER_OK;
+}
+
+deer_status deer_get_profile(deer_ctx* c, deer_profile* out) {
+    if (!c || !out) return fail(c, DEER_ERR_INVALID_ARG, "NULL argument");
+    *out = c->prof;
+    return DEER_OK;
+}
+
+const char* deer_last_error(const deer_ctx* c) {
+    return c ? c->last_error.c_str() : g_last_error.c_str();
+}
+
+void deer_destroy(deer_ctx* c) {
+    if (!c) return;
+    for (auto& e : c->ev)
+        if (e) (void)hipEventDestroy(e);
+    if (c->h_err) (void)hipHostFree(c->h_err);
+    delete c;
+}
+
+}  // extern "C"

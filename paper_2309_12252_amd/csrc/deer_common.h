@@ -1,0 +1,173 @@
+// Shared declarations of the DEER HIP library (device helpers and the launch interface
+// between the host driver and the kernel translation units).  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace deer {
+
+// ---------------------------------------------------------------------------------------
+// Scan launch description.  One launch solves y_k = A_k y_{k-1} + b_k, k = 0..T-1 (scan
+// positions), for B sequences (Sec. 3.3 eq. 9-10, Sec. 3.4 eq. 11).  In reverse mode scan
+// position k stands for array index T-1-k and uses the TRANSPOSE of the matrix stored at
+// index T-k (none for k = 0), which is the dual operator of Sec. 3.1.1 eq. 7.
+// All strides are per sequence and counted in scalars.
+// ---------------------------------------------------------------------------------------
+struct ScanParams {
+    const void* A;       // [B][T][n][n]
+    const void* bv;      // [B][T][n]
+    const void* y0;      // [B][n] or nullptr (zeros)
+    void* out;           // [B][T][n]
+    const void* yold;    // previous iterate laid out like out, or nullptr (no error reduction)
+    long long strideA, strideb, strideOut, strideOld;
+    int B, T;
+    int L;               // scan positions per lane (VALU kernel)
+    int tiles;           // tiles per sequence
+    int reverse;
+    unsigned epoch;      // flags carry (epoch << 2) | state, so stale flags need no clearing
+    unsigned* flags;     // [B * tiles]
+    void* aggM;          // [B * tiles][n*n]  tile aggregates
+    void* aggv;          // [B * tiles][n]
+    void* incl;          // [B * tiles][n]    inclusive carry after the tile
+    unsigned* ticket;    // tile dispenser for this launch (zero on entry)
+    void* err;           // max |out - yold| as raw bits of a non-negative scalar, or nullptr
+    unsigned* status;    // set non-zero when a bounded wait ran out
+};
+
+enum : unsigned { TILE_INVALID = 0u, TILE_AGGREGATE = 1u, TILE_INCLUSIVE = 2u };
+constexpr unsigned kSpinLimit = 1u << 22;   // polls before a waiting tile gives up
+
+// ---------------------------------------------------------------------------------------
+// Device helpers
+// ---------------------------------------------------------------------------------------
+
+template <int BYTES> struct VecOf;
+template <> struct VecOf<16> { using type = uint4; };
+template <> struct VecOf<8> { using type = uint2; };
+template <> struct VecOf<4> { using type = unsigned; };
+
+// Copy COUNT scalars between a register array and memory with the widest access that divides
+// COUNT * sizeof(S); the address must be aligned to that width (guaranteed by the layouts used).
+template <typename S, int COUNT>
+__device__ __forceinline__ void vload(S* dst, const S* __restrict__ src) {
+    constexpr int bytes = COUNT * (int)sizeof(S);
+    constexpr int W = (bytes % 16 == 0) ? 16 : ((bytes % 8 == 0) ? 8 : 4);
+    using V = typename VecOf<W>::type;
+    constexpr int NV = bytes / W;
+    constexpr int PER = W / (int)sizeof(S);
+    static_assert(W >= (int)sizeof(S), "scalar wider than access");
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        V v = reinterpret_cast<const V*>(src)[i];
+        const S* p = reinterpret_cast<const S*>(&v);
+#pragma unroll
+        for (int j = 0; j < PER; ++j) dst[i * PER + j] = p[j];
+    }
+}
+
+template <typename S, int COUNT>
+__device__ __forceinline__ void vstore(S* __restrict__ dst, const S* src) {
+    constexpr int bytes = COUNT * (int)sizeof(S);
+    constexpr int W = (bytes % 16 == 0) ? 16 : ((bytes % 8 == 0) ? 8 : 4);
+    using V = typename VecOf<W>::type;
+    constexpr int NV = bytes / W;
+    constexpr int PER = W / (int)sizeof(S);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        V v;
+        S* p = reinterpret_cast<S*>(&v);
+#pragma unroll
+        for (int j = 0; j < PER; ++j) p[j] = src[i * PER + j];
+        reinterpret_cast<V*>(dst)[i] = v;
+    }
+}
+
+// Loads that must observe what another workgroup published (tile aggregates, carries).
+__device__ __forceinline__ float coherent_load(const float* p) {
+    unsigned u = __hip_atomic_load(reinterpret_cast<const unsigned*>(p), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+    return __uint_as_float(u);
+}
+__device__ __forceinline__ double coherent_load(const double* p) {
+    unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
+                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __longlong_as_double((long long)u);
+}
+
+__device__ __forceinline__ unsigned flag_load(const unsigned* p) {
+    return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void flag_store(unsigned* p, unsigned v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// max-reduce a non-negative value (NaN mapped to +inf by the caller) into *err as raw bits
+__device__ __forceinline__ void err_atomic_max(void* err, float v) {
+    atomicMax(reinterpret_cast<unsigned*>(err), __float_as_uint(v));
+}
+__device__ __forceinline__ void err_atomic_max(void* err, double v) {
+    atomicMax(reinterpret_cast<unsigned long long*>(err), (unsigned long long)__double_as_longlong(v));
+}
+
+template <typename S>
+__device__ __forceinline__ S abs_or_inf(S d) {
+    d = d < S(0) ? -d : d;
+    // a NaN difference must not be lost in the max: report +inf instead
+    return (d == d) ? d : S(INFINITY);
+}
+
+template <typename S>
+__device__ __forceinline__ S wave_max(S v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        S u = __shfl_xor(v, o);
+        v = u > v ? u : v;
+    }
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// Launchers implemented in the kernel translation units.  Each returns hipGetLastError().
+// ---------------------------------------------------------------------------------------
+struct GruParams {
+    const void* theta; const void* x; const void* y0; const void* y;  // y: current iterate [B,T,n]
+    void* J; void* rhs;                                               // outputs [B,T,n,n], [B,T,n]
+    int B, T, n, d;
+};
+
+struct GruVjpParams {
+    const void* theta; const void* x; const void* y0; const void* y; const void* lam;
+    void* dx;          // [B,T,d] or nullptr
+    void* dy0;         // [B,n] or nullptr
+    void* partial;     // [blocks][theta_count] per-block partial sums
+    void* dtheta;      // [theta_count]
+    int B, T, n, d;
+    int blocks;
+};
+
+struct MlpParams {
+    const void* theta; const void* y;     // y [B,T,n]
+    void* G; void* z;                     // outputs: G = -df/dy [B,T,n,n], z = f + G y [B,T,n]
+    int B, T, n, width;
+};
+
+struct OdeDiscParams {
+    const void* G; const void* z;         // [B,T,n,n], [B,T,n]
+    void* Gbar; void* zbar;               // [B,T-1,n,n], [B,T-1,n]
+    int B, T, n;
+    double dt;
+};
+
+hipError_t launch_scan_valu(int dtype, int n, const ScanParams& p, hipStream_t s);
+hipError_t launch_scan_mfma(int dtype, int n, const ScanParams& p, hipStream_t s);
+int scan_valu_tile(int n, int L);          // scan positions per tile
+int scan_mfma_tile(int dtype, int n);
+hipError_t launch_gru_funceval(int dtype, const GruParams& p, hipStream_t s);
+hipError_t launch_gru_vjp(int dtype, const GruVjpParams& p, hipStream_t s);
+int gru_vjp_blocks(int n, long long steps);
+hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s);
+hipError_t launch_ode_discretise(int dtype, const OdeDiscParams& p, hipStream_t s);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_pin_first(int dtype, void* y, const void* y0, int B, int T, int n, hipStream_t s);
+
+}  // namespace deer

@@ -1,0 +1,350 @@
+// GRU cell kernels.
+//   gru_funceval_kernel: for every sequence position, f(h, x), the Jacobian J = df/dh and the
+//     right-hand side of the linear recurrence, rhs = f - J h (the paper carries G = -J and
+//     z = f + G h, Sec. 3.1 eq. 3 and 5; the sign is folded so that y_i = J_i y_{i-1} + rhs_i).
+//     h is the previous iterate shifted by one position, y0 at the first position (Sec. 3.2).
+//   gru_vjp_kernel: vector-Jacobian product of f with the scanned cotangent lam at every position
+//     (Sec. 3.1.1 eq. 7, outer bracket): dL/dx per position, dL/dy0, and per-wavefront partial sums
+//     of dL/dtheta that gru_vjp_reduce_kernel adds up in a fixed order (run-to-run identical).
+//
+// Cell (gates r, z, candidate c; reset applied after the hidden projection):
+//   r = sig(W_r x + b_r + U_r h)   z = sig(W_z x + b_z + U_z h)
+//   q = U_c h + b_hc               c = tanh(W_c x + b_c + r q)        f = (1 - z) c + z h
+//   J = diag(z) + diag((h - c) z (1 - z)) U_z + diag((1 - z)(1 - c^2)) [diag(r) U_c + diag(q r (1 - r)) U_r]
+//
+// Work split: one thread per (position, state row i).  Row i of J needs only row i of the gates
+// and of U, so threads never talk to each other in the forward kernel; the n threads of a position
+// sit in consecutive lanes and write n*n consecutive scalars of J (fully coalesced).  U rows live in
+// registers, W (runtime input size) in LDS with an odd row stride.
+#include "deer_common.h"
+
+namespace deer {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxD = 16;
+
+__device__ __forceinline__ float sigmoid_(float a) { return 1.0f / (1.0f + expf(-a)); }
+__device__ __forceinline__ double sigmoid_(double a) { return 1.0 / (1.0 + exp(-a)); }
+__device__ __forceinline__ float tanh_(float a) { return tanhf(a); }
+__device__ __forceinline__ double tanh_(double a) { return tanh(a); }
+
+template <typename S, int N>
+struct RowWeights {
+    S Ur[N], Uz[N], Uc[N];
+    S br, bz, bc, bh;
+};
+
+template <typename S, int N>
+__device__ __forceinline__ void load_row_weights(const S* __restrict__ theta, int d, int i, RowWeights<S, N>& w,
+                                                 S* sW, int ds, int tid) {
+    for (int q = tid; q < 3 * N * d; q += kThreads) sW[(q / d) * ds + (q % d)] = theta[q];
+    const S* U = theta + 3 * N * d;
+    const S* bias = U + 3 * N * N;
+    vload<S, N>(w.Ur, U + (long long)(i)*N);
+    vload<S, N>(w.Uz, U + (long long)(N + i) * N);
+    vload<S, N>(w.Uc, U + (long long)(2 * N + i) * N);
+    w.br = bias[i];
+    w.bz = bias[N + i];
+    w.bc = bias[2 * N + i];
+    w.bh = bias[3 * N + i];
+}
+
+template <typename S, int N>
+struct Gates {
+    S r, z, q, c, hi;
+};
+
+// gates of row i at (h, x)
+template <typename S, int N>
+__device__ __forceinline__ void row_gates(const RowWeights<S, N>& w, const S* sW, int ds, int d, int i,
+                                          const S* h, const S* __restrict__ xp, Gates<S, N>& g) {
+    S ar = w.br, az = w.bz, ac = w.bc, q = w.bh;
+    for (int k = 0; k < d; ++k) {
+        const S xv = xp[k];
+        ar += sW[(i)*ds + k] * xv;
+        az += sW[(N + i) * ds + k] * xv;
+        ac += sW[(2 * N + i) * ds + k] * xv;
+    }
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        ar += w.Ur[j] * h[j];
+        az += w.Uz[j] * h[j];
+        q += w.Uc[j] * h[j];
+    }
+    g.r = sigmoid_(ar);
+    g.z = sigmoid_(az);
+    g.q = q;
+    g.c = tanh_(ac + g.r * q);
+}
+
+template <typename S, int N>
+__global__ __launch_bounds__(kThreads) void gru_funceval_kernel(GruParams p) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    S* sW = reinterpret_cast<S*>(smem_raw);
+    const int tid = threadIdx.x;
+    const int d = p.d, ds = d | 1;
+    constexpr int SPB = kThreads / N;   // positions per block pass
+    const int i = tid % N;
+    const int sg = tid / N;
+    const S* __restrict__ theta = reinterpret_cast<const S*>(p.theta);
+    const S* __restrict__ x = reinterpret_cast<const S*>(p.x);
+    const S* __restrict__ y0 = reinterpret_cast<const S*>(p.y0);
+    const S* __restrict__ y = reinterpret_cast<const S*>(p.y);
+    S* __restrict__ J = reinterpret_cast<S*>(p.J);
+    S* __restrict__ rhs = reinterpret_cast<S*>(p.rhs);
+
+    RowWeights<S, N> w;
+    load_row_weights<S, N>(theta, d, i, w, sW, ds, tid);
+    __syncthreads();
+
+    const long long total = (long long)p.B * p.T;
+    for (long long s = (long long)blockIdx.x * SPB + sg; s < total; s += (long long)gridDim.x * SPB) {
+        const long long bi = s / p.T;
+        const int ti = (int)(s - bi * p.T);
+        const S* hp = (ti == 0) ? (y0 + bi * N) : (y + (s - 1) * N);
+        S h[N];
+        vload<S, N>(h, hp);
+        const S hi = hp[i];
+        Gates<S, N> g;
+        row_gates<S, N>(w, sW, ds, d, i, h, x + s * d, g);
+        const S f = (S(1) - g.z) * g.c + g.z * hi;
+        const S pz = (hi - g.c) * g.z * (S(1) - g.z);
+        const S sc = (S(1) - g.z) * (S(1) - g.c * g.c);
+        const S sr = sc * g.r;
+        const S st = sc * g.q * g.r * (S(1) - g.r);
+        S Jrow[N];
+        S acc = f;
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            S jv = pz * w.Uz[j] + sr * w.Uc[j] + st * w.Ur[j];
+            jv += (j == i) ? g.z : S(0);
+            Jrow[j] = jv;
+            acc -= jv * h[j];
+        }
+        vstore<S, N>(J + (s * N + i) * N, Jrow);
+        rhs[s * N + i] = acc;
+    }
+}
+
+// sum over the lanes that hold the same state row (lane stride N inside a wavefront)
+template <typename S, int N>
+__device__ __forceinline__ S sum_same_row(S v) {
+#pragma unroll
+    for (int o = N; o < 64; o <<= 1) v += __shfl_xor(v, o);
+    return v;
+}
+// sum over the N lanes of one position
+template <typename S, int N>
+__device__ __forceinline__ S sum_position(S v) {
+#pragma unroll
+    for (int o = 1; o < N; o <<= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+template <typename S, int N>
+__global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    S* sW = reinterpret_cast<S*>(smem_raw);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int d = p.d, ds = d | 1;
+    constexpr int SPB = kThreads / N;
+    const int i = tid % N;
+    const int sg = tid / N;
+    const S* __restrict__ theta = reinterpret_cast<const S*>(p.theta);
+    const S* __restrict__ x = reinterpret_cast<const S*>(p.x);
+    const S* __restrict__ y0 = reinterpret_cast<const S*>(p.y0);
+    const S* __restrict__ y = reinterpret_cast<const S*>(p.y);
+    const S* __restrict__ lam = reinterpret_cast<const S*>(p.lam);
+    S* __restrict__ dx = reinterpret_cast<S*>(p.dx);
+    S* __restrict__ dy0 = reinterpret_cast<S*>(p.dy0);
+
+    RowWeights<S, N> w;
+    load_row_weights<S, N>(theta, d, i, w, sW, ds, tid);
+    __syncthreads();
+
+    S aUr[N], aUz[N], aUc[N], aWr[kMaxD], aWz[kMaxD], aWc[kMaxD];
+    S abr = S(0), abz = S(0), abc = S(0), abh = S(0);
+#pragma unroll
+    for (int j = 0; j < N; ++j) aUr[j] = aUz[j] = aUc[j] = S(0);
+#pragma unroll
+    for (int k = 0; k < kMaxD; ++k) aWr[k] = aWz[k] = aWc[k] = S(0);
+
+    const long long total = (long long)p.B * p.T;
+    // every thread of a block runs the same number of passes so that the shuffles below always
+    // see whole positions; a pass past the end contributes zeros
+    const long long passes = (total + (long long)gridDim.x * SPB - 1) / ((long long)gridDim.x * SPB);
+    for (long long it = 0; it < passes; ++it) {
+        const long long s = (it * gridDim.x + blockIdx.x) * SPB + sg;
+        const bool live = s < total;
+        const long long sc_ = live ? s : 0;
+        const long long bi = sc_ / p.T;
+        const int ti = (int)(sc_ - bi * p.T);
+        const S* hp = (ti == 0) ? (y0 + bi * N) : (y + (sc_ - 1) * N);
+        S h[N];
+        vload<S, N>(h, hp);
+        const S hi = hp[i];
+        const S* xp = x + sc_ * d;
+        Gates<S, N> g;
+        row_gates<S, N>(w, sW, ds, d, i, h, xp, g);
+        const S lm = live ? lam[sc_ * N + i] : S(0);
+        const S dcand = lm * (S(1) - g.z);
+        const S dac = dcand * (S(1) - g.c * g.c);
+        const S daz = lm * (hi - g.c) * g.z * (S(1) - g.z);
+        const S dq = dac * g.r;
+        const S dar = dac * g.q * g.r * (S(1) - g.r);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            aUr[j] += dar * h[j];
+            aUz[j] += daz * h[j];
+            aUc[j] += dq * h[j];
+        }
+        abr += dar; abz += daz; abc += dac; abh += dq;
+#pragma unroll
+        for (int k = 0; k < kMaxD; ++k) {
+            if (k < d) {
+                const S xv = xp[k];
+                aWr[k] += dar * xv;
+                aWz[k] += daz * xv;
+                aWc[k] += dac * xv;
+                if (dx) {
+                    S part = sW[(i)*ds + k] * dar + sW[(N + i) * ds + k] * daz + sW[(2 * N + i) * ds + k] * dac;
+                    part = sum_position<S, N>(part);
+                    if (live && i == (k % N)) dx[sc_ * d + k] = part;
+                }
+            }
+        }
+        if (dy0 && ti == 0) {
+            // dL/dy0 = J_1^T lam_1, row j: z_j lam_j + sum_i (U_r[i][j] dar_i + U_z[i][j] daz_i + U_c[i][j] dq_i)
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                S part = w.Ur[j] * dar + w.Uz[j] * daz + w.Uc[j] * dq;
+                part += (j == i) ? g.z * lm : S(0);
+                part = sum_position<S, N>(part);
+                if (live && i == j) dy0[bi * N + j] = part;
+            }
+        }
+    }
+
+    // per-wavefront partial sums, written without atomics: row (block * 4 + wave) of p.partial
+    const long long P = 3LL * N * d + 3LL * N * N + 4LL * N;
+    S* __restrict__ prow = reinterpret_cast<S*>(p.partial) + ((long long)blockIdx.x * (kThreads / 64) + (tid >> 6)) * P;
+    const bool writer = lane < N;   // the first position group of the wavefront holds the totals
+#pragma unroll
+    for (int k = 0; k < kMaxD; ++k) {
+        if (k < d) {
+            const S a = sum_same_row<S, N>(aWr[k]), b = sum_same_row<S, N>(aWz[k]), c = sum_same_row<S, N>(aWc[k]);
+            if (writer) {
+                prow[(long long)(i)*d + k] = a;
+                prow[(long long)(N + i) * d + k] = b;
+                prow[(long long)(2 * N + i) * d + k] = c;
+            }
+        }
+    }
+    S* pU = prow + 3LL * N * d;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const S a = sum_same_row<S, N>(aUr[j]), b = sum_same_row<S, N>(aUz[j]), c = sum_same_row<S, N>(aUc[j]);
+        if (writer) {
+            pU[(long long)(i)*N + j] = a;
+            pU[(long long)(N + i) * N + j] = b;
+            pU[(long long)(2 * N + i) * N + j] = c;
+        }
+    }
+    S* pb = pU + 3LL * N * N;
+    {
+        const S a = sum_same_row<S, N>(abr), b = sum_same_row<S, N>(abz), c = sum_same_row<S, N>(abc),
+                e = sum_same_row<S, N>(abh);
+        if (writer) {
+            pb[i] = a;
+            pb[N + i] = b;
+            pb[2 * N + i] = c;
+            pb[3 * N + i] = e;
+        }
+    }
+}
+
+template <typename S>
+__global__ __launch_bounds__(256) void gru_vjp_reduce_kernel(const S* __restrict__ partial, S* __restrict__ dtheta,
+                                                             long long P, int rows) {
+    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (q >= P) return;
+    S s = S(0);
+    for (int r = 0; r < rows; ++r) s += partial[(long long)r * P + q];
+    dtheta[q] = s;
+}
+
+template <typename S, int N>
+hipError_t launch_fe(const GruParams& p, hipStream_t s) {
+    constexpr int SPB = kThreads / N;
+    const long long total = (long long)p.B * p.T;
+    long long blocks = (total + SPB - 1) / SPB;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    const size_t shmem = (size_t)3 * N * (p.d | 1) * sizeof(S);
+    hipLaunchKernelGGL((gru_funceval_kernel<S, N>), dim3((unsigned)blocks), dim3(kThreads), shmem, s, p);
+    return hipGetLastError();
+}
+
+template <typename S>
+hipError_t launch_fe_s(const GruParams& p, hipStream_t s) {
+    switch (p.n) {
+        case 1: return launch_fe<S, 1>(p, s);
+        case 2: return launch_fe<S, 2>(p, s);
+        case 4: return launch_fe<S, 4>(p, s);
+        case 8: return launch_fe<S, 8>(p, s);
+        case 16: return launch_fe<S, 16>(p, s);
+        case 32: return launch_fe<S, 32>(p, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <typename S, int N>
+hipError_t launch_vjp(const GruVjpParams& p, hipStream_t s) {
+    const size_t shmem = (size_t)3 * N * (p.d | 1) * sizeof(S);
+    hipLaunchKernelGGL((gru_vjp_kernel<S, N>), dim3((unsigned)p.blocks), dim3(kThreads), shmem, s, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const long long P = 3LL * N * p.d + 3LL * N * N + 4LL * N;
+    hipLaunchKernelGGL((gru_vjp_reduce_kernel<S>), dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<const S*>(p.partial), reinterpret_cast<S*>(p.dtheta), P,
+                       p.blocks * (kThreads / 64));
+    return hipGetLastError();
+}
+
+template <typename S>
+hipError_t launch_vjp_s(const GruVjpParams& p, hipStream_t s) {
+    switch (p.n) {
+        case 1: return launch_vjp<S, 1>(p, s);
+        case 2: return launch_vjp<S, 2>(p, s);
+        case 4: return launch_vjp<S, 4>(p, s);
+        case 8: return launch_vjp<S, 8>(p, s);
+        case 16: return launch_vjp<S, 16>(p, s);
+        case 32: return launch_vjp<S, 32>(p, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+int gru_vjp_blocks(int n, long long steps) {
+    const int spb = kThreads / n;
+    long long blocks = (steps + spb - 1) / spb;
+    if (blocks > 512) blocks = 512;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
+hipError_t launch_gru_funceval(int dtype, const GruParams& p, hipStream_t s) {
+    if (p.d < 1 || p.d > kMaxD) return hipErrorInvalidValue;
+    return dtype == 0 ? launch_fe_s<float>(p, s) : launch_fe_s<double>(p, s);
+}
+
+hipError_t launch_gru_vjp(int dtype, const GruVjpParams& p, hipStream_t s) {
+    if (p.d < 1 || p.d > kMaxD) return hipErrorInvalidValue;
+    return dtype == 0 ? launch_vjp_s<float>(p, s) : launch_vjp_s<double>(p, s);
+}
+
+}  // namespace deer

@@ -1,0 +1,324 @@
+// NeuralODE kernels: dy/dt = f(y), f an MLP with two tanh hidden layers (Sec. 3.3).
+//   mlp_funceval_kernel: at every grid point of the current iterate, f(y), J = df/dy =
+//     W3 D2 W2 D1 W1 (D = diag(1 - tanh^2)), and the pair the paper's linear ODE uses:
+//     G = -J and z = f + G y (Sec. 3.1 eq. 5, Sec. 3.3 eq. 8).
+//   ode_discretise_kernel: per interval, midpoint values Gc = (G_i + G_{i+1})/2, zc likewise,
+//     Gbar = exp(-Gc dt) and zbar = Gc^{-1}(I - Gbar) zc (Sec. 3.3 eq. 9), the latter evaluated as
+//     dt * phi1(-Gc dt) zc with phi1(X) = sum_k X^k/(k+1)!, which equals the printed formula when
+//     Gc is invertible and stays finite when it is not.
+//   pin_first_kernel: y[b,0,:] = y0[b,:] (the first grid point is the initial condition).
+//
+// mlp_funceval work split: the n threads of a grid point sit in consecutive lanes; thread j owns
+// column j of J and the hidden units j, j+n, j+2n, ... of both layers; activations are shared
+// with cross-lane shuffles.  Weights are read with wave-uniform addresses (scalar loads).
+#include "deer_common.h"
+
+namespace deer {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ float tanh_(float a) { return tanhf(a); }
+__device__ __forceinline__ double tanh_(double a) { return tanh(a); }
+
+template <typename S, int N, int W>
+__global__ __launch_bounds__(kThreads) void mlp_funceval_kernel(MlpParams p) {
+    static_assert(W % N == 0, "hidden width must be a multiple of the state size");
+    constexpr int UPT = W / N;   // hidden units per thread
+    constexpr int SPB = kThreads / N;
+    const int tid = threadIdx.x;
+    const int j = tid % N;
+    const int sg = tid / N;
+    const int lane = tid & 63;
+    const int base = lane - j;   // first lane of this grid point's group
+    const S* __restrict__ th = reinterpret_cast<const S*>(p.theta);
+    const S* __restrict__ W1 = th;                 // [W][N]
+    const S* __restrict__ b1 = W1 + W * N;         // [W]
+    const S* __restrict__ W2 = b1 + W;             // [W][W]
+    const S* __restrict__ b2 = W2 + W * W;         // [W]
+    const S* __restrict__ W3 = b2 + W;             // [N][W]
+    const S* __restrict__ b3 = W3 + N * W;         // [N]
+    const S* __restrict__ y = reinterpret_cast<const S*>(p.y);
+    S* __restrict__ G = reinterpret_cast<S*>(p.G);
+    S* __restrict__ z = reinterpret_cast<S*>(p.z);
+
+    const long long total = (long long)p.B * p.T;
+    const long long passes = (total + (long long)gridDim.x * SPB - 1) / ((long long)gridDim.x * SPB);
+    for (long long it = 0; it < passes; ++it) {
+        const long long s = (it * gridDim.x + blockIdx.x) * SPB + sg;
+        const bool live = s < total;
+        const long long sc = live ? s : 0;
+        S yv[N];
+        vload<S, N>(yv, y + sc * N);
+
+        // layer 1: this thread's units, then all-gather
+        S a1[W];
+        {
+            S mine[UPT];
+#pragma unroll
+            for (int u = 0; u < UPT; ++u) {
+                const int m = u * N + j;
+                S a = b1[m];
+#pragma unroll
+                for (int k = 0; k < N; ++k) a += W1[m * N + k] * yv[k];
+                mine[u] = tanh_(a);
+            }
+#pragma unroll
+            for (int u = 0; u < UPT; ++u)
+#pragma unroll
+                for (int q = 0; q < N; ++q) a1[u * N + q] = __shfl(mine[u], base + q);
+        }
+        // layer 2
+        S a2[W];
+        {
+            S mine[UPT];
+#pragma unroll
+            for (int u = 0; u < UPT; ++u) {
+                const int m = u * N + j;
+                S a = b2[m];
+#pragma unroll
+                for (int k = 0; k < W; ++k) a += W2[m * W + k] * a1[k];
+                mine[u] = tanh_(a);
+            }
+#pragma unroll
+            for (int u = 0; u < UPT; ++u)
+#pragma unroll
+                for (int q = 0; q < N; ++q) a2[u * N + q] = __shfl(mine[u], base + q);
+        }
+        // f_j
+        S fj = b3[j];
+#pragma unroll
+        for (int k = 0; k < W; ++k) fj += W3[j * W + k] * a2[k];
+
+        // column j of J: W3 D2 W2 D1 W1[:, j]
+        S u1[W];
+#pragma unroll
+        for (int m = 0; m < W; ++m) u1[m] = (S(1) - a1[m] * a1[m]) * W1[m * N + j];
+        S u2[W];
+#pragma unroll
+        for (int m = 0; m < W; ++m) {
+            S a = S(0);
+#pragma unroll
+            for (int k = 0; k < W; ++k) a += W2[m * W + k] * u1[k];
+            u2[m] = (S(1) - a2[m] * a2[m]) * a;
+        }
+        const S yj = y[sc * N + j];
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            S a = S(0);
+#pragma unroll
+            for (int k = 0; k < W; ++k) a += W3[i * W + k] * u2[k];
+            // a = J[i][j];  G = -J;  z_i = f_i + sum_j G[i][j] y_j
+            if (live) G[(sc * N + i) * N + j] = -a;
+            S part = -a * yj;
+#pragma unroll
+            for (int o = 1; o < N; o <<= 1) part += __shfl_xor(part, o);
+            const S fi = __shfl(fj, base + i);
+            if (live && j == i) z[sc * N + i] = fi + part;
+        }
+    }
+}
+
+// ---- ODE discretisation: one thread per interval, n x n matrices in registers ----
+
+template <typename S, int N>
+__device__ __forceinline__ void matmul_reg(const S* A, const S* Bm, S* C) {
+#pragma unroll
+    for (int r = 0; r < N; ++r)
+#pragma unroll
+        for (int c = 0; c < N; ++c) {
+            S s = S(0);
+#pragma unroll
+            for (int k = 0; k < N; ++k) s += A[r * N + k] * Bm[k * N + c];
+            C[r * N + c] = s;
+        }
+}
+
+template <typename S> struct SeriesTol;
+template <> struct SeriesTol<float> { static constexpr float v = 1e-10f; };
+template <> struct SeriesTol<double> { static constexpr double v = 1e-19; };
+
+template <typename S, int N>
+__global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams p) {
+    const long long nint = (long long)p.B * (p.T - 1);
+    const long long q = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (q >= nint) return;
+    const long long bi = q / (p.T - 1);
+    const long long i = q - bi * (p.T - 1);
+    const S* __restrict__ G = reinterpret_cast<const S*>(p.G) + (bi * p.T + i) * (N * N);
+    const S* __restrict__ z = reinterpret_cast<const S*>(p.z) + (bi * p.T + i) * N;
+    S* __restrict__ Gbar = reinterpret_cast<S*>(p.Gbar) + q * (N * N);
+    S* __restrict__ zbar = reinterpret_cast<S*>(p.zbar) + q * N;
+    const S dt = (S)p.dt;
+
+    // X = -Gc dt / 2^sq with max-row-sum norm at most 1/2
+    S X[N * N], zc[N];
+    {
+        S G0[N * N], G1[N * N], z0[N], z1[N];
+        vload<S, N * N>(G0, G);
+        vload<S, N * N>(G1, G + N * N);
+        vload<S, N>(z0, z);
+        vload<S, N>(z1, z + N);
+#pragma unroll
+        for (int k = 0; k < N * N; ++k) X[k] = S(-0.5) * (G0[k] + G1[k]) * dt;
+#pragma unroll
+        for (int k = 0; k < N; ++k) zc[k] = S(0.5) * (z0[k] + z1[k]);
+    }
+    S norm = S(0);
+#pragma unroll
+    for (int r = 0; r < N; ++r) {
+        S s = S(0);
+#pragma unroll
+        for (int c = 0; c < N; ++c) s += (X[r * N + c] < S(0) ? -X[r * N + c] : X[r * N + c]);
+        norm = s > norm ? s : norm;
+    }
+    int sq = 0;
+    S scale = S(1);
+    while (norm > S(0.5) && sq < 40) { norm *= S(0.5); scale *= S(0.5); ++sq; }
+    if (!(norm == norm)) sq = 0;
+#pragma unroll
+    for (int k = 0; k < N * N; ++k) X[k] *= scale;
+
+    // Taylor series of exp(X) (matrix) and phi1(X) zc (vector), until the bound norm^k/k! on the
+    // next term is below the working precision
+    S E[N * N], term[N * N], pv[N], wv[N];
+#pragma unroll
+    for (int k = 0; k < N * N; ++k) { const S id = ((k / N) == (k % N)) ? S(1) : S(0); E[k] = id; term[k] = id; }
+#pragma unroll
+    for (int k = 0; k < N; ++k) { pv[k] = zc[k]; wv[k] = zc[k]; }
+    S bound = S(1);
+    for (int k = 1; k <= 24; ++k) {
+        bound *= norm / (S)k;
+        S nt[N * N];
+        matmul_reg<S, N>(term, X, nt);
+        const S inv = S(1) / (S)k;
+#pragma unroll
+        for (int e = 0; e < N * N; ++e) { term[e] = nt[e] * inv; E[e] += term[e]; }
+        // w_k = X w_{k-1} / (k+1)
+        S nw[N];
+        const S inv1 = S(1) / (S)(k + 1);
+#pragma unroll
+        for (int r = 0; r < N; ++r) {
+            S s = S(0);
+#pragma unroll
+            for (int c = 0; c < N; ++c) s += X[r * N + c] * wv[c];
+            nw[r] = s * inv1;
+        }
+#pragma unroll
+        for (int r = 0; r < N; ++r) { wv[r] = nw[r]; pv[r] += nw[r]; }
+        if (bound < SeriesTol<S>::v) break;
+    }
+    // undo the scaling: phi1(2X) v = (exp(X) + I) phi1(X) v / 2, exp(2X) = exp(X)^2
+    for (int sstep = 0; sstep < sq; ++sstep) {
+        S nv[N];
+#pragma unroll
+        for (int r = 0; r < N; ++r) {
+            S s = pv[r];
+#pragma unroll
+            for (int c = 0; c < N; ++c) s += E[r * N + c] * pv[c];
+            nv[r] = S(0.5) * s;
+        }
+#pragma unroll
+        for (int r = 0; r < N; ++r) pv[r] = nv[r];
+        S E2[N * N];
+        matmul_reg<S, N>(E, E, E2);
+#pragma unroll
+        for (int e = 0; e < N * N; ++e) E[e] = E2[e];
+    }
+#pragma unroll
+    for (int r = 0; r < N; ++r) pv[r] *= dt;
+    vstore<S, N * N>(Gbar, E);
+    vstore<S, N>(zbar, pv);
+}
+
+template <typename S>
+__global__ __launch_bounds__(256) void pin_first_kernel(S* __restrict__ y, const S* __restrict__ y0, int B, int T,
+                                                        int n) {
+    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (q >= (long long)B * n) return;
+    const long long b = q / n;
+    const int c = (int)(q - b * n);
+    y[b * T * n + c] = y0[q];
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, size_t n16) {
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < n16; q += (size_t)gridDim.x * 256) p[q] = zero;
+}
+
+template <typename S, int N, int W>
+hipError_t launch_mlp_nw(const MlpParams& p, hipStream_t s) {
+    constexpr int SPB = kThreads / N;
+    const long long total = (long long)p.B * p.T;
+    long long blocks = (total + SPB - 1) / SPB;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((mlp_funceval_kernel<S, N, W>), dim3((unsigned)blocks), dim3(kThreads), 0, s, p);
+    return hipGetLastError();
+}
+
+template <typename S, int N>
+hipError_t launch_mlp_n(const MlpParams& p, hipStream_t s) {
+    switch (p.width) {
+        case 16: if constexpr (16 % N == 0) return launch_mlp_nw<S, N, 16>(p, s); else return hipErrorInvalidValue;
+        case 32: if constexpr (32 % N == 0) return launch_mlp_nw<S, N, 32>(p, s); else return hipErrorInvalidValue;
+        case 64: if constexpr (64 % N == 0) return launch_mlp_nw<S, N, 64>(p, s); else return hipErrorInvalidValue;
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <typename S>
+hipError_t launch_mlp_s(const MlpParams& p, hipStream_t s) {
+    switch (p.n) {
+        case 2: return launch_mlp_n<S, 2>(p, s);
+        case 4: return launch_mlp_n<S, 4>(p, s);
+        case 8: return launch_mlp_n<S, 8>(p, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <typename S>
+hipError_t launch_disc_s(const OdeDiscParams& p, hipStream_t s) {
+    const long long nint = (long long)p.B * (p.T - 1);
+    dim3 grid((unsigned)((nint + kThreads - 1) / kThreads));
+    switch (p.n) {
+        case 2: hipLaunchKernelGGL((ode_discretise_kernel<S, 2>), grid, dim3(kThreads), 0, s, p); break;
+        case 4: hipLaunchKernelGGL((ode_discretise_kernel<S, 4>), grid, dim3(kThreads), 0, s, p); break;
+        case 8: hipLaunchKernelGGL((ode_discretise_kernel<S, 8>), grid, dim3(kThreads), 0, s, p); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s) {
+    return dtype == 0 ? launch_mlp_s<float>(p, s) : launch_mlp_s<double>(p, s);
+}
+
+hipError_t launch_ode_discretise(int dtype, const OdeDiscParams& p, hipStream_t s) {
+    return dtype == 0 ? launch_disc_s<float>(p, s) : launch_disc_s<double>(p, s);
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+    // bytes must be a multiple of 16 and p 16-byte aligned (workspace sections are)
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<uint4*>(p), n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_pin_first(int dtype, void* y, const void* y0, int B, int T, int n, hipStream_t s) {
+    const long long q = (long long)B * n;
+    dim3 grid((unsigned)((q + 255) / 256));
+    if (dtype == 0)
+        hipLaunchKernelGGL((pin_first_kernel<float>), grid, dim3(256), 0, s, (float*)y, (const float*)y0, B, T, n);
+    else
+        hipLaunchKernelGGL((pin_first_kernel<double>), grid, dim3(256), 0, s, (double*)y, (const double*)y0, B, T, n);
+    return hipGetLastError();
+}
+
+}  // namespace deer

@@ -1,0 +1,427 @@
+// Inverse linear operator for n = 16 and n = 32: single-pass blocked associative scan over affine
+// pairs (A | b) with the operator of Sec. 3.3 eq. 10, the matrix-matrix part on the matrix cores.
+//
+// Every n x n matrix is handled as (n/16)^2 blocks of 16 x 16 and multiplied with the 16x16x4 MFMA
+// instruction (fp32 and fp64 forms share one register layout):
+//   A operand  : lane (g = lane/16, r = lane%16) supplies A[r][g]           (16 x 4 slice)
+//   B operand  : lane (g, c = lane%16)           supplies B[g][c]           (4 x 16 slice)
+//   accumulator: lane (g, c), register v         holds    D[4g + v][c]
+// A running product P is kept in accumulator layout.  Register v of a block of P, used directly as
+// the B operand, is the 4 x 16 slice made of rows {4g + v}; the matching A operand is the 16 x 4
+// slice made of columns {4g + v}, v = 0..3, which is one contiguous 4-scalar load per lane from a
+// row-major matrix.  So P <- A_t P needs no data movement between accumulators and operands.
+//
+// Structure of one tile (WAVES wavefronts, LW scan positions per wavefront):
+//   1. each wavefront loads its LW pairs into registers (A-operand layout) and composes them
+//      serially: P <- A_t P on the matrix cores, v <- A_t v + b_t on the vector ALUs;
+//   2. wavefront totals meet in LDS; wavefront 0 composes them into the tile total;
+//   3. decoupled look-back across tiles through HBM exactly as in the small-n kernel (tile index
+//      from an atomic ticket, flags AGGREGATE / INCLUSIVE tagged with a launch epoch, window of 64
+//      predecessors, forward fold of totals from the nearest known inclusive carry, bounded waits);
+//   4. each wavefront derives its starting state from the carry and walks its register-resident
+//      pairs again (y <- A_t y + b_t), writing y and reducing max|y - y_previous_iterate|.
+#include "deer_common.h"
+
+namespace deer {
+
+namespace {
+
+template <typename S> struct Mfma;
+template <> struct Mfma<float> {
+    using Acc = float __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ Acc run(float a, float b, Acc c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Mfma<double> {
+    using Acc = double __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ Acc run(double a, double b, Acc c) {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+    }
+};
+
+// sum over the four lane groups g (lanes r, r+16, r+32, r+48)
+template <typename S>
+__device__ __forceinline__ S sum_groups(S v) {
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+template <typename S, int N, int LW, int WAVES, bool REV>
+__global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
+    constexpr int NB = N / 16;
+    constexpr int LD = N + 1;   // LDS row stride of a wavefront total
+    constexpr int TILE = LW * WAVES;
+    using Acc = typename Mfma<S>::Acc;
+
+    __shared__ unsigned s_ticket;
+    __shared__ S sM[WAVES][N * LD];   // wavefront totals, row-major, padded rows
+    __shared__ S sv[WAVES][N];
+    __shared__ S sT[N * LD];          // tile total
+    __shared__ S sTv[N];
+    __shared__ S sC[WAVES][N];        // carry entering each wavefront
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int g = lane >> 4;
+    const int r = lane & 15;
+
+    if (tid == 0) s_ticket = atomicAdd(p.ticket, 1u);
+    __syncthreads();
+    const unsigned tk = s_ticket;
+    const int b = (int)(tk % (unsigned)p.B);
+    const int t = (int)(tk / (unsigned)p.B);
+    if (t >= p.tiles) return;
+
+    const S* __restrict__ Ab = reinterpret_cast<const S*>(p.A) + (long long)b * p.strideA;
+    const S* __restrict__ bb = reinterpret_cast<const S*>(p.bv) + (long long)b * p.strideb;
+    S* __restrict__ ob = reinterpret_cast<S*>(p.out) + (long long)b * p.strideOut;
+    const S* __restrict__ oldb =
+        p.yold ? reinterpret_cast<const S*>(p.yold) + (long long)b * p.strideOld : nullptr;
+    const long long e0 = (long long)t * TILE + (long long)wave * LW;
+
+    // ---- 1a. load this wavefront's pairs ----
+    S a[LW][NB][NB][4];   // a[i][I][K][v] = A_e[16I + r][16K + 4g + v]
+    S bel[LW][NB];        // bel[i][I]     = b_e[16I + r]
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+        const long long e = e0 + i;
+        if (e < p.T) {
+            if constexpr (!REV) {
+                const S* Ae = Ab + e * (N * N);
+#pragma unroll
+                for (int I = 0; I < NB; ++I)
+#pragma unroll
+                    for (int K = 0; K < NB; ++K) vload<S, 4>(a[i][I][K], Ae + (16 * I + r) * N + 16 * K + 4 * g);
+#pragma unroll
+                for (int I = 0; I < NB; ++I) bel[i][I] = bb[e * N + 16 * I + r];
+            } else {
+                // dual operator: vector index T-1-e, transpose of the matrix stored at index T-e
+#pragma unroll
+                for (int I = 0; I < NB; ++I) bel[i][I] = bb[((long long)p.T - 1 - e) * N + 16 * I + r];
+                if (e == 0) {
+#pragma unroll
+                    for (int I = 0; I < NB; ++I)
+#pragma unroll
+                        for (int K = 0; K < NB; ++K)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) a[i][I][K][v] = S(0);
+                } else {
+                    const S* Ae = Ab + ((long long)p.T - e) * (N * N);
+#pragma unroll
+                    for (int I = 0; I < NB; ++I)
+#pragma unroll
+                        for (int K = 0; K < NB; ++K)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) a[i][I][K][v] = Ae[(16 * K + 4 * g + v) * N + 16 * I + r];
+                }
+            }
+        } else {
+            // past the end of the sequence: the identity pair
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+                bel[i][I] = S(0);
+#pragma unroll
+                for (int K = 0; K < NB; ++K)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) a[i][I][K][v] = (I == K && r == 4 * g + v) ? S(1) : S(0);
+            }
+        }
+    }
+
+    // ---- 1b. serial composition: P <- A_e P (MFMA), vec <- A_e vec + b_e (VALU) ----
+    Acc P[NB][NB];
+#pragma unroll
+    for (int I = 0; I < NB; ++I)
+#pragma unroll
+        for (int J = 0; J < NB; ++J)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) P[I][J][v] = (I == J && 4 * g + v == r) ? S(1) : S(0);
+    S vr[NB];        // vec in row layout:    vr[I]    = vec[16I + r]
+    S vc[NB][4];     // vec in column layout: vc[K][v] = vec[16K + 4g + v]
+#pragma unroll
+    for (int I = 0; I < NB; ++I) {
+        vr[I] = S(0);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) vc[I][v] = S(0);
+    }
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+        Acc Pn[NB][NB];
+#pragma unroll
+        for (int I = 0; I < NB; ++I)
+#pragma unroll
+            for (int J = 0; J < NB; ++J) {
+                Acc acc = {S(0), S(0), S(0), S(0)};
+#pragma unroll
+                for (int K = 0; K < NB; ++K)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc = Mfma<S>::run(a[i][I][K][v], P[K][J][v], acc);
+                Pn[I][J] = acc;
+            }
+#pragma unroll
+        for (int I = 0; I < NB; ++I) {
+            S s = S(0);
+#pragma unroll
+            for (int K = 0; K < NB; ++K)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) s += a[i][I][K][v] * vc[K][v];
+            vr[I] = sum_groups<S>(s) + bel[i][I];
+        }
+#pragma unroll
+        for (int K = 0; K < NB; ++K)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) vc[K][v] = __shfl(vr[K], 4 * g + v);
+#pragma unroll
+        for (int I = 0; I < NB; ++I)
+#pragma unroll
+            for (int J = 0; J < NB; ++J) P[I][J] = Pn[I][J];
+    }
+
+    // wavefront total -> LDS (row-major)
+#pragma unroll
+    for (int I = 0; I < NB; ++I) {
+#pragma unroll
+        for (int J = 0; J < NB; ++J)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sM[wave][(16 * I + 4 * g + v) * LD + 16 * J + r] = P[I][J][v];
+        if (g == 0) sv[wave][16 * I + r] = vr[I];
+    }
+    __syncthreads();
+
+    // ---- 2. tile total (wavefront 0), 3. look-back ----
+    const long long slot = (long long)b * p.tiles + t;
+    if (wave == 0) {
+#pragma unroll 1
+        for (int w = 1; w < WAVES; ++w) {
+            S am[NB][NB][4];
+#pragma unroll
+            for (int I = 0; I < NB; ++I)
+#pragma unroll
+                for (int K = 0; K < NB; ++K)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) am[I][K][v] = sM[w][(16 * I + r) * LD + 16 * K + 4 * g + v];
+            Acc Pn[NB][NB];
+#pragma unroll
+            for (int I = 0; I < NB; ++I)
+#pragma unroll
+                for (int J = 0; J < NB; ++J) {
+                    Acc acc = {S(0), S(0), S(0), S(0)};
+#pragma unroll
+                    for (int K = 0; K < NB; ++K)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc = Mfma<S>::run(am[I][K][v], P[K][J][v], acc);
+                    Pn[I][J] = acc;
+                }
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+                S s = S(0);
+#pragma unroll
+                for (int K = 0; K < NB; ++K)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) s += am[I][K][v] * vc[K][v];
+                vr[I] = sum_groups<S>(s) + sv[w][16 * I + r];
+            }
+#pragma unroll
+            for (int K = 0; K < NB; ++K)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) vc[K][v] = __shfl(vr[K], 4 * g + v);
+#pragma unroll
+            for (int I = 0; I < NB; ++I)
+#pragma unroll
+                for (int J = 0; J < NB; ++J) P[I][J] = Pn[I][J];
+        }
+        // tile total -> LDS (for the inclusive carry) and HBM (for successors)
+        S* gM = reinterpret_cast<S*>(p.aggM) + slot * (N * N);
+        S* gv = reinterpret_cast<S*>(p.aggv) + slot * N;
+        S* gi = reinterpret_cast<S*>(p.incl) + slot * N;
+        const unsigned tag = p.epoch << 2;
+#pragma unroll
+        for (int I = 0; I < NB; ++I) {
+#pragma unroll
+            for (int J = 0; J < NB; ++J)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    sT[(16 * I + 4 * g + v) * LD + 16 * J + r] = P[I][J][v];
+                    if (t > 0) gM[(16 * I + 4 * g + v) * N + 16 * J + r] = P[I][J][v];
+                }
+            if (g == 0) {
+                sTv[16 * I + r] = vr[I];
+                if (t > 0) gv[16 * I + r] = vr[I];
+            }
+        }
+        if (t > 0) {
+            __threadfence();
+            if (lane == 0) flag_store(&p.flags[slot], tag | TILE_AGGREGATE);
+        }
+
+        // lane j inspects predecessor t-1-j; index -1 is the given initial state
+        const int idx = t - 1 - lane;
+        int k = -1;
+        unsigned spins = 0;
+        while (true) {
+            unsigned st;
+            if (idx >= 0) {
+                const unsigned f = flag_load(&p.flags[(long long)b * p.tiles + idx]);
+                st = ((f >> 2) == p.epoch) ? (f & 3u) : TILE_INVALID;
+            } else {
+                st = (idx == -1) ? TILE_INCLUSIVE : 3u;
+            }
+            const unsigned long long incl_mask = __ballot(st == TILE_INCLUSIVE);
+            const unsigned long long wait_mask = __ballot(st == TILE_INVALID);
+            if (incl_mask != 0ull) {
+                const int first = __ffsll((long long)incl_mask) - 1;
+                const unsigned long long below = (first == 0) ? 0ull : ((1ull << first) - 1ull);
+                if ((wait_mask & below) == 0ull) { k = first; break; }
+            }
+            if (++spins > kSpinLimit) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+
+        // carry in row layout yr[I] = y[16I + r], column layout yc[K][v] = y[16K + 4g + v]
+        S yr[NB], yc[NB][4];
+#pragma unroll
+        for (int I = 0; I < NB; ++I) yr[I] = S(0);
+        if (k < 0) {
+            if (lane == 0) atomicOr(p.status, 1u);
+        } else {
+            const int far = t - 1 - k;   // tile whose inclusive carry is known (-1: initial state)
+            if (far >= 0) {
+                const S* pi = reinterpret_cast<const S*>(p.incl) + ((long long)b * p.tiles + far) * N;
+#pragma unroll
+                for (int I = 0; I < NB; ++I) yr[I] = coherent_load(pi + 16 * I + r);
+            } else if (p.y0) {
+                const S* y0b = reinterpret_cast<const S*>(p.y0) + (long long)b * N;
+#pragma unroll
+                for (int I = 0; I < NB; ++I) yr[I] = y0b[16 * I + r];
+            }
+#pragma unroll
+            for (int K = 0; K < NB; ++K)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], 4 * g + v);
+            // fold the totals of tiles far+1 .. t-1 forward
+#pragma unroll 1
+            for (int q = far + 1; q <= t - 1; ++q) {
+                const S* pM = reinterpret_cast<const S*>(p.aggM) + ((long long)b * p.tiles + q) * (N * N);
+                const S* pv = reinterpret_cast<const S*>(p.aggv) + ((long long)b * p.tiles + q) * N;
+                S ny[NB];
+#pragma unroll
+                for (int I = 0; I < NB; ++I) {
+                    S s = S(0);
+#pragma unroll
+                    for (int K = 0; K < NB; ++K)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            s += coherent_load(pM + (16 * I + r) * N + 16 * K + 4 * g + v) * yc[K][v];
+                    ny[I] = sum_groups<S>(s) + coherent_load(pv + 16 * I + r);
+                }
+#pragma unroll
+                for (int I = 0; I < NB; ++I) yr[I] = ny[I];
+#pragma unroll
+                for (int K = 0; K < NB; ++K)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], 4 * g + v);
+            }
+        }
+        // carry into LDS, inclusive carry of this tile = (tile total) applied to it
+        if (g == 0) {
+#pragma unroll
+            for (int I = 0; I < NB; ++I) sC[0][16 * I + r] = yr[I];
+        }
+        if (lane < N) {
+            S s = sTv[lane];
+            for (int q = 0; q < N; ++q) s += sT[lane * LD + q] * sC[0][q];
+            gi[lane] = s;
+        }
+        __threadfence();
+        if (lane == 0) flag_store(&p.flags[slot], tag | TILE_INCLUSIVE);
+    }
+    __syncthreads();
+
+    // ---- 4. carry entering this wavefront, then the second walk over the resident pairs ----
+    for (int w = 0; w < wave; ++w) {
+        // sC[wave] <- M_w * (carry entering w) + v_w, built up in place from sC[0]
+        S s = S(0);
+        if (lane < N) {
+            const S* cin = (w == 0) ? sC[0] : sC[wave];
+            s = sv[w][lane];
+            for (int q = 0; q < N; ++q) s += sM[w][lane * LD + q] * cin[q];
+        }
+        if (lane < N) sC[wave][lane] = s;
+    }
+    S yc[NB][4], yr[NB];
+#pragma unroll
+    for (int K = 0; K < NB; ++K)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) yc[K][v] = sC[wave][16 * K + 4 * g + v];
+
+    S emax = S(0);
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+        const long long e = e0 + i;
+#pragma unroll
+        for (int I = 0; I < NB; ++I) {
+            S s = S(0);
+#pragma unroll
+            for (int K = 0; K < NB; ++K)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) s += a[i][I][K][v] * yc[K][v];
+            yr[I] = sum_groups<S>(s) + bel[i][I];
+        }
+        if (e < p.T && g == 0) {
+            const long long oi = (REV ? ((long long)p.T - 1 - e) : e) * N;
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+                ob[oi + 16 * I + r] = yr[I];
+                if (oldb) {
+                    const S dq = abs_or_inf<S>(yr[I] - oldb[oi + 16 * I + r]);
+                    emax = dq > emax ? dq : emax;
+                }
+            }
+        }
+#pragma unroll
+        for (int K = 0; K < NB; ++K)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], 4 * g + v);
+    }
+    if (p.err) {
+        emax = wave_max<S>(emax);
+        if (lane == 0) err_atomic_max(p.err, emax);
+    }
+}
+
+template <typename S, int N> struct MfmaShape;
+template <> struct MfmaShape<float, 16> { static constexpr int LW = 16, WAVES = 8; };
+template <> struct MfmaShape<float, 32> { static constexpr int LW = 8, WAVES = 8; };
+template <> struct MfmaShape<double, 16> { static constexpr int LW = 8, WAVES = 8; };
+template <> struct MfmaShape<double, 32> { static constexpr int LW = 4, WAVES = 8; };
+
+template <typename S, int N>
+hipError_t launch_n(const ScanParams& p, hipStream_t s) {
+    constexpr int LW = MfmaShape<S, N>::LW, WAVES = MfmaShape<S, N>::WAVES;
+    dim3 grid((unsigned)((long long)p.B * p.tiles));
+    if (p.reverse)
+        hipLaunchKernelGGL((scan_mfma_kernel<S, N, LW, WAVES, true>), grid, dim3(64 * WAVES), 0, s, p);
+    else
+        hipLaunchKernelGGL((scan_mfma_kernel<S, N, LW, WAVES, false>), grid, dim3(64 * WAVES), 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int scan_mfma_tile(int dtype, int n) {
+    if (dtype == 0) return n == 16 ? MfmaShape<float, 16>::LW * MfmaShape<float, 16>::WAVES
+                                   : MfmaShape<float, 32>::LW * MfmaShape<float, 32>::WAVES;
+    return n == 16 ? MfmaShape<double, 16>::LW * MfmaShape<double, 16>::WAVES
+                   : MfmaShape<double, 32>::LW * MfmaShape<double, 32>::WAVES;
+}
+
+hipError_t launch_scan_mfma(int dtype, int n, const ScanParams& p, hipStream_t s) {
+    if (n != 16 && n != 32) return hipErrorInvalidValue;
+    if (dtype == 0) return n == 16 ? launch_n<float, 16>(p, s) : launch_n<float, 32>(p, s);
+    return n == 16 ? launch_n<double, 16>(p, s) : launch_n<double, 32>(p, s);
+}
+
+}  // namespace deer

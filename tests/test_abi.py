@@ -1,0 +1,57 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header declares, and its
+argument validation works without a GPU.  No compute calls."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2309_12252_amd import deer
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "deer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(deer_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = deer.load_library()
+    names = declared_symbols()
+    assert set(names) == set(deer.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_theta_count_and_validation_on_host():
+    gru = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 16, 10000, 8, d=4)
+    assert deer.theta_count(gru) == 3 * 8 * 4 + 3 * 8 * 8 + 4 * 8
+    mlp = deer.make_config(deer.DEER_CELL_MLP_ODE, deer.DEER_F32, 8, 100000, 8, mlp_width=32,
+                           mlp_hidden_layers=2, t0=0.0, t1=10.0)
+    assert deer.theta_count(mlp) == 32 * 8 + 32 + 32 * 32 + 32 + 8 * 32 + 8
+    assert deer.workspace_bytes(gru) > 16 * 10000 * 8 * 8 * 4
+    assert deer.workspace_bytes(mlp) > 2 * 8 * 100000 * 8 * 8 * 4 - 8 * 64 * 4
+    with pytest.raises(deer.DeerError) as e:
+        deer.workspace_bytes(deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 1, 10, 5, d=2))
+    assert e.value.status == deer.DEER_ERR_UNSUPPORTED
+    with pytest.raises(deer.DeerError) as e:
+        deer.workspace_bytes(deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 0, 10, 4, d=2))
+    assert e.value.status == deer.DEER_ERR_INVALID_ARG
+    with pytest.raises(deer.DeerError) as e:
+        deer.workspace_bytes(deer.make_config(deer.DEER_CELL_MLP_ODE, deer.DEER_F32, 1, 10, 8, mlp_width=32,
+                                              mlp_hidden_layers=3, t0=0.0, t1=1.0))
+    assert e.value.status == deer.DEER_ERR_UNSUPPORTED
+
+
+def test_create_rejects_bad_arguments_without_touching_the_gpu():
+    lib = deer.load_library()
+    cfg = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 1, 10, 4, d=2)
+    handle = ctypes.c_void_p(None)
+    st = lib.deer_create(ctypes.byref(cfg), None, 1 << 20, None, ctypes.byref(handle))
+    assert st == deer.DEER_ERR_WORKSPACE and not handle.value
+    st = lib.deer_create(ctypes.byref(cfg), ctypes.c_void_p(256), 16, None, ctypes.byref(handle))
+    assert st == deer.DEER_ERR_WORKSPACE and not handle.value
+    assert b"workspace" in lib.deer_last_error(None)
+    assert lib.deer_eval(None, None, None, None, None, 1e-4, 1, None, None, None, None) == deer.DEER_ERR_INVALID_ARG
