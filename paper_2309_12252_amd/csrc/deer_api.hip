@@ -194,12 +194,13 @@ void prof_collect(deer_ctx* c) {
 
 // One scan launch over the context's shapes.
 hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, void* out, const void* yold,
-                    long long strideA, long long strideb, long long strideOut, int reverse, int slot, bool want_err) {
+                    long long strideA, long long strideb, long long strideOut, int reverse, int slot, bool want_err,
+                    int delta = 0) {
     const deer_config& g = c->cfg;
     ScanParams p{};
     p.A = A; p.bv = bv; p.y0 = y0; p.out = out; p.yold = yold;
     p.strideA = strideA; p.strideb = strideb; p.strideOut = strideOut; p.strideOld = strideOut;
-    p.B = g.B; p.T = c->plan.scan_T; p.L = c->plan.L; p.tiles = c->plan.tiles; p.reverse = reverse;
+    p.B = g.B; p.T = c->plan.scan_T; p.L = c->plan.L; p.tiles = c->plan.tiles; p.reverse = reverse; p.delta = delta;
     p.epoch = ++c->epoch;
     if (c->epoch >= (1u << 30)) c->epoch = 0;   // flags are re-zeroed by the caller path below when this wraps
     p.flags = reinterpret_cast<unsigned*>(c->ws + c->plan.off_flags);
@@ -340,13 +341,14 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
             prof_begin(c, KIND_FUNCEVAL);
             HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
             prof_end(c);
-            OdeDiscParams dp{J, rhs, Gbar, zbar, g.B, g.T, g.n, (g.t1 - g.t0) / (double)(g.T - 1)};
+            OdeDiscParams dp{J, rhs, cur, Gbar, zbar, g.B, g.T, g.n, (g.t1 - g.t0) / (double)(g.T - 1)};
             prof_begin(c, KIND_DISC);
             HIPCHK(c, launch_ode_discretise(g.dtype, dp, c->stream));
             prof_end(c);
-            // positions 1..T-1 of the trajectory; position 0 stays y0
-            HIPCHK(c, run_scan(c, Gbar, zbar, d_y0, nxt + n * esz, cur + n * esz, (long long)((T - 1) * n * n),
-                               (long long)((T - 1) * n), (long long)(T * n), 0, slot, true));
+            // correction form: the scan solves delta_{i+1} = Gbar_i delta_i + res_i from delta_0 = 0 and
+            // writes y_next = y + delta at positions 1..T-1; position 0 stays y0
+            HIPCHK(c, run_scan(c, Gbar, zbar, nullptr, nxt + n * esz, cur + n * esz, (long long)((T - 1) * n * n),
+                               (long long)((T - 1) * n), (long long)(T * n), 0, slot, true, 1));
         }
         HIPCHK(c, hipMemcpyAsync(c->h_err, ctl_err(c, slot), 8, hipMemcpyDeviceToHost, c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));

@@ -24,6 +24,7 @@ struct ScanParams {
     int L;               // scan positions per lane (VALU kernel)
     int tiles;           // tiles per sequence
     int reverse;
+    int delta;           // 1: the scan solves for a correction; out = yold + y and the error is max|y|
     unsigned epoch;      // flags carry (epoch << 2) | state, so stale flags need no clearing
     unsigned* flags;     // [B * tiles]
     void* aggM;          // [B * tiles][n*n]  tile aggregates
@@ -153,7 +154,8 @@ struct MlpParams {
 
 struct OdeDiscParams {
     const void* G; const void* z;         // [B,T,n,n], [B,T,n]
-    void* Gbar; void* zbar;               // [B,T-1,n,n], [B,T-1,n]
+    const void* y;                        // current iterate [B,T,n]
+    void* Gbar; void* res;                // [B,T-1,n,n] exp(-Gc dt), [B,T-1,n] residual of the iterate
     int B, T, n;
     double dt;
 };

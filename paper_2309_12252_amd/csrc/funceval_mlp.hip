@@ -5,7 +5,10 @@
 //   ode_discretise_kernel: per interval, midpoint values Gc = (G_i + G_{i+1})/2, zc likewise,
 //     Gbar = exp(-Gc dt) and zbar = Gc^{-1}(I - Gbar) zc (Sec. 3.3 eq. 9), the latter evaluated as
 //     dt * phi1(-Gc dt) zc with phi1(X) = sum_k X^k/(k+1)!, which equals the printed formula when
-//     Gc is invertible and stays finite when it is not.
+//     Gc is invertible and stays finite when it is not.  The kernel hands the scan the pair
+//     (Gbar | res) with res = Gbar y_i + zbar - y_{i+1}, the residual of the current iterate: the
+//     scan then solves for the correction y_next - y, which is the same Newton step in exact
+//     arithmetic but keeps fp32 rounding relative to the (small) correction instead of to y.
 //   pin_first_kernel: y[b,0,:] = y0[b,:] (the first grid point is the initial condition).
 //
 // mlp_funceval work split: the n threads of a grid point sit in consecutive lanes; thread j owns
@@ -148,8 +151,9 @@ __global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams 
     const long long i = q - bi * (p.T - 1);
     const S* __restrict__ G = reinterpret_cast<const S*>(p.G) + (bi * p.T + i) * (N * N);
     const S* __restrict__ z = reinterpret_cast<const S*>(p.z) + (bi * p.T + i) * N;
+    const S* __restrict__ y = reinterpret_cast<const S*>(p.y) + (bi * p.T + i) * N;
     S* __restrict__ Gbar = reinterpret_cast<S*>(p.Gbar) + q * (N * N);
-    S* __restrict__ zbar = reinterpret_cast<S*>(p.zbar) + q * N;
+    S* __restrict__ res = reinterpret_cast<S*>(p.res) + q * N;
     const S dt = (S)p.dt;
 
     // X = -Gc dt / 2^sq with max-row-sum norm at most 1/2
@@ -180,21 +184,16 @@ __global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams 
 #pragma unroll
     for (int k = 0; k < N * N; ++k) X[k] *= scale;
 
-    // Taylor series of exp(X) (matrix) and phi1(X) zc (vector), until the bound norm^k/k! on the
-    // next term is below the working precision
-    S E[N * N], term[N * N], pv[N], wv[N];
+    // Taylor series of D = exp(X) - I (matrix, identity left out so that nothing of size |X| is
+    // rounded against 1) and of phi1(X) zc (vector), until the bound norm^k/k! on the next term is
+    // below the working precision
+    S D[N * N], term[N * N], pv[N], wv[N];
 #pragma unroll
-    for (int k = 0; k < N * N; ++k) { const S id = ((k / N) == (k % N)) ? S(1) : S(0); E[k] = id; term[k] = id; }
+    for (int k = 0; k < N * N; ++k) { D[k] = X[k]; term[k] = X[k]; }
 #pragma unroll
     for (int k = 0; k < N; ++k) { pv[k] = zc[k]; wv[k] = zc[k]; }
-    S bound = S(1);
+    S bound = norm;
     for (int k = 1; k <= 24; ++k) {
-        bound *= norm / (S)k;
-        S nt[N * N];
-        matmul_reg<S, N>(term, X, nt);
-        const S inv = S(1) / (S)k;
-#pragma unroll
-        for (int e = 0; e < N * N; ++e) { term[e] = nt[e] * inv; E[e] += term[e]; }
         // w_k = X w_{k-1} / (k+1)
         S nw[N];
         const S inv1 = S(1) / (S)(k + 1);
@@ -208,28 +207,47 @@ __global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams 
 #pragma unroll
         for (int r = 0; r < N; ++r) { wv[r] = nw[r]; pv[r] += nw[r]; }
         if (bound < SeriesTol<S>::v) break;
+        // term_{k+1} = term_k X / (k+1)
+        bound *= norm * inv1;
+        S nt[N * N];
+        matmul_reg<S, N>(term, X, nt);
+#pragma unroll
+        for (int e = 0; e < N * N; ++e) { term[e] = nt[e] * inv1; D[e] += term[e]; }
     }
-    // undo the scaling: phi1(2X) v = (exp(X) + I) phi1(X) v / 2, exp(2X) = exp(X)^2
+    // undo the scaling: phi1(2X) v = (exp(X) + I) phi1(X) v / 2 = phi1(X) v + D phi1(X) v / 2,
+    // exp(2X) - I = 2D + D^2
     for (int sstep = 0; sstep < sq; ++sstep) {
         S nv[N];
 #pragma unroll
         for (int r = 0; r < N; ++r) {
-            S s = pv[r];
+            S s = S(0);
 #pragma unroll
-            for (int c = 0; c < N; ++c) s += E[r * N + c] * pv[c];
-            nv[r] = S(0.5) * s;
+            for (int c = 0; c < N; ++c) s += D[r * N + c] * pv[c];
+            nv[r] = pv[r] + S(0.5) * s;
         }
 #pragma unroll
         for (int r = 0; r < N; ++r) pv[r] = nv[r];
-        S E2[N * N];
-        matmul_reg<S, N>(E, E, E2);
+        S D2[N * N];
+        matmul_reg<S, N>(D, D, D2);
 #pragma unroll
-        for (int e = 0; e < N * N; ++e) E[e] = E2[e];
+        for (int e = 0; e < N * N; ++e) D[e] = S(2) * D[e] + D2[e];
+    }
+    // residual of the current iterate in the discretised recurrence (Sec. 3.3 eq. 9):
+    // res = Gbar y_i + zbar - y_{i+1} = D y_i + dt phi1 zc - (y_{i+1} - y_i)
+    S y0v[N], y1v[N], rv[N];
+    vload<S, N>(y0v, y);
+    vload<S, N>(y1v, y + N);
+#pragma unroll
+    for (int r = 0; r < N; ++r) {
+        S s = S(0);
+#pragma unroll
+        for (int c = 0; c < N; ++c) s += D[r * N + c] * y0v[c];
+        rv[r] = (s + dt * pv[r]) - (y1v[r] - y0v[r]);
     }
 #pragma unroll
-    for (int r = 0; r < N; ++r) pv[r] *= dt;
-    vstore<S, N * N>(Gbar, E);
-    vstore<S, N>(zbar, pv);
+    for (int e = 0; e < N * N; ++e) D[e] += ((e / N) == (e % N)) ? S(1) : S(0);
+    vstore<S, N * N>(Gbar, D);
+    vstore<S, N>(res, rv);
 }
 
 template <typename S>

@@ -2,14 +2,15 @@
 // pairs (A | b) with the operator of Sec. 3.3 eq. 10, the matrix-matrix part on the matrix cores.
 //
 // Every n x n matrix is handled as (n/16)^2 blocks of 16 x 16 and multiplied with the 16x16x4 MFMA
-// instruction (fp32 and fp64 forms share one register layout):
+// instruction:
 //   A operand  : lane (g = lane/16, r = lane%16) supplies A[r][g]           (16 x 4 slice)
 //   B operand  : lane (g, c = lane%16)           supplies B[g][c]           (4 x 16 slice)
-//   accumulator: lane (g, c), register v         holds    D[4g + v][c]
+//   accumulator: lane (g, c), register v         holds    D[4g + v][c] (fp32) or D[4v + g][c] (fp64)
 // A running product P is kept in accumulator layout.  Register v of a block of P, used directly as
-// the B operand, is the 4 x 16 slice made of rows {4g + v}; the matching A operand is the 16 x 4
-// slice made of columns {4g + v}, v = 0..3, which is one contiguous 4-scalar load per lane from a
-// row-major matrix.  So P <- A_t P needs no data movement between accumulators and operands.
+// the B operand, is the 4 x 16 slice made of rows {idx(g, v)}; the matching A operand is the 16 x 4
+// slice made of columns {idx(g, v)}.  For fp32 (idx = 4g + v) that is one contiguous 4-scalar load
+// per lane from a row-major matrix; for fp64 (idx = 4v + g) four strided loads.  So P <- A_t P needs
+// no data movement between accumulators and operands.
 //
 // Structure of one tile (WAVES wavefronts, LW scan positions per wavefront):
 //   1. each wavefront loads its LW pairs into registers (A-operand layout) and composes them
@@ -38,6 +39,18 @@ template <> struct Mfma<double> {
     static __device__ __forceinline__ Acc run(double a, double b, Acc c) {
         return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
     }
+};
+
+// Index (row of an accumulator block, or k inside a 16-wide slice) that register v of lane group g
+// stands for.  The fp32 instruction keeps rows 4g + v in lane group g, the fp64 one rows 4v + g.
+template <typename S> struct Lay;
+template <> struct Lay<float> {
+    static constexpr bool contiguous = true;
+    static __device__ __forceinline__ int idx(int g, int v) { return 4 * g + v; }
+};
+template <> struct Lay<double> {
+    static constexpr bool contiguous = false;
+    static __device__ __forceinline__ int idx(int g, int v) { return 4 * v + g; }
 };
 
 // sum over the four lane groups g (lanes r, r+16, r+32, r+48)
@@ -83,7 +96,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
     const long long e0 = (long long)t * TILE + (long long)wave * LW;
 
     // ---- 1a. load this wavefront's pairs ----
-    S a[LW][NB][NB][4];   // a[i][I][K][v] = A_e[16I + r][16K + 4g + v]
+    S a[LW][NB][NB][4];   // a[i][I][K][v] = A_e[16I + r][16K + idx(g, v)]
     S bel[LW][NB];        // bel[i][I]     = b_e[16I + r]
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
@@ -94,7 +107,15 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
                 for (int I = 0; I < NB; ++I)
 #pragma unroll
-                    for (int K = 0; K < NB; ++K) vload<S, 4>(a[i][I][K], Ae + (16 * I + r) * N + 16 * K + 4 * g);
+                    for (int K = 0; K < NB; ++K) {
+                        if constexpr (Lay<S>::contiguous) {
+                            vload<S, 4>(a[i][I][K], Ae + (16 * I + r) * N + 16 * K + 4 * g);
+                        } else {
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                a[i][I][K][v] = Ae[(16 * I + r) * N + 16 * K + Lay<S>::idx(g, v)];
+                        }
+                    }
 #pragma unroll
                 for (int I = 0; I < NB; ++I) bel[i][I] = bb[e * N + 16 * I + r];
             } else {
@@ -115,7 +136,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
                         for (int K = 0; K < NB; ++K)
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) a[i][I][K][v] = Ae[(16 * K + 4 * g + v) * N + 16 * I + r];
+                            for (int v = 0; v < 4; ++v) a[i][I][K][v] = Ae[(16 * K + Lay<S>::idx(g, v)) * N + 16 * I + r];
                 }
             }
         } else {
@@ -126,7 +147,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
                 for (int K = 0; K < NB; ++K)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) a[i][I][K][v] = (I == K && r == 4 * g + v) ? S(1) : S(0);
+                    for (int v = 0; v < 4; ++v) a[i][I][K][v] = (I == K && r == Lay<S>::idx(g, v)) ? S(1) : S(0);
             }
         }
     }
@@ -138,9 +159,9 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
         for (int J = 0; J < NB; ++J)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) P[I][J][v] = (I == J && 4 * g + v == r) ? S(1) : S(0);
+            for (int v = 0; v < 4; ++v) P[I][J][v] = (I == J && Lay<S>::idx(g, v) == r) ? S(1) : S(0);
     S vr[NB];        // vec in row layout:    vr[I]    = vec[16I + r]
-    S vc[NB][4];     // vec in column layout: vc[K][v] = vec[16K + 4g + v]
+    S vc[NB][4];     // vec in column layout: vc[K][v] = vec[16K + idx(g, v)]
 #pragma unroll
     for (int I = 0; I < NB; ++I) {
         vr[I] = S(0);
@@ -173,7 +194,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
         for (int K = 0; K < NB; ++K)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) vc[K][v] = __shfl(vr[K], 4 * g + v);
+            for (int v = 0; v < 4; ++v) vc[K][v] = __shfl(vr[K], Lay<S>::idx(g, v));
 #pragma unroll
         for (int I = 0; I < NB; ++I)
 #pragma unroll
@@ -186,7 +207,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
         for (int J = 0; J < NB; ++J)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) sM[wave][(16 * I + 4 * g + v) * LD + 16 * J + r] = P[I][J][v];
+            for (int v = 0; v < 4; ++v) sM[wave][(16 * I + Lay<S>::idx(g, v)) * LD + 16 * J + r] = P[I][J][v];
         if (g == 0) sv[wave][16 * I + r] = vr[I];
     }
     __syncthreads();
@@ -202,7 +223,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
                 for (int K = 0; K < NB; ++K)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) am[I][K][v] = sM[w][(16 * I + r) * LD + 16 * K + 4 * g + v];
+                    for (int v = 0; v < 4; ++v) am[I][K][v] = sM[w][(16 * I + r) * LD + 16 * K + Lay<S>::idx(g, v)];
             Acc Pn[NB][NB];
 #pragma unroll
             for (int I = 0; I < NB; ++I)
@@ -227,7 +248,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
             for (int K = 0; K < NB; ++K)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) vc[K][v] = __shfl(vr[K], 4 * g + v);
+                for (int v = 0; v < 4; ++v) vc[K][v] = __shfl(vr[K], Lay<S>::idx(g, v));
 #pragma unroll
             for (int I = 0; I < NB; ++I)
 #pragma unroll
@@ -244,8 +265,8 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
             for (int J = 0; J < NB; ++J)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    sT[(16 * I + 4 * g + v) * LD + 16 * J + r] = P[I][J][v];
-                    if (t > 0) gM[(16 * I + 4 * g + v) * N + 16 * J + r] = P[I][J][v];
+                    sT[(16 * I + Lay<S>::idx(g, v)) * LD + 16 * J + r] = P[I][J][v];
+                    if (t > 0) gM[(16 * I + Lay<S>::idx(g, v)) * N + 16 * J + r] = P[I][J][v];
                 }
             if (g == 0) {
                 sTv[16 * I + r] = vr[I];
@@ -280,7 +301,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
             __builtin_amdgcn_s_sleep(2);
         }
 
-        // carry in row layout yr[I] = y[16I + r], column layout yc[K][v] = y[16K + 4g + v]
+        // carry in row layout yr[I] = y[16I + r], column layout yc[K][v] = y[16K + idx(g, v)]
         S yr[NB], yc[NB][4];
 #pragma unroll
         for (int I = 0; I < NB; ++I) yr[I] = S(0);
@@ -300,7 +321,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
             for (int K = 0; K < NB; ++K)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], 4 * g + v);
+                for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], Lay<S>::idx(g, v));
             // fold the totals of tiles far+1 .. t-1 forward
 #pragma unroll 1
             for (int q = far + 1; q <= t - 1; ++q) {
@@ -314,7 +335,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
                     for (int K = 0; K < NB; ++K)
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
-                            s += coherent_load(pM + (16 * I + r) * N + 16 * K + 4 * g + v) * yc[K][v];
+                            s += coherent_load(pM + (16 * I + r) * N + 16 * K + Lay<S>::idx(g, v)) * yc[K][v];
                     ny[I] = sum_groups<S>(s) + coherent_load(pv + 16 * I + r);
                 }
 #pragma unroll
@@ -322,7 +343,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
                 for (int K = 0; K < NB; ++K)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], 4 * g + v);
+                    for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], Lay<S>::idx(g, v));
             }
         }
         // carry into LDS, inclusive carry of this tile = (tile total) applied to it
@@ -355,7 +376,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
     for (int K = 0; K < NB; ++K)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) yc[K][v] = sC[wave][16 * K + 4 * g + v];
+        for (int v = 0; v < 4; ++v) yc[K][v] = sC[wave][16 * K + Lay<S>::idx(g, v)];
 
     S emax = S(0);
 #pragma unroll
@@ -374,17 +395,20 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
             const long long oi = (REV ? ((long long)p.T - 1 - e) : e) * N;
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
-                ob[oi + 16 * I + r] = yr[I];
+                S wv = yr[I];
                 if (oldb) {
-                    const S dq = abs_or_inf<S>(yr[I] - oldb[oi + 16 * I + r]);
+                    const S yo = oldb[oi + 16 * I + r];
+                    const S dq = abs_or_inf<S>(p.delta ? yr[I] : yr[I] - yo);
                     emax = dq > emax ? dq : emax;
+                    if (p.delta) wv += yo;
                 }
+                ob[oi + 16 * I + r] = wv;
             }
         }
 #pragma unroll
         for (int K = 0; K < NB; ++K)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], 4 * g + v);
+            for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], Lay<S>::idx(g, v));
     }
     if (p.err) {
         emax = wave_max<S>(emax);

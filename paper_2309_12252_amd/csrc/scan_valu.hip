@@ -320,15 +320,18 @@ __global__ __launch_bounds__(kThreads) void scan_valu_kernel(ScanParams p) {
             load_elem<S, N, REV>(Ab, bb, p.T, (int)e, Am, bvv);
             matvec<S, N>(Am, bvv, y);
             const long long oi = (REV ? (long long)(p.T - 1 - e) : e) * N;
-            vstore<S, N>(ob + oi, y);
             if (oldb) {
-                S yo[N];
+                S yo[N], wv[N];
                 vload<S, N>(yo, oldb + oi);
 #pragma unroll
                 for (int q = 0; q < N; ++q) {
-                    const S dq = abs_or_inf<S>(y[q] - yo[q]);
+                    wv[q] = p.delta ? yo[q] + y[q] : y[q];
+                    const S dq = abs_or_inf<S>(p.delta ? y[q] : y[q] - yo[q]);
                     emax = dq > emax ? dq : emax;
                 }
+                vstore<S, N>(ob + oi, wv);
+            } else {
+                vstore<S, N>(ob + oi, y);
             }
         }
     }
