@@ -21,6 +21,9 @@ constexpr int kSlots = 256;          // ticket / error slots, one per scan launc
 constexpr size_t kAlign = 256;
 
 thread_local std::string g_last_error;
+#ifdef DEER_SCAN_TIMING
+unsigned long long* g_timing = nullptr;
+#endif
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -29,12 +32,12 @@ struct Plan {
     int scan_T;          // scan positions per sequence
     int tile;            // scan positions per tile
     int tiles;           // tiles per sequence
-    int L;               // positions per lane (VALU scan)
+    int L;               // positions per lane group (VALU scan)
+    int W;               // wavefronts per tile (VALU scan)
     bool mfma;
     int vjp_blocks;
     // byte offsets into the workspace
-    size_t off_J, off_rhs, off_ybuf, off_Gbar, off_zbar, off_flags, off_aggM, off_aggv, off_incl,
-        off_ctl, off_partial, total;
+    size_t off_J, off_rhs, off_ybuf, off_Gbar, off_zbar, off_aggW, off_inclW, off_ctl, off_partial, total;
 };
 
 size_t theta_count(const deer_config* c) {
@@ -92,17 +95,20 @@ Plan make_plan(const deer_config* c) {
         p.L = 0;
         p.tile = scan_mfma_tile(c->dtype, c->n);
     } else {
-        // positions per lane: enough tiles to fill the chip, long enough serial runs to amortise
-        // the log-step scan across lanes
-        const long long S = (long long)B * p.scan_T;
-        long long L = (S + 256LL * 1024 - 1) / (256LL * 1024);
-        if (L < 2) L = 2;
-        if (L > 16) L = 16;
-        L = env_int("DEER_SCAN_L", (int)L);
-        if (L < 1) L = 1;
-        if (L > 64) L = 64;
-        p.L = (int)L;
-        p.tile = scan_valu_tile(c->n, p.L);
+        // positions per group of lanes (1, 2, 4 or 8): the longest serial run that still leaves
+        // enough tiles to fill the chip
+        int W = env_int("DEER_SCAN_W", 8);
+        if (W != 4 && W != 8) W = 8;
+        if (64 / c->n < W) W = 4;
+        p.W = W;
+        int L = (c->dtype == DEER_F64 && c->n == 8) ? 4 : 8;   // fp64, n = 8: L = 8 would spill registers
+        const int Lmax = L;
+        while (L > 1 && (long long)B * ((p.scan_T + scan_valu_tile(c->n, L, W) - 1) / scan_valu_tile(c->n, L, W)) < 512) L >>= 1;
+        L = env_int("DEER_SCAN_L", L);
+        if (L != 1 && L != 2 && L != 4 && L != 8) L = Lmax;
+        if (L > Lmax) L = Lmax;
+        p.L = L;
+        p.tile = scan_valu_tile(c->n, p.L, W);
     }
     p.tiles = (p.scan_T + p.tile - 1) / p.tile;
     if (p.tiles < 1) p.tiles = 1;
@@ -116,10 +122,9 @@ Plan make_plan(const deer_config* c) {
     p.off_Gbar = take(ode ? B * (T - 1) * n * n * p.esz : 0);
     p.off_zbar = take(ode ? B * (T - 1) * n * p.esz : 0);
     const size_t nt = B * (size_t)p.tiles;
-    p.off_flags = take(nt * 4);
-    p.off_aggM = take(nt * n * n * p.esz);
-    p.off_aggv = take(nt * n * p.esz);
-    p.off_incl = take(nt * n * p.esz);
+    // published tile totals and carries: one 64-bit tagged word per 32 bits of payload
+    p.off_aggW = take(nt * (n * n + n) * (p.esz / 4) * 8);
+    p.off_inclW = take(nt * n * (p.esz / 4) * 8);
     p.off_ctl = take((size_t)kSlots * 4 + (size_t)kSlots * 8 + 16);   // tickets, err bits, status
     p.off_partial = take((size_t)p.vjp_blocks * 4 * theta_count(c) * p.esz);
     p.total = off;
@@ -202,14 +207,21 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
     p.strideA = strideA; p.strideb = strideb; p.strideOut = strideOut; p.strideOld = strideOut;
     p.B = g.B; p.T = c->plan.scan_T; p.L = c->plan.L; p.tiles = c->plan.tiles; p.reverse = reverse; p.delta = delta;
     p.epoch = ++c->epoch;
-    if (c->epoch >= (1u << 30)) c->epoch = 0;   // flags are re-zeroed by the caller path below when this wraps
-    p.flags = reinterpret_cast<unsigned*>(c->ws + c->plan.off_flags);
-    p.aggM = c->ws + c->plan.off_aggM;
-    p.aggv = c->ws + c->plan.off_aggv;
-    p.incl = c->ws + c->plan.off_incl;
+    if (c->epoch >= (1u << 30)) c->epoch = 0;   // published words are re-zeroed at the next call (zero_ctl)
+    p.aggW = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_aggW);
+    p.inclW = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_inclW);
+    p.W = c->plan.W;
     p.ticket = ctl_ticket(c, slot);
     p.err = want_err ? ctl_err(c, slot) : nullptr;
     p.status = ctl_status(c);
+#ifdef DEER_SCAN_TIMING
+    {
+        static unsigned long long* dbg = nullptr;
+        if (!dbg) (void)hipMalloc(&dbg, (size_t)1 << 26);
+        p.timing = dbg;
+        g_timing = dbg;
+    }
+#endif
     prof_begin(c, KIND_SCAN);
     hipError_t e = c->plan.mfma ? launch_scan_mfma(g.dtype, g.n, p, c->stream)
                                 : launch_scan_valu(g.dtype, g.n, p, c->stream);
@@ -219,9 +231,8 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
 
 deer_status zero_ctl(deer_ctx* c) {
     HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_ctl, ctl_bytes(), c->stream));
-    if (c->epoch == 0) {
-        const size_t fb = align_up((size_t)c->cfg.B * c->plan.tiles * 4);
-        HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_flags, fb, c->stream));
+    if (c->epoch == 0) {   // the epoch counter wrapped: forget everything published so far
+        HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_aggW, c->plan.off_ctl - c->plan.off_aggW, c->stream));
     }
     return DEER_OK;
 }
@@ -278,8 +289,10 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
     for (auto& e : c->ev) e = nullptr;
     hipError_t e = hipHostMalloc(&c->h_err, 16, hipHostMallocDefault);
     for (int i = 0; i < 16 && e == hipSuccess; ++i) e = hipEventCreate(&c->ev[i]);
-    if (e == hipSuccess) e = launch_fill_zero(c->ws + plan.off_flags, align_up((size_t)cfg->B * plan.tiles * 4), c->stream);
     if (e == hipSuccess) e = launch_fill_zero(c->ws + plan.off_ctl, ctl_bytes(), c->stream);
+    // tagged words must not carry a valid tag by accident: epochs start at 1, so zeros never match
+    if (e == hipSuccess)
+        e = launch_fill_zero(c->ws + plan.off_aggW, plan.off_ctl - plan.off_aggW, c->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
         std::string msg = std::string("deer_create: ") + hipGetErrorString(e);
@@ -438,6 +451,10 @@ deer_status deer_get_profile(deer_ctx* c, deer_profile* out) {
     *out = c->prof;
     return DEER_OK;
 }
+
+#ifdef DEER_SCAN_TIMING
+void* deer_debug_timing() { return g_timing; }
+#endif
 
 const char* deer_last_error(const deer_ctx* c) {
     return c ? c->last_error.c_str() : g_last_error.c_str();

@@ -21,19 +21,27 @@ struct ScanParams {
     const void* yold;    // previous iterate laid out like out, or nullptr (no error reduction)
     long long strideA, strideb, strideOut, strideOld;
     int B, T;
-    int L;               // scan positions per lane (VALU kernel)
+    int L;               // scan positions per lane group (VALU kernel)
+    int W;               // wavefronts per tile (VALU kernel): 4 or 8
     int tiles;           // tiles per sequence
     int reverse;
     int delta;           // 1: the scan solves for a correction; out = yold + y and the error is max|y|
-    unsigned epoch;      // flags carry (epoch << 2) | state, so stale flags need no clearing
-    unsigned* flags;     // [B * tiles]
-    void* aggM;          // [B * tiles][n*n]  tile aggregates
-    void* aggv;          // [B * tiles][n]
-    void* incl;          // [B * tiles][n]    inclusive carry after the tile
+    unsigned epoch;      // tags carry (epoch << 2) | state, so words of earlier launches need no clearing
+    unsigned long long* aggW;   // [B * tiles][(n*n + n) * words per scalar] tile totals (M row-major, then v)
+    unsigned long long* inclW;  // [B * tiles][n * words per scalar] inclusive carry after the tile
     unsigned* ticket;    // tile dispenser for this launch (zero on entry)
     void* err;           // max |out - yold| as raw bits of a non-negative scalar, or nullptr
     unsigned* status;    // set non-zero when a bounded wait ran out
+#ifdef DEER_SCAN_TIMING
+    unsigned long long* timing;   // development builds only: [B * tiles][8] timestamps of the tile's phases
+#endif
 };
+
+#ifdef DEER_SCAN_TIMING
+#define DEER_STAMP(p, slot, j, cond) do { if ((p).timing && (cond)) (p).timing[(slot) * 8 + (j)] = wall_clock64(); } while (0)
+#else
+#define DEER_STAMP(p, slot, j, cond) do { } while (0)
+#endif
 
 enum : unsigned { TILE_INVALID = 0u, TILE_AGGREGATE = 1u, TILE_INCLUSIVE = 2u };
 constexpr unsigned kSpinLimit = 1u << 22;   // polls before a waiting tile gives up
@@ -83,23 +91,51 @@ __device__ __forceinline__ void vstore(S* __restrict__ dst, const S* src) {
     }
 }
 
-// Loads that must observe what another workgroup published (tile aggregates, carries).
-__device__ __forceinline__ float coherent_load(const float* p) {
-    unsigned u = __hip_atomic_load(reinterpret_cast<const unsigned*>(p), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-    return __uint_as_float(u);
-}
-__device__ __forceinline__ double coherent_load(const double* p) {
-    unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
-                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return __longlong_as_double((long long)u);
-}
-
-__device__ __forceinline__ unsigned flag_load(const unsigned* p) {
-    return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void flag_store(unsigned* p, unsigned v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+// ---------------------------------------------------------------------------------------
+// Self-validating words for data handed from one workgroup to another inside a launch.
+// Every 32 bits of payload travel in one 64-bit word together with a 32-bit tag
+// (launch epoch << 2 | state), written and read with single 64-bit agent-scope atomics.  A reader
+// accepts a word only if its tag matches, so no ordering between the words, no fence and no cache
+// write-back or invalidation is needed: a word is either the expected one or not there yet.
+// ---------------------------------------------------------------------------------------
+template <typename S> struct TaggedWords;
+template <> struct TaggedWords<float> {
+    static constexpr int per_scalar = 1;
+    static __device__ __forceinline__ void put(unsigned long long* base, long long idx, float v, unsigned tag) {
+        __hip_atomic_store(base + idx, ((unsigned long long)tag << 32) | __float_as_uint(v), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    static __device__ __forceinline__ bool get(const unsigned long long* base, long long idx, unsigned tag, float& v) {
+        const unsigned long long w = __hip_atomic_load(base + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v = __uint_as_float((unsigned)(w & 0xffffffffull));
+        return (unsigned)(w >> 32) == tag;
+    }
+};
+template <> struct TaggedWords<double> {
+    static constexpr int per_scalar = 2;
+    static __device__ __forceinline__ void put(unsigned long long* base, long long idx, double v, unsigned tag) {
+        const unsigned long long u = (unsigned long long)__double_as_longlong(v);
+        __hip_atomic_store(base + 2 * idx, ((unsigned long long)tag << 32) | (u & 0xffffffffull), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(base + 2 * idx + 1, ((unsigned long long)tag << 32) | (u >> 32), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    static __device__ __forceinline__ bool get(const unsigned long long* base, long long idx, unsigned tag, double& v) {
+        const unsigned long long lo = __hip_atomic_load(base + 2 * idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long hi = __hip_atomic_load(base + 2 * idx + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v = __longlong_as_double((long long)((hi << 32) | (lo & 0xffffffffull)));
+        return (unsigned)(lo >> 32) == tag && (unsigned)(hi >> 32) == tag;
+    }
+};
+// read a word that is known to be on its way; gives up (returns false) after kSpinLimit polls
+template <typename S>
+__device__ __forceinline__ bool tagged_get_wait(const unsigned long long* base, long long idx, unsigned tag, S& v) {
+    unsigned spins = 0;
+    while (!TaggedWords<S>::get(base, idx, tag, v)) {
+        if (++spins > kSpinLimit) return false;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    return true;
 }
 
 // max-reduce a non-negative value (NaN mapped to +inf by the caller) into *err as raw bits
@@ -162,7 +198,7 @@ struct OdeDiscParams {
 
 hipError_t launch_scan_valu(int dtype, int n, const ScanParams& p, hipStream_t s);
 hipError_t launch_scan_mfma(int dtype, int n, const ScanParams& p, hipStream_t s);
-int scan_valu_tile(int n, int L);          // scan positions per tile
+int scan_valu_tile(int n, int L, int W);   // scan positions per tile
 int scan_mfma_tile(int dtype, int n);
 hipError_t launch_gru_funceval(int dtype, const GruParams& p, hipStream_t s);
 hipError_t launch_gru_vjp(int dtype, const GruVjpParams& p, hipStream_t s);

@@ -16,9 +16,10 @@
 //   1. each wavefront loads its LW pairs into registers (A-operand layout) and composes them
 //      serially: P <- A_t P on the matrix cores, v <- A_t v + b_t on the vector ALUs;
 //   2. wavefront totals meet in LDS; wavefront 0 composes them into the tile total;
-//   3. decoupled look-back across tiles through HBM exactly as in the small-n kernel (tile index
-//      from an atomic ticket, flags AGGREGATE / INCLUSIVE tagged with a launch epoch, window of 64
-//      predecessors, forward fold of totals from the nearest known inclusive carry, bounded waits);
+//   3. decoupled look-back across tiles through HBM as in the small-n kernel (tile index from an
+//      atomic ticket, totals and inclusive carries published as self-validating tagged words,
+//      window of 64 predecessors, forward fold of totals from the nearest known inclusive carry with
+//      the next total requested while the current one is applied, bounded waits);
 //   4. each wavefront derives its starting state from the carry and walks its register-resident
 //      pairs again (y <- A_t y + b_t), writing y and reducing max|y - y_previous_iterate|.
 #include "deer_common.h"
@@ -254,11 +255,14 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
                 for (int J = 0; J < NB; ++J) P[I][J] = Pn[I][J];
         }
-        // tile total -> LDS (for the inclusive carry) and HBM (for successors)
-        S* gM = reinterpret_cast<S*>(p.aggM) + slot * (N * N);
-        S* gv = reinterpret_cast<S*>(p.aggv) + slot * N;
-        S* gi = reinterpret_cast<S*>(p.incl) + slot * N;
-        const unsigned tag = p.epoch << 2;
+        // tile total -> LDS (for the inclusive carry) and HBM (for successors, as tagged words)
+        constexpr int WS = TaggedWords<S>::per_scalar;
+        constexpr int AGG_WORDS = (N * N + N) * WS;
+        const unsigned tagA = (p.epoch << 2) | TILE_AGGREGATE;
+        const unsigned tagI = (p.epoch << 2) | TILE_INCLUSIVE;
+        const unsigned long long* aggSeq = p.aggW + (long long)b * p.tiles * AGG_WORDS;
+        const unsigned long long* inclSeq = p.inclW + (long long)b * p.tiles * (N * WS);
+        unsigned long long* mine = p.aggW + slot * AGG_WORDS;
 #pragma unroll
         for (int I = 0; I < NB; ++I) {
 #pragma unroll
@@ -266,27 +270,26 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     sT[(16 * I + Lay<S>::idx(g, v)) * LD + 16 * J + r] = P[I][J][v];
-                    if (t > 0) gM[(16 * I + Lay<S>::idx(g, v)) * N + 16 * J + r] = P[I][J][v];
+                    if (t > 0) TaggedWords<S>::put(mine, (16 * I + Lay<S>::idx(g, v)) * N + 16 * J + r, P[I][J][v], tagA);
                 }
             if (g == 0) {
                 sTv[16 * I + r] = vr[I];
-                if (t > 0) gv[16 * I + r] = vr[I];
+                if (t > 0) TaggedWords<S>::put(mine, N * N + 16 * I + r, vr[I], tagA);
             }
         }
-        if (t > 0) {
-            __threadfence();
-            if (lane == 0) flag_store(&p.flags[slot], tag | TILE_AGGREGATE);
-        }
 
-        // lane j inspects predecessor t-1-j; index -1 is the given initial state
+        // lane j inspects predecessor t-1-j (index -1 is the given initial state): inclusive carry
+        // known, total known, or nothing yet, judged by one word of each
         const int idx = t - 1 - lane;
         int k = -1;
         unsigned spins = 0;
         while (true) {
             unsigned st;
             if (idx >= 0) {
-                const unsigned f = flag_load(&p.flags[(long long)b * p.tiles + idx]);
-                st = ((f >> 2) == p.epoch) ? (f & 3u) : TILE_INVALID;
+                S dummy;
+                if (TaggedWords<S>::get(inclSeq + (long long)idx * (N * WS), 0, tagI, dummy)) st = TILE_INCLUSIVE;
+                else if (TaggedWords<S>::get(aggSeq + (long long)idx * AGG_WORDS, N * N, tagA, dummy)) st = TILE_AGGREGATE;
+                else st = TILE_INVALID;
             } else {
                 st = (idx == -1) ? TILE_INCLUSIVE : 3u;
             }
@@ -298,21 +301,20 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
                 if ((wait_mask & below) == 0ull) { k = first; break; }
             }
             if (++spins > kSpinLimit) break;
-            __builtin_amdgcn_s_sleep(2);
+            __builtin_amdgcn_s_sleep(1);
         }
 
         // carry in row layout yr[I] = y[16I + r], column layout yc[K][v] = y[16K + idx(g, v)]
         S yr[NB], yc[NB][4];
 #pragma unroll
         for (int I = 0; I < NB; ++I) yr[I] = S(0);
-        if (k < 0) {
-            if (lane == 0) atomicOr(p.status, 1u);
-        } else {
+        bool ok = k >= 0;
+        if (ok) {
             const int far = t - 1 - k;   // tile whose inclusive carry is known (-1: initial state)
             if (far >= 0) {
-                const S* pi = reinterpret_cast<const S*>(p.incl) + ((long long)b * p.tiles + far) * N;
 #pragma unroll
-                for (int I = 0; I < NB; ++I) yr[I] = coherent_load(pi + 16 * I + r);
+                for (int I = 0; I < NB; ++I)
+                    ok = tagged_get_wait<S>(inclSeq + (long long)far * (N * WS), 16 * I + r, tagI, yr[I]) && ok;
             } else if (p.y0) {
                 const S* y0b = reinterpret_cast<const S*>(p.y0) + (long long)b * N;
 #pragma unroll
@@ -322,21 +324,58 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
             for (int K = 0; K < NB; ++K)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], Lay<S>::idx(g, v));
-            // fold the totals of tiles far+1 .. t-1 forward
-#pragma unroll 1
-            for (int q = far + 1; q <= t - 1; ++q) {
-                const S* pM = reinterpret_cast<const S*>(p.aggM) + ((long long)b * p.tiles + q) * (N * N);
-                const S* pv = reinterpret_cast<const S*>(p.aggv) + ((long long)b * p.tiles + q) * N;
-                S ny[NB];
+            // fold the totals of tiles far+1 .. t-1 forward; the next total is requested before the
+            // current one is applied
+            S am[NB][NB][4], av[NB];
+            bool got = true;
+            auto fetch_total = [&](int q) {
+                const unsigned long long* src = aggSeq + (long long)q * AGG_WORDS;
+                got = true;
 #pragma unroll
                 for (int I = 0; I < NB; ++I) {
-                    S s = S(0);
 #pragma unroll
                     for (int K = 0; K < NB; ++K)
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
-                            s += coherent_load(pM + (16 * I + r) * N + 16 * K + Lay<S>::idx(g, v)) * yc[K][v];
-                    ny[I] = sum_groups<S>(s) + coherent_load(pv + 16 * I + r);
+                            got = TaggedWords<S>::get(src, (16 * I + r) * N + 16 * K + Lay<S>::idx(g, v), tagA, am[I][K][v]) && got;
+                    got = TaggedWords<S>::get(src, N * N + 16 * I + r, tagA, av[I]) && got;
+                }
+            };
+            if (far + 1 <= t - 1) fetch_total(far + 1);
+#pragma unroll 1
+            for (int q = far + 1; q <= t - 1; ++q) {
+                if (__ballot(!got) != 0ull) {
+                    // rare: part of this total was still in flight; wait for it word by word
+                    const unsigned long long* src = aggSeq + (long long)q * AGG_WORDS;
+#pragma unroll
+                    for (int I = 0; I < NB; ++I) {
+#pragma unroll
+                        for (int K = 0; K < NB; ++K)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                ok = tagged_get_wait<S>(src, (16 * I + r) * N + 16 * K + Lay<S>::idx(g, v), tagA, am[I][K][v]) && ok;
+                        ok = tagged_get_wait<S>(src, N * N + 16 * I + r, tagA, av[I]) && ok;
+                    }
+                }
+                S cm[NB][NB][4], cv[NB];
+#pragma unroll
+                for (int I = 0; I < NB; ++I) {
+                    cv[I] = av[I];
+#pragma unroll
+                    for (int K = 0; K < NB; ++K)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) cm[I][K][v] = am[I][K][v];
+                }
+                if (q + 1 <= t - 1) fetch_total(q + 1);
+                S ny[NB];
+#pragma unroll
+                for (int I = 0; I < NB; ++I) {
+                    S sacc = S(0);
+#pragma unroll
+                    for (int K = 0; K < NB; ++K)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) sacc += cm[I][K][v] * yc[K][v];
+                    ny[I] = sum_groups<S>(sacc) + cv[I];
                 }
 #pragma unroll
                 for (int I = 0; I < NB; ++I) yr[I] = ny[I];
@@ -346,18 +385,19 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
                     for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], Lay<S>::idx(g, v));
             }
         }
+        if (__ballot(!ok) != 0ull) {
+            if (lane == 0) atomicOr(p.status, 1u);
+        }
         // carry into LDS, inclusive carry of this tile = (tile total) applied to it
         if (g == 0) {
 #pragma unroll
             for (int I = 0; I < NB; ++I) sC[0][16 * I + r] = yr[I];
         }
         if (lane < N) {
-            S s = sTv[lane];
-            for (int q = 0; q < N; ++q) s += sT[lane * LD + q] * sC[0][q];
-            gi[lane] = s;
+            S sacc = sTv[lane];
+            for (int q = 0; q < N; ++q) sacc += sT[lane * LD + q] * sC[0][q];
+            TaggedWords<S>::put(p.inclW + slot * (N * WS), lane, sacc, tagI);
         }
-        __threadfence();
-        if (lane == 0) flag_store(&p.flags[slot], tag | TILE_INCLUSIVE);
     }
     __syncthreads();
 
