@@ -19,6 +19,7 @@ namespace {
 
 constexpr int kSlots = 256;          // ticket / error slots, one per scan launch between refills
 constexpr size_t kAlign = 256;
+constexpr int kMaxEvents = 24;      // timed launches between two host synchronisations
 
 thread_local std::string g_last_error;
 #ifdef DEER_SCAN_TIMING
@@ -96,14 +97,14 @@ Plan make_plan(const deer_config* c) {
         p.tile = scan_mfma_tile(c->dtype, c->n);
     } else {
         // positions per group of lanes (1, 2, 4 or 8): the longest serial run that still leaves
-        // enough tiles to fill the chip
+        // at least one tile per compute unit
         int W = env_int("DEER_SCAN_W", 8);
         if (W != 4 && W != 8) W = 8;
         if (64 / c->n < W) W = 4;
         p.W = W;
         int L = (c->dtype == DEER_F64 && c->n == 8) ? 4 : 8;   // fp64, n = 8: L = 8 would spill registers
         const int Lmax = L;
-        while (L > 1 && (long long)B * ((p.scan_T + scan_valu_tile(c->n, L, W) - 1) / scan_valu_tile(c->n, L, W)) < 512) L >>= 1;
+        while (L > 1 && (long long)B * ((p.scan_T + scan_valu_tile(c->n, L, W) - 1) / scan_valu_tile(c->n, L, W)) < 256) L >>= 1;
         L = env_int("DEER_SCAN_L", L);
         if (L != 1 && L != 2 && L != 4 && L != 8) L = Lmax;
         if (L > Lmax) L = Lmax;
@@ -139,11 +140,13 @@ struct deer_ctx {
     hipStream_t stream;
     char* ws;
     unsigned epoch;
-    void* h_err;            // pinned, 16 bytes
+    void* h_err;            // pinned, kSlots * 8 bytes
+    int batch;              // Newton iterations enqueued per host round trip
     bool profiling;
     deer_profile prof;
-    hipEvent_t ev[16];
-    int ev_kind[8];
+    hipEvent_t ev[2 * kMaxEvents];
+    int ev_kind[kMaxEvents];
+    int ev_iter[kMaxEvents];   // Newton iteration the launch belongs to (-1: always counted)
     int ev_used;
     std::string last_error;
 };
@@ -172,19 +175,22 @@ unsigned* ctl_status(deer_ctx* c) {
 }
 size_t ctl_bytes() { return align_up((size_t)kSlots * 4 + (size_t)kSlots * 8 + 16); }
 
-void prof_begin(deer_ctx* c, int kind) {
-    if (!c->profiling || c->ev_used >= 8) return;
+void prof_begin(deer_ctx* c, int kind, int iter = -1) {
+    if (!c->profiling || c->ev_used >= kMaxEvents) return;
     c->ev_kind[c->ev_used] = kind;
+    c->ev_iter[c->ev_used] = iter;
     (void)hipEventRecord(c->ev[2 * c->ev_used], c->stream);
 }
 void prof_end(deer_ctx* c) {
-    if (!c->profiling || c->ev_used >= 8) return;
+    if (!c->profiling || c->ev_used >= kMaxEvents) return;
     (void)hipEventRecord(c->ev[2 * c->ev_used + 1], c->stream);
     c->ev_used++;
 }
-// call after the stream has been synchronised
-void prof_collect(deer_ctx* c) {
+// Call after the stream has been synchronised.  Launches of Newton iterations >= iters_done were
+// enqueued ahead of the convergence test and returned at once: they are not counted.
+void prof_collect(deer_ctx* c, int iters_done = 1 << 30) {
     for (int i = 0; i < c->ev_used; ++i) {
+        if (c->ev_iter[i] >= iters_done) continue;
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, c->ev[2 * i], c->ev[2 * i + 1]) != hipSuccess) continue;
         switch (c->ev_kind[i]) {
@@ -200,7 +206,7 @@ void prof_collect(deer_ctx* c) {
 // One scan launch over the context's shapes.
 hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, void* out, const void* yold,
                     long long strideA, long long strideb, long long strideOut, int reverse, int slot, bool want_err,
-                    int delta = 0) {
+                    int delta = 0, Gate gate = Gate{nullptr, 0.0}, int iter = -1) {
     const deer_config& g = c->cfg;
     ScanParams p{};
     p.A = A; p.bv = bv; p.y0 = y0; p.out = out; p.yold = yold;
@@ -214,6 +220,7 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
     p.ticket = ctl_ticket(c, slot);
     p.err = want_err ? ctl_err(c, slot) : nullptr;
     p.status = ctl_status(c);
+    p.gate = gate;
 #ifdef DEER_SCAN_TIMING
     {
         static unsigned long long* dbg = nullptr;
@@ -222,7 +229,7 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
         g_timing = dbg;
     }
 #endif
-    prof_begin(c, KIND_SCAN);
+    prof_begin(c, KIND_SCAN, iter);
     hipError_t e = c->plan.mfma ? launch_scan_mfma(g.dtype, g.n, p, c->stream)
                                 : launch_scan_valu(g.dtype, g.n, p, c->stream);
     prof_end(c);
@@ -287,8 +294,11 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
     c->prof = deer_profile{};
     c->ev_used = 0;
     for (auto& e : c->ev) e = nullptr;
-    hipError_t e = hipHostMalloc(&c->h_err, 16, hipHostMallocDefault);
-    for (int i = 0; i < 16 && e == hipSuccess; ++i) e = hipEventCreate(&c->ev[i]);
+    hipError_t e = hipHostMalloc(&c->h_err, (size_t)kSlots * 8, hipHostMallocDefault);
+    for (int i = 0; i < 2 * kMaxEvents && e == hipSuccess; ++i) e = hipEventCreate(&c->ev[i]);
+    c->batch = env_int("DEER_BATCH", 4);
+    if (c->batch < 1) c->batch = 1;
+    if (c->batch > 8) c->batch = 8;
     if (e == hipSuccess) e = launch_fill_zero(c->ws + plan.off_ctl, ctl_bytes(), c->stream);
     // tagged words must not carry a valid tag by accident: epochs start at 1, so zeros never match
     if (e == hipSuccess)
@@ -331,52 +341,69 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
         HIPCHK(c, launch_pin_first(g.dtype, nxt, d_y0, g.B, g.T, g.n, c->stream));
     }
 
+    // Iteration k reads buf[k & 1] and writes buf[(k + 1) & 1].  Up to c->batch iterations are enqueued
+    // per host round trip; from the second one of a batch on, the kernels check the previous
+    // iteration's error on the device and return at once when it already met tol.
+    char* buf[2] = {cur, nxt};
     double err = 1e10;
     int it = 0;
     bool nonfinite = false;
-    while (err > tol && it < max_iter) {
-        const int slot = it % kSlots;
-        if (it > 0 && slot == 0) {
+    while (err > tol && it < max_iter && !nonfinite) {
+        const int slot0 = it % kSlots;
+        if (it > 0 && slot0 == 0) {
             st = zero_ctl(c);
             if (st != DEER_OK) return st;
         }
-        if (!ode) {
-            GruParams gp{d_theta, d_x, d_y0, cur, J, rhs, g.B, g.T, g.n, g.d};
-            prof_begin(c, KIND_FUNCEVAL);
-            HIPCHK(c, launch_gru_funceval(g.dtype, gp, c->stream));
-            prof_end(c);
-            HIPCHK(c, run_scan(c, J, rhs, d_y0, nxt, cur, (long long)(T * n * n), (long long)(T * n),
-                               (long long)(T * n), 0, slot, true));
-        } else {
-            char* Gbar = c->ws + c->plan.off_Gbar;
-            char* zbar = c->ws + c->plan.off_zbar;
-            MlpParams mp{d_theta, cur, J, rhs, g.B, g.T, g.n, g.mlp_width};
-            prof_begin(c, KIND_FUNCEVAL);
-            HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
-            prof_end(c);
-            OdeDiscParams dp{J, rhs, cur, Gbar, zbar, g.B, g.T, g.n, (g.t1 - g.t0) / (double)(g.T - 1)};
-            prof_begin(c, KIND_DISC);
-            HIPCHK(c, launch_ode_discretise(g.dtype, dp, c->stream));
-            prof_end(c);
-            // correction form: the scan solves delta_{i+1} = Gbar_i delta_i + res_i from delta_0 = 0 and
-            // writes y_next = y + delta at positions 1..T-1; position 0 stays y0
-            HIPCHK(c, run_scan(c, Gbar, zbar, nullptr, nxt + n * esz, cur + n * esz, (long long)((T - 1) * n * n),
-                               (long long)((T - 1) * n), (long long)(T * n), 0, slot, true, 1));
+        int nb = max_iter - it;
+        if (nb > c->batch) nb = c->batch;
+        if (nb > kSlots - slot0) nb = kSlots - slot0;
+        for (int j = 0; j < nb; ++j) {
+            const int k = it + j, slot = slot0 + j;
+            char* src = buf[k & 1];
+            char* dst = buf[(k + 1) & 1];
+            const Gate gate = (j == 0) ? Gate{nullptr, 0.0} : Gate{ctl_err(c, slot - 1), tol};
+            if (!ode) {
+                GruParams gp{d_theta, d_x, d_y0, src, J, rhs, g.B, g.T, g.n, g.d, gate};
+                prof_begin(c, KIND_FUNCEVAL, k);
+                HIPCHK(c, launch_gru_funceval(g.dtype, gp, c->stream));
+                prof_end(c);
+                HIPCHK(c, run_scan(c, J, rhs, d_y0, dst, src, (long long)(T * n * n), (long long)(T * n),
+                                   (long long)(T * n), 0, slot, true, 0, gate, k));
+            } else {
+                char* Gbar = c->ws + c->plan.off_Gbar;
+                char* zbar = c->ws + c->plan.off_zbar;
+                MlpParams mp{d_theta, src, J, rhs, g.B, g.T, g.n, g.mlp_width, gate};
+                prof_begin(c, KIND_FUNCEVAL, k);
+                HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
+                prof_end(c);
+                OdeDiscParams dp{J, rhs, src, Gbar, zbar, g.B, g.T, g.n, (g.t1 - g.t0) / (double)(g.T - 1), gate};
+                prof_begin(c, KIND_DISC, k);
+                HIPCHK(c, launch_ode_discretise(g.dtype, dp, c->stream));
+                prof_end(c);
+                // correction form: the scan solves delta_{i+1} = Gbar_i delta_i + res_i from delta_0 = 0 and
+                // writes y_next = y + delta at positions 1..T-1; position 0 stays y0
+                HIPCHK(c, run_scan(c, Gbar, zbar, nullptr, dst + n * esz, src + n * esz, (long long)((T - 1) * n * n),
+                                   (long long)((T - 1) * n), (long long)(T * n), 0, slot, true, 1, gate, k));
+            }
         }
-        HIPCHK(c, hipMemcpyAsync(c->h_err, ctl_err(c, slot), 8, hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipMemcpyAsync(c->h_err, ctl_err(c, slot0), (size_t)nb * 8, hipMemcpyDeviceToHost, c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
-        prof_collect(c);
-        if (g.dtype == DEER_F32) {
-            float f;
-            std::memcpy(&f, c->h_err, 4);
-            err = (double)f;
-        } else {
-            std::memcpy(&err, c->h_err, 8);
+        for (int j = 0; j < nb; ++j) {
+            const char* ep = reinterpret_cast<const char*>(c->h_err) + (size_t)j * 8;
+            if (g.dtype == DEER_F32) {
+                float f;
+                std::memcpy(&f, ep, 4);
+                err = (double)f;
+            } else {
+                std::memcpy(&err, ep, 8);
+            }
+            ++it;
+            if (!std::isfinite(err)) { nonfinite = true; break; }
+            if (!(err > tol)) break;
         }
-        char* tmp = cur; cur = nxt; nxt = tmp;
-        ++it;
-        if (!std::isfinite(err)) { nonfinite = true; break; }
+        prof_collect(c, it);
     }
+    cur = buf[it & 1];
     st = check_status(c);
     if (cur != reinterpret_cast<char*>(d_y)) {
         HIPCHK(c, hipMemcpyAsync(d_y, cur, ybytes, hipMemcpyDeviceToDevice, c->stream));
@@ -405,7 +432,7 @@ deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const v
     deer_status st = zero_ctl(c);
     if (st != DEER_OK) return st;
     // Jacobians at the given trajectory (the right-hand side output is not used)
-    GruParams gp{d_theta, d_x, d_y0, d_y, J, rhs, g.B, g.T, g.n, g.d};
+    GruParams gp{d_theta, d_x, d_y0, d_y, J, rhs, g.B, g.T, g.n, g.d, Gate{nullptr, 0.0}};
     prof_begin(c, KIND_FUNCEVAL);
     HIPCHK(c, launch_gru_funceval(g.dtype, gp, c->stream));
     prof_end(c);

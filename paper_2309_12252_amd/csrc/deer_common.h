@@ -6,6 +6,21 @@
 
 namespace deer {
 
+// Device-side iteration control: kernels of Newton iteration k are enqueued before the error of
+// iteration k-1 has been read back.  They look at that error themselves and return at once when it
+// already met the tolerance (or was never written, which reads as zero), so a batch of iterations
+// can be enqueued without a host round trip in between.
+struct Gate {
+    const void* prev_err;   // raw bits of the previous iteration's max|dy| (same scalar type), or nullptr
+    double tol;
+};
+template <typename S>
+__device__ __forceinline__ bool gate_closed(const Gate& g) {
+    if (!g.prev_err) return false;
+    const S e = *reinterpret_cast<const S*>(g.prev_err);
+    return (double)e <= g.tol;
+}
+
 // ---------------------------------------------------------------------------------------
 // Scan launch description.  One launch solves y_k = A_k y_{k-1} + b_k, k = 0..T-1 (scan
 // positions), for B sequences (Sec. 3.3 eq. 9-10, Sec. 3.4 eq. 11).  In reverse mode scan
@@ -32,6 +47,7 @@ struct ScanParams {
     unsigned* ticket;    // tile dispenser for this launch (zero on entry)
     void* err;           // max |out - yold| as raw bits of a non-negative scalar, or nullptr
     unsigned* status;    // set non-zero when a bounded wait ran out
+    Gate gate;
 #ifdef DEER_SCAN_TIMING
     unsigned long long* timing;   // development builds only: [B * tiles][8] timestamps of the tile's phases
 #endif
@@ -170,6 +186,7 @@ struct GruParams {
     const void* theta; const void* x; const void* y0; const void* y;  // y: current iterate [B,T,n]
     void* J; void* rhs;                                               // outputs [B,T,n,n], [B,T,n]
     int B, T, n, d;
+    Gate gate;
 };
 
 struct GruVjpParams {
@@ -186,6 +203,7 @@ struct MlpParams {
     const void* theta; const void* y;     // y [B,T,n]
     void* G; void* z;                     // outputs: G = -df/dy [B,T,n,n], z = f + G y [B,T,n]
     int B, T, n, width;
+    Gate gate;
 };
 
 struct OdeDiscParams {
@@ -194,6 +212,7 @@ struct OdeDiscParams {
     void* Gbar; void* res;                // [B,T-1,n,n] exp(-Gc dt), [B,T-1,n] residual of the iterate
     int B, T, n;
     double dt;
+    Gate gate;
 };
 
 hipError_t launch_scan_valu(int dtype, int n, const ScanParams& p, hipStream_t s);

@@ -81,6 +81,7 @@ __device__ __forceinline__ void row_gates(const RowWeights<S, N>& w, const S* sW
 
 template <typename S, int N>
 __global__ __launch_bounds__(kThreads) void gru_funceval_kernel(GruParams p) {
+    if (gate_closed<S>(p.gate)) return;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     S* sW = reinterpret_cast<S*>(smem_raw);
     const int tid = threadIdx.x;

@@ -27,6 +27,7 @@ __device__ __forceinline__ double tanh_(double a) { return tanh(a); }
 
 template <typename S, int N, int W>
 __global__ __launch_bounds__(kThreads) void mlp_funceval_kernel(MlpParams p) {
+    if (gate_closed<S>(p.gate)) return;
     static_assert(W % N == 0, "hidden width must be a multiple of the state size");
     constexpr int UPT = W / N;   // hidden units per thread
     constexpr int SPB = kThreads / N;
@@ -144,6 +145,7 @@ template <> struct SeriesTol<double> { static constexpr double v = 1e-19; };
 
 template <typename S, int N>
 __global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams p) {
+    if (gate_closed<S>(p.gate)) return;
     const long long nint = (long long)p.B * (p.T - 1);
     const long long q = (long long)blockIdx.x * kThreads + threadIdx.x;
     if (q >= nint) return;

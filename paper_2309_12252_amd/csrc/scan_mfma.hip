@@ -63,7 +63,7 @@ __device__ __forceinline__ S sum_groups(S v) {
 }
 
 template <typename S, int N, int LW, int WAVES, bool REV>
-__global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
+__global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) {
     constexpr int NB = N / 16;
     constexpr int LD = N + 1;   // LDS row stride of a wavefront total
     constexpr int TILE = LW * WAVES;
@@ -75,7 +75,12 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
     __shared__ S sT[N * LD];          // tile total
     __shared__ S sTv[N];
     __shared__ S sC[WAVES][N];        // carry entering each wavefront
+    constexpr int HOPS = (sizeof(S) == 4) ? 8 : 4;   // predecessor totals staged in LDS per round
+    __shared__ S sHop[HOPS][N * LD + N];
+    __shared__ int s_k;               // hops between this tile and the nearest known inclusive carry
+    __shared__ int s_ok;
 
+    if (gate_closed<S>(p.gate)) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -95,6 +100,8 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
     const S* __restrict__ oldb =
         p.yold ? reinterpret_cast<const S*>(p.yold) + (long long)b * p.strideOld : nullptr;
     const long long e0 = (long long)t * TILE + (long long)wave * LW;
+    const long long slot = (long long)b * p.tiles + t;
+    DEER_STAMP(p, slot, 0, tid == 0);
 
     // ---- 1a. load this wavefront's pairs ----
     S a[LW][NB][NB][4];   // a[i][I][K][v] = A_e[16I + r][16K + idx(g, v)]
@@ -151,6 +158,16 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
                     for (int v = 0; v < 4; ++v) a[i][I][K][v] = (I == K && r == Lay<S>::idx(g, v)) ? S(1) : S(0);
             }
         }
+    }
+
+    // the previous iterate at this wavefront's positions, requested now so that it is there for step 4
+    S yo[LW][NB];
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+        const long long e = e0 + i;
+#pragma unroll
+        for (int I = 0; I < NB; ++I)
+            yo[i][I] = (oldb && e < p.T && g == 0) ? oldb[(REV ? ((long long)p.T - 1 - e) : e) * N + 16 * I + r] : S(0);
     }
 
     // ---- 1b. serial composition: P <- A_e P (MFMA), vec <- A_e vec + b_e (VALU) ----
@@ -214,7 +231,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
     __syncthreads();
 
     // ---- 2. tile total (wavefront 0), 3. look-back ----
-    const long long slot = (long long)b * p.tiles + t;
+    DEER_STAMP(p, slot, 1, tid == 0);
     if (wave == 0) {
 #pragma unroll 1
         for (int w = 1; w < WAVES; ++w) {
@@ -278,6 +295,7 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
             }
         }
 
+        DEER_STAMP(p, slot, 2, lane == 0);
         // lane j inspects predecessor t-1-j (index -1 is the given initial state): inclusive carry
         // known, total known, or nothing yet, judged by one word of each
         const int idx = t - 1 - lane;
@@ -304,102 +322,112 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
             __builtin_amdgcn_s_sleep(1);
         }
 
-        // carry in row layout yr[I] = y[16I + r], column layout yc[K][v] = y[16K + idx(g, v)]
-        S yr[NB], yc[NB][4];
-#pragma unroll
-        for (int I = 0; I < NB; ++I) yr[I] = S(0);
+        DEER_STAMP(p, slot, 3, lane == 0);
+        if (lane == 0) { s_k = k; s_ok = 1; }
+    }
+    __syncthreads();
+
+    // ---- 3b. fold the totals of the k predecessors between the known inclusive carry and this tile.
+    // All wavefronts stage the totals into LDS (coalesced tagged words, HOPS tiles per round); wavefront
+    // 0 applies them in order, one matrix row per lane, with the running carry in sC[0].
+    {
+        constexpr int WS = TaggedWords<S>::per_scalar;
+        constexpr int AGG_WORDS = (N * N + N) * WS;
+        const unsigned tagA = (p.epoch << 2) | TILE_AGGREGATE;
+        const unsigned tagI = (p.epoch << 2) | TILE_INCLUSIVE;
+        const unsigned long long* aggSeq = p.aggW + (long long)b * p.tiles * AGG_WORDS;
+        const unsigned long long* inclSeq = p.inclW + (long long)b * p.tiles * (N * WS);
+        const int k = s_k;
+        const int far = t - 1 - k;   // tile whose inclusive carry is known (-1: the initial state)
         bool ok = k >= 0;
-        if (ok) {
-            const int far = t - 1 - k;   // tile whose inclusive carry is known (-1: initial state)
-            if (far >= 0) {
-#pragma unroll
-                for (int I = 0; I < NB; ++I)
-                    ok = tagged_get_wait<S>(inclSeq + (long long)far * (N * WS), 16 * I + r, tagI, yr[I]) && ok;
-            } else if (p.y0) {
-                const S* y0b = reinterpret_cast<const S*>(p.y0) + (long long)b * N;
-#pragma unroll
-                for (int I = 0; I < NB; ++I) yr[I] = y0b[16 * I + r];
+        if (wave == 0 && lane < N) {
+            S y = S(0);
+            if (ok) {
+                if (far >= 0) ok = tagged_get_wait<S>(inclSeq + (long long)far * (N * WS), lane, tagI, y);
+                else if (p.y0) y = reinterpret_cast<const S*>(p.y0)[(long long)b * N + lane];
             }
-#pragma unroll
-            for (int K = 0; K < NB; ++K)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], Lay<S>::idx(g, v));
-            // fold the totals of tiles far+1 .. t-1 forward; the next total is requested before the
-            // current one is applied
-            S am[NB][NB][4], av[NB];
+            sC[0][lane] = y;
+        }
+        for (int q0 = far + 1; k >= 0 && q0 <= t - 1; q0 += HOPS) {   // uniform: k, far and t are the same for every thread
+            const int nh = (t - q0 < HOPS) ? (t - q0) : HOPS;
+            // every lane requests all its words of all its tiles before looking at any of them
+            constexpr int TOT = N * N + N;
+            constexpr int PER = (TOT + 63) / 64;              // words per lane and tile
+            constexpr int HPW = (HOPS + WAVES - 1) / WAVES;   // tiles per wavefront and round
+            S vals[HPW][PER];
             bool got = true;
-            auto fetch_total = [&](int q) {
-                const unsigned long long* src = aggSeq + (long long)q * AGG_WORDS;
-                got = true;
 #pragma unroll
-                for (int I = 0; I < NB; ++I) {
+            for (int hh = 0; hh < HPW; ++hh) {
+                const int h = wave + hh * WAVES;
+                if (h < nh) {
+                    const unsigned long long* src = aggSeq + (long long)(q0 + h) * AGG_WORDS;
 #pragma unroll
-                    for (int K = 0; K < NB; ++K)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            got = TaggedWords<S>::get(src, (16 * I + r) * N + 16 * K + Lay<S>::idx(g, v), tagA, am[I][K][v]) && got;
-                    got = TaggedWords<S>::get(src, N * N + 16 * I + r, tagA, av[I]) && got;
-                }
-            };
-            if (far + 1 <= t - 1) fetch_total(far + 1);
-#pragma unroll 1
-            for (int q = far + 1; q <= t - 1; ++q) {
-                if (__ballot(!got) != 0ull) {
-                    // rare: part of this total was still in flight; wait for it word by word
-                    const unsigned long long* src = aggSeq + (long long)q * AGG_WORDS;
-#pragma unroll
-                    for (int I = 0; I < NB; ++I) {
-#pragma unroll
-                        for (int K = 0; K < NB; ++K)
-#pragma unroll
-                            for (int v = 0; v < 4; ++v)
-                                ok = tagged_get_wait<S>(src, (16 * I + r) * N + 16 * K + Lay<S>::idx(g, v), tagA, am[I][K][v]) && ok;
-                        ok = tagged_get_wait<S>(src, N * N + 16 * I + r, tagA, av[I]) && ok;
+                    for (int j = 0; j < PER; ++j) {
+                        const int e = lane + 64 * j;
+                        if (e < TOT) got = TaggedWords<S>::get(src, e, tagA, vals[hh][j]) && got;
                     }
                 }
-                S cm[NB][NB][4], cv[NB];
-#pragma unroll
-                for (int I = 0; I < NB; ++I) {
-                    cv[I] = av[I];
-#pragma unroll
-                    for (int K = 0; K < NB; ++K)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) cm[I][K][v] = am[I][K][v];
-                }
-                if (q + 1 <= t - 1) fetch_total(q + 1);
-                S ny[NB];
-#pragma unroll
-                for (int I = 0; I < NB; ++I) {
-                    S sacc = S(0);
-#pragma unroll
-                    for (int K = 0; K < NB; ++K)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) sacc += cm[I][K][v] * yc[K][v];
-                    ny[I] = sum_groups<S>(sacc) + cv[I];
-                }
-#pragma unroll
-                for (int I = 0; I < NB; ++I) yr[I] = ny[I];
-#pragma unroll
-                for (int K = 0; K < NB; ++K)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) yc[K][v] = __shfl(yr[K], Lay<S>::idx(g, v));
             }
-        }
-        if (__ballot(!ok) != 0ull) {
-            if (lane == 0) atomicOr(p.status, 1u);
-        }
-        // carry into LDS, inclusive carry of this tile = (tile total) applied to it
-        if (g == 0) {
+            if (__ballot(!got) != 0ull) {
+                // rare: part of a total was still in flight; wait for it word by word
 #pragma unroll
-            for (int I = 0; I < NB; ++I) sC[0][16 * I + r] = yr[I];
+                for (int hh = 0; hh < HPW; ++hh) {
+                    const int h = wave + hh * WAVES;
+                    if (h < nh) {
+                        const unsigned long long* src = aggSeq + (long long)(q0 + h) * AGG_WORDS;
+#pragma unroll
+                        for (int j = 0; j < PER; ++j) {
+                            const int e = lane + 64 * j;
+                            if (e < TOT) ok = tagged_get_wait<S>(src, e, tagA, vals[hh][j]) && ok;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int hh = 0; hh < HPW; ++hh) {
+                const int h = wave + hh * WAVES;
+                if (h < nh) {
+#pragma unroll
+                    for (int j = 0; j < PER; ++j) {
+                        const int e = lane + 64 * j;
+                        if (e < TOT) {
+                            const int dst = (e < N * N) ? ((e / N) * LD + (e % N)) : (N * LD + (e - N * N));
+                            sHop[h][dst] = vals[hh][j];
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            if (wave == 0) {
+                for (int h = 0; h < nh; ++h) {
+                    S acc = S(0);
+                    if (lane < N) {
+                        acc = sHop[h][N * LD + lane];
+#pragma unroll 8
+                        for (int q = 0; q < N; ++q) acc += sHop[h][lane * LD + q] * sC[0][q];
+                    }
+                    if (lane < N) sC[0][lane] = acc;
+                }
+            }
+            __syncthreads();
         }
-        if (lane < N) {
-            S sacc = sTv[lane];
-            for (int q = 0; q < N; ++q) sacc += sT[lane * LD + q] * sC[0][q];
-            TaggedWords<S>::put(p.inclW + slot * (N * WS), lane, sacc, tagI);
+        if (!ok) s_ok = 0;
+        if (wave == 0) {
+            DEER_STAMP(p, slot, 4, lane == 0);
+#ifdef DEER_SCAN_TIMING
+            if (p.timing && lane == 0) p.timing[slot * 8 + 7] = (unsigned long long)(k < 0 ? 0 : k);
+#endif
+            // inclusive carry of this tile = (tile total) applied to the carry
+            if (lane < N) {
+                S sacc = sTv[lane];
+                for (int q = 0; q < N; ++q) sacc += sT[lane * LD + q] * sC[0][q];
+                TaggedWords<S>::put(p.inclW + slot * (N * WS), lane, sacc, tagI);
+            }
+            DEER_STAMP(p, slot, 5, lane == 0);
         }
     }
     __syncthreads();
+    if (tid == 0 && s_ok == 0) atomicOr(p.status, 1u);
 
     // ---- 4. carry entering this wavefront, then the second walk over the resident pairs ----
     for (int w = 0; w < wave; ++w) {
@@ -437,10 +465,9 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
             for (int I = 0; I < NB; ++I) {
                 S wv = yr[I];
                 if (oldb) {
-                    const S yo = oldb[oi + 16 * I + r];
-                    const S dq = abs_or_inf<S>(p.delta ? yr[I] : yr[I] - yo);
+                    const S dq = abs_or_inf<S>(p.delta ? yr[I] : yr[I] - yo[i][I]);
                     emax = dq > emax ? dq : emax;
-                    if (p.delta) wv += yo;
+                    if (p.delta) wv += yo[i][I];
                 }
                 ob[oi + 16 * I + r] = wv;
             }
@@ -454,10 +481,11 @@ __global__ __launch_bounds__(64 * WAVES) void scan_mfma_kernel(ScanParams p) {
         emax = wave_max<S>(emax);
         if (lane == 0) err_atomic_max(p.err, emax);
     }
+    DEER_STAMP(p, slot, 6, tid == 0);
 }
 
 template <typename S, int N> struct MfmaShape;
-template <> struct MfmaShape<float, 16> { static constexpr int LW = 16, WAVES = 8; };
+template <> struct MfmaShape<float, 16> { static constexpr int LW = 16, WAVES = 4; };
 template <> struct MfmaShape<float, 32> { static constexpr int LW = 8, WAVES = 8; };
 template <> struct MfmaShape<double, 16> { static constexpr int LW = 8, WAVES = 8; };
 template <> struct MfmaShape<double, 32> { static constexpr int LW = 4, WAVES = 8; };

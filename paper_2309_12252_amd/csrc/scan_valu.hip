@@ -194,6 +194,7 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p) {
     __shared__ S sEv[W][N];
     __shared__ S sCarry[N];
 
+    if (gate_closed<S>(p.gate)) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -221,6 +222,13 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p) {
     S Ar[L][N], be[L];
 #pragma unroll
     for (int l = 0; l < L; ++l) load_row<S, N, REV>(Ab, bb, T, e0 + l, i, Ar[l], be[l]);
+    // the previous iterate at this group's positions, requested now so that it is there for step 5
+    S yo[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        const long long e = e0 + l;
+        yo[l] = (oldb && e < T) ? oldb[(REV ? (T - 1 - e) : e) * N + i] : S(0);
+    }
     S M[N], v;
 #pragma unroll
     for (int c = 0; c < N; ++c) M[c] = (c == i) ? S(1) : S(0);
@@ -361,6 +369,9 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p) {
             if (lane == 0) atomicOr(p.status, 1u);
         }
         DEER_STAMP(p, slot, 4, lane == 0);
+#ifdef DEER_SCAN_TIMING
+        if (p.timing && lane == 0) p.timing[slot * 8 + 7] = (unsigned long long)(k < 0 ? 0 : k);
+#endif
         if (group == 0) sCarry[i] = y;
         // inclusive carry of this tile: (tile total) applied to the carry
         if (group == W - 1) {
@@ -390,10 +401,9 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p) {
             const long long oi = (REV ? (T - 1 - e) : e) * N + i;
             S w = y;
             if (oldb) {
-                const S yo = oldb[oi];
-                const S dq = abs_or_inf<S>(p.delta ? y : y - yo);
+                const S dq = abs_or_inf<S>(p.delta ? y : y - yo[l]);
                 emax = dq > emax ? dq : emax;
-                if (p.delta) w += yo;
+                if (p.delta) w += yo[l];
             }
             ob[oi] = w;
         }
