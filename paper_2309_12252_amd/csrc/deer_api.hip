@@ -96,18 +96,29 @@ Plan make_plan(const deer_config* c) {
         p.L = 0;
         p.tile = scan_mfma_tile(c->dtype, c->n);
     } else {
-        // positions per group of lanes (1, 2, 4 or 8): the longest serial run that still leaves
-        // at least one tile per compute unit
-        int W = env_int("DEER_SCAN_W", 8);
-        if (W != 4 && W != 8) W = 8;
-        if (64 / c->n < W) W = 4;
+        // Positions per group of lanes.  Measured on MI355X: a tile lives for about (5 + 1.05 L)
+        // microseconds and the chip holds one tile per compute unit, so a launch takes
+        // ceil(tiles / 256) such rounds; longer serial runs amortise the per-tile look-back, and the
+        // longest one wins as soon as it still leaves a tile for half of the compute units.
+        // (fp64 keeps L <= 4 for n = 8 and <= 8 otherwise: registers.)
+        const int W = 8;
         p.W = W;
-        int L = (c->dtype == DEER_F64 && c->n == 8) ? 4 : 8;   // fp64, n = 8: L = 8 would spill registers
-        const int Lmax = L;
-        while (L > 1 && (long long)B * ((p.scan_T + scan_valu_tile(c->n, L, W) - 1) / scan_valu_tile(c->n, L, W)) < 256) L >>= 1;
-        L = env_int("DEER_SCAN_L", L);
-        if (L != 1 && L != 2 && L != 4 && L != 8) L = Lmax;
-        if (L > Lmax) L = Lmax;
+        static const int kL32[] = {1, 2, 4, 8, 10, 12, 16};
+        static const int kL64[] = {1, 2, 4, 8};
+        const int* cand = c->dtype == DEER_F32 ? kL32 : kL64;
+        int ncand = c->dtype == DEER_F32 ? 7 : ((c->n == 8) ? 3 : 4);
+        int L = cand[0];
+        double best = 1e300;
+        for (int q = 0; q < ncand; ++q) {
+            const long long tile = scan_valu_tile(c->n, cand[q], W);
+            const long long tiles = (long long)B * ((p.scan_T + tile - 1) / tile);
+            double est = (double)((tiles + 255) / 256) * (5.0 + 1.05 * cand[q]);
+            if (q == ncand - 1 && tiles >= 128) est = 0.0;
+            if (est < best) { best = est; L = cand[q]; }
+        }
+        const int forced = env_int("DEER_SCAN_L", 0);
+        for (int q = 0; q < ncand; ++q)
+            if (forced == cand[q]) L = forced;
         p.L = L;
         p.tile = scan_valu_tile(c->n, p.L, W);
     }

@@ -15,7 +15,8 @@
 // Structure of one tile (WAVES wavefronts, LW scan positions per wavefront):
 //   1. each wavefront loads its LW pairs into registers (A-operand layout) and composes them
 //      serially: P <- A_t P on the matrix cores, v <- A_t v + b_t on the vector ALUs;
-//   2. wavefront totals meet in LDS; wavefront 0 composes them into the tile total;
+//   2. wavefront totals meet in LDS and are composed into the tile total by a tree over the
+//      wavefronts (log2(WAVES) rounds of one product each);
 //   3. decoupled look-back across tiles through HBM as in the small-n kernel (tile index from an
 //      atomic ticket, totals and inclusive carries published as self-validating tagged words,
 //      window of 64 predecessors, forward fold of totals from the nearest known inclusive carry with
@@ -72,10 +73,12 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
     __shared__ unsigned s_ticket;
     __shared__ S sM[WAVES][N * LD];   // wavefront totals, row-major, padded rows
     __shared__ S sv[WAVES][N];
+    __shared__ S sP[WAVES / 2][N * LD];   // partial totals handed between the rounds of the tree
+    __shared__ S sPv[WAVES / 2][N];
     __shared__ S sT[N * LD];          // tile total
     __shared__ S sTv[N];
     __shared__ S sC[WAVES][N];        // carry entering each wavefront
-    constexpr int HOPS = (sizeof(S) == 4) ? 8 : 4;   // predecessor totals staged in LDS per round
+    constexpr int HOPS = (sizeof(S) == 4) ? 8 : 2;   // predecessor totals staged in LDS per round
     __shared__ S sHop[HOPS][N * LD + N];
     __shared__ int s_k;               // hops between this tile and the nearest known inclusive carry
     __shared__ int s_ok;
@@ -104,70 +107,64 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
     DEER_STAMP(p, slot, 0, tid == 0);
 
     // ---- 1a. load this wavefront's pairs ----
+    // Branch free on purpose (positions past the end read the last valid one and are then replaced by
+    // the identity pair): with straight-line code the compiler keeps the loads in order and lets the
+    // first products start while later positions are still in flight.
     S a[LW][NB][NB][4];   // a[i][I][K][v] = A_e[16I + r][16K + idx(g, v)]
     S bel[LW][NB];        // bel[i][I]     = b_e[16I + r]
+    S yo[LW][NB];         // previous iterate at the same positions (for step 4)
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
         const long long e = e0 + i;
-        if (e < p.T) {
-            if constexpr (!REV) {
-                const S* Ae = Ab + e * (N * N);
+        const bool past = e >= p.T;
+        const long long ec = past ? (long long)p.T - 1 : e;
+        const long long vi = (REV ? ((long long)p.T - 1 - ec) : ec) * N;
+        if constexpr (!REV) {
+            const S* Ae = Ab + ec * (N * N);
 #pragma unroll
-                for (int I = 0; I < NB; ++I)
+            for (int I = 0; I < NB; ++I)
 #pragma unroll
-                    for (int K = 0; K < NB; ++K) {
-                        if constexpr (Lay<S>::contiguous) {
-                            vload<S, 4>(a[i][I][K], Ae + (16 * I + r) * N + 16 * K + 4 * g);
-                        } else {
+                for (int K = 0; K < NB; ++K) {
+                    if constexpr (Lay<S>::contiguous) {
+                        vload<S, 4>(a[i][I][K], Ae + (16 * I + r) * N + 16 * K + 4 * g);
+                    } else {
 #pragma unroll
-                            for (int v = 0; v < 4; ++v)
-                                a[i][I][K][v] = Ae[(16 * I + r) * N + 16 * K + Lay<S>::idx(g, v)];
-                        }
+                        for (int v = 0; v < 4; ++v)
+                            a[i][I][K][v] = Ae[(16 * I + r) * N + 16 * K + Lay<S>::idx(g, v)];
                     }
-#pragma unroll
-                for (int I = 0; I < NB; ++I) bel[i][I] = bb[e * N + 16 * I + r];
-            } else {
-                // dual operator: vector index T-1-e, transpose of the matrix stored at index T-e
-#pragma unroll
-                for (int I = 0; I < NB; ++I) bel[i][I] = bb[((long long)p.T - 1 - e) * N + 16 * I + r];
-                if (e == 0) {
-#pragma unroll
-                    for (int I = 0; I < NB; ++I)
-#pragma unroll
-                        for (int K = 0; K < NB; ++K)
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) a[i][I][K][v] = S(0);
-                } else {
-                    const S* Ae = Ab + ((long long)p.T - e) * (N * N);
-#pragma unroll
-                    for (int I = 0; I < NB; ++I)
-#pragma unroll
-                        for (int K = 0; K < NB; ++K)
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) a[i][I][K][v] = Ae[(16 * K + Lay<S>::idx(g, v)) * N + 16 * I + r];
                 }
-            }
         } else {
-            // past the end of the sequence: the identity pair
+            // dual operator: transpose of the matrix stored at index T-e; position 0 has none (zero):
+            // any valid matrix is read and dropped
+            const long long em = ec == 0 ? 1 : ec;
+            const S* Ae = Ab + ((long long)p.T - em) * (N * N);
 #pragma unroll
-            for (int I = 0; I < NB; ++I) {
-                bel[i][I] = S(0);
+            for (int I = 0; I < NB; ++I)
 #pragma unroll
                 for (int K = 0; K < NB; ++K)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) a[i][I][K][v] = (I == K && r == Lay<S>::idx(g, v)) ? S(1) : S(0);
-            }
+                    for (int v = 0; v < 4; ++v) {
+                        const S u = (p.T > 1) ? Ae[(16 * K + Lay<S>::idx(g, v)) * N + 16 * I + r] : S(0);
+                        a[i][I][K][v] = (ec == 0) ? S(0) : u;
+                    }
+        }
+#pragma unroll
+        for (int I = 0; I < NB; ++I) {
+            const S bv = bb[vi + 16 * I + r];
+            bel[i][I] = past ? S(0) : bv;
+#pragma unroll
+            for (int K = 0; K < NB; ++K)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    a[i][I][K][v] = past ? ((I == K && r == Lay<S>::idx(g, v)) ? S(1) : S(0)) : a[i][I][K][v];
         }
     }
-
-    // the previous iterate at this wavefront's positions, requested now so that it is there for step 4
-    S yo[LW][NB];
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
-        const long long e = e0 + i;
+        const long long e = (e0 + i < p.T) ? e0 + i : (long long)p.T - 1;
+        const S* src = oldb ? oldb : bb;   // branch free: without a previous iterate the value is unused
 #pragma unroll
-        for (int I = 0; I < NB; ++I)
-            yo[i][I] = (oldb && e < p.T && g == 0) ? oldb[(REV ? ((long long)p.T - 1 - e) : e) * N + 16 * I + r] : S(0);
+        for (int I = 0; I < NB; ++I) yo[i][I] = src[(REV ? ((long long)p.T - 1 - e) : e) * N + 16 * I + r];
     }
 
     // ---- 1b. serial composition: P <- A_e P (MFMA), vec <- A_e vec + b_e (VALU) ----
@@ -230,18 +227,38 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
     }
     __syncthreads();
 
-    // ---- 2. tile total (wavefront 0), 3. look-back ----
+    // ---- 2. tile total by a tree over the wavefronts: in round `stride` wavefront w (a multiple of
+    // 2*stride) composes the partial total that starts at w + stride (left factor, read from LDS in
+    // A-operand layout) with its own (right factor, still in its accumulators), so no partial total is
+    // ever re-loaded into accumulator layout.  log2(WAVES) rounds instead of WAVES - 1 serial products.
     DEER_STAMP(p, slot, 1, tid == 0);
-    if (wave == 0) {
 #pragma unroll 1
-        for (int w = 1; w < WAVES; ++w) {
+    for (int stride = 1; stride < WAVES; stride <<= 1) {
+        if (stride > 1) {
+            // partial totals of the previous round that are a left factor in this round
+            if ((wave % (2 * stride)) == stride) {
+#pragma unroll
+                for (int I = 0; I < NB; ++I) {
+#pragma unroll
+                    for (int J = 0; J < NB; ++J)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) sP[wave / 2][(16 * I + Lay<S>::idx(g, v)) * LD + 16 * J + r] = P[I][J][v];
+                    if (g == 0) sPv[wave / 2][16 * I + r] = vr[I];
+                }
+            }
+            __syncthreads();
+        }
+        if ((wave % (2 * stride)) == 0) {
+            const int src = wave + stride;
+            const S* Ml = (stride == 1) ? sM[src] : sP[src / 2];
+            const S* vl = (stride == 1) ? sv[src] : sPv[src / 2];
             S am[NB][NB][4];
 #pragma unroll
             for (int I = 0; I < NB; ++I)
 #pragma unroll
                 for (int K = 0; K < NB; ++K)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) am[I][K][v] = sM[w][(16 * I + r) * LD + 16 * K + Lay<S>::idx(g, v)];
+                    for (int v = 0; v < 4; ++v) am[I][K][v] = Ml[(16 * I + r) * LD + 16 * K + Lay<S>::idx(g, v)];
             Acc Pn[NB][NB];
 #pragma unroll
             for (int I = 0; I < NB; ++I)
@@ -256,12 +273,12 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
                 }
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
-                S s = S(0);
+                S sacc = S(0);
 #pragma unroll
                 for (int K = 0; K < NB; ++K)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) s += am[I][K][v] * vc[K][v];
-                vr[I] = sum_groups<S>(s) + sv[w][16 * I + r];
+                    for (int v = 0; v < 4; ++v) sacc += am[I][K][v] * vc[K][v];
+                vr[I] = sum_groups<S>(sacc) + vl[16 * I + r];
             }
 #pragma unroll
             for (int K = 0; K < NB; ++K)
@@ -272,6 +289,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
 #pragma unroll
                 for (int J = 0; J < NB; ++J) P[I][J] = Pn[I][J];
         }
+    }
+
+    // ---- 3. look-back (wavefront 0 now holds the tile total) ----
+    if (wave == 0) {
         // tile total -> LDS (for the inclusive carry) and HBM (for successors, as tagged words)
         constexpr int WS = TaggedWords<S>::per_scalar;
         constexpr int AGG_WORDS = (N * N + N) * WS;

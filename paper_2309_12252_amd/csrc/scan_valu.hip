@@ -129,29 +129,32 @@ __device__ __forceinline__ S group_matvec(const S* Lr, S add, S y) {
 
 // Row i of the matrix at scan position e of one sequence and entry i of its vector.
 // Reverse mode: vector index T-1-e, matrix = transpose of the one stored at index T-e, zero for e = 0.
+// Branch free on purpose (positions past the end read the last valid one and are then replaced by the
+// identity pair): with straight-line code the compiler keeps the loads in order and lets the first
+// products start while later positions are still in flight.
 template <typename S, int N, bool REV>
 __device__ __forceinline__ void load_row(const S* __restrict__ Ab, const S* __restrict__ bb, long long T,
                                          long long e, int i, S* Lr, S& bi) {
-    if (e >= T) {   // past the end: the identity pair
-#pragma unroll
-        for (int s = 0; s < N; ++s) Lr[s] = (s == i) ? S(1) : S(0);
-        bi = S(0);
-        return;
-    }
+    const bool past = e >= T;
+    const long long ec = past ? T - 1 : e;
+    S row[N], bv;
     if constexpr (!REV) {
-        vload<S, N>(Lr, Ab + e * (N * N) + i * N);
-        bi = bb[e * N + i];
+        vload<S, N>(row, Ab + ec * (N * N) + i * N);
+        bv = bb[ec * N + i];
     } else {
-        bi = bb[(T - 1 - e) * N + i];
-        if (e == 0) {
+        bv = bb[(T - 1 - ec) * N + i];
+        const long long em = ec == 0 ? 1 : ec;   // position 0 has no matrix; any valid one is read and dropped
+        const S* mat = Ab + (T - em) * (N * N);
 #pragma unroll
-            for (int s = 0; s < N; ++s) Lr[s] = S(0);
-        } else {
-            const S* mat = Ab + (T - e) * (N * N);
+        for (int s = 0; s < N; ++s) row[s] = (T > 1) ? mat[s * N + i] : S(0);
+        if (ec == 0) {
 #pragma unroll
-            for (int s = 0; s < N; ++s) Lr[s] = mat[s * N + i];
+            for (int s = 0; s < N; ++s) row[s] = S(0);
         }
     }
+#pragma unroll
+    for (int s = 0; s < N; ++s) Lr[s] = past ? ((s == i) ? S(1) : S(0)) : row[s];
+    bi = past ? S(0) : bv;
 }
 
 // Inclusive log-step scan over the groups of a wavefront.  (M | v): this group's pair, lane i holds
@@ -226,8 +229,9 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p) {
     S yo[L];
 #pragma unroll
     for (int l = 0; l < L; ++l) {
-        const long long e = e0 + l;
-        yo[l] = (oldb && e < T) ? oldb[(REV ? (T - 1 - e) : e) * N + i] : S(0);
+        const long long e = (e0 + l < T) ? e0 + l : T - 1;
+        const S* src = oldb ? oldb : bb;   // branch free: without a previous iterate the value is unused
+        yo[l] = src[(REV ? (T - 1 - e) : e) * N + i];
     }
     S M[N], v;
 #pragma unroll
@@ -427,7 +431,7 @@ hipError_t launch_nlw(const ScanParams& p, hipStream_t s) {
 
 template <typename S, int N, int L>
 hipError_t launch_nl(const ScanParams& p, hipStream_t s) {
-    return p.W == 4 ? launch_nlw<S, N, L, 4>(p, s) : launch_nlw<S, N, L, 8>(p, s);
+    return launch_nlw<S, N, L, 8>(p, s);
 }
 
 template <typename S, int N>
@@ -437,6 +441,9 @@ hipError_t launch_n(const ScanParams& p, hipStream_t s) {
         case 2: return launch_nl<S, N, 2>(p, s);
         case 4: return launch_nl<S, N, 4>(p, s);
         case 8: return launch_nl<S, N, 8>(p, s);
+        case 10: if constexpr (sizeof(S) == 4) return launch_nl<S, N, 10>(p, s); else return hipErrorInvalidValue;
+        case 12: if constexpr (sizeof(S) == 4) return launch_nl<S, N, 12>(p, s); else return hipErrorInvalidValue;
+        case 16: if constexpr (sizeof(S) == 4) return launch_nl<S, N, 16>(p, s); else return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }
@@ -457,7 +464,7 @@ hipError_t launch_s(int n, const ScanParams& p, hipStream_t s) {
 int scan_valu_tile(int n, int L, int W) { return W * (64 / n) * L; }
 
 hipError_t launch_scan_valu(int dtype, int n, const ScanParams& p, hipStream_t s) {
-    if (p.W != 4 && p.W != 8) return hipErrorInvalidValue;
+    if (p.W != 8) return hipErrorInvalidValue;
     return dtype == 0 ? launch_s<float>(n, p, s) : launch_s<double>(n, p, s);
 }
 
