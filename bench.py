@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration (1-based), default 2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scan-stream", type=str, default="",
+                    help="n,B,T: time deer_linrec_solve alone on a random stream of that shape and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -59,6 +61,27 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4,
                           "launches": 5}))
+        return
+    if args.scan_stream:
+        n, B, T = [int(v) for v in args.scan_stream.split(",")]
+        A, b, y0 = inputs.scan_inputs(1, B, T, n)
+        cfg = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, B, T, n, d=1)
+        sctx = deer.DeerContext(cfg, device=dev)
+        dA, db, dy0 = [torch.from_numpy(a).to(dev) for a in (A, b, y0)]
+        out = torch.empty((B, T, n), dtype=torch.float32, device=dev)
+        for _ in range(3):
+            sctx.linrec_solve(dA, db, dy0, out=out)
+        sctx.set_profiling(True)
+        for _ in range(args.steps):
+            sctx.linrec_solve(dA, db, dy0, out=out)
+        prof = sctx.profile()
+        ms = prof["scan_ms"] / max(1, prof["scan_launches"])
+        nbytes = 4 * (n * n + 2 * n) * B * T   # J, b in; y out (no previous iterate in this entry point)
+        print(json.dumps({"scan_stream": {"n": n, "B": B, "T": T}, "avg_launch_ms": ms, "algorithmic_bytes": nbytes,
+                          "achieved_GBs": nbytes / (ms * 1e-3) / 1e9, "frac_of_8TBs": nbytes / (ms * 1e-3) / 8e12,
+                          "algorithmic_flops": (2 * n ** 3 + 4 * n * n) * B * T,
+                          "achieved_TFLOPs": (2 * n ** 3 + 4 * n * n) * B * T / (ms * 1e-3) / 1e12}))
+        sctx.close()
         return
     w = inputs.config(args.config)
     ctx = deer.context_for(w, device=dev)

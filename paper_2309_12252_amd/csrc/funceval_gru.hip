@@ -101,15 +101,49 @@ __global__ __launch_bounds__(kThreads) void gru_funceval_kernel(GruParams p) {
     __syncthreads();
 
     const long long total = (long long)p.B * p.T;
-    for (long long s = (long long)blockIdx.x * SPB + sg; s < total; s += (long long)gridDim.x * SPB) {
+    const long long stride = (long long)gridDim.x * SPB;
+    // Software pipeline: the operands of the next position are requested before the current one is
+    // computed, so the loop does not expose a memory round trip per position.
+    S hn[N], hin = S(0), xn[kMaxD];
+    auto fetch = [&](long long s) {
         const long long bi = s / p.T;
         const int ti = (int)(s - bi * p.T);
         const S* hp = (ti == 0) ? (y0 + bi * N) : (y + (s - 1) * N);
-        S h[N];
-        vload<S, N>(h, hp);
-        const S hi = hp[i];
+        vload<S, N>(hn, hp);
+        hin = hp[i];
+#pragma unroll
+        for (int k = 0; k < kMaxD; ++k) xn[k] = (k < d) ? x[s * d + k] : S(0);
+    };
+    long long s = (long long)blockIdx.x * SPB + sg;
+    if (s < total) fetch(s);
+    for (; s < total; s += stride) {
+        S h[N], xv[kMaxD];
+#pragma unroll
+        for (int j = 0; j < N; ++j) h[j] = hn[j];
+#pragma unroll
+        for (int k = 0; k < kMaxD; ++k) xv[k] = xn[k];
+        const S hi = hin;
+        if (s + stride < total) fetch(s + stride);
+        S ar = w.br, az = w.bz, ac = w.bc, q = w.bh;
+#pragma unroll
+        for (int k = 0; k < kMaxD; ++k) {
+            if (k < d) {
+                ar += sW[(i)*ds + k] * xv[k];
+                az += sW[(N + i) * ds + k] * xv[k];
+                ac += sW[(2 * N + i) * ds + k] * xv[k];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            ar += w.Ur[j] * h[j];
+            az += w.Uz[j] * h[j];
+            q += w.Uc[j] * h[j];
+        }
         Gates<S, N> g;
-        row_gates<S, N>(w, sW, ds, d, i, h, x + s * d, g);
+        g.r = sigmoid_(ar);
+        g.z = sigmoid_(az);
+        g.q = q;
+        g.c = tanh_(ac + g.r * q);
         const S f = (S(1) - g.z) * g.c + g.z * hi;
         const S pz = (hi - g.c) * g.z * (S(1) - g.z);
         const S sc = (S(1) - g.z) * (S(1) - g.c * g.c);
@@ -282,7 +316,7 @@ hipError_t launch_fe(const GruParams& p, hipStream_t s) {
     constexpr int SPB = kThreads / N;
     const long long total = (long long)p.B * p.T;
     long long blocks = (total + SPB - 1) / SPB;
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks > 256 * 8) blocks = 256 * 8;
     if (blocks < 1) blocks = 1;
     const size_t shmem = (size_t)3 * N * (p.d | 1) * sizeof(S);
     hipLaunchKernelGGL((gru_funceval_kernel<S, N>), dim3((unsigned)blocks), dim3(kThreads), shmem, s, p);

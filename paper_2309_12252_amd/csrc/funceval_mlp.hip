@@ -11,9 +11,10 @@
 //     arithmetic but keeps fp32 rounding relative to the (small) correction instead of to y.
 //   pin_first_kernel: y[b,0,:] = y0[b,:] (the first grid point is the initial condition).
 //
-// mlp_funceval work split: the n threads of a grid point sit in consecutive lanes; thread j owns
-// column j of J and the hidden units j, j+n, j+2n, ... of both layers; activations are shared
-// with cross-lane shuffles.  Weights are read with wave-uniform addresses (scalar loads).
+// mlp_funceval work split (generic kernel: fp64, n < 8): the n threads of a grid point sit in
+// consecutive lanes; thread j owns column j of J and the hidden units j, j+n, j+2n, ... of both
+// layers; activations are shared with cross-lane shuffles.  Weights are read with wave-uniform
+// addresses (scalar loads).  fp32 with n = 8 runs on the matrix cores (mlp_funceval_mfma_kernel).
 #include "deer_common.h"
 
 namespace deer {
@@ -120,6 +121,156 @@ __global__ __launch_bounds__(kThreads) void mlp_funceval_kernel(MlpParams p) {
             for (int o = 1; o < N; o <<= 1) part += __shfl_xor(part, o);
             const S fi = __shfl(fj, base + i);
             if (live && j == i) z[sc * N + i] = fi + part;
+        }
+    }
+}
+
+// ---- MLP field on the matrix cores (fp32, n = 8, hidden width a multiple of 16) ----
+//
+// A wavefront handles 16 grid points at a time.  All products run on v_mfma_f32_16x16x4f32; matrices
+// flow from one stage to the next in accumulator layout, which is directly a valid B operand (lane
+// group g, register v = row 4g + v of a 16-row block), so no stage needs a transpose:
+//   Z1 = W1 Y + b1 (columns = the 16 points), A1 = tanh Z1, D1 = 1 - A1^2
+//   Z2 = W2 A1 + b2,                         A2 = tanh Z2, D2 = 1 - A2^2
+//   f  = W3 A2 + b3
+//   J y = W3 D2 W2 D1 (W1 y): the same chain applied to D1 * (Z1 - b1)        -> z = f - J y
+//   J   = W3 D2 W2 D1 W1 for every point: the columns of the right factor are (point, j) pairs, 16 at a
+//         time (two points x 8 columns); D1 and D2 of the right point reach a lane by one shuffle each.
+// Rows 8..15 of the W3 products are padding (n = 8).
+typedef float mlp_acc __attribute__((ext_vector_type(4)));
+
+template <int WB>   // hidden width / 16
+__global__ __launch_bounds__(kThreads) void mlp_funceval_mfma_kernel(MlpParams p) {
+    if (gate_closed<float>(p.gate)) return;
+    constexpr int W = 16 * WB, N = 8;
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 4, c = lane & 15;
+    const float* __restrict__ th = reinterpret_cast<const float*>(p.theta);
+    const float* __restrict__ W1 = th;
+    const float* __restrict__ b1 = W1 + W * N;
+    const float* __restrict__ W2 = b1 + W;
+    const float* __restrict__ b2 = W2 + W * W;
+    const float* __restrict__ W3 = b2 + W;
+    const float* __restrict__ b3 = W3 + N * W;
+    const float* __restrict__ y = reinterpret_cast<const float*>(p.y);
+    float* __restrict__ G = reinterpret_cast<float*>(p.G);
+    float* __restrict__ z = reinterpret_cast<float*>(p.z);
+
+    // weights in operand layouts (c doubles as the row index r of A operands)
+    float w1a[WB][2];          // A operand of stage 1: W1[16I + c][4kk + g]
+    mlp_acc b1c[WB], b2c[WB];  // biases in accumulator layout: b[16I + 4g + v]
+    float w2a[WB][WB][4];      // A operand: W2[16I + c][16K + 4g + v]
+    float w3a[WB][4];          // A operand: W3[c][16K + 4g + v], rows >= 8 are zero
+    mlp_acc b3c;
+    float w1b[WB][4];          // W1[16K + 4g + v][c & 7], the column factor of D1 W1
+#pragma unroll
+    for (int I = 0; I < WB; ++I) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) w1a[I][kk] = W1[(16 * I + c) * N + 4 * kk + g];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            b1c[I][v] = b1[16 * I + 4 * g + v];
+            b2c[I][v] = b2[16 * I + 4 * g + v];
+            w1b[I][v] = W1[(16 * I + 4 * g + v) * N + (c & 7)];
+            w3a[I][v] = (c < N) ? W3[c * W + 16 * I + 4 * g + v] : 0.0f;
+        }
+#pragma unroll
+        for (int K = 0; K < WB; ++K)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) w2a[I][K][v] = W2[(16 * I + c) * W + 16 * K + 4 * g + v];
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) b3c[v] = (4 * g + v < N) ? b3[4 * g + v] : 0.0f;
+
+    const long long total = (long long)p.B * p.T;
+    const long long nblk = (total + 15) / 16;
+    const long long wave0 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
+    for (long long blk = wave0; blk < nblk; blk += nwaves) {
+        const long long s0 = blk * 16;
+        const long long sc = (s0 + c < total) ? s0 + c : total - 1;
+        float yb[2];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) yb[kk] = y[sc * N + 4 * kk + g];
+
+        mlp_acc a1[WB], d1[WB], q1[WB];
+#pragma unroll
+        for (int I = 0; I < WB; ++I) {
+            mlp_acc acc = b1c[I];
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1a[I][kk], yb[kk], acc, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float t = tanhf(acc[v]);
+                a1[I][v] = t;
+                d1[I][v] = 1.0f - t * t;
+                q1[I][v] = d1[I][v] * (acc[v] - b1c[I][v]);
+            }
+        }
+        mlp_acc a2[WB], d2[WB], q2[WB];
+#pragma unroll
+        for (int I = 0; I < WB; ++I) {
+            mlp_acc acc = b2c[I], accq = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int K = 0; K < WB; ++K)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w2a[I][K][v], a1[K][v], acc, 0, 0, 0);
+                    accq = __builtin_amdgcn_mfma_f32_16x16x4f32(w2a[I][K][v], q1[K][v], accq, 0, 0, 0);
+                }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float t = tanhf(acc[v]);
+                a2[I][v] = t;
+                d2[I][v] = 1.0f - t * t;
+                q2[I][v] = d2[I][v] * accq[v];
+            }
+        }
+        {
+            mlp_acc f = b3c, jy = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int K = 0; K < WB; ++K)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    f = __builtin_amdgcn_mfma_f32_16x16x4f32(w3a[K][v], a2[K][v], f, 0, 0, 0);
+                    jy = __builtin_amdgcn_mfma_f32_16x16x4f32(w3a[K][v], q2[K][v], jy, 0, 0, 0);
+                }
+            // z = f + G y = f - J y at point s0 + c, rows 4g + v < 8
+            if (g < 2 && s0 + c < total) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) z[(s0 + c) * N + 4 * g + v] = f[v] - jy[v];
+            }
+        }
+        // Jacobians, two points (16 columns) per round
+#pragma unroll 2
+        for (int cb = 0; cb < 8; ++cb) {
+            const int src = (lane & 48) + 2 * cb + ((lane >> 3) & 1);   // lane holding D of this column's point
+            float u1[WB][4];
+#pragma unroll
+            for (int K = 0; K < WB; ++K)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) u1[K][v] = __shfl(d1[K][v], src) * w1b[K][v];
+            float u2[WB][4];
+#pragma unroll
+            for (int I = 0; I < WB; ++I) {
+                mlp_acc t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int K = 0; K < WB; ++K)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) t = __builtin_amdgcn_mfma_f32_16x16x4f32(w2a[I][K][v], u1[K][v], t, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) u2[I][v] = __shfl(d2[I][v], src) * t[v];
+            }
+            mlp_acc jb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int K = 0; K < WB; ++K)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) jb = __builtin_amdgcn_mfma_f32_16x16x4f32(w3a[K][v], u2[K][v], jb, 0, 0, 0);
+            const long long sp = s0 + 2 * cb + (c >> 3);
+            if (g < 2 && sp < total) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) G[(sp * N + 4 * g + v) * N + (c & 7)] = -jb[v];
+            }
         }
     }
 }
@@ -314,6 +465,17 @@ hipError_t launch_disc_s(const OdeDiscParams& p, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s) {
+    if (dtype == 0 && p.n == 8 && (p.width == 16 || p.width == 32 || p.width == 64)) {
+        const long long nblk = ((long long)p.B * p.T + 15) / 16;   // one wavefront per 16 grid points
+        long long blocks = (nblk + 3) / 4;
+        if (blocks > 256 * 4) blocks = 256 * 4;
+        if (blocks < 1) blocks = 1;
+        dim3 grid((unsigned)blocks), blk(kThreads);
+        if (p.width == 16) hipLaunchKernelGGL((mlp_funceval_mfma_kernel<1>), grid, blk, 0, s, p);
+        else if (p.width == 32) hipLaunchKernelGGL((mlp_funceval_mfma_kernel<2>), grid, blk, 0, s, p);
+        else hipLaunchKernelGGL((mlp_funceval_mfma_kernel<4>), grid, blk, 0, s, p);
+        return hipGetLastError();
+    }
     return dtype == 0 ? launch_mlp_s<float>(p, s) : launch_mlp_s<double>(p, s);
 }
 

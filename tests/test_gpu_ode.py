@@ -19,7 +19,7 @@ def check(w, dtype, tol=None):
     assert d <= TOL_ABS[dtype], (w.name, dtype, d)
 
 
-@pytest.mark.parametrize("n,width", [(2, 16), (4, 32), (8, 32), (8, 64)])
+@pytest.mark.parametrize("n,width", [(2, 16), (4, 32), (8, 16), (8, 32), (8, 64)])
 @pytest.mark.parametrize("dtype", [deer.DEER_F32, deer.DEER_F64])
 def test_small_ode_shapes(n, width, dtype):
     tol = 1e-4 if dtype == deer.DEER_F32 else 1e-7
