@@ -2,11 +2,11 @@
 
 A step is one deer_eval(): the whole Newton solve (every iteration: f + Jacobian at all positions,
 the blocked scan, the convergence test) over one batch of synthetic input that is already resident
-in HBM.  The workload is the benchmark's configs[1]: GRU, d=4, n=8, T=10,000, B=16, fp32.
+in HBM.  The default workload is the second benchmark configuration: GRU, d=4, n=8, T=10,000, B=16, fp32.
 
-Prints one JSON line: whole-job throughput in sequence-steps/s, the roofline fraction of the dominant
-kernel (the scan; duration from HIP events on the library's stream) and the CPU oracle's throughput on
-the host cores as a reported baseline.
+Prints one JSON line: whole-job throughput in sequence-steps/s, the roofline entry of the kernel that
+takes most of the step (duration from HIP events on the library's stream) and the CPU oracle's
+throughput on the host cores as a reported baseline.
 """
 import argparse
 import json
@@ -23,10 +23,71 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
-def scan_algorithmic_bytes_per_step(n, esz=4):
+VALU_F32_PEAK_TFLOPS = 157.3   # published fp32 vector peak (256 CUs x 128 lanes x 2 (packed) x 2 (fma) x 2.4 GHz)
+MFMA_F32_PEAK_TFLOPS = 157.3   # published dense fp32 matrix peak
+
+
+def scan_bytes_per_position(n, esz=4):
     # read J (n*n) and the right-hand side (n), write y (n), read the previous iterate (n) for the
     # fused convergence maximum
     return esz * (n * n + 3 * n)
+
+
+def scan_flops_per_position(n):
+    # composition of the pair into the running product (2 n^3 + 2 n^2) and the second walk (2 n^2)
+    return 2 * n ** 3 + 4 * n * n
+
+
+def fused_flops_per_position(n, d):
+    # GRU gates 2*3n(n+d), Jacobian rows 2*4n^2 (three scaled rows + diagonal), right-hand side 2n^2,
+    # about 30 n elementwise operations, and the scan's own work
+    return 6 * n * (n + d) + 8 * n * n + 2 * n * n + 30 * n + scan_flops_per_position(n)
+
+
+def mlp_flops_per_point(n, width):
+    # f: 2(wn + w^2 + nw); J y for the right-hand side: the same chain again; J = W3 D2 W2 D1 W1: 2 w^2 n + 2 n w n
+    # plus the two diagonal scalings (2 w n each)
+    chain = 2 * (width * n + width * width + n * width)
+    return 2 * chain + 2 * width * width * n + 2 * n * width * n + 4 * width * n
+
+
+def dominant_roofline(kind, ms, w):
+    """Roofline entry of the kernel that takes most of a step (durations from HIP events)."""
+    from paper_2309_12252_amd import inputs
+    ode = w.cell == inputs.CELL_MLP_ODE
+    positions = w.B * ((w.T - 1) if (ode and kind != "funceval") else w.T)
+    sec = ms * 1e-3
+    if kind == "fused":
+        fl = fused_flops_per_position(w.n, w.d) * positions
+        a = fl / sec / 1e12
+        return {"bound": "alu", "achieved": round(a, 2), "peak": VALU_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(a / VALU_F32_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": "GRU cell + affine scan in one launch (n=%d)" % w.n, "avg_launch_us": round(1e3 * ms, 2),
+                "algorithmic_flops_per_launch": fl,
+                "hbm_bytes_per_launch": 4 * (2 * w.n + w.d) * positions}
+    if kind == "scan" and w.n >= 16:
+        fl = scan_flops_per_position(w.n) * positions
+        a = fl / sec / 1e12
+        return {"bound": "mfma", "achieved": round(a, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(a / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None, "kernel": "affine scan (n=%d)" % w.n,
+                "avg_launch_us": round(1e3 * ms, 2), "algorithmic_flops_per_launch": fl,
+                "hbm_bytes_per_launch": scan_bytes_per_position(w.n) * positions}
+    if kind == "funceval" and ode and w.n == 8:
+        fl = mlp_flops_per_point(w.n, w.mlp_width) * positions
+        a = fl / sec / 1e12
+        return {"bound": "mfma", "achieved": round(a, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(a / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None, "kernel": "MLP field + Jacobian",
+                "avg_launch_us": round(1e3 * ms, 2), "algorithmic_flops_per_launch": fl}
+    if kind == "scan":
+        nbytes = scan_bytes_per_position(w.n) * positions
+    elif kind == "discretise":
+        nbytes = 4 * (2 * w.n * w.n + 3 * w.n) * positions    # G, z, y in; Gbar, residual out
+    else:
+        nbytes = 4 * (w.n * w.n + 2 * w.n + w.d) * positions   # GRU cell: y, x in; J, rhs out
+    a = nbytes / sec / 1e9
+    return {"bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(a / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "%s (n=%d)" % (kind, w.n),
+            "avg_launch_us": round(1e3 * ms, 2), "algorithmic_bytes_per_launch": nbytes}
 
 
 def main():
@@ -111,18 +172,13 @@ def main():
     torch.cuda.synchronize()
     prof = ctx.profile()
     ctx.set_profiling(False)
-    scan_ms = prof["scan_ms"] / max(1, prof["scan_launches"])
-    scan_T = w.T - 1 if w.cell == inputs.CELL_MLP_ODE else w.T
-    alg_bytes = scan_algorithmic_bytes_per_step(w.n) * w.B * scan_T
-    achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "scan_traffic.json")
+    per_launch = {k: prof[k + "_ms"] / max(1, prof[k + "_launches"]) for k in ("funceval", "discretise", "scan", "fused")}
+    totals = {k: prof[k + "_ms"] for k in per_launch}
+    dominant = max(totals, key=totals.get)
+    roofline = dominant_roofline(dominant, per_launch[dominant], w)
+    tpath = os.path.join(ROOT, "profiles", "kernel_traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(w.name)
-    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "kernel": "affine scan (n=%d)" % w.n, "avg_launch_us": round(1e3 * scan_ms, 2),
-                "algorithmic_bytes_per_launch": alg_bytes}
+        roofline["traffic"] = json.load(open(tpath)).get(w.name, {}).get(dominant)
 
     out = {"metric": "DEER sequence-steps/s (B*T/s), forward eval to convergence", "value": value,
            "unit": "sequence-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -131,10 +187,7 @@ def main():
            "config": {"workload": w.name, "cell": "gru" if w.cell == inputs.CELL_GRU else "mlp_ode", "B": w.B,
                       "T": w.T, "n": w.n, "d": w.d, "tol": w.tol, "max_iter": w.max_iter,
                       "newton_iterations": iters, "converged": bool(conv)},
-           "kernels_ms_per_launch": {
-               "funceval": prof["funceval_ms"] / max(1, prof["funceval_launches"]),
-               "discretise": prof["discretise_ms"] / max(1, prof["discretise_launches"]),
-               "scan": scan_ms},
+           "kernels_ms_per_launch": per_launch,
            "roofline": roofline}
 
     if not args.no_cpu_baseline:

@@ -77,6 +77,7 @@ typedef struct {
     double discretise_ms; int64_t discretise_launches; /* ODE only: exp(-G dt), phi1                 */
     double scan_ms;       int64_t scan_launches;       /* inverse linear operator (+ fused max|dy|)  */
     double vjp_ms;        int64_t vjp_launches;        /* GRU VJP + parameter-gradient reduction     */
+    double fused_ms;      int64_t fused_launches;      /* GRU, n <= 8: cell + scan + max|dy| in one   */
 } deer_profile;
 
 /* Number of parameters in the flat theta of this configuration (layouts above); 0 if invalid. */

@@ -36,6 +36,8 @@ struct Plan {
     int L;               // positions per lane group (VALU scan)
     int W;               // wavefronts per tile (VALU scan)
     bool mfma;
+    bool fused;          // GRU with n <= 8: Newton steps run the scan with the cell evaluated in place
+    int fused_L, fused_W, fused_tiles;
     int vjp_blocks;
     // byte offsets into the workspace
     size_t off_J, off_rhs, off_ybuf, off_Gbar, off_zbar, off_aggW, off_inclW, off_ctl, off_partial, total;
@@ -124,6 +126,32 @@ Plan make_plan(const deer_config* c) {
     }
     p.tiles = (p.scan_T + p.tile - 1) / p.tile;
     if (p.tiles < 1) p.tiles = 1;
+    p.fused = false;
+    p.fused_tiles = 0;
+    if (!ode && !p.mfma && c->d <= 8 && env_int("DEER_FUSED", 1) != 0) {
+        // The fused step spends more time per position on arithmetic and none on loading matrices:
+        // shorter serial runs than the plain scan, so that more tiles are in flight.
+        static const int kLf[] = {1, 2, 4, 8, 16};
+        const int ncand = c->dtype == DEER_F32 ? 5 : ((c->n == 8) ? 3 : 4);
+        int L = kLf[0];
+        double best = 1e300;
+        for (int q = 0; q < ncand; ++q) {
+            const long long tile = scan_valu_tile(c->n, kLf[q], p.W);
+            const long long tiles = (long long)B * ((p.scan_T + tile - 1) / tile);
+            const double est = (double)((tiles + 255) / 256) * (5.0 + 1.6 * kLf[q]);
+            if (est < best) { best = est; L = kLf[q]; }
+        }
+        const int forced = env_int("DEER_FUSED_L", 0);
+        if (forced > 0) L = forced;
+        p.fused_W = env_int("DEER_FUSED_W", 8);
+        if (scan_gru_fused_supported(c->n, c->d, L)) {
+            p.fused = true;
+            p.fused_L = L;
+            const int tile = scan_valu_tile(c->n, L, p.fused_W);
+            p.fused_tiles = (p.scan_T + tile - 1) / tile;
+            if (p.fused_tiles < 1) p.fused_tiles = 1;
+        }
+    }
     p.vjp_blocks = c->cell == DEER_CELL_GRU ? gru_vjp_blocks(c->n, (long long)B * T) : 0;
 
     size_t off = 0;
@@ -133,7 +161,7 @@ Plan make_plan(const deer_config* c) {
     p.off_ybuf = take(B * T * n * p.esz);
     p.off_Gbar = take(ode ? B * (T - 1) * n * n * p.esz : 0);
     p.off_zbar = take(ode ? B * (T - 1) * n * p.esz : 0);
-    const size_t nt = B * (size_t)p.tiles;
+    const size_t nt = B * (size_t)(p.tiles > p.fused_tiles ? p.tiles : p.fused_tiles);
     // published tile totals and carries: one 64-bit tagged word per 32 bits of payload
     p.off_aggW = take(nt * (n * n + n) * (p.esz / 4) * 8);
     p.off_inclW = take(nt * n * (p.esz / 4) * 8);
@@ -151,8 +179,9 @@ struct deer_ctx {
     hipStream_t stream;
     char* ws;
     unsigned epoch;
-    void* h_err;            // pinned, kSlots * 8 bytes
-    int batch;              // Newton iterations enqueued per host round trip
+    void* h_err;            // pinned: kSlots * 8 bytes of error words, then the status word
+    int batch;              // Newton iterations enqueued per host round trip when nothing better is known
+    int last_iters;         // iterations the previous deer_eval() took (0: none yet)
     bool profiling;
     deer_profile prof;
     hipEvent_t ev[2 * kMaxEvents];
@@ -164,7 +193,7 @@ struct deer_ctx {
 
 namespace {
 
-enum { KIND_FUNCEVAL = 0, KIND_DISC = 1, KIND_SCAN = 2, KIND_VJP = 3 };
+enum { KIND_FUNCEVAL = 0, KIND_DISC = 1, KIND_SCAN = 2, KIND_VJP = 3, KIND_FUSED = 4 };
 
 deer_status fail(deer_ctx* ctx, deer_status st, const std::string& msg) {
     if (ctx) ctx->last_error = msg;
@@ -208,6 +237,7 @@ void prof_collect(deer_ctx* c, int iters_done = 1 << 30) {
             case KIND_FUNCEVAL: c->prof.funceval_ms += ms; c->prof.funceval_launches++; break;
             case KIND_DISC: c->prof.discretise_ms += ms; c->prof.discretise_launches++; break;
             case KIND_SCAN: c->prof.scan_ms += ms; c->prof.scan_launches++; break;
+            case KIND_FUSED: c->prof.fused_ms += ms; c->prof.fused_launches++; break;
             default: c->prof.vjp_ms += ms; c->prof.vjp_launches++; break;
         }
     }
@@ -217,7 +247,8 @@ void prof_collect(deer_ctx* c, int iters_done = 1 << 30) {
 // One scan launch over the context's shapes.
 hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, void* out, const void* yold,
                     long long strideA, long long strideb, long long strideOut, int reverse, int slot, bool want_err,
-                    int delta = 0, Gate gate = Gate{nullptr, 0.0}, int iter = -1) {
+                    int delta = 0, Gate gate = Gate{nullptr, 0.0}, int iter = -1, const void* fused_theta = nullptr,
+                    const void* fused_x = nullptr) {
     const deer_config& g = c->cfg;
     ScanParams p{};
     p.A = A; p.bv = bv; p.y0 = y0; p.out = out; p.yold = yold;
@@ -240,9 +271,17 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
         g_timing = dbg;
     }
 #endif
-    prof_begin(c, KIND_SCAN, iter);
-    hipError_t e = c->plan.mfma ? launch_scan_mfma(g.dtype, g.n, p, c->stream)
-                                : launch_scan_valu(g.dtype, g.n, p, c->stream);
+    hipError_t e;
+    if (fused_theta) {
+        p.L = c->plan.fused_L;
+        p.W = c->plan.fused_W;
+        p.tiles = c->plan.fused_tiles;
+        prof_begin(c, KIND_FUSED, iter);
+        e = launch_scan_gru_fused(g.dtype, g.n, p, fused_theta, fused_x, g.d, c->stream);
+    } else {
+        prof_begin(c, KIND_SCAN, iter);
+        e = c->plan.mfma ? launch_scan_mfma(g.dtype, g.n, p, c->stream) : launch_scan_valu(g.dtype, g.n, p, c->stream);
+    }
     prof_end(c);
     return e;
 }
@@ -305,9 +344,10 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
     c->prof = deer_profile{};
     c->ev_used = 0;
     for (auto& e : c->ev) e = nullptr;
-    hipError_t e = hipHostMalloc(&c->h_err, (size_t)kSlots * 8, hipHostMallocDefault);
+    hipError_t e = hipHostMalloc(&c->h_err, (size_t)kSlots * 8 + 8, hipHostMallocDefault);
     for (int i = 0; i < 2 * kMaxEvents && e == hipSuccess; ++i) e = hipEventCreate(&c->ev[i]);
     c->batch = env_int("DEER_BATCH", 4);
+    c->last_iters = 0;
     if (c->batch < 1) c->batch = 1;
     if (c->batch > 8) c->batch = 8;
     if (e == hipSuccess) e = launch_fill_zero(c->ws + plan.off_ctl, ctl_bytes(), c->stream);
@@ -340,40 +380,62 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
     const size_t ybytes = B * T * n * esz;
     char* J = c->ws + c->plan.off_J;
     char* rhs = c->ws + c->plan.off_rhs;
-    char* cur = c->ws + c->plan.off_ybuf;   // current iterate
-    char* nxt = reinterpret_cast<char*>(d_y);
 
-    deer_status st = zero_ctl(c);
-    if (st != DEER_OK) return st;
-    if (d_y_guess) HIPCHK(c, hipMemcpyAsync(cur, d_y_guess, ybytes, hipMemcpyDeviceToDevice, c->stream));
-    else HIPCHK(c, launch_fill_zero(cur, align_up(ybytes), c->stream));
+    // Iteration k reads buf[k & 1] and writes buf[(k + 1) & 1].  The buffers are ordered so that the
+    // iterate expected to be the last one (same count as the previous call on this context) lands in d_y
+    // without a final copy.
+    const int expect = c->last_iters > 0 ? c->last_iters : 1;
+    char* buf[2];
+    buf[expect & 1] = reinterpret_cast<char*>(d_y);
+    buf[(expect + 1) & 1] = c->ws + c->plan.off_ybuf;
+
+    deer_status st = DEER_OK;
+    if (d_y_guess) {
+        st = zero_ctl(c);
+        if (st != DEER_OK) return st;
+        if (d_y_guess != buf[0])
+            HIPCHK(c, hipMemcpyAsync(buf[0], d_y_guess, ybytes, hipMemcpyDeviceToDevice, c->stream));
+    } else {
+        if (c->epoch == 0) {   // the epoch counter wrapped: forget everything published so far
+            HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_aggW, c->plan.off_ctl - c->plan.off_aggW, c->stream));
+        }
+        HIPCHK(c, launch_fill_zero2(c->ws + c->plan.off_ctl, ctl_bytes(), buf[0], ybytes, c->stream));
+    }
     if (ode) {
-        HIPCHK(c, launch_pin_first(g.dtype, cur, d_y0, g.B, g.T, g.n, c->stream));
-        HIPCHK(c, launch_pin_first(g.dtype, nxt, d_y0, g.B, g.T, g.n, c->stream));
+        HIPCHK(c, launch_pin_first(g.dtype, buf[0], d_y0, g.B, g.T, g.n, c->stream));
+        HIPCHK(c, launch_pin_first(g.dtype, buf[1], d_y0, g.B, g.T, g.n, c->stream));
     }
 
-    // Iteration k reads buf[k & 1] and writes buf[(k + 1) & 1].  Up to c->batch iterations are enqueued
-    // per host round trip; from the second one of a batch on, the kernels check the previous
-    // iteration's error on the device and return at once when it already met tol.
-    char* buf[2] = {cur, nxt};
+    // Up to nb iterations are enqueued per host round trip; from the second one of a batch on, the
+    // kernels check the previous iteration's error on the device and return at once when it already
+    // met tol.  The first batch is as long as the previous call's iteration count (a solver called
+    // again on similar input converges in about as many steps), later ones are short.
     double err = 1e10;
     int it = 0;
     bool nonfinite = false;
+    unsigned status = 0;
     while (err > tol && it < max_iter && !nonfinite) {
         const int slot0 = it % kSlots;
         if (it > 0 && slot0 == 0) {
             st = zero_ctl(c);
             if (st != DEER_OK) return st;
         }
+        int want = c->batch;
+        if (it == 0 && c->last_iters > 0) want = c->last_iters < 8 ? c->last_iters : 8;
+        if (it > 0 && c->last_iters > 0) want = 2;
         int nb = max_iter - it;
-        if (nb > c->batch) nb = c->batch;
+        if (nb > want) nb = want;
         if (nb > kSlots - slot0) nb = kSlots - slot0;
         for (int j = 0; j < nb; ++j) {
             const int k = it + j, slot = slot0 + j;
             char* src = buf[k & 1];
             char* dst = buf[(k + 1) & 1];
             const Gate gate = (j == 0) ? Gate{nullptr, 0.0} : Gate{ctl_err(c, slot - 1), tol};
-            if (!ode) {
+            if (c->plan.fused) {
+                // cell and scan in one launch; the matrices stay in registers
+                HIPCHK(c, run_scan(c, nullptr, nullptr, d_y0, dst, src, 0, 0, (long long)(T * n), 0, slot, true, 0, gate,
+                                   k, d_theta, d_x));
+            } else if (!ode) {
                 GruParams gp{d_theta, d_x, d_y0, src, J, rhs, g.B, g.T, g.n, g.d, gate};
                 prof_begin(c, KIND_FUNCEVAL, k);
                 HIPCHK(c, launch_gru_funceval(g.dtype, gp, c->stream));
@@ -397,10 +459,14 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
                                    (long long)((T - 1) * n), (long long)(T * n), 0, slot, true, 1, gate, k));
             }
         }
-        HIPCHK(c, hipMemcpyAsync(c->h_err, ctl_err(c, slot0), (size_t)nb * 8, hipMemcpyDeviceToHost, c->stream));
+        // error words of the batch and the status word come back with one synchronisation
+        char* h = reinterpret_cast<char*>(c->h_err);
+        HIPCHK(c, hipMemcpyAsync(h, ctl_err(c, slot0), (size_t)nb * 8, hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipMemcpyAsync(h + (size_t)kSlots * 8, ctl_status(c), 4, hipMemcpyDeviceToHost, c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
+        std::memcpy(&status, h + (size_t)kSlots * 8, 4);
         for (int j = 0; j < nb; ++j) {
-            const char* ep = reinterpret_cast<const char*>(c->h_err) + (size_t)j * 8;
+            const char* ep = h + (size_t)j * 8;
             if (g.dtype == DEER_F32) {
                 float f;
                 std::memcpy(&f, ep, 4);
@@ -413,13 +479,15 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
             if (!(err > tol)) break;
         }
         prof_collect(c, it);
+        if (status != 0) break;
     }
-    cur = buf[it & 1];
-    st = check_status(c);
-    if (cur != reinterpret_cast<char*>(d_y)) {
-        HIPCHK(c, hipMemcpyAsync(d_y, cur, ybytes, hipMemcpyDeviceToDevice, c->stream));
+    if (it > 0) c->last_iters = it;
+    char* fin = buf[it & 1];
+    if (fin != reinterpret_cast<char*>(d_y)) {
+        HIPCHK(c, hipMemcpyAsync(d_y, fin, ybytes, hipMemcpyDeviceToDevice, c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
     }
+    if (status != 0) st = fail(c, DEER_ERR_HIP, "scan kernel: a tile waited too long for its predecessors");
     *iters = it;
     *final_err = err;
     *converged = (err <= tol) ? 1 : 0;

@@ -218,6 +218,10 @@ struct OdeDiscParams {
 hipError_t launch_scan_valu(int dtype, int n, const ScanParams& p, hipStream_t s);
 hipError_t launch_scan_mfma(int dtype, int n, const ScanParams& p, hipStream_t s);
 int scan_valu_tile(int n, int L, int W);   // scan positions per tile
+// scan with the GRU cell evaluated in place of the loads (forward, n <= 8, d <= 8); p.A / p.bv unused
+bool scan_gru_fused_supported(int n, int d, int L);
+hipError_t launch_scan_gru_fused(int dtype, int n, const ScanParams& p, const void* theta, const void* x, int d,
+                                 hipStream_t s);
 int scan_mfma_tile(int dtype, int n);
 hipError_t launch_gru_funceval(int dtype, const GruParams& p, hipStream_t s);
 hipError_t launch_gru_vjp(int dtype, const GruVjpParams& p, hipStream_t s);
@@ -225,6 +229,7 @@ int gru_vjp_blocks(int n, long long steps);
 hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s);
 hipError_t launch_ode_discretise(int dtype, const OdeDiscParams& p, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_fill_zero2(void* a, size_t abytes, void* b, size_t bbytes, hipStream_t s);
 hipError_t launch_pin_first(int dtype, void* y, const void* y0, int B, int T, int n, hipStream_t s);
 
 }  // namespace deer

@@ -418,6 +418,23 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, s
     for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < n16; q += (size_t)gridDim.x * 256) p[q] = zero;
 }
 
+// zero two ranges in one launch: a (16-byte aligned, n16a uint4) and b (4-byte aligned, nwb words)
+__global__ __launch_bounds__(256) void fill_zero2_kernel(uint4* __restrict__ a, size_t n16a, unsigned* __restrict__ b,
+                                                         size_t nwb) {
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    const size_t stride = (size_t)gridDim.x * 256;
+    const size_t first = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (size_t q = first; q < n16a; q += stride) a[q] = zero;
+    size_t head = ((16 - (reinterpret_cast<uintptr_t>(b) & 15)) & 15) / 4;   // words in front of the aligned body
+    if (head > nwb) head = nwb;
+    const size_t body = (nwb - head) / 4;
+    uint4* bb = reinterpret_cast<uint4*>(b + head);
+    for (size_t q = first; q < body; q += stride) bb[q] = zero;
+    if (first < head) b[first] = 0u;
+    const size_t tail0 = head + 4 * body;
+    if (tail0 + first < nwb) b[tail0 + first] = 0u;   // fewer than 4 words
+}
+
 template <typename S, int N, int W>
 hipError_t launch_mlp_nw(const MlpParams& p, hipStream_t s) {
     constexpr int SPB = kThreads / N;
@@ -490,6 +507,18 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
     size_t blocks = (n16 + 255) / 256;
     if (blocks > 1024) blocks = 1024;
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<uint4*>(p), n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_zero2(void* a, size_t abytes, void* b, size_t bbytes, hipStream_t s) {
+    // a: 16-byte aligned, abytes a multiple of 16; b: 4-byte aligned, bbytes a multiple of 4
+    const size_t n16 = abytes / 16, nw = bbytes / 4;
+    size_t most = n16 > nw / 4 ? n16 : nw / 4;
+    size_t blocks = (most + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(fill_zero2_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<uint4*>(a), n16,
+                       reinterpret_cast<unsigned*>(b), nw);
     return hipGetLastError();
 }
 

@@ -1,0 +1,596 @@
+// Kernel template of the single-pass scan for small state sizes (n <= 8) and its DPP helpers.
+// Included by the translation units that instantiate it: the plain scan (pairs read from memory)
+// and the scan with the GRU cell evaluated in place of the loads.
+#pragma once
+#include "deer_common.h"
+
+namespace deer {
+
+namespace {
+
+// ---- DPP helpers ----
+template <int CTRL, int BANK_MASK, bool BOUND>
+__device__ __forceinline__ float dpp(float old, float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(x), CTRL, 0xf, BANK_MASK, BOUND));
+}
+template <int CTRL, int BANK_MASK, bool BOUND>
+__device__ __forceinline__ double dpp(double old, double x) {
+    const long long u = __double_as_longlong(x), o = __double_as_longlong(old);
+    const int lo = __builtin_amdgcn_update_dpp((int)(o & 0xffffffffll), (int)(u & 0xffffffffll), CTRL, 0xf, BANK_MASK, BOUND);
+    const int hi = __builtin_amdgcn_update_dpp((int)(o >> 32), (int)(u >> 32), CTRL, 0xf, BANK_MASK, BOUND);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+// broadcast of lane q of every quad
+template <int Q, typename S>
+__device__ __forceinline__ S quad_bcast(S x) { return dpp<0x55 * Q, 0xf, true>(S(0), x); }
+
+// For n = 8 a group is two quads.  mirror(x) reverses the group (lane i gets the value of lane 7 - i),
+// so every lane sees the other quad's four values next to its own quad's.  Broadcasting lane k of
+// the own quad of x gives entry 4*hi + k of the group (hi = 1 in the upper quad); broadcasting lane
+// 3 - k of the own quad of mirror(x) gives entry 4*(1 - hi) + k.  A dot product of a register row with
+// the group's values thus takes the row SWIZZLED: slot s holds column s ^ (4*hi), i.e. the halves of
+// the row are swapped in the lanes of the upper quad.  Every left factor below is kept in that
+// form (for n < 8 the swizzle is the identity).
+template <typename S, int N>
+__device__ __forceinline__ S mirror(S x) {
+    if constexpr (N == 8) return dpp<0x141, 0xf, true>(S(0), x);
+    else return x;
+}
+// column held by slot s of a swizzled row in lane i of the group
+template <int N>
+__device__ __forceinline__ int swz_col(int s, int i) {
+    if constexpr (N == 8) return s ^ (i & 4);
+    else return s;
+}
+template <typename S, int N>
+__device__ __forceinline__ void swizzle_row(const S* nat, S* out, int i) {
+    if constexpr (N == 8) {
+        const bool hi = (i & 4) != 0;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) out[s] = hi ? nat[s ^ 4] : nat[s];
+    } else {
+#pragma unroll
+        for (int s = 0; s < N; ++s) out[s] = nat[s];
+    }
+}
+// N scalars of a row-major matrix row at `row`, swizzled for lane i (two half loads for n = 8)
+template <typename S, int N>
+__device__ __forceinline__ void load_swizzled(S* out, const S* __restrict__ row, int i) {
+    if constexpr (N == 8) {
+        const int h = i & 4;
+        vload<S, 4>(out, row + h);
+        vload<S, 4>(out + 4, row + (4 - h));
+    } else {
+        vload<S, N>(out, row);
+    }
+}
+// value of x in the lane that slot s of a swizzled row refers to (xm: mirror(x))
+template <typename S, int N, int s>
+__device__ __forceinline__ S fetch(S x, S xm) {
+    if constexpr (N == 1) return x;
+    else if constexpr (N == 2) return dpp<(s == 0 ? 0xA0 : 0xF5), 0xf, true>(S(0), x);
+    else if constexpr (N == 4) return quad_bcast<s>(x);
+    else if constexpr (s < 4) return quad_bcast<s>(x);
+    else return quad_bcast<7 - s>(xm);
+}
+
+// acc += sum_s Ls[s] * (value of x in the lane slot s refers to)
+template <typename S, int N, int s = 0>
+struct RowDot {
+    static __device__ __forceinline__ void run(const S* Ls, S x, S xm, S& acc) {
+        acc += Ls[s] * fetch<S, N, s>(x, xm);
+        if constexpr (s + 1 < N) RowDot<S, N, s + 1>::run(Ls, x, xm, acc);
+    }
+};
+
+#include "scan_valu_dpp.inc"
+
+// acc[0..K) += (swizzled row Ls) . (column values spread over the group), K columns given in x
+template <typename S, int N, int K>
+__device__ __forceinline__ void row_dots(const S* Ls, const S* x, S* acc) {
+    if constexpr (sizeof(S) == 4 && N == 8 && (K == 4 || K == 1)) {
+        float xm[K];
+#pragma unroll
+        for (int c = 0; c < K; ++c) xm[c] = mirror<float, 8>(x[c]);
+        if constexpr (K == 4) dpp_dot8_4(Ls, x, xm, acc); else dpp_dot8_1(Ls, x, xm, acc);
+    } else if constexpr (sizeof(S) == 4 && N == 4 && (K == 4 || K == 1)) {
+        if constexpr (K == 4) dpp_dot4_4(Ls, x, acc); else dpp_dot4_1(Ls, x, acc);
+    } else if constexpr (sizeof(S) == 4 && N == 2 && (K == 2 || K == 1)) {
+        if constexpr (K == 2) dpp_dot2_2(Ls, x, acc); else dpp_dot2_1(Ls, x, acc);
+    } else {
+#pragma unroll
+        for (int c = 0; c < K; ++c) RowDot<S, N>::run(Ls, x[c], mirror<S, N>(x[c]), acc[c]);
+    }
+}
+
+// Lr: row i of the left matrix, swizzled.  (M | v): right pair, lane i holds row i / entry i in natural
+// column order.  Result (natural order): row i of Lmat * M and entry i of Lmat * v + add.
+// Must be called by whole wavefronts (the cross-lane operands come from every lane of the group).
+template <typename S, int N>
+__device__ __forceinline__ void group_apply(const S* Lr, S add, S* M, S& v) {
+    constexpr int K = (N >= 4) ? 4 : N;   // columns per block
+    S R[N];
+#pragma unroll
+    for (int c = 0; c < N; ++c) R[c] = S(0);
+#pragma unroll
+    for (int c0 = 0; c0 < N; c0 += K) row_dots<S, N, K>(Lr, M + c0, R + c0);
+    S nv = add;
+    row_dots<S, N, 1>(Lr, &v, &nv);
+#pragma unroll
+    for (int c = 0; c < N; ++c) M[c] = R[c];
+    v = nv;
+}
+// entry i of Lmat * y + add, y spread over the group
+template <typename S, int N>
+__device__ __forceinline__ S group_matvec(const S* Lr, S add, S y) {
+    S nv = add;
+    row_dots<S, N, 1>(Lr, &y, &nv);
+    return nv;
+}
+
+// Rows i (swizzled) of the matrices at scan positions e0 .. e0+L-1 of one sequence and entries i of
+// their vectors.  Reverse mode: vector index T-1-e, matrix = transpose of the one stored at index T-e,
+// zero for e = 0.  FULL: all positions are inside the sequence (and e0 > 0 in reverse mode), so one
+// base address with constant offsets serves all loads.  Otherwise branch free with clamping (positions
+// past the end read the last valid one and are then replaced by the identity pair): with
+// straight-line code the compiler keeps the loads in order and lets the first products start while
+// later positions are still in flight.
+template <typename S, int N, int L, bool REV, bool FULL>
+__device__ __forceinline__ void load_pairs(const S* __restrict__ Ab, const S* __restrict__ bb, long long T,
+                                           long long e0, int i, S (*Ar)[N], S* be) {
+    constexpr int H = (N == 8) ? 4 : 0;
+    const int h = (N == 8) ? (i & 4) : 0;
+    if constexpr (FULL && !REV) {
+        const S* rowa = Ab + e0 * (N * N) + i * N + h;         // first half of the swizzled row
+        const S* rowb = Ab + e0 * (N * N) + i * N + (H - h);   // second half (n = 8)
+        const S* bp = bb + e0 * N + i;
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            if constexpr (N == 8) {
+                vload<S, 4>(Ar[l], rowa + l * (N * N));
+                vload<S, 4>(Ar[l] + 4, rowb + l * (N * N));
+            } else {
+                vload<S, N>(Ar[l], rowa + l * (N * N));
+            }
+            be[l] = bp[l * N];
+        }
+    } else if constexpr (FULL && REV) {
+        // column i of the matrix stored at index T - e, rows in swizzled order
+        const S* cola = Ab + (T - e0) * (N * N) + h * N + i;
+        const S* colb = Ab + (T - e0) * (N * N) + (H - h) * N + i;
+        const S* bp = bb + (T - 1 - e0) * N + i;
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+#pragma unroll
+            for (int s = 0; s < N; ++s)
+                Ar[l][s] = (N == 8 && s >= 4) ? colb[(s - 4) * N - l * (N * N)] : cola[s * N - l * (N * N)];
+            be[l] = bp[-l * N];
+        }
+    } else {
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            const long long e = e0 + l;
+            const bool past = e >= T;
+            const long long ec = past ? T - 1 : e;
+            S row[N], bv;
+            if constexpr (!REV) {
+                load_swizzled<S, N>(row, Ab + ec * (N * N) + i * N, i);
+                bv = bb[ec * N + i];
+            } else {
+                bv = bb[(T - 1 - ec) * N + i];
+                const long long em = ec == 0 ? 1 : ec;   // position 0 has no matrix; any valid one is read and dropped
+                const S* mat = Ab + (T - em) * (N * N);
+                const S* lo = mat + h * N + i;
+                const S* hi = mat + (H - h) * N + i;
+#pragma unroll
+                for (int s = 0; s < N; ++s) {
+                    const S* src = (N == 8 && s >= 4) ? hi + (s - 4) * N : lo + s * N;
+                    row[s] = (T > 1) ? *src : S(0);
+                }
+                if (ec == 0) {
+#pragma unroll
+                    for (int s = 0; s < N; ++s) row[s] = S(0);
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < N; ++s) Ar[l][s] = past ? ((swz_col<N>(s, i) == i) ? S(1) : S(0)) : row[s];
+            be[l] = past ? S(0) : bv;
+        }
+    }
+}
+
+// entry i of the previous iterate (or any array laid out like the output) at positions e0 .. e0+L-1
+template <typename S, int N, int L, bool REV, bool FULL>
+__device__ __forceinline__ void load_previous(const S* __restrict__ src, long long T, long long e0, int i, S* yo) {
+    if constexpr (FULL) {
+        const S* bp = src + (REV ? (T - 1 - e0) : e0) * N + i;
+#pragma unroll
+        for (int l = 0; l < L; ++l) yo[l] = bp[REV ? -l * N : l * N];
+    } else {
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            const long long e = (e0 + l < T) ? e0 + l : T - 1;
+            yo[l] = src[(REV ? (T - 1 - e) : e) * N + i];
+        }
+    }
+}
+
+// Source of the pairs when the GRU cell is evaluated inside the scan: the pair at position e is
+// (J_e | f_e - J_e h_e) with h_e the previous iterate at e-1 (y0 for e = 0), Sec. 3.1 eq. 3 and 5 with the
+// sign folded as in the stand-alone cell kernel.  theta uses that kernel's layout.
+struct GruFeed {
+    const void* theta;
+    const void* x;   // [B][T][d]
+    int d;           // <= DP
+};
+
+// fp32: hardware exp2 and reciprocal (about 1 ulp each).  The absolute error of both functions stays
+// below 3e-7, far inside the convergence tolerance of the fp32 iteration; overflow of exp2 gives the
+// correct limits (1/inf = 0).
+__device__ __forceinline__ float feed_sigmoid(float a) {
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * a));
+}
+__device__ __forceinline__ float feed_tanh(float a) {
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.88539008177792681f * a));
+}
+__device__ __forceinline__ double feed_sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
+__device__ __forceinline__ double feed_tanh(double a) { return tanh(a); }
+
+// The pairs of positions e0 .. e0+L-1 from the GRU cell.  yo: previous iterate at these positions
+// (already requested); oldb: previous iterate of the sequence; DP: input width the x loops are unrolled for.
+template <typename S, int N, int L, int DP, bool FULL>
+__device__ __forceinline__ void gru_pairs(const GruFeed& gf, const S* __restrict__ y0p, const S* __restrict__ oldb,
+                                          int b, long long T, long long e0, int i, const S* yo, S (*Ar)[N], S* be) {
+    // row i of the cell's weights
+    const S* __restrict__ th = reinterpret_cast<const S*>(gf.theta);
+    const int d = gf.d;
+    const S* __restrict__ U = th + 3 * N * d;
+    const S* __restrict__ bias = U + 3 * N * N;
+    S Ur[N], Uz[N], Uc[N], Wr[DP], Wz[DP], Wc[DP];
+    load_swizzled<S, N>(Ur, U + i * N, i);
+    load_swizzled<S, N>(Uz, U + (N + i) * N, i);
+    load_swizzled<S, N>(Uc, U + (2 * N + i) * N, i);
+    S E[N];   // row i of the identity, swizzled
+#pragma unroll
+    for (int j = 0; j < N; ++j) E[j] = (swz_col<N>(j, i) == i) ? S(1) : S(0);
+#pragma unroll
+    for (int k = 0; k < DP; ++k) {
+        const int kc = k < d ? k : d - 1;   // columns past d read a valid one and count as zero
+        const S a = th[i * d + kc], bq = th[(N + i) * d + kc], c = th[(2 * N + i) * d + kc];
+        Wr[k] = k < d ? a : S(0);
+        Wz[k] = k < d ? bq : S(0);
+        Wc[k] = k < d ? c : S(0);
+    }
+    const S br = bias[i], bz = bias[N + i], bc = bias[2 * N + i], bh = bias[3 * N + i];
+    const S* __restrict__ xb = reinterpret_cast<const S*>(gf.x) + (long long)b * T * d;
+    // state in front of the first position of this group
+    S h;
+    {
+        const long long ef = e0 < T ? e0 : T;
+        const S a = oldb[(ef > 0 ? ef - 1 : 0) * N + i];
+        const S c0 = y0p ? y0p[(long long)b * N + i] : S(0);
+        h = ef > 0 ? a : c0;
+    }
+    // input projections of all positions first: their loads are all in flight before the
+    // cross-lane products start (those are opaque to the scheduler, loads do not move across them)
+    S pr[L], pq[L], pc[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        const long long e = (FULL || e0 + l < T) ? e0 + l : T - 1;
+        S ar = br, az = bz, ac = bc;
+#pragma unroll
+        for (int k = 0; k < DP; ++k) {
+            const S xv = xb[e * d + (k < d ? k : d - 1)];
+            ar += Wr[k] * xv;
+            az += Wz[k] * xv;
+            ac += Wc[k] * xv;
+        }
+        pr[l] = ar; pq[l] = az; pc[l] = ac;
+    }
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        S ar = pr[l], az = pq[l], ac = pc[l], q = bh;
+        row_dots<S, N, 1>(Ur, &h, &ar);
+        row_dots<S, N, 1>(Uz, &h, &az);
+        row_dots<S, N, 1>(Uc, &h, &q);
+        const S r = feed_sigmoid(ar), z = feed_sigmoid(az);
+        const S c = feed_tanh(ac + r * q);
+        const S f = (S(1) - z) * c + z * h;
+        const S pz = (h - c) * z * (S(1) - z);
+        const S sc = (S(1) - z) * (S(1) - c * c);
+        const S sr = sc * r;
+        const S st = sc * q * r * (S(1) - r);
+        S Jrow[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) Jrow[j] = pz * Uz[j] + (sr * Uc[j] + (st * Ur[j] + z * E[j]));
+        S Jh = S(0);
+        row_dots<S, N, 1>(Jrow, &h, &Jh);
+        if constexpr (FULL) {
+#pragma unroll
+            for (int j = 0; j < N; ++j) Ar[l][j] = Jrow[j];
+            be[l] = f - Jh;
+        } else {
+            const bool past = e0 + l >= T;
+#pragma unroll
+            for (int j = 0; j < N; ++j) Ar[l][j] = past ? E[j] : Jrow[j];
+            be[l] = past ? S(0) : f - Jh;
+        }
+        h = yo[l];
+    }
+}
+
+// Inclusive log-step scan over the groups of a wavefront.  (M | v): this group's pair, lane i holds
+// row i.  Afterwards group g holds pair_g o ... o pair_0.
+template <typename S, int N>
+__device__ __forceinline__ void scan_groups(S* M, S& v, int group, int i, int ngroups_active) {
+    constexpr int NG = 64 / N;
+#pragma unroll
+    for (int d = 1; d < NG; d <<= 1) {
+        if (d >= ngroups_active) break;   // uniform
+        S Mo[N], vo;
+#pragma unroll
+        for (int c = 0; c < N; ++c) Mo[c] = __shfl_up(M[c], d * N);
+        vo = __shfl_up(v, d * N);
+        // (mine) after (other): rows of mine times other
+        const S keepv = v;
+        S keepM[N], leftM[N];
+#pragma unroll
+        for (int c = 0; c < N; ++c) keepM[c] = M[c];
+        swizzle_row<S, N>(keepM, leftM, i);
+        group_apply<S, N>(leftM, keepv, Mo, vo);
+        const bool upd = group >= d;
+#pragma unroll
+        for (int c = 0; c < N; ++c) M[c] = upd ? Mo[c] : keepM[c];
+        v = upd ? vo : keepv;
+    }
+}
+
+// DP = 0: pairs are read from p.A / p.bv.  DP > 0: pairs come from the GRU cell (forward scans only),
+// DP being the input width the x loops are unrolled for.
+template <typename S, int N, int L, int W, bool REV, int DP>
+__global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed gf) {
+    static_assert(DP == 0 || !REV, "the fused cell feeds forward scans only");
+    constexpr int NG = 64 / N;        // groups per wavefront
+    constexpr int TILE = W * NG * L;  // scan positions per tile
+    constexpr int WS = TaggedWords<S>::per_scalar;
+    constexpr int AGG_WORDS = (N * N + N) * WS;   // words of one published tile total
+    static_assert(NG >= W, "wavefront 0 scans one wavefront total per group");
+
+    __shared__ unsigned s_ticket;
+    __shared__ S sM[W][N * N];    // wavefront totals
+    __shared__ S sv[W][N];
+    __shared__ S sEM[W][N * N];   // prefix in front of each wavefront (exclusive)
+    __shared__ S sEv[W][N];
+    __shared__ S sCarry[N];
+
+    if (gate_closed<S>(p.gate)) return;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int group = lane / N;
+    const int i = lane % N;
+
+    if (tid == 0) s_ticket = atomicAdd(p.ticket, 1u);
+    __syncthreads();
+    const unsigned tk = s_ticket;
+    const int b = (int)(tk % (unsigned)p.B);
+    const int t = (int)(tk / (unsigned)p.B);
+    if (t >= p.tiles) return;
+
+    const S* __restrict__ Ab = reinterpret_cast<const S*>(p.A) + (long long)b * p.strideA;
+    const S* __restrict__ bb = reinterpret_cast<const S*>(p.bv) + (long long)b * p.strideb;
+    S* __restrict__ ob = reinterpret_cast<S*>(p.out) + (long long)b * p.strideOut;
+    const S* __restrict__ oldb =
+        p.yold ? reinterpret_cast<const S*>(p.yold) + (long long)b * p.strideOld : nullptr;
+    const long long T = p.T;
+    const long long e0 = (long long)t * TILE + (long long)(wave * NG + group) * L;
+    const long long slot = (long long)b * p.tiles + t;
+    DEER_STAMP(p, slot, 0, tid == 0);
+
+    // ---- 1. this group's pairs (kept for the second walk), then their composition ----
+    // A tile that lies completely inside the sequence takes the FULL variants: one base address with
+    // constant offsets and no end-of-sequence handling.
+    const bool full = (long long)(t + 1) * TILE <= T && (!REV || t > 0);
+    S Ar[L][N], be[L], yo[L];
+    if (full) {
+        if constexpr (DP == 0) load_pairs<S, N, L, REV, true>(Ab, bb, T, e0, i, Ar, be);
+        load_previous<S, N, L, REV, true>(oldb ? oldb : bb, T, e0, i, yo);
+        if constexpr (DP > 0) gru_pairs<S, N, L, DP, true>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
+    } else {
+        if constexpr (DP == 0) load_pairs<S, N, L, REV, false>(Ab, bb, T, e0, i, Ar, be);
+        load_previous<S, N, L, REV, false>(oldb ? oldb : bb, T, e0, i, yo);
+        if constexpr (DP > 0) gru_pairs<S, N, L, DP, false>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
+    }
+    S M[N], v;
+#pragma unroll
+    for (int c = 0; c < N; ++c) M[c] = (c == i) ? S(1) : S(0);
+    v = S(0);
+#pragma unroll
+    for (int l = 0; l < L; ++l) group_apply<S, N>(Ar[l], be[l], M, v);
+
+    // ---- 2. scan over the groups of the wavefront; keep the exclusive prefix ----
+    scan_groups<S, N>(M, v, group, i, NG);
+    if (group == NG - 1) {
+#pragma unroll
+        for (int c = 0; c < N; ++c) sM[wave][i * N + c] = M[c];
+        sv[wave][i] = v;
+    }
+    S Pex[N], pex;   // exclusive prefix of this group inside its wavefront (row i, swizzled)
+    {
+        S nat[N];
+#pragma unroll
+        for (int c = 0; c < N; ++c) {
+            const S u = __shfl_up(M[c], N);
+            nat[c] = group == 0 ? ((c == i) ? S(1) : S(0)) : u;
+        }
+        swizzle_row<S, N>(nat, Pex, i);
+        const S u = __shfl_up(v, N);
+        pex = group == 0 ? S(0) : u;
+    }
+    __syncthreads();
+
+    // ---- 3. wavefront 0: scan of the wavefront totals; 4. look-back ----
+    DEER_STAMP(p, slot, 1, tid == 0);
+    if (wave == 0) {
+        S Mt[N], vt;
+        {
+            // groups beyond the number of wavefronts hold the identity pair
+            const bool has = group < W;
+            const int gw = has ? group : W - 1;
+#pragma unroll
+            for (int c = 0; c < N; ++c) {
+                const S u = sM[gw][i * N + c];
+                Mt[c] = has ? u : ((c == i) ? S(1) : S(0));
+            }
+            const S u = sv[gw][i];
+            vt = has ? u : S(0);
+        }
+        scan_groups<S, N>(Mt, vt, group, i, W);
+        // group g now holds the prefix through wavefront g: it is the prefix in front of wavefront g+1
+        if (group < W - 1) {
+#pragma unroll
+            for (int c = 0; c < N; ++c) sEM[group + 1][i * N + c] = Mt[c];
+            sEv[group + 1][i] = vt;
+        }
+        const unsigned tagA = (p.epoch << 2) | TILE_AGGREGATE;
+        const unsigned tagI = (p.epoch << 2) | TILE_INCLUSIVE;
+        const unsigned long long* aggSeq = p.aggW + (long long)b * p.tiles * AGG_WORDS;
+        const unsigned long long* inclSeq = p.inclW + (long long)b * p.tiles * (N * WS);
+        if (t > 0 && group == W - 1) {
+            unsigned long long* mine = p.aggW + slot * AGG_WORDS;
+#pragma unroll
+            for (int c = 0; c < N; ++c) TaggedWords<S>::put(mine, i * N + c, Mt[c], tagA);
+            TaggedWords<S>::put(mine, N * N + i, vt, tagA);
+        }
+        DEER_STAMP(p, slot, 2, lane == 0);
+
+        // lane j inspects predecessor t-1-j (index -1 is the given initial state): inclusive carry
+        // known, total known, or nothing yet, judged by one word of each
+        int k = -1;
+        {
+            const int idx = t - 1 - lane;
+            unsigned spins = 0;
+            while (true) {
+                unsigned st;
+                if (idx >= 0) {
+                    S dummy;
+                    if (TaggedWords<S>::get(inclSeq + (long long)idx * (N * WS), 0, tagI, dummy)) st = TILE_INCLUSIVE;
+                    else if (TaggedWords<S>::get(aggSeq + (long long)idx * AGG_WORDS, N * N, tagA, dummy)) st = TILE_AGGREGATE;
+                    else st = TILE_INVALID;
+                } else {
+                    st = (idx == -1) ? TILE_INCLUSIVE : 3u;
+                }
+                const unsigned long long incl_mask = __ballot(st == TILE_INCLUSIVE);
+                const unsigned long long wait_mask = __ballot(st == TILE_INVALID);
+                if (incl_mask != 0ull) {
+                    const int first = __ffsll((long long)incl_mask) - 1;
+                    const unsigned long long below = (first == 0) ? 0ull : ((1ull << first) - 1ull);
+                    if ((wait_mask & below) == 0ull) { k = first; break; }
+                }
+                if (++spins > kSpinLimit) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
+        }
+        DEER_STAMP(p, slot, 3, lane == 0);
+
+        // carry: entry i in the lanes of group 0
+        S y = S(0);
+        bool ok = k >= 0;
+        if (ok) {
+            const int far = t - 1 - k;   // tile whose inclusive carry is known (-1: the initial state)
+            if (group == 0) {
+                if (far >= 0) ok = tagged_get_wait<S>(inclSeq + (long long)far * (N * WS), i, tagI, y);
+                else if (p.y0) y = reinterpret_cast<const S*>(p.y0)[(long long)b * N + i];
+            }
+            // fold the totals of tiles far+1 .. t-1 forward, NG of them per round: group g fetches
+            // tile q0 + g, then the running value walks through the groups in order
+            for (int q0 = far + 1; q0 <= t - 1; q0 += NG) {
+                const int q = q0 + group;
+                const bool valid = q <= t - 1;
+                S Lr[N], hv;
+                {
+                    // groups past the last predecessor re-read it and then act as the identity pair
+                    const unsigned long long* src = aggSeq + (long long)(valid ? q : t - 1) * AGG_WORDS;
+                    // all words are requested at once; the per-word wait is only a fallback for the
+                    // rare case that a word of a total is still in flight when its first word is seen
+                    S row[N], u;
+                    bool got = true;
+#pragma unroll
+                    for (int c = 0; c < N; ++c) got = TaggedWords<S>::get(src, i * N + swz_col<N>(c, i), tagA, row[c]) && got;
+                    got = TaggedWords<S>::get(src, N * N + i, tagA, u) && got;
+                    if (__ballot(!got) != 0ull) {
+#pragma unroll
+                        for (int c = 0; c < N; ++c) ok = tagged_get_wait<S>(src, i * N + swz_col<N>(c, i), tagA, row[c]) && ok;
+                        ok = tagged_get_wait<S>(src, N * N + i, tagA, u) && ok;
+                    }
+                    hv = valid ? u : S(0);
+#pragma unroll
+                    for (int c = 0; c < N; ++c) Lr[c] = valid ? row[c] : ((swz_col<N>(c, i) == i) ? S(1) : S(0));
+                }
+#pragma unroll 1
+                for (int g = 0; g < NG; ++g) {
+                    const S ny = group_matvec<S, N>(Lr, hv, y);
+                    if (group == g) y = ny;
+                    const S pass = __shfl_up(y, N);
+                    if (group == g + 1) y = pass;
+                }
+                // the running value sits in the last group: bring it back to group 0
+                const S back = __shfl(y, i + (NG - 1) * N);
+                if (group == 0) y = back;
+            }
+        }
+        if (__ballot(!ok) != 0ull) {
+            if (lane == 0) atomicOr(p.status, 1u);
+        }
+        DEER_STAMP(p, slot, 4, lane == 0);
+#ifdef DEER_SCAN_TIMING
+        if (p.timing && lane == 0) p.timing[slot * 8 + 7] = (unsigned long long)(k < 0 ? 0 : k);
+#endif
+        if (group == 0) sCarry[i] = y;
+        // inclusive carry of this tile: (tile total) applied to the carry
+        if (group == W - 1) {
+            const S c = sCarry[i];
+            S left[N];
+            swizzle_row<S, N>(Mt, left, i);
+            TaggedWords<S>::put(p.inclW + slot * (N * WS), i, group_matvec<S, N>(left, vt, c), tagI);
+        }
+        DEER_STAMP(p, slot, 5, lane == 0);
+    }
+    __syncthreads();
+
+    // ---- 5. starting state of this group, then the second walk over the resident pairs ----
+    S y = sCarry[i];
+    if (wave > 0) {
+        S row[N];
+#pragma unroll
+        for (int c = 0; c < N; ++c) row[c] = sEM[wave][i * N + swz_col<N>(c, i)];
+        y = group_matvec<S, N>(row, sEv[wave][i], y);
+    }
+    y = group_matvec<S, N>(Pex, pex, y);
+
+    S emax = S(0);
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        const long long e = e0 + l;
+        y = group_matvec<S, N>(Ar[l], be[l], y);
+        if (full || e < T) {
+            const long long oi = (REV ? (T - 1 - e) : e) * N + i;
+            S w = y;
+            if (oldb) {
+                const S dq = abs_or_inf<S>(p.delta ? y : y - yo[l]);
+                emax = dq > emax ? dq : emax;
+                if (p.delta) w += yo[l];
+            }
+            ob[oi] = w;
+        }
+    }
+    if (p.err) {
+        emax = wave_max<S>(emax);
+        if (lane == 0) err_atomic_max(p.err, emax);
+    }
+    DEER_STAMP(p, slot, 6, tid == 0);
+}
+
+}  // namespace
+
+}  // namespace deer

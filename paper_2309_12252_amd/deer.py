@@ -31,7 +31,8 @@ class DeerProfile(ctypes.Structure):
     _fields_ = [("funceval_ms", ctypes.c_double), ("funceval_launches", ctypes.c_int64),
                 ("discretise_ms", ctypes.c_double), ("discretise_launches", ctypes.c_int64),
                 ("scan_ms", ctypes.c_double), ("scan_launches", ctypes.c_int64),
-                ("vjp_ms", ctypes.c_double), ("vjp_launches", ctypes.c_int64)]
+                ("vjp_ms", ctypes.c_double), ("vjp_launches", ctypes.c_int64),
+                ("fused_ms", ctypes.c_double), ("fused_launches", ctypes.c_int64)]
 
 
 class DeerError(RuntimeError):
