@@ -141,10 +141,12 @@ Plan make_plan(const deer_config* c) {
             const double est = (double)((tiles + 255) / 256) * (5.0 + 1.6 * kLf[q]);
             if (est < best) { best = est; L = kLf[q]; }
         }
-        const int forced = env_int("DEER_FUSED_L", 0);
-        if (forced > 0) L = forced;
-        p.fused_W = env_int("DEER_FUSED_W", 8);
-        if (scan_gru_fused_supported(c->n, c->d, L)) {
+        // tuning knobs: honoured when the requested variant exists
+        p.fused_W = 8;
+        const int fl = env_int("DEER_FUSED_L", 0), fw = env_int("DEER_FUSED_W", 0);
+        if (fw > 0 && scan_gru_fused_supported(c->dtype, c->n, c->d, L, fw)) p.fused_W = fw;
+        if (fl > 0 && scan_gru_fused_supported(c->dtype, c->n, c->d, fl, p.fused_W)) L = fl;
+        if (scan_gru_fused_supported(c->dtype, c->n, c->d, L, p.fused_W)) {
             p.fused = true;
             p.fused_L = L;
             const int tile = scan_valu_tile(c->n, L, p.fused_W);

@@ -219,7 +219,7 @@ hipError_t launch_scan_valu(int dtype, int n, const ScanParams& p, hipStream_t s
 hipError_t launch_scan_mfma(int dtype, int n, const ScanParams& p, hipStream_t s);
 int scan_valu_tile(int n, int L, int W);   // scan positions per tile
 // scan with the GRU cell evaluated in place of the loads (forward, n <= 8, d <= 8); p.A / p.bv unused
-bool scan_gru_fused_supported(int n, int d, int L);
+bool scan_gru_fused_supported(int dtype, int n, int d, int L, int W);
 hipError_t launch_scan_gru_fused(int dtype, int n, const ScanParams& p, const void* theta, const void* x, int d,
                                  hipStream_t s);
 int scan_mfma_tile(int dtype, int n);

@@ -58,8 +58,13 @@ hipError_t launch_fused_s(int n, const ScanParams& p, const GruFeed& gf, hipStre
 
 }  // namespace
 
-bool scan_gru_fused_supported(int n, int d, int L) {
-    return n >= 1 && n <= 8 && (n & (n - 1)) == 0 && d >= 1 && d <= 8 && (L == 1 || L == 2 || L == 4 || L == 8 || L == 10 || L == 12 || L == 16);
+// mirrors the instantiations reachable through launch_fused_s
+bool scan_gru_fused_supported(int dtype, int n, int d, int L, int W) {
+    if (!(n == 1 || n == 2 || n == 4 || n == 8) || d < 1 || d > 8) return false;
+    if (!(W == 8 || (W == 4 && n >= 4))) return false;
+    if (L == 1 || L == 2 || L == 4 || L == 8) return true;
+    if (dtype != 0) return false;
+    return L == 16 || (n == 8 && (L == 10 || L == 12));
 }
 
 hipError_t launch_scan_gru_fused(int dtype, int n, const ScanParams& p, const void* theta, const void* x, int d,

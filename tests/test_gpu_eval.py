@@ -5,7 +5,9 @@ import pytest
 
 import oracle
 from paper_2309_12252_amd import deer, inputs
-from helpers import TOL_ABS, gpu_eval, oracle_eval, oracle_cell
+import torch
+
+from helpers import DEV, TOL_ABS, dev, gpu_eval, host, oracle_eval, oracle_cell
 from conftest import read_golden
 
 pytestmark = pytest.mark.gpu
@@ -87,3 +89,61 @@ def test_nonfinite_input_is_reported():
     w.x[0, 17, 1] = np.nan
     y, it, err, conv, st = gpu_eval(w, allow_nonfinite=True)
     assert st == deer.DEER_ERR_NONFINITE and it == 1 and not conv
+
+
+@pytest.mark.parametrize("env", [
+    {"DEER_FUSED": "0"},
+    {"DEER_FUSED": "0", "DEER_SCAN_L": "1"}, {"DEER_FUSED": "0", "DEER_SCAN_L": "2"},
+    {"DEER_FUSED": "0", "DEER_SCAN_L": "8"}, {"DEER_FUSED": "0", "DEER_SCAN_L": "10"},
+    {"DEER_FUSED": "0", "DEER_SCAN_L": "12"}, {"DEER_FUSED": "0", "DEER_SCAN_L": "16"},
+    {"DEER_FUSED_L": "1"}, {"DEER_FUSED_L": "2"}, {"DEER_FUSED_L": "4"}, {"DEER_FUSED_L": "8"},
+    {"DEER_FUSED_L": "10"}, {"DEER_FUSED_L": "12"}, {"DEER_FUSED_L": "16"},
+    {"DEER_FUSED_L": "4", "DEER_FUSED_W": "4"}, {"DEER_FUSED_L": "10", "DEER_FUSED_W": "4"},
+    {"DEER_FUSED_L": "16", "DEER_FUSED_W": "4"},
+], ids=lambda e: ",".join("%s=%s" % kv for kv in sorted(e.items())))
+def test_kernel_variants_n8(env, monkeypatch):
+    # the tuning knobs select other instantiations of the step kernels (positions per lane group,
+    # wavefronts per tile, cell inside or outside the scan); every one must give the same trajectory
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    for k, (B, T, d) in enumerate([(3, 1100, 4), (2, 4097, 7), (1, 9, 1)]):
+        w = inputs.gru_workload("variant_T%d" % T, 900 + k, B=B, T=T, n=8, d=d)
+        check(w, deer.DEER_F32)
+    if int(env.get("DEER_FUSED_L", env.get("DEER_SCAN_L", "1"))) <= 4:
+        w = inputs.gru_workload("variant64", 910, B=2, T=1500, n=8, d=4, tol=GOLD["tol_f64"])
+        check(w, deer.DEER_F64)
+
+
+@pytest.mark.parametrize("n", [2, 4])
+@pytest.mark.parametrize("env", [{"DEER_FUSED": "0"}, {"DEER_FUSED_L": "16"}, {"DEER_FUSED_L": "8", "DEER_FUSED_W": "4"}],
+                         ids=["unfused", "fusedL16", "fusedL8W4"])
+def test_kernel_variants_small_n(n, env, monkeypatch):
+    if n == 2 and env.get("DEER_FUSED_W") == "4":
+        env = {"DEER_FUSED_L": "8"}   # four wavefronts per tile exist for n >= 4 only
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    w = inputs.gru_workload("variant_n%d" % n, 920 + n, B=2, T=5000, n=n, d=3)
+    check(w, deer.DEER_F32)
+
+
+def test_repeated_calls_on_one_context():
+    # a context remembers how many iterations the last call took (it sizes the first batch of launches
+    # and picks the buffer order from it); results must not depend on that memory
+    w = inputs.gru_workload("repeat", 77, B=2, T=3000, n=8, d=4)
+    yo, _, _, _ = oracle_eval(w, tol=1e-9, max_iter=50)
+    ctx = deer.context_for(w, dtype=deer.DEER_F32, device=DEV)
+    th, x, y0 = dev(w.theta, deer.DEER_F32), dev(w.x, deer.DEER_F32), dev(w.y0, deer.DEER_F32)
+    try:
+        seen = []
+        for tol, max_iter, guess in [(1e-4, 50, None), (1e-4, 50, None), (1e-4, 2, None), (1e-4, 50, None),
+                                     (1e-4, 50, yo), (1e-4, 50, None), (1e-4, 3, None), (1e-4, 1, yo), (1e-4, 50, None)]:
+            y, it, err, conv, st = ctx.eval(th, x, y0, y_guess=dev(guess, deer.DEER_F32), tol=tol, max_iter=max_iter)
+            torch.cuda.synchronize()
+            ref, ito, erro, _ = oracle_eval(w, tol=tol, max_iter=max_iter, guess=guess)
+            assert st == deer.DEER_OK and abs(it - ito) <= 1, (tol, max_iter, it, ito)
+            if it == ito:
+                assert np.abs(host(y) - ref).max() <= 1e-4, (tol, max_iter, guess is not None)
+            seen.append(it)
+        assert len(set(seen)) > 1
+    finally:
+        ctx.close()
