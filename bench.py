@@ -178,7 +178,12 @@ def main():
     roofline = dominant_roofline(dominant, per_launch[dominant], w)
     tpath = os.path.join(ROOT, "profiles", "kernel_traffic.json")
     if os.path.exists(tpath):
-        roofline["traffic"] = json.load(open(tpath)).get(w.name, {}).get(dominant)
+        # HBM bytes per launch from the committed rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, calibrated)
+        tr = json.load(open(tpath)).get(w.name, {}).get(dominant)
+        if tr:
+            roofline["traffic"] = tr["total_bytes"]
+            roofline["traffic_fetched"] = tr["fetched_bytes"]
+            roofline["traffic_written"] = tr["written_bytes"]
 
     out = {"metric": "DEER sequence-steps/s (B*T/s), forward eval to convergence", "value": value,
            "unit": "sequence-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -131,11 +131,12 @@ Plan make_plan(const deer_config* c) {
     if (!ode && !p.mfma && c->d <= 8 && env_int("DEER_FUSED", 1) != 0) {
         // The fused step spends more time per position on arithmetic and none on loading matrices:
         // shorter serial runs than the plain scan, so that more tiles are in flight.
-        static const int kLf[] = {1, 2, 4, 8, 16};
-        const int ncand = c->dtype == DEER_F32 ? 5 : ((c->n == 8) ? 3 : 4);
+        static const int kLf[] = {1, 2, 4, 8, 12, 16};
+        const int ncand = c->dtype == DEER_F32 ? 6 : ((c->n == 8) ? 3 : 4);
         int L = kLf[0];
         double best = 1e300;
         for (int q = 0; q < ncand; ++q) {
+            if (!scan_gru_fused_supported(c->dtype, c->n, c->d, kLf[q], 8)) continue;
             const long long tile = scan_valu_tile(c->n, kLf[q], p.W);
             const long long tiles = (long long)B * ((p.scan_T + tile - 1) / tile);
             const double est = (double)((tiles + 255) / 256) * (5.0 + 1.6 * kLf[q]);
@@ -269,7 +270,8 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
     {
         static unsigned long long* dbg = nullptr;
         if (!dbg) (void)hipMalloc(&dbg, (size_t)1 << 26);
-        p.timing = dbg;
+        // eight segments of 2^20 words, one per launch in turn, so consecutive launches can be compared
+        p.timing = dbg + (size_t)(p.epoch & 7u) * ((size_t)1 << 20);
         g_timing = dbg;
     }
 #endif

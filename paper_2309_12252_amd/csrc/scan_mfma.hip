@@ -83,15 +83,20 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
     __shared__ int s_k;               // hops between this tile and the nearest known inclusive carry
     __shared__ int s_ok;
 
-    if (gate_closed<S>(p.gate)) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int g = lane >> 4;
     const int r = lane & 15;
 
-    if (tid == 0) s_ticket = atomicAdd(p.ticket, 1u);
+    // the ticket and the gate's error word are requested together: one memory round trip, not two
+    // (with a closed gate every workgroup of the launch returns, so the drawn tickets do not matter)
+    unsigned drawn = 0u;
+    if (tid == 0) drawn = atomicAdd(p.ticket, 1u);
+    const bool closed = gate_closed<S>(p.gate);
+    if (tid == 0) s_ticket = drawn;
     __syncthreads();
+    if (closed) return;
     const unsigned tk = s_ticket;
     const int b = (int)(tk % (unsigned)p.B);
     const int t = (int)(tk / (unsigned)p.B);

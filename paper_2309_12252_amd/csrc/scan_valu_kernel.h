@@ -363,15 +363,20 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     __shared__ S sEv[W][N];
     __shared__ S sCarry[N];
 
-    if (gate_closed<S>(p.gate)) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int group = lane / N;
     const int i = lane % N;
 
-    if (tid == 0) s_ticket = atomicAdd(p.ticket, 1u);
+    // the ticket and the gate's error word are requested together: one memory round trip, not two
+    // (with a closed gate every workgroup of the launch returns, so the drawn tickets do not matter)
+    unsigned drawn = 0u;
+    if (tid == 0) drawn = atomicAdd(p.ticket, 1u);
+    const bool closed = gate_closed<S>(p.gate);
+    if (tid == 0) s_ticket = drawn;
     __syncthreads();
+    if (closed) return;
     const unsigned tk = s_ticket;
     const int b = (int)(tk % (unsigned)p.B);
     const int t = (int)(tk / (unsigned)p.B);
@@ -581,7 +586,7 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
                 emax = dq > emax ? dq : emax;
                 if (p.delta) w += yo[l];
             }
-            ob[oi] = w;
+            __builtin_nontemporal_store(w, ob + oi);   // streamed out: nothing of it is read again in this launch
         }
     }
     if (p.err) {
