@@ -78,6 +78,8 @@ typedef struct {
     double scan_ms;       int64_t scan_launches;       /* inverse linear operator (+ fused max|dy|)  */
     double vjp_ms;        int64_t vjp_launches;        /* GRU VJP + parameter-gradient reduction     */
     double fused_ms;      int64_t fused_launches;      /* GRU, n <= 8: cell + scan + max|dy| in one   */
+    double newton_ms;     int64_t newton_launches;     /* GRU, small problems: a whole solve in one   */
+    int64_t newton_iterations;                         /* Newton iterations inside those launches     */
 } deer_profile;
 
 /* Number of parameters in the flat theta of this configuration (layouts above); 0 if invalid. */

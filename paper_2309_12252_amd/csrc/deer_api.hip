@@ -40,7 +40,7 @@ struct Plan {
     int fused_L, fused_W, fused_tiles;
     int vjp_blocks;
     // byte offsets into the workspace
-    size_t off_J, off_rhs, off_ybuf, off_Gbar, off_zbar, off_aggW, off_inclW, off_ctl, off_partial, total;
+    size_t off_J, off_rhs, off_ybuf, off_Gbar, off_zbar, off_aggW, off_inclW, off_barrier, off_ctl, off_partial, total;
 };
 
 size_t theta_count(const deer_config* c) {
@@ -168,6 +168,8 @@ Plan make_plan(const deer_config* c) {
     // published tile totals and carries: one 64-bit tagged word per 32 bits of payload
     p.off_aggW = take(nt * (n * n + n) * (p.esz / 4) * 8);
     p.off_inclW = take(nt * n * (p.esz / 4) * 8);
+    // slots of the one-launch solve's grid barrier (two banks, one tagged scalar per workgroup)
+    p.off_barrier = take(p.fused ? 2 * B * (size_t)p.fused_tiles * (p.esz / 4) * 8 : 0);
     p.off_ctl = take((size_t)kSlots * 4 + (size_t)kSlots * 8 + 16);   // tickets, err bits, status
     p.off_partial = take((size_t)p.vjp_blocks * 4 * theta_count(c) * p.esz);
     p.total = off;
@@ -185,6 +187,7 @@ struct deer_ctx {
     void* h_err;            // pinned: kSlots * 8 bytes of error words, then the status word
     int batch;              // Newton iterations enqueued per host round trip when nothing better is known
     int last_iters;         // iterations the previous deer_eval() took (0: none yet)
+    bool one_launch;        // GRU, n <= 8, every tile resident at once: all iterations run in one launch
     bool profiling;
     deer_profile prof;
     hipEvent_t ev[2 * kMaxEvents];
@@ -196,7 +199,7 @@ struct deer_ctx {
 
 namespace {
 
-enum { KIND_FUNCEVAL = 0, KIND_DISC = 1, KIND_SCAN = 2, KIND_VJP = 3, KIND_FUSED = 4 };
+enum { KIND_FUNCEVAL = 0, KIND_DISC = 1, KIND_SCAN = 2, KIND_VJP = 3, KIND_FUSED = 4, KIND_NEWTON = 5 };
 
 deer_status fail(deer_ctx* ctx, deer_status st, const std::string& msg) {
     if (ctx) ctx->last_error = msg;
@@ -241,6 +244,7 @@ void prof_collect(deer_ctx* c, int iters_done = 1 << 30) {
             case KIND_DISC: c->prof.discretise_ms += ms; c->prof.discretise_launches++; break;
             case KIND_SCAN: c->prof.scan_ms += ms; c->prof.scan_launches++; break;
             case KIND_FUSED: c->prof.fused_ms += ms; c->prof.fused_launches++; break;
+            case KIND_NEWTON: c->prof.newton_ms += ms; c->prof.newton_launches++; break;
             default: c->prof.vjp_ms += ms; c->prof.vjp_launches++; break;
         }
     }
@@ -307,6 +311,80 @@ deer_status check_status(deer_ctx* c) {
     return DEER_OK;
 }
 
+// *busy is set when the one-launch solve gave up waiting (the device is shared with other work): the caller
+// then takes the launch-per-iteration path
+deer_status eval_one_launch(bool* busy, deer_ctx* c, const void* d_theta, const void* d_x, const void* d_y0, const void* d_y_guess,
+                            double tol, int32_t max_iter, void* d_y, int32_t* iters, double* final_err,
+                            int32_t* converged) {
+    const deer_config& g = c->cfg;
+    const size_t n = (size_t)g.n, T = (size_t)g.T;
+    deer_status st = zero_ctl(c);
+    if (st != DEER_OK) return st;
+    NewtonParams q{};
+    ScanParams& p = q.scan;
+    p.y0 = d_y0; p.out = d_y; p.yold = d_y_guess;
+    p.strideOut = (long long)(T * n); p.strideOld = (long long)(T * n);
+    p.B = g.B; p.T = g.T; p.L = c->plan.fused_L; p.W = 8; p.tiles = c->plan.fused_tiles;
+    if (c->epoch + (unsigned)max_iter + 1u >= (1u << 30)) {   // not enough epochs left: start over
+        c->epoch = 0;
+        st = zero_ctl(c);
+        if (st != DEER_OK) return st;
+    }
+    p.epoch = c->epoch + 1;
+    c->epoch += (unsigned)max_iter + 1u;
+    p.aggW = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_aggW);
+    p.inclW = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_inclW);
+    p.status = ctl_status(c);
+    p.gate = Gate{nullptr, 0.0};
+    q.feed = GruFeed{d_theta, d_x, g.d};
+    q.err = reinterpret_cast<unsigned long long*>(ctl_err(c, 0));
+    q.barrier = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_barrier);
+    q.result = reinterpret_cast<int*>(ctl_status(c)) + 1;
+    q.tol = tol;
+    q.max_iter = max_iter;
+#ifdef DEER_SCAN_TIMING
+    {
+        static unsigned long long* dbg = nullptr;
+        if (!dbg) (void)hipMalloc(&dbg, (size_t)1 << 26);
+        p.timing = dbg;
+        g_timing = dbg;
+    }
+#endif
+    prof_begin(c, KIND_NEWTON);
+    HIPCHK(c, launch_gru_newton(g.dtype, g.n, q, c->stream));
+    prof_end(c);
+    char* h = reinterpret_cast<char*>(c->h_err);
+    HIPCHK(c, hipMemcpyAsync(h, ctl_err(c, 0), (size_t)max_iter * 8, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(h + (size_t)kSlots * 8, ctl_status(c), 8, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    unsigned status = 0;
+    int it = 0;
+    std::memcpy(&status, h + (size_t)kSlots * 8, 4);
+    std::memcpy(&it, h + (size_t)kSlots * 8 + 4, 4);
+    prof_collect(c);
+    if (status != 0) {
+        HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_ctl, ctl_bytes(), c->stream));
+        *busy = true;
+        return DEER_OK;
+    }
+    if (it < 1 || it > max_iter) return fail(c, DEER_ERR_HIP, "one-launch solve returned an impossible iteration count");
+    double err;
+    if (g.dtype == DEER_F32) {
+        float f;
+        std::memcpy(&f, h + (size_t)(it - 1) * 8, 4);
+        err = (double)f;
+    } else {
+        std::memcpy(&err, h + (size_t)(it - 1) * 8, 8);
+    }
+    if (c->profiling) c->prof.newton_iterations += it;
+    c->last_iters = it;
+    *iters = it;
+    *final_err = err;
+    *converged = (err <= tol) ? 1 : 0;
+    if (!std::isfinite(err)) return fail(c, DEER_ERR_NONFINITE, "the iteration produced a non-finite value");
+    return DEER_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -348,7 +426,7 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
     c->prof = deer_profile{};
     c->ev_used = 0;
     for (auto& e : c->ev) e = nullptr;
-    hipError_t e = hipHostMalloc(&c->h_err, (size_t)kSlots * 8 + 8, hipHostMallocDefault);
+    hipError_t e = hipHostMalloc(&c->h_err, (size_t)kSlots * 8 + 16, hipHostMallocDefault);
     for (int i = 0; i < 2 * kMaxEvents && e == hipSuccess; ++i) e = hipEventCreate(&c->ev[i]);
     c->batch = env_int("DEER_BATCH", 4);
     c->last_iters = 0;
@@ -365,6 +443,11 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
         return fail(nullptr, DEER_ERR_HIP, msg);
     }
     c->epoch = 1;
+    c->one_launch = false;
+    if (plan.fused && plan.fused_W == 8 && env_int("DEER_ONE_LAUNCH", 1) != 0) {
+        const long long grid = (long long)cfg->B * plan.fused_tiles;
+        c->one_launch = grid <= (long long)gru_newton_capacity(cfg->dtype, cfg->n, cfg->d, plan.fused_L);
+    }
     *out = c;
     return DEER_OK;
 }
@@ -384,6 +467,13 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
     const size_t ybytes = B * T * n * esz;
     char* J = c->ws + c->plan.off_J;
     char* rhs = c->ws + c->plan.off_rhs;
+
+    if (c->one_launch && max_iter >= 1 && max_iter <= kSlots) {
+        bool busy = false;
+        deer_status s1 = eval_one_launch(&busy, c, d_theta, d_x, d_y0, d_y_guess, tol, max_iter, d_y, iters, final_err, converged);
+        if (!busy) return s1;
+        // a workgroup waited too long for the others (the device is shared): solve again launch by launch
+    }
 
     // Iteration k reads buf[k & 1] and writes buf[(k + 1) & 1].  The buffers are ordered so that the
     // iterate expected to be the last one (same count as the previous call on this context) lands in d_y

@@ -59,6 +59,27 @@ struct ScanParams {
 #define DEER_STAMP(p, slot, j, cond) do { } while (0)
 #endif
 
+// Source of the pairs when the GRU cell is evaluated inside the scan: the pair at position e is
+// (J_e | f_e - J_e h_e) with h_e the previous iterate at e-1 (y0 for e = 0), Sec. 3.1 eq. 3 and 5 with the
+// sign folded as in the stand-alone cell kernel.  theta uses that kernel's layout.
+struct GruFeed {
+    const void* theta;
+    const void* x;   // [B][T][d]
+    int d;           // <= DP
+};
+
+// One launch that runs all Newton iterations of a GRU problem (n <= 8) whose tiles are all resident.
+struct NewtonParams {
+    ScanParams scan;           // y0, out, yold = initial guess or nullptr (zeros), shapes, published-word regions,
+                               // epoch of the first iteration (iteration k uses epoch + k), status
+    GruFeed feed;
+    unsigned long long* err;      // [max_iter] 8-byte slots: max|dy| of every iteration (for the host)
+    unsigned long long* barrier;  // [2][workgroups][words per scalar] tagged words, no valid tag on entry
+    int* result;               // number of iterations performed
+    double tol;
+    int max_iter;              // >= 1
+};
+
 enum : unsigned { TILE_INVALID = 0u, TILE_AGGREGATE = 1u, TILE_INCLUSIVE = 2u };
 constexpr unsigned kSpinLimit = 1u << 22;   // polls before a waiting tile gives up
 
@@ -220,6 +241,9 @@ hipError_t launch_scan_mfma(int dtype, int n, const ScanParams& p, hipStream_t s
 int scan_valu_tile(int n, int L, int W);   // scan positions per tile
 // scan with the GRU cell evaluated in place of the loads (forward, n <= 8, d <= 8); p.A / p.bv unused
 bool scan_gru_fused_supported(int dtype, int n, int d, int L, int W);
+// all iterations in one launch: workgroups the current device holds at once (0: no such variant), launcher
+int gru_newton_capacity(int dtype, int n, int d, int L);
+hipError_t launch_gru_newton(int dtype, int n, const NewtonParams& q, hipStream_t s);
 hipError_t launch_scan_gru_fused(int dtype, int n, const ScanParams& p, const void* theta, const void* x, int d,
                                  hipStream_t s);
 int scan_mfma_tile(int dtype, int n);

@@ -215,15 +215,6 @@ __device__ __forceinline__ void load_previous(const S* __restrict__ src, long lo
     }
 }
 
-// Source of the pairs when the GRU cell is evaluated inside the scan: the pair at position e is
-// (J_e | f_e - J_e h_e) with h_e the previous iterate at e-1 (y0 for e = 0), Sec. 3.1 eq. 3 and 5 with the
-// sign folded as in the stand-alone cell kernel.  theta uses that kernel's layout.
-struct GruFeed {
-    const void* theta;
-    const void* x;   // [B][T][d]
-    int d;           // <= DP
-};
-
 // fp32: hardware exp2 and reciprocal (about 1 ulp each).  The absolute error of both functions stays
 // below 3e-7, far inside the convergence tolerance of the fp32 iteration; overflow of exp2 gives the
 // correct limits (1/inf = 0).
@@ -236,33 +227,101 @@ __device__ __forceinline__ float feed_tanh(float a) {
 __device__ __forceinline__ double feed_sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
 __device__ __forceinline__ double feed_tanh(double a) { return tanh(a); }
 
+// Row i of the GRU cell's weights in the layouts the fused step uses
+template <typename S, int N, int DP>
+struct GruRow {
+    S Ur[N], Uz[N], Uc[N];   // rows of the hidden-to-hidden matrices, swizzled
+    S E[N];                  // row i of the identity, swizzled
+    S Wr[DP], Wz[DP], Wc[DP];
+    S br, bz, bc, bh;
+};
+
+template <typename S, int N, int DP>
+__device__ __forceinline__ void load_gru_row(const GruFeed& gf, int i, GruRow<S, N, DP>& w) {
+    const S* __restrict__ th = reinterpret_cast<const S*>(gf.theta);
+    const int d = gf.d;
+    const S* __restrict__ U = th + 3 * N * d;
+    const S* __restrict__ bias = U + 3 * N * N;
+    load_swizzled<S, N>(w.Ur, U + i * N, i);
+    load_swizzled<S, N>(w.Uz, U + (N + i) * N, i);
+    load_swizzled<S, N>(w.Uc, U + (2 * N + i) * N, i);
+#pragma unroll
+    for (int j = 0; j < N; ++j) w.E[j] = (swz_col<N>(j, i) == i) ? S(1) : S(0);
+#pragma unroll
+    for (int k = 0; k < DP; ++k) {
+        const int kc = k < d ? k : d - 1;   // columns past d read a valid one and count as zero
+        const S a = th[i * d + kc], bq = th[(N + i) * d + kc], c = th[(2 * N + i) * d + kc];
+        w.Wr[k] = k < d ? a : S(0);
+        w.Wz[k] = k < d ? bq : S(0);
+        w.Wc[k] = k < d ? c : S(0);
+    }
+    w.br = bias[i]; w.bz = bias[N + i]; w.bc = bias[2 * N + i]; w.bh = bias[3 * N + i];
+}
+
+// input projections W x + b of row i at positions e0 .. e0+L-1 (xb: inputs of the sequence)
+template <typename S, int N, int L, int DP, bool FULL>
+__device__ __forceinline__ void gru_project(const GruRow<S, N, DP>& w, const S* __restrict__ xb, int d, long long T,
+                                            long long e0, S* pr, S* pq, S* pc) {
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        const long long e = (FULL || e0 + l < T) ? e0 + l : T - 1;
+        S ar = w.br, az = w.bz, ac = w.bc;
+#pragma unroll
+        for (int k = 0; k < DP; ++k) {
+            const S xv = xb[e * d + (k < d ? k : d - 1)];
+            ar += w.Wr[k] * xv;
+            az += w.Wz[k] * xv;
+            ac += w.Wc[k] * xv;
+        }
+        pr[l] = ar; pq[l] = az; pc[l] = ac;
+    }
+}
+
+// Rows i of the pairs (J_e | f_e - J_e h_e) at positions e0 .. e0+L-1.  h: entry i of the state in front
+// of the first position; yo: entries i of the previous iterate at these positions (h of the next one).
+template <typename S, int N, int L, int DP, bool FULL>
+__device__ __forceinline__ void gru_rows(const GruRow<S, N, DP>& w, const S* pr, const S* pq, const S* pc, S h,
+                                         const S* yo, long long T, long long e0, S (*Ar)[N], S* be) {
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        S ar = pr[l], az = pq[l], ac = pc[l], q = w.bh;
+        row_dots<S, N, 1>(w.Ur, &h, &ar);
+        row_dots<S, N, 1>(w.Uz, &h, &az);
+        row_dots<S, N, 1>(w.Uc, &h, &q);
+        const S r = feed_sigmoid(ar), z = feed_sigmoid(az);
+        const S c = feed_tanh(ac + r * q);
+        const S f = (S(1) - z) * c + z * h;
+        const S pz = (h - c) * z * (S(1) - z);
+        const S sc = (S(1) - z) * (S(1) - c * c);
+        const S sr = sc * r;
+        const S st = sc * q * r * (S(1) - r);
+        S Jrow[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) Jrow[j] = pz * w.Uz[j] + (sr * w.Uc[j] + (st * w.Ur[j] + z * w.E[j]));
+        S Jh = S(0);
+        row_dots<S, N, 1>(Jrow, &h, &Jh);
+        if constexpr (FULL) {
+#pragma unroll
+            for (int j = 0; j < N; ++j) Ar[l][j] = Jrow[j];
+            be[l] = f - Jh;
+        } else {
+            const bool past = e0 + l >= T;
+#pragma unroll
+            for (int j = 0; j < N; ++j) Ar[l][j] = past ? w.E[j] : Jrow[j];
+            be[l] = past ? S(0) : f - Jh;
+        }
+        h = yo[l];
+    }
+}
+
 // The pairs of positions e0 .. e0+L-1 from the GRU cell.  yo: previous iterate at these positions
 // (already requested); oldb: previous iterate of the sequence; DP: input width the x loops are unrolled for.
 template <typename S, int N, int L, int DP, bool FULL>
 __device__ __forceinline__ void gru_pairs(const GruFeed& gf, const S* __restrict__ y0p, const S* __restrict__ oldb,
                                           int b, long long T, long long e0, int i, const S* yo, S (*Ar)[N], S* be) {
-    // row i of the cell's weights
-    const S* __restrict__ th = reinterpret_cast<const S*>(gf.theta);
-    const int d = gf.d;
-    const S* __restrict__ U = th + 3 * N * d;
-    const S* __restrict__ bias = U + 3 * N * N;
-    S Ur[N], Uz[N], Uc[N], Wr[DP], Wz[DP], Wc[DP];
-    load_swizzled<S, N>(Ur, U + i * N, i);
-    load_swizzled<S, N>(Uz, U + (N + i) * N, i);
-    load_swizzled<S, N>(Uc, U + (2 * N + i) * N, i);
-    S E[N];   // row i of the identity, swizzled
-#pragma unroll
-    for (int j = 0; j < N; ++j) E[j] = (swz_col<N>(j, i) == i) ? S(1) : S(0);
-#pragma unroll
-    for (int k = 0; k < DP; ++k) {
-        const int kc = k < d ? k : d - 1;   // columns past d read a valid one and count as zero
-        const S a = th[i * d + kc], bq = th[(N + i) * d + kc], c = th[(2 * N + i) * d + kc];
-        Wr[k] = k < d ? a : S(0);
-        Wz[k] = k < d ? bq : S(0);
-        Wc[k] = k < d ? c : S(0);
-    }
-    const S br = bias[i], bz = bias[N + i], bc = bias[2 * N + i], bh = bias[3 * N + i];
-    const S* __restrict__ xb = reinterpret_cast<const S*>(gf.x) + (long long)b * T * d;
+    GruRow<S, N, DP> w;
+    load_gru_row<S, N, DP>(gf, i, w);
+    const S* __restrict__ xb = reinterpret_cast<const S*>(gf.x) + (long long)b * T * gf.d;
     // state in front of the first position of this group
     S h;
     {
@@ -274,49 +333,8 @@ __device__ __forceinline__ void gru_pairs(const GruFeed& gf, const S* __restrict
     // input projections of all positions first: their loads are all in flight before the
     // cross-lane products start (those are opaque to the scheduler, loads do not move across them)
     S pr[L], pq[L], pc[L];
-#pragma unroll
-    for (int l = 0; l < L; ++l) {
-        const long long e = (FULL || e0 + l < T) ? e0 + l : T - 1;
-        S ar = br, az = bz, ac = bc;
-#pragma unroll
-        for (int k = 0; k < DP; ++k) {
-            const S xv = xb[e * d + (k < d ? k : d - 1)];
-            ar += Wr[k] * xv;
-            az += Wz[k] * xv;
-            ac += Wc[k] * xv;
-        }
-        pr[l] = ar; pq[l] = az; pc[l] = ac;
-    }
-#pragma unroll
-    for (int l = 0; l < L; ++l) {
-        S ar = pr[l], az = pq[l], ac = pc[l], q = bh;
-        row_dots<S, N, 1>(Ur, &h, &ar);
-        row_dots<S, N, 1>(Uz, &h, &az);
-        row_dots<S, N, 1>(Uc, &h, &q);
-        const S r = feed_sigmoid(ar), z = feed_sigmoid(az);
-        const S c = feed_tanh(ac + r * q);
-        const S f = (S(1) - z) * c + z * h;
-        const S pz = (h - c) * z * (S(1) - z);
-        const S sc = (S(1) - z) * (S(1) - c * c);
-        const S sr = sc * r;
-        const S st = sc * q * r * (S(1) - r);
-        S Jrow[N];
-#pragma unroll
-        for (int j = 0; j < N; ++j) Jrow[j] = pz * Uz[j] + (sr * Uc[j] + (st * Ur[j] + z * E[j]));
-        S Jh = S(0);
-        row_dots<S, N, 1>(Jrow, &h, &Jh);
-        if constexpr (FULL) {
-#pragma unroll
-            for (int j = 0; j < N; ++j) Ar[l][j] = Jrow[j];
-            be[l] = f - Jh;
-        } else {
-            const bool past = e0 + l >= T;
-#pragma unroll
-            for (int j = 0; j < N; ++j) Ar[l][j] = past ? E[j] : Jrow[j];
-            be[l] = past ? S(0) : f - Jh;
-        }
-        h = yo[l];
-    }
+    gru_project<S, N, L, DP, FULL>(w, xb, gf.d, T, e0, pr, pq, pc);
+    gru_rows<S, N, L, DP, FULL>(w, pr, pq, pc, h, yo, T, e0, Ar, be);
 }
 
 // Inclusive log-step scan over the groups of a wavefront.  (M | v): this group's pair, lane i holds
@@ -345,67 +363,33 @@ __device__ __forceinline__ void scan_groups(S* M, S& v, int group, int i, int ng
     }
 }
 
-// DP = 0: pairs are read from p.A / p.bv.  DP > 0: pairs come from the GRU cell (forward scans only),
-// DP being the input width the x loops are unrolled for.
-template <typename S, int N, int L, int W, bool REV, int DP>
-__global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed gf) {
-    static_assert(DP == 0 || !REV, "the fused cell feeds forward scans only");
-    constexpr int NG = 64 / N;        // groups per wavefront
-    constexpr int TILE = W * NG * L;  // scan positions per tile
+// LDS of one tile
+template <typename S, int N, int W>
+struct TileShared {
+    S M[W][N * N];    // wavefront totals
+    S v[W][N];
+    S EM[W][N * N];   // prefix in front of each wavefront (exclusive)
+    S Ev[W][N];
+    S carry[N];       // state entering the tile
+};
+
+// Steps 1b-4 of a tile: composition of the group's L pairs, the scans inside the tile, publication of
+// the tile total and the look-back along sequence b (tile t of p.tiles; tags carry `epoch`).  Called by
+// all threads of the workgroup; contains two barriers.  On return sh.carry holds the state entering
+// the tile and (Pex | pex) the prefix of this group inside its wavefront (row i, swizzled).
+template <typename S, int N, int L, int W>
+__device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N, W>& sh, const S (*Ar)[N], const S* be,
+                                           int b, int t, unsigned epoch, S* Pex, S& pex) {
+    constexpr int NG = 64 / N;
     constexpr int WS = TaggedWords<S>::per_scalar;
     constexpr int AGG_WORDS = (N * N + N) * WS;   // words of one published tile total
     static_assert(NG >= W, "wavefront 0 scans one wavefront total per group");
-
-    __shared__ unsigned s_ticket;
-    __shared__ S sM[W][N * N];    // wavefront totals
-    __shared__ S sv[W][N];
-    __shared__ S sEM[W][N * N];   // prefix in front of each wavefront (exclusive)
-    __shared__ S sEv[W][N];
-    __shared__ S sCarry[N];
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int group = lane / N;
     const int i = lane % N;
-
-    // the ticket and the gate's error word are requested together: one memory round trip, not two
-    // (with a closed gate every workgroup of the launch returns, so the drawn tickets do not matter)
-    unsigned drawn = 0u;
-    if (tid == 0) drawn = atomicAdd(p.ticket, 1u);
-    const bool closed = gate_closed<S>(p.gate);
-    if (tid == 0) s_ticket = drawn;
-    __syncthreads();
-    if (closed) return;
-    const unsigned tk = s_ticket;
-    const int b = (int)(tk % (unsigned)p.B);
-    const int t = (int)(tk / (unsigned)p.B);
-    if (t >= p.tiles) return;
-
-    const S* __restrict__ Ab = reinterpret_cast<const S*>(p.A) + (long long)b * p.strideA;
-    const S* __restrict__ bb = reinterpret_cast<const S*>(p.bv) + (long long)b * p.strideb;
-    S* __restrict__ ob = reinterpret_cast<S*>(p.out) + (long long)b * p.strideOut;
-    const S* __restrict__ oldb =
-        p.yold ? reinterpret_cast<const S*>(p.yold) + (long long)b * p.strideOld : nullptr;
-    const long long T = p.T;
-    const long long e0 = (long long)t * TILE + (long long)(wave * NG + group) * L;
     const long long slot = (long long)b * p.tiles + t;
-    DEER_STAMP(p, slot, 0, tid == 0);
-
-    // ---- 1. this group's pairs (kept for the second walk), then their composition ----
-    // A tile that lies completely inside the sequence takes the FULL variants: one base address with
-    // constant offsets and no end-of-sequence handling.
-    const bool full = (long long)(t + 1) * TILE <= T && (!REV || t > 0);
-    S Ar[L][N], be[L], yo[L];
-    if (full) {
-        if constexpr (DP == 0) load_pairs<S, N, L, REV, true>(Ab, bb, T, e0, i, Ar, be);
-        load_previous<S, N, L, REV, true>(oldb ? oldb : bb, T, e0, i, yo);
-        if constexpr (DP > 0) gru_pairs<S, N, L, DP, true>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
-    } else {
-        if constexpr (DP == 0) load_pairs<S, N, L, REV, false>(Ab, bb, T, e0, i, Ar, be);
-        load_previous<S, N, L, REV, false>(oldb ? oldb : bb, T, e0, i, yo);
-        if constexpr (DP > 0) gru_pairs<S, N, L, DP, false>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
-    }
     S M[N], v;
 #pragma unroll
     for (int c = 0; c < N; ++c) M[c] = (c == i) ? S(1) : S(0);
@@ -417,10 +401,9 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     scan_groups<S, N>(M, v, group, i, NG);
     if (group == NG - 1) {
 #pragma unroll
-        for (int c = 0; c < N; ++c) sM[wave][i * N + c] = M[c];
-        sv[wave][i] = v;
+        for (int c = 0; c < N; ++c) sh.M[wave][i * N + c] = M[c];
+        sh.v[wave][i] = v;
     }
-    S Pex[N], pex;   // exclusive prefix of this group inside its wavefront (row i, swizzled)
     {
         S nat[N];
 #pragma unroll
@@ -444,21 +427,21 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
             const int gw = has ? group : W - 1;
 #pragma unroll
             for (int c = 0; c < N; ++c) {
-                const S u = sM[gw][i * N + c];
+                const S u = sh.M[gw][i * N + c];
                 Mt[c] = has ? u : ((c == i) ? S(1) : S(0));
             }
-            const S u = sv[gw][i];
+            const S u = sh.v[gw][i];
             vt = has ? u : S(0);
         }
         scan_groups<S, N>(Mt, vt, group, i, W);
         // group g now holds the prefix through wavefront g: it is the prefix in front of wavefront g+1
         if (group < W - 1) {
 #pragma unroll
-            for (int c = 0; c < N; ++c) sEM[group + 1][i * N + c] = Mt[c];
-            sEv[group + 1][i] = vt;
+            for (int c = 0; c < N; ++c) sh.EM[group + 1][i * N + c] = Mt[c];
+            sh.Ev[group + 1][i] = vt;
         }
-        const unsigned tagA = (p.epoch << 2) | TILE_AGGREGATE;
-        const unsigned tagI = (p.epoch << 2) | TILE_INCLUSIVE;
+        const unsigned tagA = (epoch << 2) | TILE_AGGREGATE;
+        const unsigned tagI = (epoch << 2) | TILE_INCLUSIVE;
         const unsigned long long* aggSeq = p.aggW + (long long)b * p.tiles * AGG_WORDS;
         const unsigned long long* inclSeq = p.inclW + (long long)b * p.tiles * (N * WS);
         if (t > 0 && group == W - 1) {
@@ -551,10 +534,10 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
 #ifdef DEER_SCAN_TIMING
         if (p.timing && lane == 0) p.timing[slot * 8 + 7] = (unsigned long long)(k < 0 ? 0 : k);
 #endif
-        if (group == 0) sCarry[i] = y;
+        if (group == 0) sh.carry[i] = y;
         // inclusive carry of this tile: (tile total) applied to the carry
         if (group == W - 1) {
-            const S c = sCarry[i];
+            const S c = sh.carry[i];
             S left[N];
             swizzle_row<S, N>(Mt, left, i);
             TaggedWords<S>::put(p.inclW + slot * (N * WS), i, group_matvec<S, N>(left, vt, c), tagI);
@@ -563,15 +546,82 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     }
     __syncthreads();
 
-    // ---- 5. starting state of this group, then the second walk over the resident pairs ----
-    S y = sCarry[i];
+}
+
+// Step 5a: the state in front of this group's first position (entry i), from the tile's carry
+template <typename S, int N, int W>
+__device__ __forceinline__ S tile_start_state(const TileShared<S, N, W>& sh, const S* Pex, S pex, int wave, int i) {
+    S y = sh.carry[i];
     if (wave > 0) {
         S row[N];
 #pragma unroll
-        for (int c = 0; c < N; ++c) row[c] = sEM[wave][i * N + swz_col<N>(c, i)];
-        y = group_matvec<S, N>(row, sEv[wave][i], y);
+        for (int c = 0; c < N; ++c) row[c] = sh.EM[wave][i * N + swz_col<N>(c, i)];
+        y = group_matvec<S, N>(row, sh.Ev[wave][i], y);
     }
     y = group_matvec<S, N>(Pex, pex, y);
+
+    return y;
+}
+
+// DP = 0: pairs are read from p.A / p.bv.  DP > 0: pairs come from the GRU cell (forward scans only),
+// DP being the input width the x loops are unrolled for.
+template <typename S, int N, int L, int W, bool REV, int DP>
+__global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed gf) {
+    static_assert(DP == 0 || !REV, "the fused cell feeds forward scans only");
+    constexpr int NG = 64 / N;        // groups per wavefront
+    constexpr int TILE = W * NG * L;  // scan positions per tile
+
+    __shared__ unsigned s_ticket;
+    __shared__ TileShared<S, N, W> sh;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int group = lane / N;
+    const int i = lane % N;
+
+    // the ticket and the gate's error word are requested together: one memory round trip, not two
+    // (with a closed gate every workgroup of the launch returns, so the drawn tickets do not matter)
+    unsigned drawn = 0u;
+    if (tid == 0) drawn = atomicAdd(p.ticket, 1u);
+    const bool closed = gate_closed<S>(p.gate);
+    if (tid == 0) s_ticket = drawn;
+    __syncthreads();
+    if (closed) return;
+    const unsigned tk = s_ticket;
+    const int b = (int)(tk % (unsigned)p.B);
+    const int t = (int)(tk / (unsigned)p.B);
+    if (t >= p.tiles) return;
+
+    const S* __restrict__ Ab = reinterpret_cast<const S*>(p.A) + (long long)b * p.strideA;
+    const S* __restrict__ bb = reinterpret_cast<const S*>(p.bv) + (long long)b * p.strideb;
+    S* __restrict__ ob = reinterpret_cast<S*>(p.out) + (long long)b * p.strideOut;
+    const S* __restrict__ oldb =
+        p.yold ? reinterpret_cast<const S*>(p.yold) + (long long)b * p.strideOld : nullptr;
+    const long long T = p.T;
+    const long long e0 = (long long)t * TILE + (long long)(wave * NG + group) * L;
+    const long long slot = (long long)b * p.tiles + t;
+    DEER_STAMP(p, slot, 0, tid == 0);
+
+    // ---- 1. this group's pairs (kept for the second walk), then their composition ----
+    // A tile that lies completely inside the sequence takes the FULL variants: one base address with
+    // constant offsets and no end-of-sequence handling.
+    const bool full = (long long)(t + 1) * TILE <= T && (!REV || t > 0);
+    S Ar[L][N], be[L], yo[L];
+    if (full) {
+        if constexpr (DP == 0) load_pairs<S, N, L, REV, true>(Ab, bb, T, e0, i, Ar, be);
+        load_previous<S, N, L, REV, true>(oldb ? oldb : bb, T, e0, i, yo);
+        if constexpr (DP > 0) gru_pairs<S, N, L, DP, true>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
+    } else {
+        if constexpr (DP == 0) load_pairs<S, N, L, REV, false>(Ab, bb, T, e0, i, Ar, be);
+        load_previous<S, N, L, REV, false>(oldb ? oldb : bb, T, e0, i, yo);
+        if constexpr (DP > 0) gru_pairs<S, N, L, DP, false>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
+    }
+    S Pex[N], pex;
+    tile_carry<S, N, L, W>(p, sh, Ar, be, b, t, p.epoch, Pex, pex);
+
+    // ---- 5. starting state of this group, then the second walk over the resident pairs ----
+    S y = tile_start_state<S, N, W>(sh, Pex, pex, wave, i);
 
     S emax = S(0);
 #pragma unroll

@@ -32,7 +32,9 @@ class DeerProfile(ctypes.Structure):
                 ("discretise_ms", ctypes.c_double), ("discretise_launches", ctypes.c_int64),
                 ("scan_ms", ctypes.c_double), ("scan_launches", ctypes.c_int64),
                 ("vjp_ms", ctypes.c_double), ("vjp_launches", ctypes.c_int64),
-                ("fused_ms", ctypes.c_double), ("fused_launches", ctypes.c_int64)]
+                ("fused_ms", ctypes.c_double), ("fused_launches", ctypes.c_int64),
+                ("newton_ms", ctypes.c_double), ("newton_launches", ctypes.c_int64),
+                ("newton_iterations", ctypes.c_int64)]
 
 
 class DeerError(RuntimeError):

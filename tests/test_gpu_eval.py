@@ -100,10 +100,15 @@ def test_nonfinite_input_is_reported():
     {"DEER_FUSED_L": "10"}, {"DEER_FUSED_L": "12"}, {"DEER_FUSED_L": "16"},
     {"DEER_FUSED_L": "4", "DEER_FUSED_W": "4"}, {"DEER_FUSED_L": "10", "DEER_FUSED_W": "4"},
     {"DEER_FUSED_L": "16", "DEER_FUSED_W": "4"},
+    {"DEER_ONE_LAUNCH": "0"},
+    {"DEER_ONE_LAUNCH": "0", "DEER_FUSED_L": "1"}, {"DEER_ONE_LAUNCH": "0", "DEER_FUSED_L": "2"},
+    {"DEER_ONE_LAUNCH": "0", "DEER_FUSED_L": "4"}, {"DEER_ONE_LAUNCH": "0", "DEER_FUSED_L": "8"},
+    {"DEER_ONE_LAUNCH": "0", "DEER_FUSED_L": "12"}, {"DEER_ONE_LAUNCH": "0", "DEER_FUSED_L": "16"},
 ], ids=lambda e: ",".join("%s=%s" % kv for kv in sorted(e.items())))
 def test_kernel_variants_n8(env, monkeypatch):
     # the tuning knobs select other instantiations of the step kernels (positions per lane group,
-    # wavefronts per tile, cell inside or outside the scan); every one must give the same trajectory
+    # wavefronts per tile, cell inside or outside the scan, all iterations in one launch or one launch
+    # per iteration); every one must give the same trajectory
     for k, v in env.items():
         monkeypatch.setenv(k, v)
     for k, (B, T, d) in enumerate([(3, 1100, 4), (2, 4097, 7), (1, 9, 1)]):
@@ -115,8 +120,9 @@ def test_kernel_variants_n8(env, monkeypatch):
 
 
 @pytest.mark.parametrize("n", [2, 4])
-@pytest.mark.parametrize("env", [{"DEER_FUSED": "0"}, {"DEER_FUSED_L": "16"}, {"DEER_FUSED_L": "8", "DEER_FUSED_W": "4"}],
-                         ids=["unfused", "fusedL16", "fusedL8W4"])
+@pytest.mark.parametrize("env", [{"DEER_FUSED": "0"}, {"DEER_FUSED_L": "16"}, {"DEER_FUSED_L": "8", "DEER_FUSED_W": "4"},
+                                 {"DEER_ONE_LAUNCH": "0"}, {"DEER_ONE_LAUNCH": "0", "DEER_FUSED_L": "16"}],
+                         ids=["unfused", "fusedL16", "fusedL8W4", "stepwise", "stepwiseL16"])
 def test_kernel_variants_small_n(n, env, monkeypatch):
     if n == 2 and env.get("DEER_FUSED_W") == "4":
         env = {"DEER_FUSED_L": "8"}   # four wavefronts per tile exist for n >= 4 only
@@ -147,3 +153,25 @@ def test_repeated_calls_on_one_context():
         assert len(set(seen)) > 1
     finally:
         ctx.close()
+
+
+def test_more_tiles_than_the_chip_holds():
+    # too many tiles to be resident at once: the solve runs one launch per iteration (fused step kernel)
+    w = inputs.gru_workload("many_tiles", 31, B=96, T=12000, n=8, d=4)
+    check(w, deer.DEER_F32)
+
+
+def test_one_launch_iteration_control():
+    # small problem: all iterations in one launch; caps, warm start and the recorded error per iteration
+    w = inputs.gru_workload("one_launch_ctl", 6, B=3, T=2500, n=8, d=5)
+    for max_iter in (1, 2, 3):
+        y, it, err, conv, st = gpu_eval(w, max_iter=max_iter)
+        yo, ito, erro, _ = oracle_eval(w, max_iter=max_iter)
+        assert st == deer.DEER_OK and it == max_iter == ito and not conv
+        assert np.abs(y - yo).max() <= 1e-4 and abs(err - erro) <= 1e-4 * max(1.0, erro)
+    yo, _, _, _ = oracle_eval(w, tol=1e-9, max_iter=50)
+    y, it, err, conv, st = gpu_eval(w, guess=yo)
+    assert st == deer.DEER_OK and it == 1 and conv and np.abs(y - yo).max() <= 1e-5
+    # fp64 through the same path
+    w64 = inputs.gru_workload("one_launch_64", 7, B=2, T=1500, n=4, d=2, tol=GOLD["tol_f64"])
+    check(w64, deer.DEER_F64)
