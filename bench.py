@@ -51,12 +51,22 @@ def mlp_flops_per_point(n, width):
     return 2 * chain + 2 * width * width * n + 2 * n * width * n + 4 * width * n
 
 
-def dominant_roofline(kind, ms, w):
+def dominant_roofline(kind, ms, w, newton_iterations=0.0):
     """Roofline entry of the kernel that takes most of a step (durations from HIP events)."""
     from paper_2309_12252_amd import inputs
     ode = w.cell == inputs.CELL_MLP_ODE
     positions = w.B * ((w.T - 1) if (ode and kind != "funceval") else w.T)
     sec = ms * 1e-3
+    if kind == "newton":
+        # the whole solve in one launch: the per-iteration work of the fused step times the iterations it ran;
+        # HBM sees the inputs and the guess once and the result once
+        fl = fused_flops_per_position(w.n, w.d) * positions * newton_iterations
+        a = fl / sec / 1e12
+        return {"bound": "alu", "achieved": round(a, 2), "peak": VALU_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(a / VALU_F32_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": "GRU Newton solve in one launch (n=%d, %g iterations)" % (w.n, newton_iterations),
+                "avg_launch_us": round(1e3 * ms, 2), "algorithmic_flops_per_launch": fl,
+                "hbm_bytes_per_launch": 4 * (w.n + w.d) * positions}
     if kind == "fused":
         fl = fused_flops_per_position(w.n, w.d) * positions
         a = fl / sec / 1e12
@@ -172,10 +182,12 @@ def main():
     torch.cuda.synchronize()
     prof = ctx.profile()
     ctx.set_profiling(False)
-    per_launch = {k: prof[k + "_ms"] / max(1, prof[k + "_launches"]) for k in ("funceval", "discretise", "scan", "fused")}
+    per_launch = {k: prof[k + "_ms"] / max(1, prof[k + "_launches"])
+                  for k in ("funceval", "discretise", "scan", "fused", "newton")}
     totals = {k: prof[k + "_ms"] for k in per_launch}
     dominant = max(totals, key=totals.get)
-    roofline = dominant_roofline(dominant, per_launch[dominant], w)
+    its = prof["newton_iterations"] / max(1, prof["newton_launches"])   # iterations inside a one-launch solve
+    roofline = dominant_roofline(dominant, per_launch[dominant], w, its)
     tpath = os.path.join(ROOT, "profiles", "kernel_traffic.json")
     if os.path.exists(tpath):
         # HBM bytes per launch from the committed rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, calibrated)
