@@ -131,15 +131,18 @@ Plan make_plan(const deer_config* c) {
     if (!ode && !p.mfma && c->d <= 8 && env_int("DEER_FUSED", 1) != 0) {
         // The fused step spends more time per position on arithmetic and none on loading matrices:
         // shorter serial runs than the plain scan, so that more tiles are in flight.
-        static const int kLf[] = {1, 2, 4, 8, 12, 16};
-        const int ncand = c->dtype == DEER_F32 ? 6 : ((c->n == 8) ? 3 : 4);
+        static const int kLf[] = {1, 2, 4, 8, 10, 12, 16};
+        const int ncand = c->dtype == DEER_F32 ? 7 : ((c->n == 8) ? 3 : 4);
         int L = kLf[0];
         double best = 1e300;
         for (int q = 0; q < ncand; ++q) {
             if (!scan_gru_fused_supported(c->dtype, c->n, c->d, kLf[q], 8)) continue;
             const long long tile = scan_valu_tile(c->n, kLf[q], p.W);
             const long long tiles = (long long)B * ((p.scan_T + tile - 1) / tile);
-            const double est = (double)((tiles + 255) / 256) * (5.0 + 1.6 * kLf[q]);
+            // per tile: a fixed part, the serial run (cheaper for small n), and the look-back along the
+            // sequence when it has more than one tile
+            const double per_pos = c->n == 8 ? 1.6 : (c->n == 4 ? 0.8 : 0.5);
+            const double est = (double)((tiles + 255) / 256) * (5.0 + per_pos * kLf[q]) + (tiles > (long long)B ? 4.0 : 0.0);
             if (est < best) { best = est; L = kLf[q]; }
         }
         // tuning knobs: honoured when the requested variant exists
@@ -318,8 +321,9 @@ deer_status eval_one_launch(bool* busy, deer_ctx* c, const void* d_theta, const 
                             int32_t* converged) {
     const deer_config& g = c->cfg;
     const size_t n = (size_t)g.n, T = (size_t)g.T;
-    deer_status st = zero_ctl(c);
-    if (st != DEER_OK) return st;
+    // No clearing launch in front: the kernel draws no tickets, writes every word the host reads, and the
+    // status word is zero unless a previous solve failed (which re-zeroes it below).
+    deer_status st = DEER_OK;
     NewtonParams q{};
     ScanParams& p = q.scan;
     p.y0 = d_y0; p.out = d_y; p.yold = d_y_guess;
@@ -354,8 +358,8 @@ deer_status eval_one_launch(bool* busy, deer_ctx* c, const void* d_theta, const 
     HIPCHK(c, launch_gru_newton(g.dtype, g.n, q, c->stream));
     prof_end(c);
     char* h = reinterpret_cast<char*>(c->h_err);
-    HIPCHK(c, hipMemcpyAsync(h, ctl_err(c, 0), (size_t)max_iter * 8, hipMemcpyDeviceToHost, c->stream));
-    HIPCHK(c, hipMemcpyAsync(h + (size_t)kSlots * 8, ctl_status(c), 8, hipMemcpyDeviceToHost, c->stream));
+    // error slots, status and iteration count are contiguous: one copy
+    HIPCHK(c, hipMemcpyAsync(h, ctl_err(c, 0), (size_t)kSlots * 8 + 8, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
     unsigned status = 0;
     int it = 0;

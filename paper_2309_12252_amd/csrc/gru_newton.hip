@@ -155,7 +155,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         }
         S gm = S(0);
         bool ok = true;
-        for (unsigned j = tid; j < G; j += 64 * W) {
+        for (unsigned j = tid; j < G && G > 1u; j += 64 * W) {   // a single workgroup has nobody to wait for
             S v = S(0);
             unsigned spins = 0;
             while (!TaggedWords<S>::get(bank, j, tagK, v)) {
@@ -169,6 +169,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
             }
             gm = v > gm ? v : gm;
         }
+        if (G == 1u) gm = emax;   // (every wavefront's own maximum; combined across wavefronts below)
         gm = wave_max<S>(gm);
         const bool wave_ok = __ballot(!ok) == 0ull;
         __syncthreads();   // s_red is reused
@@ -234,6 +235,7 @@ int dispatch_n(int op, int L, int d, const NewtonParams* q, hipStream_t s) {
         case 2: return dispatch_nl<S, N, 2>(op, d, q, s);
         case 4: return dispatch_nl<S, N, 4>(op, d, q, s);
         case 8: return dispatch_nl<S, N, 8>(op, d, q, s);
+        case 10: if constexpr (sizeof(S) == 4 && N == 8) return dispatch_nl<S, N, 10>(op, d, q, s); else break;
         case 12: if constexpr (sizeof(S) == 4 && N == 8) return dispatch_nl<S, N, 12>(op, d, q, s); else break;
         case 16: if constexpr (sizeof(S) == 4) return dispatch_nl<S, N, 16>(op, d, q, s); else break;
         default: break;
