@@ -122,7 +122,7 @@ Plan make_plan(const deer_config* c) {
         for (int q = 0; q < ncand; ++q)
             if (forced == cand[q]) L = forced;
         p.L = L;
-        p.tile = scan_valu_tile(c->n, p.L, W);
+        p.tile = scan_valu_tile(c->n, p.L, p.W);
     }
     p.tiles = (p.scan_T + p.tile - 1) / p.tile;
     if (p.tiles < 1) p.tiles = 1;

@@ -636,7 +636,7 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
                 emax = dq > emax ? dq : emax;
                 if (p.delta) w += yo[l];
             }
-            __builtin_nontemporal_store(w, ob + oi);   // streamed out: nothing of it is read again in this launch
+            ob[oi] = w;
         }
     }
     if (p.err) {
