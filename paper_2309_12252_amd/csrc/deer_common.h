@@ -68,6 +68,19 @@ struct GruFeed {
     int d;           // <= DP
 };
 
+// Activations of the fused GRU steps.
+// fp32: hardware exp2 and reciprocal (about 1 ulp each).  The absolute error of both functions stays
+// below 3e-7, far inside the convergence tolerance of the fp32 iteration; overflow of exp2 gives the
+// correct limits (1/inf = 0).
+__device__ __forceinline__ float feed_sigmoid(float a) {
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * a));
+}
+__device__ __forceinline__ float feed_tanh(float a) {
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.88539008177792681f * a));
+}
+__device__ __forceinline__ double feed_sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
+__device__ __forceinline__ double feed_tanh(double a) { return tanh(a); }
+
 // One launch that runs all Newton iterations of a GRU problem (n <= 8) whose tiles are all resident.
 struct NewtonParams {
     ScanParams scan;           // y0, out, yold = initial guess or nullptr (zeros), shapes, published-word regions,
@@ -238,6 +251,9 @@ struct OdeDiscParams {
 
 hipError_t launch_scan_valu(int dtype, int n, const ScanParams& p, hipStream_t s);
 hipError_t launch_scan_mfma(int dtype, int n, const ScanParams& p, hipStream_t s);
+// MFMA scan with the GRU cell evaluated in place of the loads (fp32, forward, n = 16 or 32, d <= 16)
+bool scan_mfma_fused_supported(int dtype, int n, int d);
+hipError_t launch_scan_mfma_fused(int n, const ScanParams& p, const void* theta, const void* x, int d, hipStream_t s);
 int scan_valu_tile(int n, int L, int W);   // scan positions per tile
 // scan with the GRU cell evaluated in place of the loads (forward, n <= 8, d <= 8); p.A / p.bv unused
 bool scan_gru_fused_supported(int dtype, int n, int d, int L, int W);

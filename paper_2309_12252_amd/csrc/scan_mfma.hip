@@ -63,8 +63,12 @@ __device__ __forceinline__ S sum_groups(S v) {
     return v;
 }
 
-template <typename S, int N, int LW, int WAVES, bool REV>
-__global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) {
+// FUSE: the pairs are not loaded but computed from the GRU cell at the previous iterate (p.yold), Sec. 3.1
+// eq. 3 and 5: J in A-operand layout straight from the gate values and the weights (kept in LDS in that
+// layout), rhs = f - J h.  fp32, forward scans only.
+template <typename S, int N, int LW, int WAVES, bool REV, bool FUSE>
+__global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, GruFeed gf) {
+    static_assert(!FUSE || (!REV && sizeof(S) == 4), "the fused cell feeds forward fp32 scans only");
     constexpr int NB = N / 16;
     constexpr int LD = N + 1;   // LDS row stride of a wavefront total
     constexpr int TILE = LW * WAVES;
@@ -82,6 +86,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
     __shared__ S sHop[HOPS][N * LD + N];
     __shared__ int s_k;               // hops between this tile and the nearest known inclusive carry
     __shared__ int s_ok;
+    // fused cell: rows of [U_gate | W_gate (16 columns, zero padded)] per gate, and the four bias vectors
+    constexpr int LDU = N + 16 + 4;
+    __shared__ __align__(16) S sU[FUSE ? 3 : 1][FUSE ? N : 1][FUSE ? LDU : 1];
+    __shared__ S sB[FUSE ? 4 : 1][FUSE ? N : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -89,14 +97,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
     const int g = lane >> 4;
     const int r = lane & 15;
 
-    // the ticket and the gate's error word are requested together: one memory round trip, not two
-    // (with a closed gate every workgroup of the launch returns, so the drawn tickets do not matter)
-    unsigned drawn = 0u;
-    if (tid == 0) drawn = atomicAdd(p.ticket, 1u);
-    const bool closed = gate_closed<S>(p.gate);
-    if (tid == 0) s_ticket = drawn;
+    if (gate_closed<S>(p.gate)) return;
+    if (tid == 0) s_ticket = atomicAdd(p.ticket, 1u);
     __syncthreads();
-    if (closed) return;
     const unsigned tk = s_ticket;
     const int b = (int)(tk % (unsigned)p.B);
     const int t = (int)(tk / (unsigned)p.B);
@@ -110,6 +113,22 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
     const long long e0 = (long long)t * TILE + (long long)wave * LW;
     const long long slot = (long long)b * p.tiles + t;
     DEER_STAMP(p, slot, 0, tid == 0);
+    if constexpr (FUSE) {
+        const S* __restrict__ th = reinterpret_cast<const S*>(gf.theta);
+        const int d = gf.d;
+        const S* __restrict__ U = th + 3 * N * d;
+        const S* __restrict__ bias = U + 3 * N * N;
+        for (int q = tid; q < 3 * N * (N + 16); q += 64 * WAVES) {
+            const int gate = q / (N * (N + 16)), rem = q % (N * (N + 16));
+            const int row = rem / (N + 16), col = rem % (N + 16);
+            S val;
+            if (col < N) val = U[(gate * N + row) * N + col];
+            else val = (col - N < d) ? th[(gate * N + row) * d + (col - N)] : S(0);
+            sU[gate][row][col] = val;
+        }
+        for (int q = tid; q < 4 * N; q += 64 * WAVES) sB[q / N][q % N] = bias[q];
+        __syncthreads();
+    }
 
     // ---- 1a. load this wavefront's pairs ----
     // Branch free on purpose (positions past the end read the last valid one and are then replaced by
@@ -119,7 +138,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
     S bel[LW][NB];        // bel[i][I]     = b_e[16I + r]
     S yo[LW][NB];         // previous iterate at the same positions (for step 4)
 #pragma unroll
-    for (int i = 0; i < LW; ++i) {
+    for (int i = 0; i < (FUSE ? 0 : LW); ++i) {
         const long long e = e0 + i;
         const bool past = e >= p.T;
         const long long ec = past ? (long long)p.T - 1 : e;
@@ -170,6 +189,106 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p) 
         const S* src = oldb ? oldb : bb;   // branch free: without a previous iterate the value is unused
 #pragma unroll
         for (int I = 0; I < NB; ++I) yo[i][I] = src[(REV ? ((long long)p.T - 1 - e) : e) * N + 16 * I + r];
+    }
+
+    if constexpr (FUSE) {
+        const int d = gf.d;
+        const S* __restrict__ xb = reinterpret_cast<const S*>(gf.x) + (long long)b * p.T * d;
+        const S* __restrict__ y0p = reinterpret_cast<const S*>(p.y0);
+        // this lane's part of the inputs: columns 4g .. 4g+3 of x (weights beyond d are zero)
+        S xc[LW][4];
+#pragma unroll
+        for (int i = 0; i < LW; ++i) {
+            const long long e = (e0 + i < p.T) ? e0 + i : (long long)p.T - 1;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int k = 4 * g + v;
+                xc[i][v] = xb[e * d + (k < d ? k : d - 1)];
+            }
+        }
+        // the state in front of every position in column layout (rows of the iterate, 16-byte loads), and
+        // in front of the first one in row layout (the later ones are yo of the position before)
+        S hcol[LW][NB][4];
+        S h0r[NB];
+#pragma unroll
+        for (int i = 0; i < LW; ++i) {
+            const long long e = (e0 + i < p.T) ? e0 + i : (long long)p.T;   // past the end: the last state
+            const S* hp = (e > 0) ? oldb + (e - 1) * N : (y0p ? y0p + (long long)b * N : nullptr);
+#pragma unroll
+            for (int K = 0; K < NB; ++K) {
+                if (hp) vload<S, 4>(hcol[i][K], hp + 16 * K + 4 * g);
+                else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) hcol[i][K][v] = S(0);
+                }
+            }
+            if (i == 0) {
+#pragma unroll
+                for (int I = 0; I < NB; ++I) h0r[I] = hp ? hp[16 * I + r] : S(0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < LW; ++i) {
+            const bool past = e0 + i >= p.T;
+            S pz[NB], sr[NB], st[NB], zz[NB], ff[NB];
+            S Uz[NB][NB][4], Uc[NB][NB][4], Ur[NB][NB][4];
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+                const int row = 16 * I + r;
+                S sar = S(0), saz = S(0), sq = S(0), sxc = S(0);
+#pragma unroll
+                for (int K = 0; K < NB; ++K) {
+                    vload<S, 4>(Ur[I][K], &sU[0][row][16 * K + 4 * g]);
+                    vload<S, 4>(Uz[I][K], &sU[1][row][16 * K + 4 * g]);
+                    vload<S, 4>(Uc[I][K], &sU[2][row][16 * K + 4 * g]);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        sar += Ur[I][K][v] * hcol[i][K][v];
+                        saz += Uz[I][K][v] * hcol[i][K][v];
+                        sq += Uc[I][K][v] * hcol[i][K][v];
+                    }
+                }
+                S wr[4], wz[4], wc[4];
+                vload<S, 4>(wr, &sU[0][row][N + 4 * g]);
+                vload<S, 4>(wz, &sU[1][row][N + 4 * g]);
+                vload<S, 4>(wc, &sU[2][row][N + 4 * g]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    sar += wr[v] * xc[i][v];
+                    saz += wz[v] * xc[i][v];
+                    sxc += wc[v] * xc[i][v];
+                }
+                const S ar = sum_groups<S>(sar) + sB[0][row];
+                const S az = sum_groups<S>(saz) + sB[1][row];
+                const S q = sum_groups<S>(sq) + sB[3][row];
+                const S ac = sum_groups<S>(sxc) + sB[2][row];
+                const S rg = feed_sigmoid(ar), z = feed_sigmoid(az);
+                const S c = feed_tanh(ac + rg * q);
+                const S h = (i == 0) ? h0r[I] : yo[i - 1][I];
+                ff[I] = (S(1) - z) * c + z * h;
+                pz[I] = (h - c) * z * (S(1) - z);
+                const S sc = (S(1) - z) * (S(1) - c * c);
+                sr[I] = sc * rg;
+                st[I] = sc * q * rg * (S(1) - rg);
+                zz[I] = z;
+            }
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+                S jh = S(0);
+#pragma unroll
+                for (int K = 0; K < NB; ++K)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        S jv = pz[I] * Uz[I][K][v] + (sr[I] * Uc[I][K][v] + st[I] * Ur[I][K][v]);
+                        const bool diag = (I == K) && (r == Lay<S>::idx(g, v));
+                        jv += diag ? zz[I] : S(0);
+                        jh += jv * hcol[i][K][v];
+                        a[i][I][K][v] = past ? (diag ? S(1) : S(0)) : jv;
+                    }
+                const S rhs = ff[I] - sum_groups<S>(jh);
+                bel[i][I] = past ? S(0) : rhs;
+            }
+        }
     }
 
     // ---- 1b. serial composition: P <- A_e P (MFMA), vec <- A_e vec + b_e (VALU) ----
@@ -521,9 +640,17 @@ hipError_t launch_n(const ScanParams& p, hipStream_t s) {
     constexpr int LW = MfmaShape<S, N>::LW, WAVES = MfmaShape<S, N>::WAVES;
     dim3 grid((unsigned)((long long)p.B * p.tiles));
     if (p.reverse)
-        hipLaunchKernelGGL((scan_mfma_kernel<S, N, LW, WAVES, true>), grid, dim3(64 * WAVES), 0, s, p);
+        hipLaunchKernelGGL((scan_mfma_kernel<S, N, LW, WAVES, true, false>), grid, dim3(64 * WAVES), 0, s, p, GruFeed{});
     else
-        hipLaunchKernelGGL((scan_mfma_kernel<S, N, LW, WAVES, false>), grid, dim3(64 * WAVES), 0, s, p);
+        hipLaunchKernelGGL((scan_mfma_kernel<S, N, LW, WAVES, false, false>), grid, dim3(64 * WAVES), 0, s, p, GruFeed{});
+    return hipGetLastError();
+}
+
+template <int N>
+hipError_t launch_fused_n(const ScanParams& p, const GruFeed& gf, hipStream_t s) {
+    constexpr int LW = MfmaShape<float, N>::LW, WAVES = MfmaShape<float, N>::WAVES;
+    dim3 grid((unsigned)((long long)p.B * p.tiles));
+    hipLaunchKernelGGL((scan_mfma_kernel<float, N, LW, WAVES, false, true>), grid, dim3(64 * WAVES), 0, s, p, gf);
     return hipGetLastError();
 }
 
@@ -534,6 +661,14 @@ int scan_mfma_tile(int dtype, int n) {
                                    : MfmaShape<float, 32>::LW * MfmaShape<float, 32>::WAVES;
     return n == 16 ? MfmaShape<double, 16>::LW * MfmaShape<double, 16>::WAVES
                    : MfmaShape<double, 32>::LW * MfmaShape<double, 32>::WAVES;
+}
+
+bool scan_mfma_fused_supported(int dtype, int n, int d) { return dtype == 0 && (n == 16 || n == 32) && d >= 1 && d <= 16; }
+
+hipError_t launch_scan_mfma_fused(int n, const ScanParams& p, const void* theta, const void* x, int d, hipStream_t s) {
+    if (!scan_mfma_fused_supported(0, n, d) || p.reverse || p.delta || !p.yold) return hipErrorInvalidValue;
+    const GruFeed gf{theta, x, d};
+    return n == 16 ? launch_fused_n<16>(p, gf, s) : launch_fused_n<32>(p, gf, s);
 }
 
 hipError_t launch_scan_mfma(int dtype, int n, const ScanParams& p, hipStream_t s) {

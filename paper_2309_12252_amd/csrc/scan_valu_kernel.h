@@ -215,18 +215,6 @@ __device__ __forceinline__ void load_previous(const S* __restrict__ src, long lo
     }
 }
 
-// fp32: hardware exp2 and reciprocal (about 1 ulp each).  The absolute error of both functions stays
-// below 3e-7, far inside the convergence tolerance of the fp32 iteration; overflow of exp2 gives the
-// correct limits (1/inf = 0).
-__device__ __forceinline__ float feed_sigmoid(float a) {
-    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * a));
-}
-__device__ __forceinline__ float feed_tanh(float a) {
-    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.88539008177792681f * a));
-}
-__device__ __forceinline__ double feed_sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
-__device__ __forceinline__ double feed_tanh(double a) { return tanh(a); }
-
 // Row i of the GRU cell's weights in the layouts the fused step uses
 template <typename S, int N, int DP>
 struct GruRow {
@@ -580,14 +568,9 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     const int group = lane / N;
     const int i = lane % N;
 
-    // the ticket and the gate's error word are requested together: one memory round trip, not two
-    // (with a closed gate every workgroup of the launch returns, so the drawn tickets do not matter)
-    unsigned drawn = 0u;
-    if (tid == 0) drawn = atomicAdd(p.ticket, 1u);
-    const bool closed = gate_closed<S>(p.gate);
-    if (tid == 0) s_ticket = drawn;
+    if (gate_closed<S>(p.gate)) return;
+    if (tid == 0) s_ticket = atomicAdd(p.ticket, 1u);
     __syncthreads();
-    if (closed) return;
     const unsigned tk = s_ticket;
     const int b = (int)(tk % (unsigned)p.B);
     const int t = (int)(tk / (unsigned)p.B);

@@ -175,3 +175,13 @@ def test_one_launch_iteration_control():
     # fp64 through the same path
     w64 = inputs.gru_workload("one_launch_64", 7, B=2, T=1500, n=4, d=2, tol=GOLD["tol_f64"])
     check(w64, deer.DEER_F64)
+
+
+@pytest.mark.parametrize("n,d", [(16, 6), (32, 8), (16, 16), (32, 1)])
+@pytest.mark.parametrize("fused", ["1", "0"], ids=["cell_in_scan", "cell_then_scan"])
+def test_kernel_variants_mfma(n, d, fused, monkeypatch):
+    # n = 16, 32 in fp32: the GRU cell inside the MFMA scan (default) or as a kernel of its own
+    monkeypatch.setenv("DEER_FUSED", fused)
+    for k, (B, T) in enumerate([(2, 1), (3, 130), (2, 4100)]):
+        w = inputs.gru_workload("mfma_n%d_T%d" % (n, T), 700 + n + k, B=B, T=T, n=n, d=d)
+        check(w, deer.DEER_F32)
