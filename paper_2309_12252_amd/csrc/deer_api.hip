@@ -193,7 +193,8 @@ struct deer_ctx {
     hipStream_t stream;
     char* ws;
     unsigned epoch;
-    void* h_err;            // pinned: kSlots * 8 bytes of error words, then the status word
+    void* h_err;            // pinned: kSlots * 8 bytes of error words, then the status word and a result word
+    void* d_h_err;          // the same memory as the device sees it
     int batch;              // Newton iterations enqueued per host round trip when nothing better is known
     int last_iters;         // iterations the previous deer_eval() took (0: none yet)
     bool one_launch;        // GRU, n <= 8, every tile resident at once: all iterations run in one launch
@@ -350,11 +351,15 @@ deer_status eval_one_launch(bool* busy, deer_ctx* c, const void* d_theta, const 
     p.status = ctl_status(c);
     p.gate = Gate{nullptr, 0.0};
     q.feed = GruFeed{d_theta, d_x, g.d};
-    q.err = reinterpret_cast<unsigned long long*>(ctl_err(c, 0));
+    // The kernel writes its per-iteration record and the iteration count straight into pinned host memory:
+    // no copy back, the stream synchronisation alone makes them visible.
+    char* h = reinterpret_cast<char*>(c->h_err);
+    q.err = reinterpret_cast<unsigned long long*>(c->d_h_err);
+    q.result = reinterpret_cast<int*>(reinterpret_cast<char*>(c->d_h_err) + (size_t)kSlots * 8 + 4);
     q.barrier = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_barrier);
-    q.result = reinterpret_cast<int*>(ctl_status(c)) + 1;
     q.tol = tol;
     q.max_iter = max_iter;
+    std::memset(h + (size_t)kSlots * 8, 0, 8);
 #ifdef DEER_SCAN_TIMING
     {
         static unsigned long long* dbg = nullptr;
@@ -366,19 +371,31 @@ deer_status eval_one_launch(bool* busy, deer_ctx* c, const void* d_theta, const 
     prof_begin(c, KIND_NEWTON);
     HIPCHK(c, launch_gru_newton(g.dtype, g.n, q, c->stream));
     prof_end(c);
-    char* h = reinterpret_cast<char*>(c->h_err);
-    // error slots, status and iteration count are contiguous: one copy
-    HIPCHK(c, hipMemcpyAsync(h, ctl_err(c, 0), (size_t)kSlots * 8 + 8, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    unsigned status = 0;
     int it = 0;
-    std::memcpy(&status, h + (size_t)kSlots * 8, 4);
     std::memcpy(&it, h + (size_t)kSlots * 8 + 4, 4);
     prof_collect(c);
-    if (status != 0) {
-        HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_ctl, ctl_bytes(), c->stream));
-        *busy = true;
-        return DEER_OK;
+    double last = 0.0;
+    if (it >= 1 && it <= max_iter) {
+        if (g.dtype == DEER_F32) {
+            float f;
+            std::memcpy(&f, h + (size_t)(it - 1) * 8, 4);
+            last = (double)f;
+        } else {
+            std::memcpy(&last, h + (size_t)(it - 1) * 8, 8);
+        }
+    }
+    if (it < 1 || it > max_iter || !std::isfinite(last)) {
+        // either the iteration blew up or a wait ran out: the status word on the device tells which
+        unsigned status = 0;
+        HIPCHK(c, hipMemcpyAsync(h + (size_t)kSlots * 8, ctl_status(c), 4, hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        std::memcpy(&status, h + (size_t)kSlots * 8, 4);
+        if (status != 0) {
+            HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_ctl, ctl_bytes(), c->stream));
+            *busy = true;
+            return DEER_OK;
+        }
     }
     if (it < 1 || it > max_iter) return fail(c, DEER_ERR_HIP, "one-launch solve returned an impossible iteration count");
     double err;
@@ -439,7 +456,9 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
     c->prof = deer_profile{};
     c->ev_used = 0;
     for (auto& e : c->ev) e = nullptr;
-    hipError_t e = hipHostMalloc(&c->h_err, (size_t)kSlots * 8 + 16, hipHostMallocDefault);
+    hipError_t e = hipHostMalloc(&c->h_err, (size_t)kSlots * 8 + 16, hipHostMallocMapped);
+    c->d_h_err = nullptr;
+    if (e == hipSuccess) e = hipHostGetDevicePointer(&c->d_h_err, c->h_err, 0);
     for (int i = 0; i < 2 * kMaxEvents && e == hipSuccess; ++i) e = hipEventCreate(&c->ev[i]);
     c->batch = env_int("DEER_BATCH", 4);
     c->last_iters = 0;

@@ -86,9 +86,10 @@ struct NewtonParams {
     ScanParams scan;           // y0, out, yold = initial guess or nullptr (zeros), shapes, published-word regions,
                                // epoch of the first iteration (iteration k uses epoch + k), status
     GruFeed feed;
-    unsigned long long* err;      // [max_iter] 8-byte slots: max|dy| of every iteration (for the host)
+    unsigned long long* err;      // [max_iter] 8-byte slots: max|dy| of every iteration, for the host (may be
+                                  // host-mapped memory); an infinite entry also stands for a wait that ran out
     unsigned long long* barrier;  // [2][workgroups][words per scalar] tagged words, no valid tag on entry
-    int* result;               // number of iterations performed
+    int* result;               // number of iterations performed (may be host-mapped memory)
     double tol;
     int max_iter;              // >= 1
 };

@@ -86,6 +86,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         h0 = ef > 0 ? a : c0;
     }
 
+    if (tid == 0) sh.failed = 0;   // (the first barrier inside tile_carry orders this before any use)
     const S tol = (S)q.tol;
     int k = 0;
     for (;;) {
@@ -136,6 +137,9 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
             yv[l] = y;
         }
         DEER_STAMP(p, (long long)b * p.tiles + t, 6, tid == 0);
+        // A tile whose look-back gave up has no valid iterate: it reports an infinite change, which stops
+        // every workgroup at this barrier and tells the host to look at the status word.
+        if (sh.failed) emax = S(INFINITY);
         // Grid-wide maximum of this iteration and barrier in one: every workgroup publishes its own
         // maximum as a tagged word in its own slot (plain stores to distinct addresses, no atomic
         // read-modify-write on a shared word), then all threads collect the slots of all workgroups.  The
@@ -183,12 +187,13 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         S e = s_red[0];
 #pragma unroll
         for (int v = 1; v < W; ++v) e = s_red[v] > e ? s_red[v] : e;
-        if (blockIdx.x == 0 && tid == 0) {   // the record for the host
-            if constexpr (sizeof(S) == 4) *reinterpret_cast<float*>(q.err + k) = e;
-            else *reinterpret_cast<double*>(q.err + k) = e;
-        }
         __syncthreads();
         const bool stop = s_stop != 0 || !(e > tol) || e >= S(INFINITY);
+        if (blockIdx.x == 0 && tid == 0) {   // the record for the host (host-visible memory)
+            const S rec = s_stop != 0 ? S(INFINITY) : e;
+            if constexpr (sizeof(S) == 4) *reinterpret_cast<float*>(q.err + k) = rec;
+            else *reinterpret_cast<double*>(q.err + k) = rec;
+        }
 #ifdef DEER_SCAN_TIMING
         if (p.timing && tid == 0) p.timing[((long long)b * p.tiles + t) * 8 + 7] = wall_clock64();
 #endif

@@ -359,6 +359,7 @@ struct TileShared {
     S EM[W][N * N];   // prefix in front of each wavefront (exclusive)
     S Ev[W][N];
     S carry[N];       // state entering the tile
+    int failed;       // set (never cleared) by tile_carry when a bounded wait ran out
 };
 
 // Steps 1b-4 of a tile: composition of the group's L pairs, the scans inside the tile, publication of
@@ -516,7 +517,10 @@ __device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N,
             }
         }
         if (__ballot(!ok) != 0ull) {
-            if (lane == 0) atomicOr(p.status, 1u);
+            if (lane == 0) {
+                atomicOr(p.status, 1u);
+                sh.failed = 1;
+            }
         }
         DEER_STAMP(p, slot, 4, lane == 0);
 #ifdef DEER_SCAN_TIMING
