@@ -67,6 +67,14 @@ def dominant_roofline(kind, ms, w, newton_iterations=0.0):
                 "kernel": "GRU Newton solve in one launch (n=%d, %g iterations)" % (w.n, newton_iterations),
                 "avg_launch_us": round(1e3 * ms, 2), "algorithmic_flops_per_launch": fl,
                 "hbm_bytes_per_launch": 4 * (w.n + w.d) * positions}
+    if kind == "fused" and w.n >= 16:
+        # the GRU step with the cell inside the MFMA scan: the matrix products dominate the arithmetic
+        fl = fused_flops_per_position(w.n, w.d) * positions
+        a = fl / sec / 1e12
+        return {"bound": "mfma", "achieved": round(a, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(a / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": "GRU cell + MFMA affine scan in one launch (n=%d)" % w.n, "avg_launch_us": round(1e3 * ms, 2),
+                "algorithmic_flops_per_launch": fl, "hbm_bytes_per_launch": 4 * (2 * w.n + w.d) * positions}
     if kind == "fused":
         fl = fused_flops_per_position(w.n, w.d) * positions
         a = fl / sec / 1e12
