@@ -55,12 +55,40 @@ template <> struct Lay<double> {
     static __device__ __forceinline__ int idx(int g, int v) { return 4 * v + g; }
 };
 
+// x + (x of the lane 32 away) and x + (x of the lane 16 away) with the gfx950 lane-swap instructions: the
+// swap of a register with itself leaves the lower (even) half in one result and the upper (odd) half in the
+// other, in every lane.  Vector ALU only, no trip through the LDS crossbar.
+__device__ __forceinline__ float plus_lane32(float x) {
+    const unsigned u = __float_as_uint(x);
+    const auto q = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+__device__ __forceinline__ float plus_lane16(float x) {
+    const unsigned u = __float_as_uint(x);
+    const auto q = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+__device__ __forceinline__ double plus_lane32(double x) {
+    const unsigned long long u = (unsigned long long)__double_as_longlong(x);
+    const unsigned lo = (unsigned)u, hi = (unsigned)(u >> 32);
+    const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    return __longlong_as_double((long long)(((unsigned long long)b[0] << 32) | a[0])) +
+           __longlong_as_double((long long)(((unsigned long long)b[1] << 32) | a[1]));
+}
+__device__ __forceinline__ double plus_lane16(double x) {
+    const unsigned long long u = (unsigned long long)__double_as_longlong(x);
+    const unsigned lo = (unsigned)u, hi = (unsigned)(u >> 32);
+    const auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    return __longlong_as_double((long long)(((unsigned long long)b[0] << 32) | a[0])) +
+           __longlong_as_double((long long)(((unsigned long long)b[1] << 32) | a[1]));
+}
+
 // sum over the four lane groups g (lanes r, r+16, r+32, r+48)
 template <typename S>
 __device__ __forceinline__ S sum_groups(S v) {
-    v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 32);
-    return v;
+    return plus_lane32(plus_lane16(v));
 }
 
 // FUSE: the pairs are not loaded but computed from the GRU cell at the previous iterate (p.yold), Sec. 3.1
