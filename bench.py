@@ -108,6 +108,41 @@ def dominant_roofline(kind, ms, w, newton_iterations=0.0):
             "avg_launch_us": round(1e3 * ms, 2), "algorithmic_bytes_per_launch": nbytes}
 
 
+def scan_stream(torch, deer, dev, n, B, T, steps):
+    """deer_linrec_solve alone on a random stream [B, T, n, n] (fp32): duration from HIP events, algorithmic
+    bytes and flop rates against the MI355X peaks."""
+    # the recipe of inputs.scan_inputs (random matrices scaled to spectral norm 0.9), drawn on the device:
+    # a multi-GB stream takes the host generator most of a minute
+    torch.manual_seed(1)
+    dA = torch.randn(B, T, n, n, device=dev)
+    # spectral norms by 12 power iterations (the batched SVD behind matrix_norm does not take millions
+    # of matrices); an estimate from below, so the scaled norms are 0.9 or slightly more
+    v = torch.randn(B, T, n, 1, device=dev)
+    for _ in range(12):
+        v = dA.transpose(-1, -2) @ (dA @ v)
+        v /= torch.linalg.vector_norm(v, dim=-2, keepdim=True)
+    dA *= 0.9 / torch.linalg.vector_norm(dA @ v, dim=-2, keepdim=True)
+    del v
+    db, dy0 = torch.randn(B, T, n, device=dev), torch.randn(B, n, device=dev)
+    cfg = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, B, T, n, d=1)
+    sctx = deer.DeerContext(cfg, device=dev)
+    out = torch.empty((B, T, n), dtype=torch.float32, device=dev)
+    for _ in range(3):
+        sctx.linrec_solve(dA, db, dy0, out=out)
+    sctx.set_profiling(True)
+    for _ in range(steps):
+        sctx.linrec_solve(dA, db, dy0, out=out)
+    prof = sctx.profile()
+    sctx.close()
+    ms = prof["scan_ms"] / max(1, prof["scan_launches"])
+    nbytes = 4 * (n * n + 2 * n) * B * T   # J, b in; y out (no previous iterate in this entry point)
+    flops = scan_flops_per_position(n) * B * T
+    return {"scan_stream": {"n": n, "B": B, "T": T}, "avg_launch_ms": ms, "algorithmic_bytes": nbytes,
+            "achieved_GBs": nbytes / (ms * 1e-3) / 1e9, "frac_of_8TBs": nbytes / (ms * 1e-3) / 8e12,
+            "algorithmic_flops": flops, "achieved_TFLOPs": flops / (ms * 1e-3) / 1e12,
+            "frac_of_mfma_f32_peak": flops / (ms * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,6 +150,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration (1-based), default 2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-scan-kernels", action="store_true",
+                    help="skip the stand-alone measurements of the scan kernels on chip-filling streams")
     ap.add_argument("--scan-stream", type=str, default="",
                     help="n,B,T: time deer_linrec_solve alone on a random stream of that shape and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -143,35 +180,7 @@ def main():
         return
     if args.scan_stream:
         n, B, T = [int(v) for v in args.scan_stream.split(",")]
-        # the recipe of inputs.scan_inputs (random matrices scaled to spectral norm 0.9), drawn on the device:
-        # a multi-GB stream takes the host generator most of a minute
-        torch.manual_seed(1)
-        dA = torch.randn(B, T, n, n, device=dev)
-        # spectral norms by 12 power iterations (the batched SVD behind matrix_norm does not take millions
-        # of matrices); an estimate from below, so the scaled norms are 0.9 or slightly more
-        v = torch.randn(B, T, n, 1, device=dev)
-        for _ in range(12):
-            v = dA.transpose(-1, -2) @ (dA @ v)
-            v /= torch.linalg.vector_norm(v, dim=-2, keepdim=True)
-        dA *= 0.9 / torch.linalg.vector_norm(dA @ v, dim=-2, keepdim=True)
-        del v
-        db, dy0 = torch.randn(B, T, n, device=dev), torch.randn(B, n, device=dev)
-        cfg = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, B, T, n, d=1)
-        sctx = deer.DeerContext(cfg, device=dev)
-        out = torch.empty((B, T, n), dtype=torch.float32, device=dev)
-        for _ in range(3):
-            sctx.linrec_solve(dA, db, dy0, out=out)
-        sctx.set_profiling(True)
-        for _ in range(args.steps):
-            sctx.linrec_solve(dA, db, dy0, out=out)
-        prof = sctx.profile()
-        ms = prof["scan_ms"] / max(1, prof["scan_launches"])
-        nbytes = 4 * (n * n + 2 * n) * B * T   # J, b in; y out (no previous iterate in this entry point)
-        print(json.dumps({"scan_stream": {"n": n, "B": B, "T": T}, "avg_launch_ms": ms, "algorithmic_bytes": nbytes,
-                          "achieved_GBs": nbytes / (ms * 1e-3) / 1e9, "frac_of_8TBs": nbytes / (ms * 1e-3) / 8e12,
-                          "algorithmic_flops": (2 * n ** 3 + 4 * n * n) * B * T,
-                          "achieved_TFLOPs": (2 * n ** 3 + 4 * n * n) * B * T / (ms * 1e-3) / 1e12}))
-        sctx.close()
+        print(json.dumps(scan_stream(torch, deer, dev, n, B, T, args.steps)))
         return
     w = inputs.config(args.config)
     ctx = deer.context_for(w, device=dev)
@@ -226,6 +235,23 @@ def main():
            "kernels_ms_per_launch": per_launch,
            "roofline": roofline}
 
+    if not args.no_scan_kernels:
+        # the scan kernels on their own, on streams that fill the chip: the HBM fraction of the n <= 8 kernel
+        # and the MFMA fraction of the n = 32 kernel (HIP events, 10 launches each)
+        ctx.close()
+        ctx = None
+        torch.cuda.empty_cache()
+        s8 = scan_stream(torch, deer, dev, 8, 16, 400000, 10)
+        torch.cuda.empty_cache()
+        s32 = scan_stream(torch, deer, dev, 32, 16, 100000, 10)
+        torch.cuda.empty_cache()
+        out["scan_kernels"] = {
+            "n8_B16_T400k": {"bound": "hbm", "achieved": round(s8["achieved_GBs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": round(s8["frac_of_8TBs"], 4), "avg_launch_us": round(1e3 * s8["avg_launch_ms"], 1)},
+            "n32_B16_T100k": {"bound": "mfma", "achieved": round(s32["achieved_TFLOPs"], 2), "peak": MFMA_F32_PEAK_TFLOPS,
+                              "unit": "TFLOP/s", "frac": round(s32["frac_of_mfma_f32_peak"], 4),
+                              "hbm_GBs": round(s32["achieved_GBs"], 1), "avg_launch_us": round(1e3 * s32["avg_launch_ms"], 1)}}
+
     if not args.no_cpu_baseline:
         import oracle
         threads = max(1, min(w.B, oracle.max_threads(), 16))
@@ -245,7 +271,8 @@ def main():
         med = float(np.median(times))
         out["cpu_baseline"] = {"value": S / med, "unit": "sequence-steps/s", "cores": threads, "kind": "oracle",
                                "sample": "the full workload (same DEER solve in fp64), median of %d runs" % len(times)}
-    ctx.close()
+    if ctx is not None:
+        ctx.close()
     print(json.dumps(out))
 
 
