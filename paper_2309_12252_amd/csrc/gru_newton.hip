@@ -88,75 +88,49 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
 
     if (tid == 0) sh.failed = 0;   // (the first barrier inside tile_carry orders this before any use)
     const S tol = (S)q.tol;
-    int k = 0;
-    for (;;) {
-        DEER_STAMP(p, (long long)b * p.tiles + t, 0, tid == 0);
-        S Ar[L][N], be[L];
-        {
-            // back from LDS; the indices pass through an opaque statement so that the loads stay inside
-            // the loop (hoisted, the values would hold registers for the whole solve)
-            int ri = i, ti = tid;
-            asm volatile("" : "+v"(ri), "+v"(ti));
-            GruRow<S, N, DP> w;
+    // After an error of e the next one is about e^2 (Newton): below this threshold the coming iteration is
+    // expected to be the last one, and the work for the one after it is not started ahead of the test.
+    const S spec_thr = (S)sqrt(q.tol);
+
+    S Ar[L][N], be[L], Pex[N], pex = S(0), Mt[N], vt = S(0);
 #pragma unroll
-            for (int c = 0; c < N; ++c) {
-                const int col = swz_col<N>(c, i);
-                w.Ur[c] = sU[ri][col];
-                w.Uz[c] = sU[ri][N + col];
-                w.Uc[c] = sU[ri][2 * N + col];
-                w.E[c] = (col == i) ? S(1) : S(0);
-            }
-            w.bh = sU[ri][3 * N];
-            S pr[L], pq[L], pc[L];
+    for (int c = 0; c < N; ++c) Mt[c] = S(0);
+    // First half of an iteration, all inside the workgroup: the pairs from the current iterate (yv, h0), their
+    // composition and the scans inside the tile.  Nothing is published.
+    auto local_half = [&]() {
+        // weights and projections come back from LDS; the indices pass through an opaque statement so that
+        // the loads stay inside the loop (hoisted, the values would hold registers for the whole solve)
+        int ri = i, ti = tid;
+        asm volatile("" : "+v"(ri), "+v"(ti));
+        GruRow<S, N, DP> w;
 #pragma unroll
-            for (int l = 0; l < L; ++l) {
-                pr[l] = sP[3 * l][ti];
-                pq[l] = sP[3 * l + 1][ti];
-                pc[l] = sP[3 * l + 2][ti];
-            }
-            if (full) gru_rows<S, N, L, DP, true>(w, pr, pq, pc, h0, yv, T, e0, Ar, be);
-            else gru_rows<S, N, L, DP, false>(w, pr, pq, pc, h0, yv, T, e0, Ar, be);
+        for (int c = 0; c < N; ++c) {
+            const int col = swz_col<N>(c, i);
+            w.Ur[c] = sU[ri][col];
+            w.Uz[c] = sU[ri][N + col];
+            w.Uc[c] = sU[ri][2 * N + col];
+            w.E[c] = (col == i) ? S(1) : S(0);
         }
-        S Pex[N], pex;
-        // The bases of the published-word regions pass through an opaque statement every iteration: the
-        // look-back's many addresses are then recomputed per iteration instead of being hoisted out of the
-        // loop, where they would occupy registers for the whole solve.
-        ScanParams pk = p;
-        asm volatile("" : "+s"(pk.aggW), "+s"(pk.inclW));
-        tile_carry<S, N, L, W>(pk, sh, Ar, be, b, t, p.epoch + (unsigned)k, Pex, pex);
-        S y = tile_start_state<S, N, W>(sh, Pex, pex, wave, i);
-        h0 = y;   // the new iterate in front of this group's first position
-        S emax = S(0);
+        w.bh = sU[ri][3 * N];
+        S pr[L], pq[L], pc[L];
 #pragma unroll
         for (int l = 0; l < L; ++l) {
-            y = group_matvec<S, N>(Ar[l], be[l], y);
-            if (full || e0 + l < T) {
-                const S dq = abs_or_inf<S>(y - yv[l]);
-                emax = dq > emax ? dq : emax;
-            }
-            yv[l] = y;
+            pr[l] = sP[3 * l][ti];
+            pq[l] = sP[3 * l + 1][ti];
+            pc[l] = sP[3 * l + 2][ti];
         }
-        DEER_STAMP(p, (long long)b * p.tiles + t, 6, tid == 0);
-        // A tile whose look-back gave up has no valid iterate: it reports an infinite change, which stops
-        // every workgroup at this barrier and tells the host to look at the status word.
-        if (sh.failed) emax = S(INFINITY);
-        // Grid-wide maximum of this iteration and barrier in one: every workgroup publishes its own
-        // maximum as a tagged word in its own slot (plain stores to distinct addresses, no atomic
-        // read-modify-write on a shared word), then all threads collect the slots of all workgroups.  The
-        // slots alternate between two banks by iteration parity: nobody can be two iterations ahead of a
-        // workgroup that has not passed the previous barrier.
-        emax = wave_max<S>(emax);
-        if (lane == 0) s_red[wave] = emax;
-        __syncthreads();
-        const unsigned G = gridDim.x;
-        unsigned long long* bank = q.barrier + (size_t)(k & 1) * G * TaggedWords<S>::per_scalar;
-        const unsigned tagK = ((p.epoch + (unsigned)k) << 2) | TILE_INCLUSIVE;
-        if (tid == 0) {
-            S m = s_red[0];
-#pragma unroll
-            for (int v = 1; v < W; ++v) m = s_red[v] > m ? s_red[v] : m;
-            TaggedWords<S>::put(bank, blockIdx.x, m, tagK);
-        }
+        if (full) gru_rows<S, N, L, DP, true>(w, pr, pq, pc, h0, yv, T, e0, Ar, be);
+        else gru_rows<S, N, L, DP, false>(w, pr, pq, pc, h0, yv, T, e0, Ar, be);
+        tile_local<S, N, L, W>(p, sh, Ar, be, b, t, Pex, pex, Mt, vt);
+    };
+
+    const unsigned G = gridDim.x;
+    // Second half of the convergence test of iteration kk: collect the maxima of all workgroups (bounded
+    // wait), record the result for the host, and say whether the solve stops here.
+    S elast = S(INFINITY);
+    auto collect = [&](int kk, S own) -> bool {
+        unsigned long long* bank = q.barrier + (size_t)(kk & 1) * G * TaggedWords<S>::per_scalar;
+        const unsigned tagK = ((p.epoch + (unsigned)kk) << 2) | TILE_INCLUSIVE;
         S gm = S(0);
         bool ok = true;
         for (unsigned j = tid; j < G && G > 1u; j += 64 * W) {   // a single workgroup has nobody to wait for
@@ -173,7 +147,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
             }
             gm = v > gm ? v : gm;
         }
-        if (G == 1u) gm = emax;   // (every wavefront's own maximum; combined across wavefronts below)
+        if (G == 1u) gm = own;   // (every wavefront's own maximum; combined across wavefronts below)
         gm = wave_max<S>(gm);
         const bool wave_ok = __ballot(!ok) == 0ull;
         __syncthreads();   // s_red is reused
@@ -191,14 +165,77 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         const bool stop = s_stop != 0 || !(e > tol) || e >= S(INFINITY);
         if (blockIdx.x == 0 && tid == 0) {   // the record for the host (host-visible memory)
             const S rec = s_stop != 0 ? S(INFINITY) : e;
-            if constexpr (sizeof(S) == 4) *reinterpret_cast<float*>(q.err + k) = rec;
-            else *reinterpret_cast<double*>(q.err + k) = rec;
+            if constexpr (sizeof(S) == 4) *reinterpret_cast<float*>(q.err + kk) = rec;
+            else *reinterpret_cast<double*>(q.err + kk) = rec;
         }
+        elast = e;
+        return stop;
+    };
+
+    // Iteration k = local half, look-back, second walk, test.  The test is split: the workgroup publishes
+    // its maximum right after the walk, and collects everybody's either at once or -- when another iteration
+    // is expected -- only after the local half of that next iteration, which needs nothing from the other
+    // workgroups, publishes nothing and leaves the new iterate alone (so it is simply dropped if the test
+    // says stop).  All conditions are the same in every workgroup.
+    int k = 0;            // iterations whose walk is done
+    bool pending = false; // the test of iteration k-1 has not been collected yet
+    S own = S(0);
+    for (;;) {
+        DEER_STAMP(p, (long long)b * p.tiles + t, 0, tid == 0);
+        local_half();
+        if (pending) {
+            const bool stop = collect(k - 1, own);
+            if (stop || k >= q.max_iter) break;
+        }
+        // The bases of the published-word regions pass through an opaque statement every iteration: the
+        // look-back's many addresses are then recomputed per iteration instead of being hoisted out of the
+        // loop, where they would occupy registers for the whole solve.
+        ScanParams pk = p;
+        asm volatile("" : "+v"(pk.aggW), "+v"(pk.inclW));
+        tile_lookback<S, N, W>(pk, sh, b, t, p.epoch + (unsigned)k, Mt, vt);
+        S y = tile_start_state<S, N, W>(sh, Pex, pex, wave, i);
+        h0 = y;   // the new iterate in front of this group's first position
+        S emax = S(0);
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            y = group_matvec<S, N>(Ar[l], be[l], y);
+            if (full || e0 + l < T) {
+                const S dq = abs_or_inf<S>(y - yv[l]);
+                emax = dq > emax ? dq : emax;
+            }
+            yv[l] = y;
+        }
+        DEER_STAMP(p, (long long)b * p.tiles + t, 6, tid == 0);
+        // A tile whose look-back gave up has no valid iterate: it reports an infinite change, which stops
+        // every workgroup at the test and tells the host to look at the status word.
+        if (sh.failed) emax = S(INFINITY);
+        // First half of the test: every workgroup publishes its own maximum as a tagged word in its own
+        // slot (plain stores to distinct addresses, no atomic read-modify-write on a shared word).  The slots
+        // alternate between two banks by iteration parity: nobody can be two iterations ahead of a workgroup
+        // that has not collected the previous test.  The exchange is also the grid barrier that keeps an
+        // iteration's look-back words from being overwritten while in use.
+        emax = wave_max<S>(emax);
+        own = emax;
+        if (lane == 0) s_red[wave] = emax;
+        __syncthreads();
+        if (tid == 0) {
+            S m = s_red[0];
+#pragma unroll
+            for (int v = 1; v < W; ++v) m = s_red[v] > m ? s_red[v] : m;
+            TaggedWords<S>::put(q.barrier + (size_t)(k & 1) * G * TaggedWords<S>::per_scalar, blockIdx.x, m,
+                                ((p.epoch + (unsigned)k) << 2) | TILE_INCLUSIVE);
+        }
+        ++k;
 #ifdef DEER_SCAN_TIMING
         if (p.timing && tid == 0) p.timing[((long long)b * p.tiles + t) * 8 + 7] = wall_clock64();
 #endif
-        ++k;
-        if (stop || k >= q.max_iter) break;
+        // After an error of e the next one is about e^2 (Newton): with the last known error above the
+        // threshold one more iteration is expected and its local half runs before the collection.
+        pending = (k < q.max_iter) && (elast > spec_thr) && G > 1u;
+        if (!pending) {
+            const bool stop = collect(k - 1, own);
+            if (stop || k >= q.max_iter) break;
+        }
     }
 
     S* __restrict__ ob = reinterpret_cast<S*>(p.out) + (long long)b * p.strideOut;

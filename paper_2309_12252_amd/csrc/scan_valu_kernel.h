@@ -362,16 +362,14 @@ struct TileShared {
     int failed;       // set (never cleared) by tile_carry when a bounded wait ran out
 };
 
-// Steps 1b-4 of a tile: composition of the group's L pairs, the scans inside the tile, publication of
-// the tile total and the look-back along sequence b (tile t of p.tiles; tags carry `epoch`).  Called by
-// all threads of the workgroup; contains two barriers.  On return sh.carry holds the state entering
-// the tile and (Pex | pex) the prefix of this group inside its wavefront (row i, swizzled).
+// Steps 1b-3 of a tile, all inside the workgroup: composition of the group's L pairs, scan over the
+// groups of every wavefront, scan of the wavefront totals by wavefront 0.  Called by all threads (one
+// barrier).  Out: (Pex | pex) the prefix of this group inside its wavefront (row i, swizzled); sh.EM/Ev the
+// prefixes in front of the wavefronts; in wavefront 0, group W-1: (Mt | vt) the tile total (natural order).
 template <typename S, int N, int L, int W>
-__device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N, W>& sh, const S (*Ar)[N], const S* be,
-                                           int b, int t, unsigned epoch, S* Pex, S& pex) {
+__device__ __forceinline__ void tile_local(const ScanParams& p, TileShared<S, N, W>& sh, const S (*Ar)[N], const S* be,
+                                           int b, int t, S* Pex, S& pex, S* Mt, S& vt) {
     constexpr int NG = 64 / N;
-    constexpr int WS = TaggedWords<S>::per_scalar;
-    constexpr int AGG_WORDS = (N * N + N) * WS;   // words of one published tile total
     static_assert(NG >= W, "wavefront 0 scans one wavefront total per group");
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -379,6 +377,7 @@ __device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N,
     const int group = lane / N;
     const int i = lane % N;
     const long long slot = (long long)b * p.tiles + t;
+    (void)slot;
     S M[N], v;
 #pragma unroll
     for (int c = 0; c < N; ++c) M[c] = (c == i) ? S(1) : S(0);
@@ -409,7 +408,6 @@ __device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N,
     // ---- 3. wavefront 0: scan of the wavefront totals; 4. look-back ----
     DEER_STAMP(p, slot, 1, tid == 0);
     if (wave == 0) {
-        S Mt[N], vt;
         {
             // groups beyond the number of wavefronts hold the identity pair
             const bool has = group < W;
@@ -429,6 +427,26 @@ __device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N,
             for (int c = 0; c < N; ++c) sh.EM[group + 1][i * N + c] = Mt[c];
             sh.Ev[group + 1][i] = vt;
         }
+    }
+}
+
+// Step 4 of a tile: publication of the tile total and the look-back along sequence b (tile t of p.tiles;
+// tags carry `epoch`).  Called by all threads; ends with a barrier after which sh.carry holds the state
+// entering the tile.  (Mt | vt): the tile total as left by tile_local.
+template <typename S, int N, int W>
+__device__ __forceinline__ void tile_lookback(const ScanParams& p, TileShared<S, N, W>& sh, int b, int t, unsigned epoch,
+                                              const S* Mt, S vt) {
+    constexpr int NG = 64 / N;
+    constexpr int WS = TaggedWords<S>::per_scalar;
+    constexpr int AGG_WORDS = (N * N + N) * WS;   // words of one published tile total
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int group = lane / N;
+    const int i = lane % N;
+    const long long slot = (long long)b * p.tiles + t;
+    (void)tid;
+    if (wave == 0) {
         const unsigned tagA = (epoch << 2) | TILE_AGGREGATE;
         const unsigned tagI = (epoch << 2) | TILE_INCLUSIVE;
         const unsigned long long* aggSeq = p.aggW + (long long)b * p.tiles * AGG_WORDS;
@@ -538,6 +556,17 @@ __device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N,
     }
     __syncthreads();
 
+}
+
+// Steps 1b-4 in one go (see tile_local and tile_lookback).
+template <typename S, int N, int L, int W>
+__device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N, W>& sh, const S (*Ar)[N], const S* be,
+                                           int b, int t, unsigned epoch, S* Pex, S& pex) {
+    S Mt[N], vt = S(0);
+#pragma unroll
+    for (int c = 0; c < N; ++c) Mt[c] = S(0);
+    tile_local<S, N, L, W>(p, sh, Ar, be, b, t, Pex, pex, Mt, vt);
+    tile_lookback<S, N, W>(p, sh, b, t, epoch, Mt, vt);
 }
 
 // Step 5a: the state in front of this group's first position (entry i), from the tile's carry
