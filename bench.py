@@ -154,6 +154,9 @@ def main():
                     help="skip the stand-alone measurements of the scan kernels on chip-filling streams")
     ap.add_argument("--scan-stream", type=str, default="",
                     help="n,B,T: time deer_linrec_solve alone on a random stream of that shape and exit")
+    ap.add_argument("--grad", action="store_true",
+                    help="time deer_grad (Jacobians at the solution, transposed reverse scan, VJP + parameter "
+                         "reduction) on the chosen GRU configuration and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -190,6 +193,36 @@ def main():
 
     def step():
         return ctx.eval(th, x, y0, tol=w.tol, max_iter=w.max_iter, out=y)
+
+    if args.grad:
+        if w.cell != inputs.CELL_GRU:
+            print("bench.py --grad: GRU configurations only", file=sys.stderr)
+            sys.exit(2)
+        y, iters, err, conv, _ = step()
+        torch.manual_seed(2)
+        g = torch.randn_like(y) / (w.B * w.T)
+        for _ in range(args.warmup):
+            ctx.grad(th, x, y0, y, g)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            ctx.grad(th, x, y0, y, g)
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        ctx.set_profiling(True)
+        for _ in range(args.steps):
+            ctx.grad(th, x, y0, y, g)
+        torch.cuda.synchronize()
+        prof = ctx.profile()
+        per = {k: prof[k + "_ms"] / max(1, prof[k + "_launches"]) for k in ("funceval", "scan", "vjp")}
+        S = w.B * w.T
+        jbytes = 4 * w.n * w.n * S
+        print(json.dumps({"deer_grad": w.name, "ms_per_call": ms, "sequence_steps_per_s": S / (ms * 1e-3),
+                          "kernels_ms_per_launch": per,
+                          "reverse_scan_GBs": 4 * (w.n * w.n + 2 * w.n) * S / (per["scan"] * 1e-3) / 1e9,
+                          "funceval_write_GBs": (jbytes + 4 * w.n * S) / (per["funceval"] * 1e-3) / 1e9}))
+        ctx.close()
+        return
 
     for _ in range(args.warmup):
         _, iters, err, conv, _ = step()

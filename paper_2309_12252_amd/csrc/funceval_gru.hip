@@ -178,7 +178,36 @@ __device__ __forceinline__ S sum_position(S v) {
     return v;
 }
 
-template <typename S, int N>
+// Sum of DP per-lane values over the N lanes of a position when DP <= N: the lanes first halve the number
+// of values they carry while doubling the lanes each value has been summed over (log2 DP rounds, DP - 1
+// shuffles in all), then finish with log2(N / DP) ordinary rounds.  Lane i ends up with the complete sum of
+// value number i / (N / DP).  Fixed order, DP - 1 + log2(N / DP) shuffles instead of DP * log2 N.
+template <typename S, int N, int DP>
+__device__ __forceinline__ S reduce_scatter_position(const S* v, int i) {
+    static_assert(DP <= N, "more values than lanes");
+    S cur[DP];
+#pragma unroll
+    for (int k = 0; k < DP; ++k) cur[k] = v[k];
+    int o = N / 2;
+#pragma unroll
+    for (int m = DP; m > 1; m >>= 1) {
+        const bool up = (i & o) != 0;
+#pragma unroll
+        for (int j = 0; j < m / 2; ++j) {
+            const S keep = up ? cur[j + m / 2] : cur[j];
+            const S send = up ? cur[j] : cur[j + m / 2];
+            cur[j] = keep + __shfl_xor(send, o);
+        }
+        o >>= 1;
+    }
+    S r = cur[0];
+#pragma unroll
+    for (int q = N / DP / 2; q >= 1; q >>= 1) r += __shfl_xor(r, q);
+    return r;
+}
+
+// DP: the input width the x loops are unrolled for (d <= DP)
+template <typename S, int N, int DP>
 __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     S* sW = reinterpret_cast<S*>(smem_raw);
@@ -200,12 +229,12 @@ __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
     load_row_weights<S, N>(theta, d, i, w, sW, ds, tid);
     __syncthreads();
 
-    S aUr[N], aUz[N], aUc[N], aWr[kMaxD], aWz[kMaxD], aWc[kMaxD];
+    S aUr[N], aUz[N], aUc[N], aWr[DP], aWz[DP], aWc[DP];
     S abr = S(0), abz = S(0), abc = S(0), abh = S(0);
 #pragma unroll
     for (int j = 0; j < N; ++j) aUr[j] = aUz[j] = aUc[j] = S(0);
 #pragma unroll
-    for (int k = 0; k < kMaxD; ++k) aWr[k] = aWz[k] = aWc[k] = S(0);
+    for (int k = 0; k < DP; ++k) aWr[k] = aWz[k] = aWc[k] = S(0);
 
     const long long total = (long long)p.B * p.T;
     // every thread of a block runs the same number of passes so that the shuffles below always
@@ -237,17 +266,30 @@ __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
             aUc[j] += dq * h[j];
         }
         abr += dar; abz += daz; abc += dac; abh += dq;
+        S dxp[DP];
 #pragma unroll
-        for (int k = 0; k < kMaxD; ++k) {
+        for (int k = 0; k < DP; ++k) {
+            dxp[k] = S(0);
             if (k < d) {
                 const S xv = xp[k];
                 aWr[k] += dar * xv;
                 aWz[k] += daz * xv;
                 aWc[k] += dac * xv;
-                if (dx) {
-                    S part = sW[(i)*ds + k] * dar + sW[(N + i) * ds + k] * daz + sW[(2 * N + i) * ds + k] * dac;
-                    part = sum_position<S, N>(part);
-                    if (live && i == (k % N)) dx[sc_ * d + k] = part;
+                dxp[k] = sW[(i)*ds + k] * dar + sW[(N + i) * ds + k] * daz + sW[(2 * N + i) * ds + k] * dac;
+            }
+        }
+        if (dx) {
+            if constexpr (DP <= N) {
+                const S tot = reduce_scatter_position<S, N, DP>(dxp, i);
+                const int k = i / (N / DP);
+                if (live && (i % (N / DP)) == 0 && k < d) dx[sc_ * d + k] = tot;
+            } else {
+#pragma unroll
+                for (int k = 0; k < DP; ++k) {
+                    if (k < d) {
+                        const S part = sum_position<S, N>(dxp[k]);
+                        if (live && i == (k % N)) dx[sc_ * d + k] = part;
+                    }
                 }
             }
         }
@@ -268,7 +310,7 @@ __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
     S* __restrict__ prow = reinterpret_cast<S*>(p.partial) + ((long long)blockIdx.x * (kThreads / 64) + (tid >> 6)) * P;
     const bool writer = lane < N;   // the first position group of the wavefront holds the totals
 #pragma unroll
-    for (int k = 0; k < kMaxD; ++k) {
+    for (int k = 0; k < DP; ++k) {
         if (k < d) {
             const S a = sum_same_row<S, N>(aWr[k]), b = sum_same_row<S, N>(aWz[k]), c = sum_same_row<S, N>(aWc[k]);
             if (writer) {
@@ -301,14 +343,36 @@ __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
     }
 }
 
+// Final sum of the per-wavefront partial rows in a fixed order (run-to-run identical): a block of 256
+// threads owns 16 consecutive parameters; thread (g, q) adds the rows g, g+16, g+32, ... of parameter q in
+// that order (eight independent loads in flight at a time), then the 16 strided sums meet in LDS and are
+// added in the order g = 0..15.
 template <typename S>
 __global__ __launch_bounds__(256) void gru_vjp_reduce_kernel(const S* __restrict__ partial, S* __restrict__ dtheta,
                                                              long long P, int rows) {
-    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (q >= P) return;
-    S s = S(0);
-    for (int r = 0; r < rows; ++r) s += partial[(long long)r * P + q];
-    dtheta[q] = s;
+    __shared__ S part[16][17];
+    const int ql = threadIdx.x & 15, g = threadIdx.x >> 4;
+    const long long q = (long long)blockIdx.x * 16 + ql;
+    S acc = S(0);
+    if (q < P) {
+        int r = g;
+        for (; r + 7 * 16 < rows; r += 8 * 16) {
+            S v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = partial[(long long)(r + 16 * u) * P + q];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+        for (; r < rows; r += 16) acc += partial[(long long)r * P + q];
+    }
+    part[g][ql] = acc;
+    __syncthreads();
+    if (g == 0 && q < P) {
+        S s = part[0][ql];
+#pragma unroll
+        for (int u = 1; u < 16; ++u) s += part[u][ql];
+        dtheta[q] = s;
+    }
 }
 
 template <typename S, int N>
@@ -339,11 +403,13 @@ hipError_t launch_fe_s(const GruParams& p, hipStream_t s) {
 template <typename S, int N>
 hipError_t launch_vjp(const GruVjpParams& p, hipStream_t s) {
     const size_t shmem = (size_t)3 * N * (p.d | 1) * sizeof(S);
-    hipLaunchKernelGGL((gru_vjp_kernel<S, N>), dim3((unsigned)p.blocks), dim3(kThreads), shmem, s, p);
+    if (p.d <= 4) hipLaunchKernelGGL((gru_vjp_kernel<S, N, 4>), dim3((unsigned)p.blocks), dim3(kThreads), shmem, s, p);
+    else if (p.d <= 8) hipLaunchKernelGGL((gru_vjp_kernel<S, N, 8>), dim3((unsigned)p.blocks), dim3(kThreads), shmem, s, p);
+    else hipLaunchKernelGGL((gru_vjp_kernel<S, N, 16>), dim3((unsigned)p.blocks), dim3(kThreads), shmem, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const long long P = 3LL * N * p.d + 3LL * N * N + 4LL * N;
-    hipLaunchKernelGGL((gru_vjp_reduce_kernel<S>), dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s,
+    hipLaunchKernelGGL((gru_vjp_reduce_kernel<S>), dim3((unsigned)((P + 15) / 16)), dim3(256), 0, s,
                        reinterpret_cast<const S*>(p.partial), reinterpret_cast<S*>(p.dtheta), P,
                        p.blocks * (kThreads / 64));
     return hipGetLastError();
