@@ -30,7 +30,7 @@ def check_grad(w, g, dtype):
     assert np.array_equal(host(dth), host(dth2))   # the reduction order is fixed: run-to-run identical
 
 
-@pytest.mark.parametrize("n,d", [(1, 1), (2, 2), (4, 3), (8, 4), (16, 6), (32, 8)])
+@pytest.mark.parametrize("n,d", [(1, 1), (2, 2), (4, 3), (8, 4), (16, 6), (32, 8), (2, 7), (4, 16), (8, 12), (32, 16)])
 @pytest.mark.parametrize("dtype", [deer.DEER_F32, deer.DEER_F64])
 def test_small_shapes(n, d, dtype):
     for k, (B, T) in enumerate([(1, 1), (2, 9), (3, 700), (2, 3001)]):
