@@ -109,7 +109,16 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
  *   final_err out err of the last iteration (1e10 if max_iter == 0)
  *   converged out 1 if final_err <= tol else 0.  Not converging is not an error: DEER_OK is returned
  *                 with iters == max_iter (Newton's method may diverge far from the solution, Sec. 3.5).
- * The convergence test is global over batch, time and state.  DEER_ERR_NONFINITE if err is NaN/Inf. */
+ * The convergence test is global over batch, time and state.  DEER_ERR_NONFINITE if err is NaN/Inf.
+ * d_y doubles as one of the two iterate buffers: it is overwritten during the call; d_y_guess may be
+ * the same buffer as d_y.  How the iterations are put on the device does not change the result and is
+ * chosen from the shapes: for the GRU with n <= 8 the cell is evaluated inside the scan kernel (the
+ * Jacobians never reach memory), and when all tiles of the problem fit on the device at once the
+ * whole solve is one kernel launch; for n = 16, 32 in fp32 the cell is evaluated inside the matrix-core
+ * scan; otherwise an iteration is a Jacobian kernel followed by a scan kernel.  Environment variables
+ * read at deer_create() can force the other paths (meant for tests and measurements):
+ * DEER_FUSED=0, DEER_ONE_LAUNCH=0, DEER_FUSED_L, DEER_FUSED_W, DEER_SCAN_L (tile shapes), DEER_BATCH
+ * (iterations enqueued per host round trip). */
 deer_status deer_eval(deer_ctx* ctx, const void* d_theta, const void* d_x, const void* d_y0,
                       const void* d_y_guess, double tol, int32_t max_iter, void* d_y,
                       int32_t* iters, double* final_err, int32_t* converged);
