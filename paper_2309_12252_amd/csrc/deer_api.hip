@@ -271,8 +271,7 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
     p.A = A; p.bv = bv; p.y0 = y0; p.out = out; p.yold = yold;
     p.strideA = strideA; p.strideb = strideb; p.strideOut = strideOut; p.strideOld = strideOut;
     p.B = g.B; p.T = c->plan.scan_T; p.L = c->plan.L; p.tiles = c->plan.tiles; p.reverse = reverse; p.delta = delta;
-    p.epoch = ++c->epoch;
-    if (c->epoch >= (1u << 30)) c->epoch = 0;   // published words are re-zeroed at the next call (zero_ctl)
+    p.epoch = ++c->epoch;   // reserve_epochs() keeps this below 2^30
     p.aggW = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_aggW);
     p.inclW = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_inclW);
     p.W = c->plan.W;
@@ -307,11 +306,23 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
     return e;
 }
 
-deer_status zero_ctl(deer_ctx* c) {
-    HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_ctl, ctl_bytes(), c->stream));
-    if (c->epoch == 0) {   // the epoch counter wrapped: forget everything published so far
+// Tags carry a 30-bit launch epoch.  Before `count` more epochs are handed out: if they would not fit,
+// start again from 1 and clear everything published so far (stale words must not carry a tag that will be
+// used again).  Called at points where no launch of this context is using the published words any more
+// in stream order: the clearing kernel is enqueued on the same stream.
+deer_status reserve_epochs(deer_ctx* c, unsigned count) {
+    if (c->epoch + count + 1u >= (1u << 30)) {
         HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_aggW, c->plan.off_ctl - c->plan.off_aggW, c->stream));
+        c->epoch = 0;
     }
+    return DEER_OK;
+}
+
+// Clears tickets, error slots and the status word; at most kSlots launches follow before the next call.
+deer_status zero_ctl(deer_ctx* c) {
+    deer_status st = reserve_epochs(c, (unsigned)kSlots + 8u);
+    if (st != DEER_OK) return st;
+    HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_ctl, ctl_bytes(), c->stream));
     return DEER_OK;
 }
 
@@ -339,11 +350,8 @@ deer_status eval_one_launch(bool* busy, deer_ctx* c, const void* d_theta, const 
     p.y0 = d_y0; p.out = d_y; p.yold = d_y_guess;
     p.strideOut = (long long)(T * n); p.strideOld = (long long)(T * n);
     p.B = g.B; p.T = g.T; p.L = c->plan.fused_L; p.W = 8; p.tiles = c->plan.fused_tiles;
-    if (c->epoch + (unsigned)max_iter + 1u >= (1u << 30)) {   // not enough epochs left: start over
-        c->epoch = 0;
-        st = zero_ctl(c);
-        if (st != DEER_OK) return st;
-    }
+    st = reserve_epochs(c, (unsigned)max_iter + 1u);
+    if (st != DEER_OK) return st;
     p.epoch = c->epoch + 1;
     c->epoch += (unsigned)max_iter + 1u;
     p.aggW = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_aggW);
@@ -475,6 +483,11 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
         return fail(nullptr, DEER_ERR_HIP, msg);
     }
     c->epoch = 1;
+    {
+        // test hook: start the epoch counter somewhere else (e.g. just below its wrap-around)
+        const int e0 = env_int("DEER_EPOCH0", 0);
+        if (e0 > 0 && (unsigned)e0 < (1u << 30)) c->epoch = (unsigned)e0;
+    }
     c->one_launch = false;
     if (plan.fused && plan.fused_W == 8 && env_int("DEER_ONE_LAUNCH", 1) != 0) {
         const long long grid = (long long)cfg->B * plan.fused_tiles;
@@ -522,9 +535,8 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
         if (d_y_guess != buf[0])
             HIPCHK(c, hipMemcpyAsync(buf[0], d_y_guess, ybytes, hipMemcpyDeviceToDevice, c->stream));
     } else {
-        if (c->epoch == 0) {   // the epoch counter wrapped: forget everything published so far
-            HIPCHK(c, launch_fill_zero(c->ws + c->plan.off_aggW, c->plan.off_ctl - c->plan.off_aggW, c->stream));
-        }
+        st = reserve_epochs(c, (unsigned)kSlots + 8u);
+        if (st != DEER_OK) return st;
         HIPCHK(c, launch_fill_zero2(c->ws + c->plan.off_ctl, ctl_bytes(), buf[0], ybytes, c->stream));
     }
     if (ode) {

@@ -185,3 +185,26 @@ def test_kernel_variants_mfma(n, d, fused, monkeypatch):
     for k, (B, T) in enumerate([(2, 1), (3, 130), (2, 4100)]):
         w = inputs.gru_workload("mfma_n%d_T%d" % (n, T), 700 + n + k, B=B, T=T, n=n, d=d)
         check(w, deer.DEER_F32)
+
+
+@pytest.mark.parametrize("one_launch", ["1", "0"], ids=["one_launch", "stepwise"])
+def test_epoch_counter_wraps(one_launch, monkeypatch):
+    # the tags of the published words carry a 30-bit launch counter; start a context just below its
+    # wrap-around and keep calling across it (forward solves, gradients and plain scans share the counter)
+    monkeypatch.setenv("DEER_EPOCH0", str((1 << 30) - 300))
+    monkeypatch.setenv("DEER_ONE_LAUNCH", one_launch)
+    w = inputs.gru_workload("wrap", 91, B=3, T=2200, n=8, d=4)
+    ref, ito, _, _ = oracle_eval(w)
+    ctx = deer.context_for(w, dtype=deer.DEER_F32, device=DEV)
+    th, x, y0 = dev(w.theta, deer.DEER_F32), dev(w.x, deer.DEER_F32), dev(w.y0, deer.DEER_F32)
+    g = np.random.default_rng(3).standard_normal(ref.shape) / np.sqrt(w.T)
+    dth_o, _, _ = oracle.gru_grad(w.n, w.d, w.theta, w.x, w.y0, ref, g)
+    try:
+        for _ in range(12):
+            y, it, err, conv, st = ctx.eval(th, x, y0, tol=w.tol, max_iter=w.max_iter)
+            assert st == deer.DEER_OK and conv and abs(it - ito) <= 1
+            assert np.abs(host(y) - ref).max() <= 1e-4
+            dth, _, _ = ctx.grad(th, x, y0, dev(ref, deer.DEER_F32), dev(g, deer.DEER_F32))
+            assert np.abs(host(dth) - dth_o).max() <= 1e-4 * max(1.0, np.abs(dth_o).max())
+    finally:
+        ctx.close()
