@@ -178,7 +178,7 @@ Plan make_plan(const deer_config* c) {
     p.off_aggW = take(nt * (n * n + n) * (p.esz / 4) * 8);
     p.off_inclW = take(nt * n * (p.esz / 4) * 8);
     // slots of the one-launch solve's grid barrier (two banks, one tagged scalar per workgroup)
-    p.off_barrier = take(p.fused ? 2 * B * (size_t)p.fused_tiles * (p.esz / 4) * 8 : 0);
+    p.off_barrier = take(p.fused ? 2 * (B * (size_t)p.fused_tiles + 4) * (p.esz / 4) * 8 : 0);   // (+4: test hook)
     p.off_ctl = take((size_t)kSlots * 4 + (size_t)kSlots * 8 + 16);   // tickets, err bits, status
     p.off_partial = take((size_t)p.vjp_blocks * 4 * theta_count(c) * p.esz);
     p.total = off;
@@ -198,6 +198,7 @@ struct deer_ctx {
     int batch;              // Newton iterations enqueued per host round trip when nothing better is known
     int last_iters;         // iterations the previous deer_eval() took (0: none yet)
     bool one_launch;        // GRU, n <= 8, every tile resident at once: all iterations run in one launch
+    unsigned test_spin_limit, test_extra_workgroups;   // test hooks of the one-launch solve's grid barrier
     bool profiling;
     deer_profile prof;
     hipEvent_t ev[2 * kMaxEvents];
@@ -367,6 +368,8 @@ deer_status eval_one_launch(bool* busy, deer_ctx* c, const void* d_theta, const 
     q.barrier = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_barrier);
     q.tol = tol;
     q.max_iter = max_iter;
+    q.spin_limit = c->test_spin_limit;
+    q.extra_workgroups = c->test_extra_workgroups;
     std::memset(h + (size_t)kSlots * 8, 0, 8);
 #ifdef DEER_SCAN_TIMING
     {
@@ -487,6 +490,13 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
         // test hook: start the epoch counter somewhere else (e.g. just below its wrap-around)
         const int e0 = env_int("DEER_EPOCH0", 0);
         if (e0 > 0 && (unsigned)e0 < (1u << 30)) c->epoch = (unsigned)e0;
+    }
+    {
+        // test hooks: make the grid barrier of the one-launch solve give up (it then reports a failure and
+        // deer_eval solves launch by launch)
+        const int sl = env_int("DEER_TEST_SPIN_LIMIT", 0), xw = env_int("DEER_TEST_EXTRA_WORKGROUPS", 0);
+        c->test_spin_limit = sl > 0 ? (unsigned)sl : kSpinLimit;
+        c->test_extra_workgroups = (xw > 0 && xw <= 4) ? (unsigned)xw : 0u;
     }
     c->one_launch = false;
     if (plan.fused && plan.fused_W == 8 && env_int("DEER_ONE_LAUNCH", 1) != 0) {

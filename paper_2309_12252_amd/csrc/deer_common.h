@@ -92,6 +92,9 @@ struct NewtonParams {
     int* result;               // number of iterations performed (may be host-mapped memory)
     double tol;
     int max_iter;              // >= 1
+    unsigned spin_limit;       // polls before a wait in the grid barrier gives up (kSpinLimit in production)
+    unsigned extra_workgroups; // test hook: the barrier also expects this many workgroups that do not exist,
+                               // so it runs into its limit and the failure path can be exercised
 };
 
 enum : unsigned { TILE_INVALID = 0u, TILE_AGGREGATE = 1u, TILE_INCLUSIVE = 2u };

@@ -124,7 +124,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         tile_local<S, N, L, W>(p, sh, Ar, be, b, t, Pex, pex, Mt, vt);
     };
 
-    const unsigned G = gridDim.x;
+    const unsigned G = gridDim.x + q.extra_workgroups;   // (extra: test hook, see NewtonParams)
     // Second half of the convergence test of iteration kk: collect the maxima of all workgroups (bounded
     // wait), record the result for the host, and say whether the solve stops here.
     S elast = S(INFINITY);
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
             unsigned spins = 0;
             while (!TaggedWords<S>::get(bank, j, tagK, v)) {
                 // give up after the bound, or as soon as another workgroup has given up
-                if (++spins > kSpinLimit ||
+                if (++spins > q.spin_limit ||
                     ((spins & 1023u) == 0u && __hip_atomic_load(p.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
                     ok = false;
                     break;

@@ -208,3 +208,25 @@ def test_epoch_counter_wraps(one_launch, monkeypatch):
             assert np.abs(host(dth) - dth_o).max() <= 1e-4 * max(1.0, np.abs(dth_o).max())
     finally:
         ctx.close()
+
+
+def test_one_launch_gives_up_and_the_solve_falls_back(monkeypatch):
+    # The grid barrier of the one-launch solve is told (test hook) to expect a workgroup that does not exist
+    # and to give up after a few polls: every workgroup leaves through the bounded wait, the host sees the
+    # failure and solves launch by launch.  The result is the usual one.
+    monkeypatch.setenv("DEER_TEST_EXTRA_WORKGROUPS", "1")
+    monkeypatch.setenv("DEER_TEST_SPIN_LIMIT", "200")
+    w = inputs.gru_workload("fallback", 17, B=4, T=3000, n=8, d=4)
+    ref, ito, _, _ = oracle_eval(w)
+    ctx = deer.context_for(w, dtype=deer.DEER_F32, device=DEV)
+    th, x, y0 = dev(w.theta, deer.DEER_F32), dev(w.x, deer.DEER_F32), dev(w.y0, deer.DEER_F32)
+    try:
+        ctx.set_profiling(True)
+        for _ in range(3):
+            y, it, err, conv, st = ctx.eval(th, x, y0, tol=w.tol, max_iter=w.max_iter)
+            assert st == deer.DEER_OK and conv and abs(it - ito) <= 1
+            assert np.abs(host(y) - ref).max() <= 1e-4
+        prof = ctx.profile()
+        assert prof["newton_launches"] == 3 and prof["fused_launches"] >= 3 * (ito - 1)
+    finally:
+        ctx.close()
