@@ -159,10 +159,12 @@ Plan make_plan(const deer_config* c) {
         }
     }
     if (!ode && p.mfma && env_int("DEER_FUSED", 1) != 0 && scan_mfma_fused_supported(c->dtype, c->n, c->d)) {
-        p.fused = true;   // the MFMA scan with the cell inside; tile shape as for the plain scan
+        p.fused = true;   // the MFMA scan with the cell inside (its own tile shape)
         p.fused_L = 0;
         p.fused_W = 0;
-        p.fused_tiles = p.tiles;
+        const int ft = scan_mfma_fused_tile(c->n);
+        p.fused_tiles = (p.scan_T + ft - 1) / ft;
+        if (p.fused_tiles < 1) p.fused_tiles = 1;
     }
     p.vjp_blocks = c->cell == DEER_CELL_GRU ? gru_vjp_blocks(c->n, (long long)B * T) : 0;
 
@@ -291,7 +293,8 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
 #endif
     hipError_t e;
     if (fused_theta && c->plan.mfma) {
-        prof_begin(c, KIND_FUSED, iter);   // same tiles as the plain MFMA scan
+        p.tiles = c->plan.fused_tiles;
+        prof_begin(c, KIND_FUSED, iter);
         e = launch_scan_mfma_fused(g.n, p, fused_theta, fused_x, g.d, c->stream);
     } else if (fused_theta) {
         p.L = c->plan.fused_L;

@@ -257,6 +257,7 @@ hipError_t launch_scan_valu(int dtype, int n, const ScanParams& p, hipStream_t s
 hipError_t launch_scan_mfma(int dtype, int n, const ScanParams& p, hipStream_t s);
 // MFMA scan with the GRU cell evaluated in place of the loads (fp32, forward, n = 16 or 32, d <= 16)
 bool scan_mfma_fused_supported(int dtype, int n, int d);
+int scan_mfma_fused_tile(int n);   // scan positions per tile of the fused step
 hipError_t launch_scan_mfma_fused(int n, const ScanParams& p, const void* theta, const void* x, int d, hipStream_t s);
 int scan_valu_tile(int n, int L, int W);   // scan positions per tile
 // scan with the GRU cell evaluated in place of the loads (forward, n <= 8, d <= 8); p.A / p.bv unused

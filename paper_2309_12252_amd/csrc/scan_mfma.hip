@@ -117,7 +117,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     // fused cell: rows of [U_gate | W_gate (16 columns, zero padded)] per gate, and the four bias vectors
     constexpr int LDU = N + 16 + 4;
     __shared__ __align__(16) S sU[FUSE ? 3 : 1][FUSE ? N : 1][FUSE ? LDU : 1];
-    __shared__ S sB[FUSE ? 4 : 1][FUSE ? N : 1];
+    __shared__ __align__(16) S sB[FUSE ? 4 : 1][FUSE ? N : 1];
+    // per wavefront: p_z, s_r, s_t, z and rhs of its LW positions, [scalar][position][row]
+    __shared__ __align__(16) S sS[FUSE ? WAVES : 1][5][FUSE ? LW : 1][FUSE ? N : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -127,20 +129,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
 
     if (gate_closed<S>(p.gate)) return;
     if (tid == 0) s_ticket = atomicAdd(p.ticket, 1u);
-    __syncthreads();
-    const unsigned tk = s_ticket;
-    const int b = (int)(tk % (unsigned)p.B);
-    const int t = (int)(tk / (unsigned)p.B);
-    if (t >= p.tiles) return;
-
-    const S* __restrict__ Ab = reinterpret_cast<const S*>(p.A) + (long long)b * p.strideA;
-    const S* __restrict__ bb = reinterpret_cast<const S*>(p.bv) + (long long)b * p.strideb;
-    S* __restrict__ ob = reinterpret_cast<S*>(p.out) + (long long)b * p.strideOut;
-    const S* __restrict__ oldb =
-        p.yold ? reinterpret_cast<const S*>(p.yold) + (long long)b * p.strideOld : nullptr;
-    const long long e0 = (long long)t * TILE + (long long)wave * LW;
-    const long long slot = (long long)b * p.tiles + t;
-    DEER_STAMP(p, slot, 0, tid == 0);
+    // the cell's weights go to LDS while the ticket is on its way (the barrier below covers both)
     if constexpr (FUSE) {
         const S* __restrict__ th = reinterpret_cast<const S*>(gf.theta);
         const int d = gf.d;
@@ -155,8 +144,21 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
             sU[gate][row][col] = val;
         }
         for (int q = tid; q < 4 * N; q += 64 * WAVES) sB[q / N][q % N] = bias[q];
-        __syncthreads();
     }
+    __syncthreads();
+    const unsigned tk = s_ticket;
+    const int b = (int)(tk % (unsigned)p.B);
+    const int t = (int)(tk / (unsigned)p.B);
+    if (t >= p.tiles) return;
+
+    const S* __restrict__ Ab = reinterpret_cast<const S*>(p.A) + (long long)b * p.strideA;
+    const S* __restrict__ bb = reinterpret_cast<const S*>(p.bv) + (long long)b * p.strideb;
+    S* __restrict__ ob = reinterpret_cast<S*>(p.out) + (long long)b * p.strideOut;
+    const S* __restrict__ oldb =
+        p.yold ? reinterpret_cast<const S*>(p.yold) + (long long)b * p.strideOld : nullptr;
+    const long long e0 = (long long)t * TILE + (long long)wave * LW;
+    const long long slot = (long long)b * p.tiles + t;
+    DEER_STAMP(p, slot, 0, tid == 0);
 
     // ---- 1a. load this wavefront's pairs ----
     // Branch free on purpose (positions past the end read the last valid one and are then replaced by
@@ -220,100 +222,106 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     }
 
     if constexpr (FUSE) {
+        // The cell at all LW positions of this wavefront at once.  Gate pre-activations are products on the
+        // matrix cores with the positions as columns: S_gate = U_gate H, H[:, c] = state in front of position
+        // c, and W_gate X likewise; A operands are read from the weight rows in LDS, B operands are one scalar
+        // of h (or x) per lane and k-step.  The results come in accumulator layout -- lane (g, c) holds rows
+        // 4g..4g+3 (per 16-row block) of position c -- where the gates, f, the three row factors of J, z and
+        // rhs = f - J h are plain elementwise work (J h = p_z (U_z h) + s_r (U_c h) + s_t (U_r h) + z h uses
+        // the same products again).  The five per-row scalars then cross to the layout the composition
+        // needs (lane (., r) <-> row r, one position after the other) through a private LDS slice.
         const int d = gf.d;
         const S* __restrict__ xb = reinterpret_cast<const S*>(gf.x) + (long long)b * p.T * d;
         const S* __restrict__ y0p = reinterpret_cast<const S*>(p.y0);
-        // this lane's part of the inputs: columns 4g .. 4g+3 of x (weights beyond d are zero)
-        S xc[LW][4];
+        S (*sSw)[LW][N] = sS[wave];
 #pragma unroll
-        for (int i = 0; i < LW; ++i) {
-            const long long e = (e0 + i < p.T) ? e0 + i : (long long)p.T - 1;
+        for (int cb = 0; cb < (LW + 15) / 16; ++cb) {
+        const int c = (16 * cb + r < LW) ? 16 * cb + r : LW - 1;   // position handled as a column (lanes beyond LW repeat the last)
+        const long long ecol = e0 + c;
+        const long long ecl = ecol < p.T ? ecol : (long long)p.T;     // past the end: the last state (result unused)
+        const S* hp = (ecl > 0) ? oldb + (ecl - 1) * N : (y0p ? y0p + (long long)b * N : nullptr);
+        const long long exl = ecol < p.T ? ecol : (long long)p.T - 1;
+        S hB[N / 4], xB[4];
+#pragma unroll
+        for (int kk = 0; kk < N / 4; ++kk) hB[kk] = hp ? hp[4 * kk + g] : S(0);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int k = 4 * kk + g;
+            xB[kk] = xb[exl * d + (k < d ? k : d - 1)];   // weights beyond d are zero
+        }
+#pragma unroll
+        for (int I = 0; I < NB; ++I) {
+            Acc uh[3], wx[3];
+#pragma unroll
+            for (int gate = 0; gate < 3; ++gate) {
+                Acc acc = {S(0), S(0), S(0), S(0)};
+#pragma unroll
+                for (int kk = 0; kk < N / 4; ++kk) acc = Mfma<S>::run(sU[gate][16 * I + r][4 * kk + g], hB[kk], acc);
+                uh[gate] = acc;
+                Acc accx = {S(0), S(0), S(0), S(0)};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    if (4 * kk < d) accx = Mfma<S>::run(sU[gate][16 * I + r][N + 4 * kk + g], xB[kk], accx);
+                wx[gate] = accx;
+            }
+            S hrow[4], br[4], bz[4], bc[4], bh[4];
+            if (hp) vload<S, 4>(hrow, hp + 16 * I + 4 * g);
+            else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) hrow[v] = S(0);
+            }
+            vload<S, 4>(br, &sB[0][16 * I + 4 * g]);
+            vload<S, 4>(bz, &sB[1][16 * I + 4 * g]);
+            vload<S, 4>(bc, &sB[2][16 * I + 4 * g]);
+            vload<S, 4>(bh, &sB[3][16 * I + 4 * g]);
+            S o_pz[4], o_sr[4], o_st[4], o_z[4], o_rhs[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int k = 4 * g + v;
-                xc[i][v] = xb[e * d + (k < d ? k : d - 1)];
+                const S rg = feed_sigmoid(uh[0][v] + wx[0][v] + br[v]);
+                const S z = feed_sigmoid(uh[1][v] + wx[1][v] + bz[v]);
+                const S q = uh[2][v] + bh[v];
+                const S cc = feed_tanh(wx[2][v] + bc[v] + rg * q);
+                const S h = hrow[v];
+                const S f = (S(1) - z) * cc + z * h;
+                const S pz = (h - cc) * z * (S(1) - z);
+                const S sc = (S(1) - z) * (S(1) - cc * cc);
+                const S sr = sc * rg;
+                const S st = sc * q * rg * (S(1) - rg);
+                o_pz[v] = pz; o_sr[v] = sr; o_st[v] = st; o_z[v] = z;
+                o_rhs[v] = f - (pz * uh[1][v] + (sr * uh[2][v] + (st * uh[0][v] + z * h)));
+            }
+            if (16 * cb + r < LW) {
+                vstore<S, 4>(&sSw[0][c][16 * I + 4 * g], o_pz);
+                vstore<S, 4>(&sSw[1][c][16 * I + 4 * g], o_sr);
+                vstore<S, 4>(&sSw[2][c][16 * I + 4 * g], o_st);
+                vstore<S, 4>(&sSw[3][c][16 * I + 4 * g], o_z);
+                vstore<S, 4>(&sSw[4][c][16 * I + 4 * g], o_rhs);
             }
         }
-        // the state in front of every position in column layout (rows of the iterate, 16-byte loads), and
-        // in front of the first one in row layout (the later ones are yo of the position before)
-        S hcol[LW][NB][4];
-        S h0r[NB];
-#pragma unroll
-        for (int i = 0; i < LW; ++i) {
-            const long long e = (e0 + i < p.T) ? e0 + i : (long long)p.T;   // past the end: the last state
-            const S* hp = (e > 0) ? oldb + (e - 1) * N : (y0p ? y0p + (long long)b * N : nullptr);
-#pragma unroll
-            for (int K = 0; K < NB; ++K) {
-                if (hp) vload<S, 4>(hcol[i][K], hp + 16 * K + 4 * g);
-                else {
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) hcol[i][K][v] = S(0);
-                }
-            }
-            if (i == 0) {
-#pragma unroll
-                for (int I = 0; I < NB; ++I) h0r[I] = hp ? hp[16 * I + r] : S(0);
-            }
-        }
+        }   // column batches
+        // J of every position in A-operand layout from its row's three factors (weights from LDS in that layout)
 #pragma unroll
         for (int i = 0; i < LW; ++i) {
             const bool past = e0 + i >= p.T;
-            S pz[NB], sr[NB], st[NB], zz[NB], ff[NB];
-            S Uz[NB][NB][4], Uc[NB][NB][4], Ur[NB][NB][4];
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
                 const int row = 16 * I + r;
-                S sar = S(0), saz = S(0), sq = S(0), sxc = S(0);
+                const S pz = sSw[0][i][row], sr = sSw[1][i][row], st = sSw[2][i][row], zz = sSw[3][i][row];
+                const S rhs = sSw[4][i][row];
 #pragma unroll
                 for (int K = 0; K < NB; ++K) {
-                    vload<S, 4>(Ur[I][K], &sU[0][row][16 * K + 4 * g]);
-                    vload<S, 4>(Uz[I][K], &sU[1][row][16 * K + 4 * g]);
-                    vload<S, 4>(Uc[I][K], &sU[2][row][16 * K + 4 * g]);
+                    S Ur[4], Uz[4], Uc[4];
+                    vload<S, 4>(Ur, &sU[0][row][16 * K + 4 * g]);
+                    vload<S, 4>(Uz, &sU[1][row][16 * K + 4 * g]);
+                    vload<S, 4>(Uc, &sU[2][row][16 * K + 4 * g]);
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        sar += Ur[I][K][v] * hcol[i][K][v];
-                        saz += Uz[I][K][v] * hcol[i][K][v];
-                        sq += Uc[I][K][v] * hcol[i][K][v];
-                    }
-                }
-                S wr[4], wz[4], wc[4];
-                vload<S, 4>(wr, &sU[0][row][N + 4 * g]);
-                vload<S, 4>(wz, &sU[1][row][N + 4 * g]);
-                vload<S, 4>(wc, &sU[2][row][N + 4 * g]);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    sar += wr[v] * xc[i][v];
-                    saz += wz[v] * xc[i][v];
-                    sxc += wc[v] * xc[i][v];
-                }
-                const S ar = sum_groups<S>(sar) + sB[0][row];
-                const S az = sum_groups<S>(saz) + sB[1][row];
-                const S q = sum_groups<S>(sq) + sB[3][row];
-                const S ac = sum_groups<S>(sxc) + sB[2][row];
-                const S rg = feed_sigmoid(ar), z = feed_sigmoid(az);
-                const S c = feed_tanh(ac + rg * q);
-                const S h = (i == 0) ? h0r[I] : yo[i - 1][I];
-                ff[I] = (S(1) - z) * c + z * h;
-                pz[I] = (h - c) * z * (S(1) - z);
-                const S sc = (S(1) - z) * (S(1) - c * c);
-                sr[I] = sc * rg;
-                st[I] = sc * q * rg * (S(1) - rg);
-                zz[I] = z;
-            }
-#pragma unroll
-            for (int I = 0; I < NB; ++I) {
-                S jh = S(0);
-#pragma unroll
-                for (int K = 0; K < NB; ++K)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        S jv = pz[I] * Uz[I][K][v] + (sr[I] * Uc[I][K][v] + st[I] * Ur[I][K][v]);
+                        S jv = pz * Uz[v] + (sr * Uc[v] + st * Ur[v]);
                         const bool diag = (I == K) && (r == Lay<S>::idx(g, v));
-                        jv += diag ? zz[I] : S(0);
-                        jh += jv * hcol[i][K][v];
+                        jv += diag ? zz : S(0);
                         a[i][I][K][v] = past ? (diag ? S(1) : S(0)) : jv;
                     }
-                const S rhs = ff[I] - sum_groups<S>(jh);
+                }
                 bel[i][I] = past ? S(0) : rhs;
             }
         }
@@ -674,9 +682,15 @@ hipError_t launch_n(const ScanParams& p, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Tile shapes of the fused step.  n = 16: longer serial runs than the plain scan (the per-tile latencies --
+// ticket, weight fill, first loads -- weigh more than the 4 MFMAs per position), as long as the registers hold.
+template <int N> struct MfmaFusedShape;
+template <> struct MfmaFusedShape<16> { static constexpr int LW = 24, WAVES = 4; };
+template <> struct MfmaFusedShape<32> { static constexpr int LW = 8, WAVES = 8; };
+
 template <int N>
 hipError_t launch_fused_n(const ScanParams& p, const GruFeed& gf, hipStream_t s) {
-    constexpr int LW = MfmaShape<float, N>::LW, WAVES = MfmaShape<float, N>::WAVES;
+    constexpr int LW = MfmaFusedShape<N>::LW, WAVES = MfmaFusedShape<N>::WAVES;
     dim3 grid((unsigned)((long long)p.B * p.tiles));
     hipLaunchKernelGGL((scan_mfma_kernel<float, N, LW, WAVES, false, true>), grid, dim3(64 * WAVES), 0, s, p, gf);
     return hipGetLastError();
@@ -689,6 +703,10 @@ int scan_mfma_tile(int dtype, int n) {
                                    : MfmaShape<float, 32>::LW * MfmaShape<float, 32>::WAVES;
     return n == 16 ? MfmaShape<double, 16>::LW * MfmaShape<double, 16>::WAVES
                    : MfmaShape<double, 32>::LW * MfmaShape<double, 32>::WAVES;
+}
+
+int scan_mfma_fused_tile(int n) {
+    return n == 16 ? MfmaFusedShape<16>::LW * MfmaFusedShape<16>::WAVES : MfmaFusedShape<32>::LW * MfmaFusedShape<32>::WAVES;
 }
 
 bool scan_mfma_fused_supported(int dtype, int n, int d) { return dtype == 0 && (n == 16 || n == 32) && d >= 1 && d <= 16; }
