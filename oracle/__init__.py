@@ -162,6 +162,24 @@ def gru_grad(n, d, theta, x, y0, y, g):
     return dtheta, dx, dy0
 
 
+def mlp_vjp(cell, theta, y, w):
+    """VJP of the MLP field at one point.  Returns (dtheta, dy)."""
+    theta, y, w = _f64(theta), _f64(y), _f64(w)
+    dth, dy = np.zeros(theta.size), np.empty(cell.n)
+    lib().oracle_mlp_vjp(ctypes.byref(cell), _p(theta), _p(y), _p(w), _p(dth), _p(dy))
+    return dth, dy
+
+
+def ode_grad(cell, theta, y, g, t0, t1):
+    """Backward derivative for the ODE form.  y, g: [B,T,n].  Returns (dtheta, dy0 [B,n])."""
+    theta, y, g = _f64(theta), _f64(y), _f64(g)
+    B, T, n = y.shape
+    dth, dy0 = np.empty(theta.size), np.empty((B, n))
+    lib().oracle_ode_grad(ctypes.byref(cell), _p(theta), ctypes.c_long(B), ctypes.c_long(T), ctypes.c_double(t0),
+                          ctypes.c_double(t1), _p(y), _p(g), _p(dth), _p(dy0))
+    return dth, dy0
+
+
 def expm_phi1(A):
     A = _f64(A)
     n = A.shape[0]

@@ -20,6 +20,7 @@
  *     midpoint values of G and z                              Sec. 3.3 eq. 8, 9; Table 3
  *   - associative operator on pairs (Gbar | zbar)             Sec. 3.3 eq. 10
  *   - backward derivative through the dual operator           Sec. 3.1.1 eq. 7
+ *     (recurrence form, and the ODE form on the discretised operator)
  *
  * Readings where the paper is silent (all listed in the design notes):
  *   - GRU cell: gates r, z, candidate c with the reset gate applied after the
@@ -595,6 +596,129 @@ int oracle_ode_deer_eval(const oracle_cell* c, const double* th, long B, long T,
     if (final_err) *final_err = err;
     free(ynew);
     return iter;
+}
+
+/* ------------------------------------- backward derivative for the ODE form -- */
+
+/* Vector-Jacobian product of the MLP field at one point: dth += (df/dtheta)^T w,
+ * dy = (df/dy)^T w.  Reverse-mode sweep through the layers of mlp_forward. */
+static void mlp_vjp(const oracle_cell* c, const double* th, const double* y, const double* w,
+                    double* dth, double* dy) {
+    int n = c->n, wd = c->width, L = c->nhid;
+    int big = (wd > n ? wd : n);
+    double* act = malloc((size_t)(L * wd + 1) * sizeof(double));
+    double* out = malloc((size_t)n * sizeof(double));
+    double* up = malloc((size_t)big * sizeof(double));     /* dL/d(output of the current layer) */
+    double* down = malloc((size_t)big * sizeof(double));   /* dL/d(input of the current layer) */
+    mlp_forward(c, th, y, act, out);
+    /* offsets of the layers inside theta */
+    size_t* off = malloc((size_t)(L + 1) * sizeof(size_t));
+    size_t o = 0;
+    int nin = n;
+    for (int l = 0; l < L; l++) { off[l] = o; o += (size_t)wd * nin + wd; nin = wd; }
+    off[L] = o;
+    /* output layer: f = W_out in + b_out */
+    {
+        const double* in = (L > 0 ? act + (L - 1) * wd : y);
+        const double* Wo = th + off[L];
+        double* dWo = dth + off[L];
+        double* dbo = dWo + (size_t)n * nin;
+        for (int i = 0; i < n; i++) {
+            for (int j = 0; j < nin; j++) dWo[i * nin + j] += w[i] * in[j];
+            dbo[i] += w[i];
+        }
+        for (int j = 0; j < nin; j++) {
+            double sacc = 0.0;
+            for (int i = 0; i < n; i++) sacc += Wo[i * nin + j] * w[i];
+            up[j] = sacc;
+        }
+    }
+    /* hidden layers, last to first: act_l = tanh(W_l in + b_l) */
+    for (int l = L - 1; l >= 0; l--) {
+        int lin = (l == 0 ? n : wd);
+        const double* in = (l == 0 ? y : act + (l - 1) * wd);
+        const double* Wl = th + off[l];
+        double* dWl = dth + off[l];
+        double* dbl = dWl + (size_t)wd * lin;
+        for (int j = 0; j < lin; j++) down[j] = 0.0;
+        for (int i = 0; i < wd; i++) {
+            double dpre = up[i] * (1.0 - act[l * wd + i] * act[l * wd + i]);
+            for (int j = 0; j < lin; j++) {
+                dWl[i * lin + j] += dpre * in[j];
+                down[j] += Wl[i * lin + j] * dpre;
+            }
+            dbl[i] += dpre;
+        }
+        memcpy(up, down, (size_t)lin * sizeof(double));
+    }
+    memcpy(dy, up, (size_t)n * sizeof(double));
+    free(act); free(out); free(up); free(down); free(off);
+}
+
+void oracle_mlp_vjp(const oracle_cell* c, const double* th, const double* y, const double* w,
+                    double* dth, double* dy) {
+    mlp_vjp(c, th, y, w, dth, dy);
+}
+
+/* Backward derivative of a loss L(y_0..y_{T-1}) for dy/dt = f(y, theta) on the grid of
+ * oracle_ode_deer_eval (Sec. 3.1.1 eq. 7 applied to the discretised operator of Sec. 3.3 eq. 8-9).
+ * With G frozen at the trajectory, a perturbation of theta moves the right-hand side by
+ * df_j = (df/dtheta)(y_j) dtheta and the trajectory by
+ *     dy_{j+1} = Gbar_j dy_j + P_j (df_j + df_{j+1})/2,   P_j = dt phi1(-Gc_j dt),  dy_0 = dy0,
+ * so with g_j = dL/dy_j
+ *     lam_{T-1} = g_{T-1},  lam_j = g_j + Gbar_j^T lam_{j+1}                  (dual operator)
+ *     w_j = ( P_j^T lam_{j+1} [j < T-1]  +  P_{j-1}^T lam_j [j > 0] ) / 2
+ *     dL/dtheta = sum_j (df/dtheta)(y_j)^T w_j,    dL/dy0 = lam_0.
+ * This is the derivative eq. 7 defines (the explicit dependence of f on theta pushed through
+ * L_G^{-1}); it differs from the derivative of the discrete solution by O(dt^2), because the latter
+ * also sees Gbar change with theta.  y: [B,T,n] trajectory, g: [B,T,n]; dth is overwritten. */
+void oracle_ode_grad(const oracle_cell* c, const double* th, long B, long T, double t0, double t1,
+                     const double* y, const double* g, double* dth, double* dy0) {
+    int n = c->n;
+    size_t nn = (size_t)n * n;
+    double dt = (t1 - t0) / (double)(T - 1);
+    long nth = oracle_theta_count(c);
+    for (long k = 0; k < nth; k++) dth[k] = 0.0;
+    double* G = malloc((size_t)T * nn * sizeof(double));
+    double* Gbar = malloc((size_t)(T - 1) * nn * sizeof(double));
+    double* P = malloc((size_t)(T - 1) * nn * sizeof(double));
+    double* lam = malloc((size_t)T * n * sizeof(double));
+    double* M = malloc(nn * sizeof(double));
+    double* w = malloc((size_t)n * sizeof(double));
+    double* dyj = malloc((size_t)n * sizeof(double));
+    for (long b = 0; b < B; b++) {
+        const double* yb = y + b * T * n;
+        const double* gb = g + b * T * n;
+        for (long j = 0; j < T; j++) {
+            mlp_jac(c, th, yb + j * n, G + j * nn);
+            for (size_t k = 0; k < nn; k++) G[j * nn + k] = -G[j * nn + k];
+        }
+        for (long j = 0; j + 1 < T; j++) {
+            for (size_t k = 0; k < nn; k++) M[k] = -0.5 * (G[j * nn + k] + G[(j + 1) * nn + k]) * dt;
+            oracle_expm_phi1(n, M, Gbar + j * nn, P + j * nn);
+            for (size_t k = 0; k < nn; k++) P[j * nn + k] *= dt;
+        }
+        memcpy(lam + (T - 1) * n, gb + (T - 1) * n, (size_t)n * sizeof(double));
+        for (long j = T - 2; j >= 0; j--)
+            for (int r = 0; r < n; r++) {
+                double sacc = gb[j * n + r];
+                for (int k = 0; k < n; k++) sacc += Gbar[j * nn + k * n + r] * lam[(j + 1) * n + k];
+                lam[j * n + r] = sacc;
+            }
+        for (long j = 0; j < T; j++) {
+            for (int r = 0; r < n; r++) {
+                double sacc = 0.0;
+                if (j + 1 < T)
+                    for (int k = 0; k < n; k++) sacc += P[j * nn + k * n + r] * lam[(j + 1) * n + k];
+                if (j > 0)
+                    for (int k = 0; k < n; k++) sacc += P[(j - 1) * nn + k * n + r] * lam[j * n + k];
+                w[r] = 0.5 * sacc;
+            }
+            mlp_vjp(c, th, yb + j * n, w, dth, dyj);
+        }
+        memcpy(dy0 + b * n, lam, (size_t)n * sizeof(double));
+    }
+    free(G); free(Gbar); free(P); free(lam); free(M); free(w); free(dyj);
 }
 
 int oracle_max_threads(void) {

@@ -152,3 +152,103 @@ def test_ode_deer_options():
     np.testing.assert_allclose(y2, y, atol=1e-10)
     _, it3, _, _ = oracle.ode_deer_eval(cell, w.theta, w.y0, T, w.t0, w.t1, tol=1e-9, max_iter=2)
     assert it3 == 2
+
+
+# ---- backward derivative for the ODE form (Sec. 3.1.1 eq. 7 on the discretised operator) ----
+
+def test_mlp_vjp_matches_finite_differences():
+    w, cell = small_ode(seed=21, n=3, width=5, nhid=2)
+    theta = w.theta.astype(np.float64)
+    rng = np.random.default_rng(2)
+    y, cot = rng.standard_normal(w.n), rng.standard_normal(w.n)
+    dth, dy = oracle.mlp_vjp(cell, theta, y, cot)
+    h = 1e-6
+    for k in range(theta.size):
+        tp, tm = theta.copy(), theta.copy()
+        tp[k] += h; tm[k] -= h
+        fd = cot @ (mlp_numpy(w.n, 5, 2, tp)(y) - mlp_numpy(w.n, 5, 2, tm)(y)) / (2 * h)
+        assert abs(dth[k] - fd) < 1e-8, k
+    f = mlp_numpy(w.n, 5, 2, theta)
+    for k in range(w.n):
+        e = np.zeros(w.n); e[k] = h
+        assert abs(dy[k] - cot @ (f(y + e) - f(y - e)) / (2 * h)) < 1e-8
+
+
+def test_ode_grad_of_a_linear_field_in_closed_form():
+    # f(y) = -A y + c: y(t_j) = E_j y0 + A^{-1}(I - E_j) c with E_j = exp(-A t_j), which the discretised
+    # recurrence reproduces exactly, and Gbar does not depend on c or y0.  For L = sum_j g_j . y_j:
+    # dL/dc = sum_j (A^{-1}(I - E_j))^T g_j and dL/dy0 = sum_j E_j^T g_j.
+    n, T, B = 3, 30, 2
+    rng = np.random.default_rng(9)
+    A = rng.standard_normal((n, n)) + 2 * np.eye(n)
+    c = rng.standard_normal(n)
+    y0 = rng.standard_normal((B, n))
+    g = rng.standard_normal((B, T, n))
+    cell = oracle.make_cell(oracle.CELL_MLP, n, 0, 0, 0)
+    theta = linear_field_theta(A, c)
+    y, it, _, _ = oracle.ode_deer_eval(cell, theta, y0, T, 0.0, 2.0, tol=1e-12, max_iter=10)
+    dth, dy0 = oracle.ode_grad(cell, theta, y, g, 0.0, 2.0)
+    t = np.linspace(0.0, 2.0, T)
+    want_c, want_y0 = np.zeros(n), np.zeros((B, n))
+    for j in range(T):
+        Ej = scipy.linalg.expm(-A * t[j])
+        Kj = np.linalg.solve(A, np.eye(n) - Ej)
+        for b in range(B):
+            want_c += Kj.T @ g[b, j]
+            want_y0[b] += Ej.T @ g[b, j]
+    np.testing.assert_allclose(dth[n * n:], want_c, rtol=1e-10, atol=1e-11)
+    np.testing.assert_allclose(dy0, want_y0, rtol=1e-10, atol=1e-11)
+
+
+def test_ode_grad_converges_to_the_continuous_gradient_at_second_order():
+    # L(theta, y0) = r . y(t1) + int q(t) . y(t) dt for the exact flow, differentiated by central differences
+    # of a tight Runge-Kutta solve of the augmented system, against the oracle's gradient with
+    # g_j = (trapezoid weight) q(t_j) (+ r at the last point): the difference must fall like dt^2.
+    w, cell = small_ode(seed=13, B=1)
+    theta = w.theta.astype(np.float64)
+    y0 = w.y0.astype(np.float64)
+    n = w.n
+    rng = np.random.default_rng(4)
+    r = rng.standard_normal(n)
+    qa, qb = rng.standard_normal(n), rng.standard_normal(n)
+    q = lambda t: qa * np.cos(2.0 * t) + qb * t
+
+    def loss(th, yy0):
+        f = mlp_numpy(n, w.mlp_width, w.mlp_hidden_layers, th)
+        rhs = lambda t, s: np.concatenate([f(s[:n]), [q(t) @ s[:n]]])
+        sol = solve_ivp(rhs, (w.t0, w.t1), np.concatenate([yy0, [0.0]]), method="DOP853", rtol=1e-13, atol=1e-14)
+        return r @ sol.y[:n, -1] + sol.y[n, -1]
+
+    dirs_th = rng.standard_normal((3, theta.size))
+    dirs_y0 = rng.standard_normal((2, n))
+    h = 1e-5
+    want_th = np.array([(loss(theta + h * v, y0[0]) - loss(theta - h * v, y0[0])) / (2 * h) for v in dirs_th])
+    want_y0 = np.array([(loss(theta, y0[0] + h * v) - loss(theta, y0[0] - h * v)) / (2 * h) for v in dirs_y0])
+    errs = []
+    for T in (21, 41, 81, 161):
+        y, it, _, _ = oracle.ode_deer_eval(cell, theta, y0, T, w.t0, w.t1, tol=1e-13, max_iter=60)
+        assert it < 60
+        t = np.linspace(w.t0, w.t1, T)
+        dt = t[1] - t[0]
+        g = np.stack([q(tj) for tj in t]) * dt
+        g[0] *= 0.5; g[-1] *= 0.5
+        g[-1] += r
+        dth, dy0 = oracle.ode_grad(cell, theta, y, g[None], w.t0, w.t1)
+        errs.append(max(np.abs(dirs_th @ dth - want_th).max(), np.abs(dirs_y0 @ dy0[0] - want_y0).max()))
+    ratios = [errs[k] / errs[k + 1] for k in range(3)]
+    assert all(3.2 < rr < 4.8 for rr in ratios), (errs, ratios)
+    assert errs[-1] < 2e-4 * max(1.0, np.abs(want_th).max())
+
+
+def test_ode_grad_is_linear_in_the_loss_gradient_and_sums_over_the_batch():
+    w, cell = small_ode(seed=17, B=2)
+    T = 25
+    y, _, _, _ = oracle.ode_deer_eval(cell, w.theta, w.y0, T, w.t0, w.t1, tol=1e-12, max_iter=60)
+    rng = np.random.default_rng(6)
+    g1, g2 = rng.standard_normal(y.shape), rng.standard_normal(y.shape)
+    a, _ = oracle.ode_grad(cell, w.theta, y, g1, w.t0, w.t1)
+    b, _ = oracle.ode_grad(cell, w.theta, y, g2, w.t0, w.t1)
+    c, _ = oracle.ode_grad(cell, w.theta, y, 2.0 * g1 - g2, w.t0, w.t1)
+    np.testing.assert_allclose(c, 2.0 * a - b, atol=1e-11)
+    one = sum(oracle.ode_grad(cell, w.theta, y[k:k + 1], g1[k:k + 1], w.t0, w.t1)[0] for k in range(2))
+    np.testing.assert_allclose(one, a, atol=1e-12)
