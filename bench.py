@@ -156,7 +156,8 @@ def main():
                     help="n,B,T: time deer_linrec_solve alone on a random stream of that shape and exit")
     ap.add_argument("--grad", action="store_true",
                     help="time deer_grad (Jacobians at the solution, transposed reverse scan, VJP + parameter "
-                         "reduction) on the chosen GRU configuration and exit")
+                         "reduction; for the ODE cell: field Jacobians, discretisation, reverse scan with one refinement, "
+                         "dual discretisation, MLP VJP) on the chosen configuration and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -195,9 +196,6 @@ def main():
         return ctx.eval(th, x, y0, tol=w.tol, max_iter=w.max_iter, out=y)
 
     if args.grad:
-        if w.cell != inputs.CELL_GRU:
-            print("bench.py --grad: GRU configurations only", file=sys.stderr)
-            sys.exit(2)
         y, iters, err, conv, _ = step()
         torch.manual_seed(2)
         g = torch.randn_like(y) / (w.B * w.T)
@@ -214,11 +212,13 @@ def main():
             ctx.grad(th, x, y0, y, g)
         torch.cuda.synchronize()
         prof = ctx.profile()
-        per = {k: prof[k + "_ms"] / max(1, prof[k + "_launches"]) for k in ("funceval", "scan", "vjp")}
+        keys = ("funceval", "scan", "vjp") if w.cell == inputs.CELL_GRU else ("funceval", "discretise", "scan", "vjp")
+        per = {k: prof[k + "_ms"] / max(1, prof[k + "_launches"]) for k in keys}
+        per_call = {k: prof[k + "_ms"] / args.steps for k in keys}
         S = w.B * w.T
         jbytes = 4 * w.n * w.n * S
         print(json.dumps({"deer_grad": w.name, "ms_per_call": ms, "sequence_steps_per_s": S / (ms * 1e-3),
-                          "kernels_ms_per_launch": per,
+                          "kernels_ms_per_launch": per, "kernels_ms_per_call": per_call,
                           "reverse_scan_GBs": 4 * (w.n * w.n + 2 * w.n) * S / (per["scan"] * 1e-3) / 1e9,
                           "funceval_write_GBs": (jbytes + 4 * w.n * S) / (per["funceval"] * 1e-3) / 1e9}))
         ctx.close()

@@ -123,14 +123,21 @@ deer_status deer_eval(deer_ctx* ctx, const void* d_theta, const void* d_x, const
                       const void* d_y_guess, double tol, int32_t max_iter, void* d_y,
                       int32_t* iters, double* final_err, int32_t* converged);
 
-/* Backward derivative for the GRU recurrence (Sec. 3.1.1 eq. 7): one reverse scan with the
- * transposed Jacobians, lam_T = g_T, lam_i = g_i + J_{i+1}^T lam_{i+1}, then the VJP of f.
+/* Backward derivative (Sec. 3.1.1 eq. 7): the cotangent g = dL/dy is pushed through the transposed,
+ * time-reversed linear operator (one reverse scan), then through the vector-Jacobian product of f.
  * The Jacobians are recomputed at the trajectory d_y that is passed in, so the trajectory may
  * come from deer_eval() or from a sequential evaluation (Sec. 3.1.1, last paragraph).
+ *   GRU:     lam_T = g_T, lam_i = g_i + J_{i+1}^T lam_{i+1};  dL/dtheta = sum_i (df/dtheta)_i^T lam_i, same for x.
+ *   MLP_ODE: on the discretised operator of Sec. 3.3 eq. 8-9 with G frozen at the trajectory:
+ *            lam_{T-1} = g_{T-1}, lam_j = g_j + Gbar_j^T lam_{j+1};  dL/dy0 = lam_0;
+ *            dL/dtheta = sum_j (df/dtheta)(y_j)^T w_j,  w_j = (P_j^T lam_{j+1} + P_{j-1}^T lam_j) / 2,
+ *            P_j = dt phi1(-Gc_j dt) (terms outside the grid dropped).  This is the derivative eq. 7 defines;
+ *            it differs from the derivative of the discrete solution by O(dt^2).  d_x, d_y0 and d_dLdx are
+ *            ignored (the field is autonomous and y[:,0,:] is the initial state).
  *   d_y        in  trajectory [B,T,n]          d_dLdy   in  g = dL/dy [B,T,n]
  *   d_dLdx     out [B,T,d], or NULL to skip    d_dLdtheta out [theta_count] (overwritten, not accumulated)
  *   d_dLdy0    out [B,n], or NULL to skip
- * DEER_ERR_UNSUPPORTED for MLP_ODE configurations. */
+ * The parameter gradient is summed in a fixed order: two calls with the same inputs return the same bits. */
 deer_status deer_grad(deer_ctx* ctx, const void* d_theta, const void* d_x, const void* d_y0,
                       const void* d_y, const void* d_dLdy, void* d_dLdx, void* d_dLdtheta,
                       void* d_dLdy0);

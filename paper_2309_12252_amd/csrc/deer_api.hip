@@ -166,7 +166,8 @@ Plan make_plan(const deer_config* c) {
         p.fused_tiles = (p.scan_T + ft - 1) / ft;
         if (p.fused_tiles < 1) p.fused_tiles = 1;
     }
-    p.vjp_blocks = c->cell == DEER_CELL_GRU ? gru_vjp_blocks(c->n, (long long)B * T) : 0;
+    p.vjp_blocks = c->cell == DEER_CELL_GRU ? gru_vjp_blocks(c->n, (long long)B * T)
+                                            : mlp_vjp_blocks(c->dtype, c->n, c->mlp_width, (long long)B * T);
 
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
@@ -182,6 +183,7 @@ Plan make_plan(const deer_config* c) {
     // slots of the one-launch solve's grid barrier (two banks, one tagged scalar per workgroup)
     p.off_barrier = take(p.fused ? 2 * (B * (size_t)p.fused_tiles + 4) * (p.esz / 4) * 8 : 0);   // (+4: test hook)
     p.off_ctl = take((size_t)kSlots * 4 + (size_t)kSlots * 8 + 16);   // tickets, err bits, status
+    // partial rows of dL/dtheta: four per block (GRU: one per wavefront), two per block (MLP: one per thread group)
     p.off_partial = take((size_t)p.vjp_blocks * 4 * theta_count(c) * p.esz);
     p.total = off;
     return p;
@@ -268,12 +270,12 @@ void prof_collect(deer_ctx* c, int iters_done = 1 << 30) {
 hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, void* out, const void* yold,
                     long long strideA, long long strideb, long long strideOut, int reverse, int slot, bool want_err,
                     int delta = 0, Gate gate = Gate{nullptr, 0.0}, int iter = -1, const void* fused_theta = nullptr,
-                    const void* fused_x = nullptr) {
+                    const void* fused_x = nullptr, int add_identity = 0) {
     const deer_config& g = c->cfg;
     ScanParams p{};
     p.A = A; p.bv = bv; p.y0 = y0; p.out = out; p.yold = yold;
     p.strideA = strideA; p.strideb = strideb; p.strideOut = strideOut; p.strideOld = strideOut;
-    p.B = g.B; p.T = c->plan.scan_T; p.L = c->plan.L; p.tiles = c->plan.tiles; p.reverse = reverse; p.delta = delta;
+    p.B = g.B; p.T = c->plan.scan_T; p.L = c->plan.L; p.tiles = c->plan.tiles; p.reverse = reverse; p.delta = delta; p.add_identity = add_identity;
     p.epoch = ++c->epoch;   // reserve_epochs() keeps this below 2^30
     p.aggW = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_aggW);
     p.inclW = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_inclW);
@@ -647,11 +649,70 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
     return DEER_OK;
 }
 
+// Backward derivative for the ODE form (Sec. 3.1.1 eq. 7 on the discretised operator of Sec. 3.3 eq. 8-9):
+// G = -df/dy at the trajectory, Gbar_i = exp(-(G_i + G_{i+1}) dt / 2), the reverse scan
+// lam_{T-1} = g_{T-1}, lam_i = g_i + Gbar_i^T lam_{i+1} for i >= 1, then per interval
+// u_i = dt phi1(.)^T lam_{i+1} (and dL/dy0 = g_0 + Gbar_0^T lam_1), and the VJP of f with
+// w_j = (u_j + u_{j-1}) / 2 at every grid point.
+static deer_status grad_ode(deer_ctx* c, const void* d_theta, const void* d_y, const void* d_dLdy, void* d_dLdtheta,
+                            void* d_dLdy0) {
+    const deer_config& g = c->cfg;
+    if (!d_theta || !d_y || !d_dLdy || !d_dLdtheta) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
+    const size_t n = (size_t)g.n, T = (size_t)g.T, esz = (size_t)c->plan.esz;
+    char* G = c->ws + c->plan.off_J;
+    char* z = c->ws + c->plan.off_rhs;       // z of the field evaluation, then the residual, then u
+    char* res = z;
+    char* u = z;
+    char* lam0 = c->ws + c->plan.off_ybuf;   // first pass of the reverse scan
+    char* lam = c->ws + c->plan.off_zbar;    // [B,T-1,n]: lam at grid points 1..T-1
+    char* Dm = c->ws + c->plan.off_Gbar;
+    const double dt = (g.t1 - g.t0) / (double)(g.T - 1);
+    const Gate open{nullptr, 0.0};
+
+    deer_status st = zero_ctl(c);
+    if (st != DEER_OK) return st;
+    MlpParams mp{d_theta, d_y, G, z, g.B, g.T, g.n, g.mlp_width, open};
+    prof_begin(c, KIND_FUNCEVAL);
+    HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
+    prof_end(c);
+    // D_i = Gbar_i - I (the residual output lands in lam and is overwritten below)
+    OdeDiscParams dp{G, z, d_y, Dm, lam, g.B, g.T, g.n, dt, open, 1};
+    prof_begin(c, KIND_DISC);
+    HIPCHK(c, launch_ode_discretise(g.dtype, dp, c->stream));
+    prof_end(c);
+    // Reverse scan over grid points 1..T-1 (matrices D_1..D_{T-2}; D_0 serves dL/dy0 only), twice: the scan
+    // works on I + D rounded to the working precision, which perturbs the generator by eps / |D|; one step of
+    // iterative refinement with the residual evaluated on D itself removes that (it matters in fp32 only,
+    // where it costs a second scan: 1.4e-4 against 1e-5 relative error of lam at T = 1e5).
+    const char* gvec = reinterpret_cast<const char*>(d_dLdy) + n * esz;
+    const long long sD = (long long)((T - 1) * n * n), sg = (long long)(T * n), sl = (long long)((T - 1) * n);
+    const bool refine = g.dtype == DEER_F32;
+    HIPCHK(c, run_scan(c, Dm, gvec, nullptr, refine ? lam0 : lam, nullptr, sD, sg, sl, 1, 0, false, 0, open, -1, nullptr,
+                       nullptr, 1));
+    if (refine) {
+        prof_begin(c, KIND_DISC);
+        HIPCHK(c, launch_ode_dual_residual(g.dtype, Dm, d_dLdy, lam0, res, g.B, g.T, g.n, c->stream));
+        prof_end(c);
+        HIPCHK(c, run_scan(c, Dm, res, nullptr, lam, lam0, sD, sl, sl, 1, 1, false, 1, open, -1, nullptr, nullptr, 1));
+    }
+    OdeDualParams up{G, lam, d_dLdy, u, d_dLdy0, g.B, g.T, g.n, dt};
+    prof_begin(c, KIND_DISC);
+    HIPCHK(c, launch_ode_dual(g.dtype, up, c->stream));
+    prof_end(c);
+    MlpVjpParams vp{d_theta, d_y, u, c->ws + c->plan.off_partial, d_dLdtheta, g.B, g.T, g.n, g.mlp_width, c->plan.vjp_blocks};
+    prof_begin(c, KIND_VJP);
+    HIPCHK(c, launch_mlp_vjp(g.dtype, vp, c->stream));
+    prof_end(c);
+    st = check_status(c);
+    prof_collect(c);
+    return st;
+}
+
 deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const void* d_y0, const void* d_y,
                       const void* d_dLdy, void* d_dLdx, void* d_dLdtheta, void* d_dLdy0) {
     if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
     const deer_config& g = c->cfg;
-    if (g.cell != DEER_CELL_GRU) return fail(c, DEER_ERR_UNSUPPORTED, "deer_grad supports the GRU cell only");
+    if (g.cell == DEER_CELL_MLP_ODE) return grad_ode(c, d_theta, d_y, d_dLdy, d_dLdtheta, d_dLdy0);
     if (!d_theta || !d_x || !d_y0 || !d_y || !d_dLdy || !d_dLdtheta)
         return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
     const size_t n = (size_t)g.n, T = (size_t)g.T;

@@ -41,6 +41,7 @@ struct ScanParams {
     int tiles;           // tiles per sequence
     int reverse;
     int delta;           // 1: the scan solves for a correction; out = yold + y and the error is max|y|
+    int add_identity;    // VALU kernel, reverse scans: 1 = the stored matrices are A - I (the identity is added on load)
     unsigned epoch;      // tags carry (epoch << 2) | state, so words of earlier launches need no clearing
     unsigned long long* aggW;   // [B * tiles][(n*n + n) * words per scalar] tile totals (M row-major, then v)
     unsigned long long* inclW;  // [B * tiles][n * words per scalar] inclusive carry after the tile
@@ -251,6 +252,26 @@ struct OdeDiscParams {
     int B, T, n;
     double dt;
     Gate gate;
+    int minus_identity;                   // 1: Gbar holds exp(-Gc dt) - I (nothing of size dt is rounded against 1)
+};
+
+struct OdeDualParams {
+    const void* G;                        // [B,T,n,n] G = -df/dy at the trajectory
+    const void* lam;                      // [B,T-1,n] scanned cotangent at grid points 1..T-1
+    const void* g;                        // [B,T,n] dL/dy (entry 0 is read when dy0 is given)
+    void* u;                              // [B,T-1,n] dt phi1(X_i)^T lam_{i+1}
+    void* dy0;                            // [B,n] or nullptr
+    int B, T, n;
+    double dt;
+};
+
+struct MlpVjpParams {
+    const void* theta; const void* y;     // y [B,T,n]
+    const void* u;                        // [B,T-1,n] from the dual discretisation
+    void* partial;                        // [blocks][theta_count] per-block partial sums
+    void* dtheta;                         // [theta_count]
+    int B, T, n, width;
+    int blocks;
 };
 
 hipError_t launch_scan_valu(int dtype, int n, const ScanParams& p, hipStream_t s);
@@ -273,6 +294,16 @@ hipError_t launch_gru_vjp(int dtype, const GruVjpParams& p, hipStream_t s);
 int gru_vjp_blocks(int n, long long steps);
 hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s);
 hipError_t launch_ode_discretise(int dtype, const OdeDiscParams& p, hipStream_t s);
+hipError_t launch_ode_dual(int dtype, const OdeDualParams& p, hipStream_t s);
+// residual of an approximate solution lam0 of the dual recurrence lam_i = g_i + (I + D_{i+1})^T lam_{i+1} over grid
+// points 1..T-1 (D [B,T-1,n,n] = Gbar - I, g [B,T,n], lam0 and res [B,T-1,n]), evaluated without forming I + D
+hipError_t launch_ode_dual_residual(int dtype, const void* D, const void* g, const void* lam0, void* res, int B, int T,
+                                    int n, hipStream_t s);
+// VJP of the MLP field with the parameter-gradient reduction; blocks from mlp_vjp_blocks()
+int mlp_vjp_blocks(int dtype, int n, int width, long long points);
+hipError_t launch_mlp_vjp(int dtype, const MlpVjpParams& p, hipStream_t s);
+// fixed-order sum of partial rows [rows][P] into out[P]
+hipError_t launch_partial_reduce(int dtype, const void* partial, void* out, long long P, int rows, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_fill_zero2(void* a, size_t abytes, void* b, size_t bbytes, hipStream_t s);
 hipError_t launch_pin_first(int dtype, void* y, const void* y0, int B, int T, int n, hipStream_t s);

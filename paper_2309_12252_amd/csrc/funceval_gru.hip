@@ -438,6 +438,18 @@ int gru_vjp_blocks(int n, long long steps) {
     return (int)blocks;
 }
 
+hipError_t launch_partial_reduce(int dtype, const void* partial, void* out, long long P, int rows, hipStream_t s) {
+    if (P < 1 || rows < 1) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((P + 15) / 16));
+    if (dtype == 0)
+        hipLaunchKernelGGL((gru_vjp_reduce_kernel<float>), grid, dim3(256), 0, s, reinterpret_cast<const float*>(partial),
+                           reinterpret_cast<float*>(out), P, rows);
+    else
+        hipLaunchKernelGGL((gru_vjp_reduce_kernel<double>), grid, dim3(256), 0, s, reinterpret_cast<const double*>(partial),
+                           reinterpret_cast<double*>(out), P, rows);
+    return hipGetLastError();
+}
+
 hipError_t launch_gru_funceval(int dtype, const GruParams& p, hipStream_t s) {
     if (p.d < 1 || p.d > kMaxD) return hipErrorInvalidValue;
     return dtype == 0 ? launch_fe_s<float>(p, s) : launch_fe_s<double>(p, s);

@@ -294,34 +294,10 @@ template <typename S> struct SeriesTol;
 template <> struct SeriesTol<float> { static constexpr float v = 1e-10f; };
 template <> struct SeriesTol<double> { static constexpr double v = 1e-19; };
 
+// D = exp(X) - I and pv = phi1(X) v for one n x n matrix held in registers (X is overwritten by its scaled
+// copy): scaling so that the max-row-sum norm is at most 1/2, Taylor series, then the doublings undone.
 template <typename S, int N>
-__global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams p) {
-    if (gate_closed<S>(p.gate)) return;
-    const long long nint = (long long)p.B * (p.T - 1);
-    const long long q = (long long)blockIdx.x * kThreads + threadIdx.x;
-    if (q >= nint) return;
-    const long long bi = q / (p.T - 1);
-    const long long i = q - bi * (p.T - 1);
-    const S* __restrict__ G = reinterpret_cast<const S*>(p.G) + (bi * p.T + i) * (N * N);
-    const S* __restrict__ z = reinterpret_cast<const S*>(p.z) + (bi * p.T + i) * N;
-    const S* __restrict__ y = reinterpret_cast<const S*>(p.y) + (bi * p.T + i) * N;
-    S* __restrict__ Gbar = reinterpret_cast<S*>(p.Gbar) + q * (N * N);
-    S* __restrict__ res = reinterpret_cast<S*>(p.res) + q * N;
-    const S dt = (S)p.dt;
-
-    // X = -Gc dt / 2^sq with max-row-sum norm at most 1/2
-    S X[N * N], zc[N];
-    {
-        S G0[N * N], G1[N * N], z0[N], z1[N];
-        vload<S, N * N>(G0, G);
-        vload<S, N * N>(G1, G + N * N);
-        vload<S, N>(z0, z);
-        vload<S, N>(z1, z + N);
-#pragma unroll
-        for (int k = 0; k < N * N; ++k) X[k] = S(-0.5) * (G0[k] + G1[k]) * dt;
-#pragma unroll
-        for (int k = 0; k < N; ++k) zc[k] = S(0.5) * (z0[k] + z1[k]);
-    }
+__device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
     S norm = S(0);
 #pragma unroll
     for (int r = 0; r < N; ++r) {
@@ -340,7 +316,7 @@ __global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams 
     // Taylor series of D = exp(X) - I (matrix, identity left out so that nothing of size |X| is
     // rounded against 1) and of phi1(X) zc (vector), until the bound norm^k/k! on the next term is
     // below the working precision
-    S D[N * N], term[N * N], pv[N], wv[N];
+    S term[N * N], wv[N];
 #pragma unroll
     for (int k = 0; k < N * N; ++k) { D[k] = X[k]; term[k] = X[k]; }
 #pragma unroll
@@ -385,6 +361,38 @@ __global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams 
 #pragma unroll
         for (int e = 0; e < N * N; ++e) D[e] = S(2) * D[e] + D2[e];
     }
+}
+
+template <typename S, int N>
+__global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams p) {
+    if (gate_closed<S>(p.gate)) return;
+    const long long nint = (long long)p.B * (p.T - 1);
+    const long long q = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (q >= nint) return;
+    const long long bi = q / (p.T - 1);
+    const long long i = q - bi * (p.T - 1);
+    const S* __restrict__ G = reinterpret_cast<const S*>(p.G) + (bi * p.T + i) * (N * N);
+    const S* __restrict__ z = reinterpret_cast<const S*>(p.z) + (bi * p.T + i) * N;
+    const S* __restrict__ y = reinterpret_cast<const S*>(p.y) + (bi * p.T + i) * N;
+    S* __restrict__ Gbar = reinterpret_cast<S*>(p.Gbar) + q * (N * N);
+    S* __restrict__ res = reinterpret_cast<S*>(p.res) + q * N;
+    const S dt = (S)p.dt;
+
+    // X = -Gc dt / 2^sq with max-row-sum norm at most 1/2
+    S X[N * N], zc[N];
+    {
+        S G0[N * N], G1[N * N], z0[N], z1[N];
+        vload<S, N * N>(G0, G);
+        vload<S, N * N>(G1, G + N * N);
+        vload<S, N>(z0, z);
+        vload<S, N>(z1, z + N);
+#pragma unroll
+        for (int k = 0; k < N * N; ++k) X[k] = S(-0.5) * (G0[k] + G1[k]) * dt;
+#pragma unroll
+        for (int k = 0; k < N; ++k) zc[k] = S(0.5) * (z0[k] + z1[k]);
+    }
+    S D[N * N], pv[N];
+    expm1_phi1v<S, N>(X, zc, D, pv);
     // residual of the current iterate in the discretised recurrence (Sec. 3.3 eq. 9):
     // res = Gbar y_i + zbar - y_{i+1} = D y_i + dt phi1 zc - (y_{i+1} - y_i)
     S y0v[N], y1v[N], rv[N];
@@ -397,10 +405,85 @@ __global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams 
         for (int c = 0; c < N; ++c) s += D[r * N + c] * y0v[c];
         rv[r] = (s + dt * pv[r]) - (y1v[r] - y0v[r]);
     }
+    if (!p.minus_identity) {
 #pragma unroll
-    for (int e = 0; e < N * N; ++e) D[e] += ((e / N) == (e % N)) ? S(1) : S(0);
+        for (int e = 0; e < N * N; ++e) D[e] += ((e / N) == (e % N)) ? S(1) : S(0);
+    }
     vstore<S, N * N>(Gbar, D);
     vstore<S, N>(res, rv);
+}
+
+// Dual of the discretisation for the backward derivative (Sec. 3.1.1 eq. 7 on the operator of Sec. 3.3
+// eq. 8-9): one thread per interval i computes u_i = dt phi1(X_i)^T lam_{i+1} = dt phi1(X_i^T) lam_{i+1} with
+// X_i = -(G_i + G_{i+1}) dt / 2, the weight with which the cotangent lam enters df/dtheta at the two ends of
+// the interval, and, for the first interval, dL/dy0 = g_0 + exp(X_0)^T lam_1.
+template <typename S, int N>
+__global__ __launch_bounds__(kThreads) void ode_dual_kernel(OdeDualParams p) {
+    const long long nint = (long long)p.B * (p.T - 1);
+    const long long q = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (q >= nint) return;
+    const long long bi = q / (p.T - 1);
+    const long long i = q - bi * (p.T - 1);
+    const S* __restrict__ G = reinterpret_cast<const S*>(p.G) + (bi * p.T + i) * (N * N);
+    const S* __restrict__ lam = reinterpret_cast<const S*>(p.lam) + q * N;   // lam at grid point i + 1
+    S* __restrict__ u = reinterpret_cast<S*>(p.u) + q * N;
+    const S dt = (S)p.dt;
+    S X[N * N], lv[N];
+    {
+        S G0[N * N], G1[N * N];
+        vload<S, N * N>(G0, G);
+        vload<S, N * N>(G1, G + N * N);
+        vload<S, N>(lv, lam);
+#pragma unroll
+        for (int r = 0; r < N; ++r)
+#pragma unroll
+            for (int c = 0; c < N; ++c) X[r * N + c] = S(-0.5) * (G0[c * N + r] + G1[c * N + r]) * dt;
+    }
+    S D[N * N], pv[N];
+    expm1_phi1v<S, N>(X, lv, D, pv);
+    S uv[N];
+#pragma unroll
+    for (int r = 0; r < N; ++r) uv[r] = dt * pv[r];
+    vstore<S, N>(u, uv);
+    if (i == 0 && p.dy0) {
+        const S* __restrict__ g0 = reinterpret_cast<const S*>(p.g) + bi * p.T * N;
+        S* __restrict__ out = reinterpret_cast<S*>(p.dy0) + bi * N;
+#pragma unroll
+        for (int r = 0; r < N; ++r) {
+            S s = lv[r];
+#pragma unroll
+            for (int c = 0; c < N; ++c) s += D[r * N + c] * lv[c];
+            out[r] = g0[r] + s;
+        }
+    }
+}
+
+// Residual of an approximate solution lam0 of the dual recurrence over grid points 1..T-1,
+//   res_i = g_i - lam0_i + lam0_{i+1} + D_i^T lam0_{i+1}   (res_{T-1} = g_{T-1} - lam0_{T-1}),
+// with D_i = exp(X_i) - I: the identity never meets D, so the residual keeps the digits of D that a product
+// with the rounded I + D loses.  One thread per (grid point, row).
+template <typename S, int N>
+__global__ __launch_bounds__(kThreads) void ode_dual_residual_kernel(const S* __restrict__ D, const S* __restrict__ g,
+                                                                     const S* __restrict__ lam0, S* __restrict__ res,
+                                                                     int B, int T) {
+    const long long T1 = T - 1;
+    const long long total = (long long)B * T1 * N;
+    const long long q = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (q >= total) return;
+    const int r = (int)(q % N);
+    const long long pi = q / N;            // (sequence, grid point - 1)
+    const long long bi = pi / T1, i1 = pi - bi * T1;
+    const S gi = g[(bi * T + i1 + 1) * N + r];
+    S acc = gi - lam0[pi * N + r];
+    if (i1 + 1 < T1) {
+        const S* __restrict__ ln = lam0 + (pi + 1) * N;
+        const S* __restrict__ Di = D + (bi * T1 + i1 + 1) * (N * N);   // interval from grid point i1+1 to i1+2
+        S s = S(0);
+#pragma unroll
+        for (int c = 0; c < N; ++c) s += Di[c * N + r] * ln[c];
+        acc = (acc + ln[r]) + s;
+    }
+    res[pi * N + r] = acc;
 }
 
 template <typename S>
@@ -479,6 +562,19 @@ hipError_t launch_disc_s(const OdeDiscParams& p, hipStream_t s) {
     return hipGetLastError();
 }
 
+template <typename S>
+hipError_t launch_dual_s(const OdeDualParams& p, hipStream_t s) {
+    const long long nint = (long long)p.B * (p.T - 1);
+    const unsigned blocks = (unsigned)((nint + kThreads - 1) / kThreads);
+    switch (p.n) {
+        case 2: hipLaunchKernelGGL((ode_dual_kernel<S, 2>), dim3(blocks), dim3(kThreads), 0, s, p); break;
+        case 4: hipLaunchKernelGGL((ode_dual_kernel<S, 4>), dim3(blocks), dim3(kThreads), 0, s, p); break;
+        case 8: hipLaunchKernelGGL((ode_dual_kernel<S, 8>), dim3(blocks), dim3(kThreads), 0, s, p); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s) {
@@ -498,6 +594,36 @@ hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s) {
 
 hipError_t launch_ode_discretise(int dtype, const OdeDiscParams& p, hipStream_t s) {
     return dtype == 0 ? launch_disc_s<float>(p, s) : launch_disc_s<double>(p, s);
+}
+
+hipError_t launch_ode_dual(int dtype, const OdeDualParams& p, hipStream_t s) {
+    if (p.T < 2) return hipErrorInvalidValue;
+    return dtype == 0 ? launch_dual_s<float>(p, s) : launch_dual_s<double>(p, s);
+}
+
+template <typename S>
+static hipError_t launch_residual_s(const void* D, const void* g, const void* lam0, void* res, int B, int T, int n,
+                                    hipStream_t s) {
+    const long long total = (long long)B * (T - 1) * n;
+    const dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    const S* Dp = reinterpret_cast<const S*>(D);
+    const S* gp = reinterpret_cast<const S*>(g);
+    const S* lp = reinterpret_cast<const S*>(lam0);
+    S* rp = reinterpret_cast<S*>(res);
+    switch (n) {
+        case 2: hipLaunchKernelGGL((ode_dual_residual_kernel<S, 2>), grid, dim3(kThreads), 0, s, Dp, gp, lp, rp, B, T); break;
+        case 4: hipLaunchKernelGGL((ode_dual_residual_kernel<S, 4>), grid, dim3(kThreads), 0, s, Dp, gp, lp, rp, B, T); break;
+        case 8: hipLaunchKernelGGL((ode_dual_residual_kernel<S, 8>), grid, dim3(kThreads), 0, s, Dp, gp, lp, rp, B, T); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_ode_dual_residual(int dtype, const void* D, const void* g, const void* lam0, void* res, int B, int T,
+                                    int n, hipStream_t s) {
+    if (T < 2) return hipErrorInvalidValue;
+    return dtype == 0 ? launch_residual_s<float>(D, g, lam0, res, B, T, n, s)
+                      : launch_residual_s<double>(D, g, lam0, res, B, T, n, s);
 }
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {

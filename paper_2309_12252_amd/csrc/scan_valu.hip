@@ -36,7 +36,15 @@ namespace {
 template <typename S, int N, int L, int W>
 hipError_t launch_nlw(const ScanParams& p, hipStream_t s) {
     dim3 grid((unsigned)((long long)p.B * p.tiles));
-    if (p.reverse)
+    if (p.add_identity) {
+        // matrices stored as A - I: reverse scans of state sizes the ODE form uses
+        if constexpr (N >= 2) {
+            if (!p.reverse) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((scan_valu_kernel<S, N, L, W, true, 0, true>), grid, dim3(64 * W), 0, s, p, GruFeed{});
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else if (p.reverse)
         hipLaunchKernelGGL((scan_valu_kernel<S, N, L, W, true, 0>), grid, dim3(64 * W), 0, s, p, GruFeed{});
     else
         hipLaunchKernelGGL((scan_valu_kernel<S, N, L, W, false, 0>), grid, dim3(64 * W), 0, s, p, GruFeed{});

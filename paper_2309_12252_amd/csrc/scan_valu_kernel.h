@@ -135,9 +135,10 @@ __device__ __forceinline__ S group_matvec(const S* Lr, S add, S y) {
 // past the end read the last valid one and are then replaced by the identity pair): with
 // straight-line code the compiler keeps the loads in order and lets the first products start while
 // later positions are still in flight.
-template <typename S, int N, int L, bool REV, bool FULL>
+template <typename S, int N, int L, bool REV, bool FULL, bool ADDI = false>
 __device__ __forceinline__ void load_pairs(const S* __restrict__ Ab, const S* __restrict__ bb, long long T,
                                            long long e0, int i, S (*Ar)[N], S* be) {
+    constexpr S addI = ADDI ? S(1) : S(0);   // ADDI: the stored matrices are A - I
     constexpr int H = (N == 8) ? 4 : 0;
     const int h = (N == 8) ? (i & 4) : 0;
     if constexpr (FULL && !REV) {
@@ -189,13 +190,20 @@ __device__ __forceinline__ void load_pairs(const S* __restrict__ Ab, const S* __
                 }
                 if (ec == 0) {
 #pragma unroll
-                    for (int s = 0; s < N; ++s) row[s] = S(0);
+                    for (int s = 0; s < N; ++s) row[s] = (swz_col<N>(s, i) == i) ? -addI : S(0);   // stays zero below
                 }
             }
 #pragma unroll
-            for (int s = 0; s < N; ++s) Ar[l][s] = past ? ((swz_col<N>(s, i) == i) ? S(1) : S(0)) : row[s];
+            for (int s = 0; s < N; ++s) Ar[l][s] = past ? ((swz_col<N>(s, i) == i) ? S(1) - addI : S(0)) : row[s];
             be[l] = past ? S(0) : bv;
         }
+    }
+    // matrices stored without their identity: put it back (slot s of lane i holds column swz_col(s, i))
+    if constexpr (ADDI) {
+#pragma unroll
+        for (int l = 0; l < L; ++l)
+#pragma unroll
+            for (int s = 0; s < N; ++s) Ar[l][s] += (swz_col<N>(s, i) == i) ? S(1) : S(0);
     }
 }
 
@@ -585,10 +593,12 @@ __device__ __forceinline__ S tile_start_state(const TileShared<S, N, W>& sh, con
 }
 
 // DP = 0: pairs are read from p.A / p.bv.  DP > 0: pairs come from the GRU cell (forward scans only),
-// DP being the input width the x loops are unrolled for.
-template <typename S, int N, int L, int W, bool REV, int DP>
+// DP being the input width the x loops are unrolled for.  ADDI: the stored matrices are A - I (the identity
+// is added on load; used by the dual recurrence of the ODE form, whose matrices are I + O(dt)).
+template <typename S, int N, int L, int W, bool REV, int DP, bool ADDI = false>
 __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed gf) {
     static_assert(DP == 0 || !REV, "the fused cell feeds forward scans only");
+    static_assert(!ADDI || DP == 0, "only stored matrices can lack their identity");
     constexpr int NG = 64 / N;        // groups per wavefront
     constexpr int TILE = W * NG * L;  // scan positions per tile
 
@@ -625,11 +635,11 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     const bool full = (long long)(t + 1) * TILE <= T && (!REV || t > 0);
     S Ar[L][N], be[L], yo[L];
     if (full) {
-        if constexpr (DP == 0) load_pairs<S, N, L, REV, true>(Ab, bb, T, e0, i, Ar, be);
+        if constexpr (DP == 0) load_pairs<S, N, L, REV, true, ADDI>(Ab, bb, T, e0, i, Ar, be);
         load_previous<S, N, L, REV, true>(oldb ? oldb : bb, T, e0, i, yo);
         if constexpr (DP > 0) gru_pairs<S, N, L, DP, true>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
     } else {
-        if constexpr (DP == 0) load_pairs<S, N, L, REV, false>(Ab, bb, T, e0, i, Ar, be);
+        if constexpr (DP == 0) load_pairs<S, N, L, REV, false, ADDI>(Ab, bb, T, e0, i, Ar, be);
         load_previous<S, N, L, REV, false>(oldb ? oldb : bb, T, e0, i, yo);
         if constexpr (DP > 0) gru_pairs<S, N, L, DP, false>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
     }

@@ -155,10 +155,11 @@ class DeerContext:
     def grad(self, theta, x, y0, y, dLdy, want_dx=True, want_dy0=True):
         """deer_grad.  Returns (dL/dtheta, dL/dx or None, dL/dy0 or None)."""
         c = self.cfg
+        ode = c.cell == DEER_CELL_MLP_ODE   # autonomous field: no inputs, hence no dL/dx; x and y0 may be None
         for t in (theta, x, y0, y, dLdy):
             self._tensor(t)
         dtheta = torch.empty(theta_count(c), dtype=self.torch_dtype, device=self.device)
-        dx = torch.empty((c.B, c.T, c.d), dtype=self.torch_dtype, device=self.device) if want_dx else None
+        dx = torch.empty((c.B, c.T, c.d), dtype=self.torch_dtype, device=self.device) if (want_dx and not ode) else None
         dy0 = torch.empty((c.B, c.n), dtype=self.torch_dtype, device=self.device) if want_dy0 else None
         st = self.lib.deer_grad(self.handle, _ptr(theta), _ptr(x), _ptr(y0), _ptr(y), _ptr(dLdy), _ptr(dx),
                                 _ptr(dtheta), _ptr(dy0))

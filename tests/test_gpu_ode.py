@@ -1,10 +1,11 @@
-"""GPU parity of deer_eval for the NeuralODE cell (MLP field, midpoint-exponential discretisation)
-against the oracle's own DEER on the same grid."""
+"""GPU parity of deer_eval and deer_grad for the NeuralODE cell (MLP field, midpoint-exponential
+discretisation) against the oracle's own DEER and dual operator on the same grid."""
 import numpy as np
 import pytest
 
+import oracle
 from paper_2309_12252_amd import deer, inputs
-from helpers import TOL_ABS, gpu_eval, oracle_eval
+from helpers import DEV, TOL_ABS, dev, gpu_eval, host, oracle_cell, oracle_eval
 
 pytestmark = pytest.mark.gpu
 
@@ -39,3 +40,49 @@ def test_coarse_grid_uses_scaling_and_squaring():
 
 def test_config5_full_size():
     check(inputs.config(5), deer.DEER_F32)
+
+
+# ---- backward derivative (Sec. 3.1.1 eq. 7 on the discretised operator) ----
+
+def rel_err(got, want):
+    return np.abs(got - want).max() / max(1.0, np.abs(want).max())
+
+
+def check_grad(w, dtype, seed=0):
+    cell = oracle_cell(w)
+    y, _, _, _ = oracle_eval(w, tol=1e-9)
+    y = y.astype(np.float32).astype(np.float64)          # what the device sees in either precision
+    g = np.random.default_rng(seed).standard_normal(y.shape) / np.sqrt(w.T)
+    g = g.astype(np.float32).astype(np.float64)
+    dth_o, dy0_o = oracle.ode_grad(cell, w.theta, y, g, w.t0, w.t1)
+    ctx = deer.context_for(w, dtype=dtype, device=DEV)
+    try:
+        dth, dx, dy0 = ctx.grad(dev(w.theta, dtype), None, None, dev(y, dtype), dev(g, dtype))
+        dth2, _, none0 = ctx.grad(dev(w.theta, dtype), None, None, dev(y, dtype), dev(g, dtype), want_dy0=False)
+    finally:
+        ctx.close()
+    assert dx is None and none0 is None
+    assert rel_err(host(dth), dth_o) <= TOL_ABS[dtype], (w.name, dtype, rel_err(host(dth), dth_o))
+    assert rel_err(host(dy0), dy0_o) <= TOL_ABS[dtype], (w.name, dtype, rel_err(host(dy0), dy0_o))
+    assert np.array_equal(host(dth), host(dth2))   # fixed reduction order: run-to-run identical
+
+
+@pytest.mark.parametrize("n,width", [(2, 16), (4, 32), (8, 16), (8, 32), (8, 64), (4, 16)])
+@pytest.mark.parametrize("dtype", [deer.DEER_F32, deer.DEER_F64])
+def test_grad_small_ode_shapes(n, width, dtype):
+    for k, (B, T, t1) in enumerate([(1, 2, 0.1), (2, 50, 1.0), (3, 1300, 2.0), (1, 5000, 4.0)]):
+        w = inputs.mlp_ode_workload("odeg_n%d_T%d" % (n, T), 50 * n + width + k, B=B, T=T, n=n, width=width, nhid=2,
+                                    t0=0.0, t1=t1, tol=1e-7)
+        check_grad(w, dtype, seed=k)
+
+
+def test_grad_coarse_grid():
+    w = inputs.mlp_ode_workload("coarse_g", 78, B=2, T=12, n=4, width=16, nhid=2, t0=0.0, t1=6.0, tol=1e-7)
+    w.theta = (w.theta * 2.0).astype(np.float32)
+    check_grad(w, deer.DEER_F32)
+    check_grad(w, deer.DEER_F64)
+
+
+def test_config5_grad_full_size():
+    print("config 5 gradient: oracle on 800k grid points", flush=True)
+    check_grad(inputs.config(5), deer.DEER_F32)
