@@ -34,7 +34,9 @@ struct RowLayout {
     __host__ __device__ RowLayout(int n, int width) {
         a1 = 0; a2 = width; d1 = 2 * width; d2 = 3 * width;
         y = 4 * width; w = y + ceil4(n); one = w + ceil4(n);
-        len = one + 4 + 4;   // "1" padded to four entries, plus four so that rows start in different banks
+        len = one + 4;       // "1" padded to four entries
+        // row length = 4 (mod 32) words: the 16-byte reads of consecutive points then fall on different banks
+        while ((len & 31) != 4) len += 4;
     }
 };
 // offsets of the staged weights in LDS: W1, b1, W2, b2, W3^T, W2^T
@@ -161,28 +163,58 @@ __global__ __launch_bounds__(kThreads) void mlp_vjp_kernel(MlpVjpParams p, int p
             for (int k = 0; k < 4; ++k) R[rl.one + k] = (valid && k == 0) ? S(1) : S(0);
         }
         __syncthreads();
+        // (all inner products run over four entries at a time: 16-byte LDS reads of the point's row and of
+        // the weights, which every lane of a wavefront reads at the same address)
         for (int h = part; h < w; h += split) {
             S a = sW[wl.b1 + h];
-            for (int k = 0; k < n; ++k) a += sW[wl.W1 + h * n + k] * R[rl.y + k];
+            if ((n & 3) == 0) {
+                for (int k = 0; k < n; k += 4) {
+                    S wv[4], yv[4];
+                    vload<S, 4>(wv, sW + wl.W1 + h * n + k);
+                    vload<S, 4>(yv, R + rl.y + k);
+                    a += wv[0] * yv[0] + wv[1] * yv[1] + wv[2] * yv[2] + wv[3] * yv[3];
+                }
+            } else {
+                for (int k = 0; k < n; ++k) a += sW[wl.W1 + h * n + k] * R[rl.y + k];
+            }
             R[rl.a1 + h] = tanh_(a);
         }
         __syncthreads();
         for (int h = part; h < w; h += split) {
             S a = sW[wl.b2 + h];
-            for (int k = 0; k < w; ++k) a += sW[wl.W2 + h * w + k] * R[rl.a1 + k];
+            for (int k = 0; k < w; k += 4) {
+                S wv[4], av[4];
+                vload<S, 4>(wv, sW + wl.W2 + h * w + k);
+                vload<S, 4>(av, R + rl.a1 + k);
+                a += wv[0] * av[0] + wv[1] * av[1] + wv[2] * av[2] + wv[3] * av[3];
+            }
             R[rl.a2 + h] = tanh_(a);
         }
         __syncthreads();
         for (int h = part; h < w; h += split) {
             S s = S(0);
-            for (int r = 0; r < n; ++r) s += sW[wl.W3T + h * n + r] * R[rl.w + r];
+            if ((n & 3) == 0) {
+                for (int r = 0; r < n; r += 4) {
+                    S wv[4], cv[4];
+                    vload<S, 4>(wv, sW + wl.W3T + h * n + r);
+                    vload<S, 4>(cv, R + rl.w + r);
+                    s += wv[0] * cv[0] + wv[1] * cv[1] + wv[2] * cv[2] + wv[3] * cv[3];
+                }
+            } else {
+                for (int r = 0; r < n; ++r) s += sW[wl.W3T + h * n + r] * R[rl.w + r];
+            }
             const S a2 = R[rl.a2 + h];
             R[rl.d2 + h] = s * (S(1) - a2 * a2);
         }
         __syncthreads();
         for (int h = part; h < w; h += split) {
             S s = S(0);
-            for (int k = 0; k < w; ++k) s += sW[wl.W2T + h * w + k] * R[rl.d2 + k];
+            for (int k = 0; k < w; k += 4) {
+                S wv[4], dv[4];
+                vload<S, 4>(wv, sW + wl.W2T + h * w + k);
+                vload<S, 4>(dv, R + rl.d2 + k);
+                s += wv[0] * dv[0] + wv[1] * dv[1] + wv[2] * dv[2] + wv[3] * dv[3];
+            }
             const S a1 = R[rl.a1 + h];
             R[rl.d1 + h] = s * (S(1) - a1 * a1);
         }
@@ -230,7 +262,7 @@ int choose_points(int n, int w, size_t* bytes) {
     const WeightLayout wl(n, w);
     const size_t wbytes = (size_t)((wl.len + 3) & ~3) * sizeof(S);
     int pts = 128;
-    while (pts > 32 && wbytes + (size_t)pts * rl.len * sizeof(S) > (size_t)150 * 1024) pts >>= 1;
+    while (pts > 32 && wbytes + (size_t)pts * rl.len * sizeof(S) > (size_t)56 * 1024) pts >>= 1;   // three blocks per compute unit
     *bytes = wbytes + (size_t)pts * rl.len * sizeof(S);
     return pts;
 }
@@ -256,7 +288,7 @@ int mlp_vjp_blocks(int dtype, int n, int width, long long points) {
     size_t bytes = 0;
     const int pts = dtype == 0 ? choose_points<float>(n, width, &bytes) : choose_points<double>(n, width, &bytes);
     long long chunks = (points + pts - 1) / pts;
-    if (chunks > 512) chunks = 512;
+    if (chunks > 768) chunks = 768;
     if (chunks < 1) chunks = 1;
     return (int)chunks;
 }
