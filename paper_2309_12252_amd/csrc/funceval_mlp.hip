@@ -336,12 +336,21 @@ __device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
 #pragma unroll
         for (int r = 0; r < N; ++r) { wv[r] = nw[r]; pv[r] += nw[r]; }
         if (bound < SeriesTol<S>::v) break;
-        // term_{k+1} = term_k X / (k+1)
+        // term_{k+1} = term_k X / (k+1), row by row in place (row r of the product needs row r of term only)
         bound *= norm * inv1;
-        S nt[N * N];
-        matmul_reg<S, N>(term, X, nt);
 #pragma unroll
-        for (int e = 0; e < N * N; ++e) { term[e] = nt[e] * inv1; D[e] += term[e]; }
+        for (int r = 0; r < N; ++r) {
+            S nr[N];
+#pragma unroll
+            for (int c = 0; c < N; ++c) {
+                S s = S(0);
+#pragma unroll
+                for (int q = 0; q < N; ++q) s += term[r * N + q] * X[q * N + c];
+                nr[c] = s * inv1;
+            }
+#pragma unroll
+            for (int c = 0; c < N; ++c) { term[r * N + c] = nr[c]; D[r * N + c] += nr[c]; }
+        }
     }
     // undo the scaling: phi1(2X) v = (exp(X) + I) phi1(X) v / 2 = phi1(X) v + D phi1(X) v / 2,
     // exp(2X) - I = 2D + D^2
@@ -356,15 +365,25 @@ __device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
         }
 #pragma unroll
         for (int r = 0; r < N; ++r) pv[r] = nv[r];
-        S D2[N * N];
-        matmul_reg<S, N>(D, D, D2);
+        // (term is dead by now: it holds the copy of D that the in-place update needs)
 #pragma unroll
-        for (int e = 0; e < N * N; ++e) D[e] = S(2) * D[e] + D2[e];
+        for (int e = 0; e < N * N; ++e) term[e] = D[e];
+#pragma unroll
+        for (int r = 0; r < N; ++r)
+#pragma unroll
+            for (int c = 0; c < N; ++c) {
+                S s = S(0);
+#pragma unroll
+                for (int q = 0; q < N; ++q) s += term[r * N + q] * term[q * N + c];
+                D[r * N + c] = S(2) * term[r * N + c] + s;
+            }
     }
 }
 
+// (two wavefronts per SIMD wanted: for n = 8 in fp32 the matrices of a thread just fit 256 registers)
 template <typename S, int N>
-__global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams p) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(sizeof(S) == 4 ? 2 : 1)))
+void ode_discretise_kernel(OdeDiscParams p) {
     if (gate_closed<S>(p.gate)) return;
     const long long nint = (long long)p.B * (p.T - 1);
     const long long q = (long long)blockIdx.x * kThreads + threadIdx.x;
@@ -418,7 +437,8 @@ __global__ __launch_bounds__(kThreads) void ode_discretise_kernel(OdeDiscParams 
 // X_i = -(G_i + G_{i+1}) dt / 2, the weight with which the cotangent lam enters df/dtheta at the two ends of
 // the interval, and, for the first interval, dL/dy0 = g_0 + exp(X_0)^T lam_1.
 template <typename S, int N>
-__global__ __launch_bounds__(kThreads) void ode_dual_kernel(OdeDualParams p) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(sizeof(S) == 4 ? 2 : 1)))
+void ode_dual_kernel(OdeDualParams p) {
     const long long nint = (long long)p.B * (p.T - 1);
     const long long q = (long long)blockIdx.x * kThreads + threadIdx.x;
     if (q >= nint) return;
