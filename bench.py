@@ -116,13 +116,17 @@ def scan_stream(torch, deer, dev, n, B, T, steps):
     torch.manual_seed(1)
     dA = torch.randn(B, T, n, n, device=dev)
     # spectral norms by 12 power iterations (the batched SVD behind matrix_norm does not take millions
-    # of matrices); an estimate from below, so the scaled norms are 0.9 or slightly more
-    v = torch.randn(B, T, n, 1, device=dev)
-    for _ in range(12):
-        v = dA.transpose(-1, -2) @ (dA @ v)
-        v /= torch.linalg.vector_norm(v, dim=-2, keepdim=True)
-    dA *= 0.9 / torch.linalg.vector_norm(dA @ v, dim=-2, keepdim=True)
-    del v
+    # of matrices); an estimate from below, so the scaled norms are 0.9 or slightly more.  In chunks of
+    # 2^22 matrices: one batched product over tens of millions of them has faulted in the library.
+    flat = dA.view(B * T, n, n)
+    for lo in range(0, B * T, 1 << 22):
+        a = flat[lo:lo + (1 << 22)]
+        v = torch.randn(a.shape[0], n, 1, device=dev)
+        for _ in range(12):
+            v = a.transpose(-1, -2) @ (a @ v)
+            v /= torch.linalg.vector_norm(v, dim=-2, keepdim=True)
+        a *= 0.9 / torch.linalg.vector_norm(a @ v, dim=-2, keepdim=True)
+        del v
     db, dy0 = torch.randn(B, T, n, device=dev), torch.randn(B, n, device=dev)
     cfg = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, B, T, n, d=1)
     sctx = deer.DeerContext(cfg, device=dev)
