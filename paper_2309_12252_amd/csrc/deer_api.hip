@@ -121,8 +121,13 @@ Plan make_plan(const deer_config* c) {
         const int forced = env_int("DEER_SCAN_L", 0);
         for (int q = 0; q < ncand; ++q)
             if (forced == cand[q]) L = forced;
-        // n = 4 in fp32 has registers for 24 positions per group: measured 4 % faster than 16 on chip-filling streams
-        if (c->dtype == DEER_F32 && c->n == 4 && (forced == 24 || (forced == 0 && L == 16))) L = 24;
+        // n = 4 in fp32 has registers for 24 positions per group: measured 4 % faster than 16 on streams that
+        // still give every compute unit a tile
+        if (c->dtype == DEER_F32 && c->n == 4) {
+            const long long tile24 = scan_valu_tile(4, 24, W);
+            const bool fills = (long long)B * ((p.scan_T + tile24 - 1) / tile24) >= 256;
+            if (forced == 24 || (forced == 0 && L == 16 && fills)) L = 24;
+        }
         p.L = L;
         p.tile = scan_valu_tile(c->n, p.L, p.W);
     }
