@@ -282,7 +282,11 @@ def main():
         torch.cuda.empty_cache()
         s32 = scan_stream(torch, deer, dev, 32, 16, 100000, 10)
         torch.cuda.empty_cache()
+        s4 = scan_stream(torch, deer, dev, 4, 16, 800000, 10)
+        torch.cuda.empty_cache()
         out["scan_kernels"] = {
+            "n4_B16_T800k": {"bound": "hbm", "achieved": round(s4["achieved_GBs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": round(s4["frac_of_8TBs"], 4), "avg_launch_us": round(1e3 * s4["avg_launch_ms"], 1)},
             "n8_B16_T400k": {"bound": "hbm", "achieved": round(s8["achieved_GBs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": round(s8["frac_of_8TBs"], 4), "avg_launch_us": round(1e3 * s8["avg_launch_ms"], 1)},
             "n32_B16_T100k": {"bound": "mfma", "achieved": round(s32["achieved_TFLOPs"], 2), "peak": MFMA_F32_PEAK_TFLOPS,
