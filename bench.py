@@ -312,6 +312,14 @@ def main():
         med = float(np.median(times))
         out["cpu_baseline"] = {"value": S / med, "unit": "sequence-steps/s", "cores": threads, "kind": "oracle",
                                "sample": "the full workload (same DEER solve in fp64), median of %d runs" % len(times)}
+        if w.cell == inputs.CELL_GRU:
+            # for context: the oracle's plain sequential evaluation of the same recurrence (what DEER replaces)
+            seq = []
+            for _ in range(5):
+                a = time.perf_counter()
+                oracle.seq_eval(cell, w.theta, w.x, w.y0, nthreads=threads)
+                seq.append(time.perf_counter() - a)
+            out["cpu_baseline"]["sequential_value"] = S / float(np.median(seq))
     if ctx is not None:
         ctx.close()
     print(json.dumps(out))

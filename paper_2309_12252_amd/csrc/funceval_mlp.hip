@@ -314,42 +314,54 @@ __device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
     for (int k = 0; k < N * N; ++k) X[k] *= scale;
 
     // Taylor series of D = exp(X) - I (matrix, identity left out so that nothing of size |X| is
-    // rounded against 1) and of phi1(X) zc (vector), until the bound norm^k/k! on the next term is
-    // below the working precision
-    S term[N * N], wv[N];
+    // rounded against 1) and of phi1(X) zc (vector), up to the first power K whose bound norm^K/K! is
+    // below the working precision.  The matrix series runs in Horner form from the innermost bracket,
+    //   D = (..((X/K + I) X/(K-1) + I) X/(K-2) ..+ I) X/1,
+    // by right-multiplications, which update a matrix row by row in place: two live matrices instead of the
+    // three a term-by-term sum needs.
+    int K = 1;
+    {
+        S bound = norm;
+        while (K < 24 && !(bound < SeriesTol<S>::v)) { ++K; bound *= norm / (S)K; }
+    }
+    {
+        const S invK = S(1) / (S)K;
 #pragma unroll
-    for (int k = 0; k < N * N; ++k) { D[k] = X[k]; term[k] = X[k]; }
-#pragma unroll
-    for (int k = 0; k < N; ++k) { pv[k] = zc[k]; wv[k] = zc[k]; }
-    S bound = norm;
-    for (int k = 1; k <= 24; ++k) {
-        // w_k = X w_{k-1} / (k+1)
-        S nw[N];
-        const S inv1 = S(1) / (S)(k + 1);
-#pragma unroll
-        for (int r = 0; r < N; ++r) {
-            S s = S(0);
-#pragma unroll
-            for (int c = 0; c < N; ++c) s += X[r * N + c] * wv[c];
-            nw[r] = s * inv1;
-        }
-#pragma unroll
-        for (int r = 0; r < N; ++r) { wv[r] = nw[r]; pv[r] += nw[r]; }
-        if (bound < SeriesTol<S>::v) break;
-        // term_{k+1} = term_k X / (k+1), row by row in place (row r of the product needs row r of term only)
-        bound *= norm * inv1;
+        for (int e = 0; e < N * N; ++e) D[e] = X[e] * invK;
+    }
+    for (int k = K - 1; k >= 1; --k) {
+        const S invk = S(1) / (S)k;
 #pragma unroll
         for (int r = 0; r < N; ++r) {
             S nr[N];
 #pragma unroll
             for (int c = 0; c < N; ++c) {
-                S s = S(0);
+                S s = X[r * N + c];
 #pragma unroll
-                for (int q = 0; q < N; ++q) s += term[r * N + q] * X[q * N + c];
-                nr[c] = s * inv1;
+                for (int q = 0; q < N; ++q) s += D[r * N + q] * X[q * N + c];
+                nr[c] = s * invk;
             }
 #pragma unroll
-            for (int c = 0; c < N; ++c) { term[r * N + c] = nr[c]; D[r * N + c] += nr[c]; }
+            for (int c = 0; c < N; ++c) D[r * N + c] = nr[c];
+        }
+    }
+    {
+        S wv[N];
+#pragma unroll
+        for (int k = 0; k < N; ++k) { pv[k] = zc[k]; wv[k] = zc[k]; }
+        for (int k = 1; k <= K; ++k) {
+            // w_k = X w_{k-1} / (k+1)
+            S nw[N];
+            const S inv1 = S(1) / (S)(k + 1);
+#pragma unroll
+            for (int r = 0; r < N; ++r) {
+                S s = S(0);
+#pragma unroll
+                for (int c = 0; c < N; ++c) s += X[r * N + c] * wv[c];
+                nw[r] = s * inv1;
+            }
+#pragma unroll
+            for (int r = 0; r < N; ++r) { wv[r] = nw[r]; pv[r] += nw[r]; }
         }
     }
     // undo the scaling: phi1(2X) v = (exp(X) + I) phi1(X) v / 2 = phi1(X) v + D phi1(X) v / 2,
@@ -365,17 +377,17 @@ __device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
         }
 #pragma unroll
         for (int r = 0; r < N; ++r) pv[r] = nv[r];
-        // (term is dead by now: it holds the copy of D that the in-place update needs)
+        // (X is dead by now: it holds the copy of D that the update needs)
 #pragma unroll
-        for (int e = 0; e < N * N; ++e) term[e] = D[e];
+        for (int e = 0; e < N * N; ++e) X[e] = D[e];
 #pragma unroll
         for (int r = 0; r < N; ++r)
 #pragma unroll
             for (int c = 0; c < N; ++c) {
                 S s = S(0);
 #pragma unroll
-                for (int q = 0; q < N; ++q) s += term[r * N + q] * term[q * N + c];
-                D[r * N + c] = S(2) * term[r * N + c] + s;
+                for (int q = 0; q < N; ++q) s += X[r * N + q] * X[q * N + c];
+                D[r * N + c] = S(2) * X[r * N + c] + s;
             }
     }
 }
