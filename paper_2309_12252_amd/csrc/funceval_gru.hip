@@ -58,28 +58,6 @@ struct Gates {
 
 // gates of row i at (h, x)
 template <typename S, int N>
-__device__ __forceinline__ void row_gates(const RowWeights<S, N>& w, const S* sW, int ds, int d, int i,
-                                          const S* h, const S* __restrict__ xp, Gates<S, N>& g) {
-    S ar = w.br, az = w.bz, ac = w.bc, q = w.bh;
-    for (int k = 0; k < d; ++k) {
-        const S xv = xp[k];
-        ar += sW[(i)*ds + k] * xv;
-        az += sW[(N + i) * ds + k] * xv;
-        ac += sW[(2 * N + i) * ds + k] * xv;
-    }
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-        ar += w.Ur[j] * h[j];
-        az += w.Uz[j] * h[j];
-        q += w.Uc[j] * h[j];
-    }
-    g.r = sigmoid_(ar);
-    g.z = sigmoid_(az);
-    g.q = q;
-    g.c = tanh_(ac + g.r * q);
-}
-
-template <typename S, int N>
 __global__ __launch_bounds__(kThreads) void gru_funceval_kernel(GruParams p) {
     if (gate_closed<S>(p.gate)) return;
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -240,20 +218,59 @@ __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
     // every thread of a block runs the same number of passes so that the shuffles below always
     // see whole positions; a pass past the end contributes zeros
     const long long passes = (total + (long long)gridDim.x * SPB - 1) / ((long long)gridDim.x * SPB);
-    for (long long it = 0; it < passes; ++it) {
+    // Software pipeline: the operands of the next pass are requested before the current one is computed, so a
+    // pass does not expose a memory round trip (the accumulators leave room for two wavefronts per SIMD only).
+    S hn[N], hin = S(0), xn[DP], lmn = S(0);
+    auto fetch = [&](long long it) {
         const long long s = (it * gridDim.x + blockIdx.x) * SPB + sg;
         const bool live = s < total;
         const long long sc_ = live ? s : 0;
         const long long bi = sc_ / p.T;
         const int ti = (int)(sc_ - bi * p.T);
         const S* hp = (ti == 0) ? (y0 + bi * N) : (y + (sc_ - 1) * N);
-        S h[N];
-        vload<S, N>(h, hp);
-        const S hi = hp[i];
-        const S* xp = x + sc_ * d;
+        vload<S, N>(hn, hp);
+        hin = hp[i];
+#pragma unroll
+        for (int k = 0; k < DP; ++k) xn[k] = (k < d) ? x[sc_ * d + k] : S(0);
+        lmn = live ? lam[sc_ * N + i] : S(0);
+    };
+    if (passes > 0) fetch(0);
+    for (long long it = 0; it < passes; ++it) {
+        const long long s = (it * gridDim.x + blockIdx.x) * SPB + sg;
+        const bool live = s < total;
+        const long long sc_ = live ? s : 0;
+        const long long bi = sc_ / p.T;
+        const int ti = (int)(sc_ - bi * p.T);
+        S h[N], xp[DP];
+#pragma unroll
+        for (int j = 0; j < N; ++j) h[j] = hn[j];
+#pragma unroll
+        for (int k = 0; k < DP; ++k) xp[k] = xn[k];
+        const S hi = hin;
+        const S lm = lmn;
+        if (it + 1 < passes) fetch(it + 1);
         Gates<S, N> g;
-        row_gates<S, N>(w, sW, ds, d, i, h, xp, g);
-        const S lm = live ? lam[sc_ * N + i] : S(0);
+        {
+            S ar = w.br, az = w.bz, ac = w.bc, q = w.bh;
+#pragma unroll
+            for (int k = 0; k < DP; ++k) {
+                if (k < d) {
+                    ar += sW[(i)*ds + k] * xp[k];
+                    az += sW[(N + i) * ds + k] * xp[k];
+                    ac += sW[(2 * N + i) * ds + k] * xp[k];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                ar += w.Ur[j] * h[j];
+                az += w.Uz[j] * h[j];
+                q += w.Uc[j] * h[j];
+            }
+            g.r = sigmoid_(ar);
+            g.z = sigmoid_(az);
+            g.q = q;
+            g.c = tanh_(ac + g.r * q);
+        }
         const S dcand = lm * (S(1) - g.z);
         const S dac = dcand * (S(1) - g.c * g.c);
         const S daz = lm * (hi - g.c) * g.z * (S(1) - g.z);
