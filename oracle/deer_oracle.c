@@ -22,7 +22,7 @@
  *   - backward derivative through the dual operator           Sec. 3.1.1 eq. 7
  *     (recurrence form, and the ODE form on the discretised operator)
  *
- * Readings where the paper is silent (all listed in the design notes):
+ * Readings where the paper is silent:
  *   - GRU cell: gates r, z, candidate c with the reset gate applied after the
  *     hidden projection; biases on the three input projections and on the
  *     candidate's hidden projection:
