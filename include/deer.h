@@ -74,10 +74,11 @@ typedef struct deer_ctx deer_ctx; /* opaque, host memory owned by the library */
 /* Accumulated per-kernel device time, filled while profiling is on (see deer_set_profiling). */
 typedef struct {
     double funceval_ms;   int64_t funceval_launches;   /* f, Jacobian and right-hand side            */
-    double discretise_ms; int64_t discretise_launches; /* ODE only: exp(-G dt), phi1                 */
+    double discretise_ms; int64_t discretise_launches; /* ODE only: exp(-G dt), phi1; in deer_grad also   */
+                                                       /* the residual and the dual discretisation       */
     double scan_ms;       int64_t scan_launches;       /* inverse linear operator (+ fused max|dy|)  */
-    double vjp_ms;        int64_t vjp_launches;        /* GRU VJP + parameter-gradient reduction     */
-    double fused_ms;      int64_t fused_launches;      /* GRU, n <= 8: cell + scan + max|dy| in one   */
+    double vjp_ms;        int64_t vjp_launches;        /* VJP of f + parameter-gradient reduction    */
+    double fused_ms;      int64_t fused_launches;      /* GRU: cell + scan + max|dy| in one launch    */
     double newton_ms;     int64_t newton_launches;     /* GRU, small problems: a whole solve in one   */
     int64_t newton_iterations;                         /* Newton iterations inside those launches     */
 } deer_profile;
