@@ -25,9 +25,10 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kMaxD = 16;
 
-__device__ __forceinline__ float sigmoid_(float a) { return 1.0f / (1.0f + expf(-a)); }
+// fp32: hardware exp2 and reciprocal (absolute error below 3e-7), as in the fused step
+__device__ __forceinline__ float sigmoid_(float a) { return feed_sigmoid(a); }
 __device__ __forceinline__ double sigmoid_(double a) { return 1.0 / (1.0 + exp(-a)); }
-__device__ __forceinline__ float tanh_(float a) { return tanhf(a); }
+__device__ __forceinline__ float tanh_(float a) { return feed_tanh(a); }
 __device__ __forceinline__ double tanh_(double a) { return tanh(a); }
 
 template <typename S, int N>

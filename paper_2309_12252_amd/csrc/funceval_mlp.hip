@@ -23,7 +23,8 @@ namespace {
 
 constexpr int kThreads = 256;
 
-__device__ __forceinline__ float tanh_(float a) { return tanhf(a); }
+// fp32: hardware exp2 and reciprocal (absolute error below 3e-7)
+__device__ __forceinline__ float tanh_(float a) { return feed_tanh(a); }
 __device__ __forceinline__ double tanh_(double a) { return tanh(a); }
 
 template <typename S, int N, int W>
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void mlp_funceval_mfma_kernel(MlpParams p
             for (int kk = 0; kk < 2; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1a[I][kk], yb[kk], acc, 0, 0, 0);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float t = tanhf(acc[v]);
+                const float t = feed_tanh(acc[v]);
                 a1[I][v] = t;
                 d1[I][v] = 1.0f - t * t;
                 q1[I][v] = d1[I][v] * (acc[v] - b1c[I][v]);
@@ -220,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void mlp_funceval_mfma_kernel(MlpParams p
                 }
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float t = tanhf(acc[v]);
+                const float t = feed_tanh(acc[v]);
                 a2[I][v] = t;
                 d2[I][v] = 1.0f - t * t;
                 q2[I][v] = d2[I][v] * accq[v];

@@ -23,7 +23,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kMaxTasks = 3;   // 4 x 4 blocks per thread (width 64: 354 tasks over 128 threads)
 
-__device__ __forceinline__ float tanh_(float a) { return tanhf(a); }
+// fp32: hardware exp2 and reciprocal (absolute error below 3e-7)
+__device__ __forceinline__ float tanh_(float a) { return feed_tanh(a); }
 __device__ __forceinline__ double tanh_(double a) { return tanh(a); }
 
 __host__ __device__ inline int ceil4(int v) { return (v + 3) & ~3; }
