@@ -740,7 +740,12 @@ deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const v
     GruVjpParams vp{d_theta, d_x, d_y0, d_y, lam, d_dLdx, d_dLdy0, c->ws + c->plan.off_partial, d_dLdtheta,
                     g.B, g.T, g.n, g.d, c->plan.vjp_blocks};
     prof_begin(c, KIND_VJP);
-    HIPCHK(c, launch_gru_vjp(g.dtype, vp, c->stream));
+    if (gru_vjp_mfma_supported(g.dtype, g.n, g.d) && env_int("DEER_VJP_MFMA", 1) != 0) {
+        HIPCHK(c, launch_gru_vjp_mfma(vp, c->stream));
+        HIPCHK(c, launch_partial_reduce(g.dtype, vp.partial, d_dLdtheta, (long long)theta_count(&g), vp.blocks * 4, c->stream));
+    } else {
+        HIPCHK(c, launch_gru_vjp(g.dtype, vp, c->stream));
+    }
     prof_end(c);
     st = check_status(c);
     prof_collect(c);

@@ -291,6 +291,9 @@ hipError_t launch_scan_gru_fused(int dtype, int n, const ScanParams& p, const vo
 int scan_mfma_tile(int dtype, int n);
 hipError_t launch_gru_funceval(int dtype, const GruParams& p, hipStream_t s);
 hipError_t launch_gru_vjp(int dtype, const GruVjpParams& p, hipStream_t s);
+// the same on the matrix cores (fp32, n = 16 or 32, d <= 16): kernel only, partial rows = blocks * 4
+bool gru_vjp_mfma_supported(int dtype, int n, int d);
+hipError_t launch_gru_vjp_mfma(const GruVjpParams& p, hipStream_t s);
 int gru_vjp_blocks(int n, long long steps);
 hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s);
 hipError_t launch_ode_discretise(int dtype, const OdeDiscParams& p, hipStream_t s);

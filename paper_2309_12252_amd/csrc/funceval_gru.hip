@@ -451,7 +451,8 @@ hipError_t launch_vjp_s(const GruVjpParams& p, hipStream_t s) {
 int gru_vjp_blocks(int n, long long steps) {
     const int spb = kThreads / n;
     long long blocks = (steps + spb - 1) / spb;
-    if (blocks > 512) blocks = 512;
+    // (n = 16: the matrix-core kernel fits three wavefronts per SIMD, i.e. 768 blocks of four)
+    if (blocks > (n == 16 ? 768 : 512)) blocks = (n == 16 ? 768 : 512);
     if (blocks < 1) blocks = 1;
     return (int)blocks;
 }
