@@ -138,7 +138,9 @@ deer_status deer_eval(deer_ctx* ctx, const void* d_theta, const void* d_x, const
  *   d_y        in  trajectory [B,T,n]          d_dLdy   in  g = dL/dy [B,T,n]
  *   d_dLdx     out [B,T,d], or NULL to skip    d_dLdtheta out [theta_count] (overwritten, not accumulated)
  *   d_dLdy0    out [B,n], or NULL to skip
- * The parameter gradient is summed in a fixed order: two calls with the same inputs return the same bits. */
+ * The parameter gradient is summed in a fixed order: two calls with the same inputs return the same bits.
+ * For the GRU in fp32 with n = 16, 32 and d <= 16 the vector-Jacobian product runs on the matrix cores;
+ * DEER_VJP_MFMA=0 (read at each call; for tests and measurements) selects the vector-ALU kernel instead. */
 deer_status deer_grad(deer_ctx* ctx, const void* d_theta, const void* d_x, const void* d_y0,
                       const void* d_y, const void* d_dLdy, void* d_dLdx, void* d_dLdtheta,
                       void* d_dLdy0);
