@@ -302,7 +302,7 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
 #endif
     hipError_t e;
     if (fused_theta && c->plan.mfma) {
-        p.tiles = c->plan.fused_tiles;
+        p.tiles = reverse ? c->plan.tiles : c->plan.fused_tiles;   // the dual scan keeps the plain scan's tile shape
         prof_begin(c, KIND_FUSED, iter);
         e = launch_scan_mfma_fused(g.n, p, fused_theta, fused_x, g.d, c->stream);
     } else if (fused_theta) {
@@ -729,14 +729,20 @@ deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const v
 
     deer_status st = zero_ctl(c);
     if (st != DEER_OK) return st;
-    // Jacobians at the given trajectory (the right-hand side output is not used)
-    GruParams gp{d_theta, d_x, d_y0, d_y, J, rhs, g.B, g.T, g.n, g.d, Gate{nullptr, 0.0}};
-    prof_begin(c, KIND_FUNCEVAL);
-    HIPCHK(c, launch_gru_funceval(g.dtype, gp, c->stream));
-    prof_end(c);
-    // lam = (dL/dy) L_G^{-1}: reverse scan with transposed Jacobians
-    HIPCHK(c, run_scan(c, J, d_dLdy, nullptr, lam, nullptr, (long long)(T * n * n), (long long)(T * n),
-                       (long long)(T * n), 1, 0, false));
+    if (c->plan.mfma && c->plan.fused && env_int("DEER_GRAD_FUSED", 1) != 0) {
+        // lam = (dL/dy) L_G^{-1} with the transposed Jacobians computed inside the reverse scan (they never reach memory)
+        HIPCHK(c, run_scan(c, nullptr, d_dLdy, nullptr, lam, d_y, 0, (long long)(T * n), (long long)(T * n), 1, 0, false, 0,
+                           Gate{nullptr, 0.0}, -1, d_theta, d_x));
+    } else {
+        // Jacobians at the given trajectory (the right-hand side output is not used)
+        GruParams gp{d_theta, d_x, d_y0, d_y, J, rhs, g.B, g.T, g.n, g.d, Gate{nullptr, 0.0}};
+        prof_begin(c, KIND_FUNCEVAL);
+        HIPCHK(c, launch_gru_funceval(g.dtype, gp, c->stream));
+        prof_end(c);
+        // lam = (dL/dy) L_G^{-1}: reverse scan with transposed Jacobians
+        HIPCHK(c, run_scan(c, J, d_dLdy, nullptr, lam, nullptr, (long long)(T * n * n), (long long)(T * n),
+                           (long long)(T * n), 1, 0, false));
+    }
     GruVjpParams vp{d_theta, d_x, d_y0, d_y, lam, d_dLdx, d_dLdy0, c->ws + c->plan.off_partial, d_dLdtheta,
                     g.B, g.T, g.n, g.d, c->plan.vjp_blocks};
     prof_begin(c, KIND_VJP);

@@ -93,10 +93,14 @@ __device__ __forceinline__ S sum_groups(S v) {
 
 // FUSE: the pairs are not loaded but computed from the GRU cell at the previous iterate (p.yold), Sec. 3.1
 // eq. 3 and 5: J in A-operand layout straight from the gate values and the weights (kept in LDS in that
-// layout), rhs = f - J h.  fp32, forward scans only.
+// layout), rhs = f - J h.  fp32 only.  FUSE with REV is the dual scan of Sec. 3.1.1 eq. 7 with the transposed
+// Jacobians computed the same way at the trajectory p.yold (scan position e carries time T-1-e: its matrix is
+// the transpose of the Jacobian at time T-e, which depends on the state at T-1-e and the input at T-e; the
+// vector is still loaded from p.bv); no convergence measure is taken.
 template <typename S, int N, int LW, int WAVES, bool REV, bool FUSE>
 __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, GruFeed gf) {
-    static_assert(!FUSE || (!REV && sizeof(S) == 4), "the fused cell feeds forward fp32 scans only");
+    static_assert(!FUSE || sizeof(S) == 4, "the fused cell feeds fp32 scans only");
+    constexpr bool DUAL = FUSE && REV;
     constexpr int NB = N / 16;
     constexpr int LD = N + 1;   // LDS row stride of a wavefront total
     constexpr int TILE = LW * WAVES;
@@ -119,7 +123,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     __shared__ __align__(16) S sU[FUSE ? 3 : 1][FUSE ? N : 1][FUSE ? LDU : 1];
     __shared__ __align__(16) S sB[FUSE ? 4 : 1][FUSE ? N : 1];
     // per wavefront: p_z, s_r, s_t, z and rhs of its LW positions, [scalar][position][row]
-    __shared__ __align__(16) S sS[FUSE ? WAVES : 1][5][FUSE ? LW : 1][FUSE ? N : 1];
+    __shared__ __align__(16) S sS[FUSE ? WAVES : 1][DUAL ? 4 : 5][FUSE ? LW : 1][FUSE ? N : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -218,7 +222,16 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
         const long long e = (e0 + i < p.T) ? e0 + i : (long long)p.T - 1;
         const S* src = oldb ? oldb : bb;   // branch free: without a previous iterate the value is unused
 #pragma unroll
-        for (int I = 0; I < NB; ++I) yo[i][I] = src[(REV ? ((long long)p.T - 1 - e) : e) * N + 16 * I + r];
+        for (int I = 0; I < NB; ++I) {
+            if constexpr (DUAL) {
+                // no previous iterate in the dual scan; its vector (the cotangent) is requested here instead
+                yo[i][I] = S(0);
+                const S bv = bb[((long long)p.T - 1 - e) * N + 16 * I + r];
+                bel[i][I] = (e0 + i < p.T) ? bv : S(0);
+            } else {
+                yo[i][I] = src[(REV ? ((long long)p.T - 1 - e) : e) * N + 16 * I + r];
+            }
+        }
     }
 
     if constexpr (FUSE) {
@@ -238,9 +251,20 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
         for (int cb = 0; cb < (LW + 15) / 16; ++cb) {
         const int c = (16 * cb + r < LW) ? 16 * cb + r : LW - 1;   // position handled as a column (lanes beyond LW repeat the last)
         const long long ecol = e0 + c;
-        const long long ecl = ecol < p.T ? ecol : (long long)p.T;     // past the end: the last state (result unused)
-        const S* hp = (ecl > 0) ? oldb + (ecl - 1) * N : (y0p ? y0p + (long long)b * N : nullptr);
-        const long long exl = ecol < p.T ? ecol : (long long)p.T - 1;
+        const S* hp;
+        long long exl;
+        if constexpr (!REV) {
+            const long long ecl = ecol < p.T ? ecol : (long long)p.T;     // past the end: the last state (result unused)
+            hp = (ecl > 0) ? oldb + (ecl - 1) * N : (y0p ? y0p + (long long)b * N : nullptr);
+            exl = ecol < p.T ? ecol : (long long)p.T - 1;
+        } else {
+            // Jacobian at time T - e; position 0 and positions past the end have none: any valid one is computed and dropped
+            long long tj = (long long)p.T - ecol;
+            tj = tj > (long long)p.T - 1 ? (long long)p.T - 1 : tj;
+            tj = tj < 0 ? 0 : tj;
+            exl = tj;
+            hp = oldb + (tj > 0 ? tj - 1 : 0) * N;
+        }
         S hB[N / 4], xB[4];
 #pragma unroll
         for (int kk = 0; kk < N / 4; ++kk) hB[kk] = hp ? hp[4 * kk + g] : S(0);
@@ -290,18 +314,54 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
                 o_pz[v] = pz; o_sr[v] = sr; o_st[v] = st; o_z[v] = z;
                 o_rhs[v] = f - (pz * uh[1][v] + (sr * uh[2][v] + (st * uh[0][v] + z * h)));
             }
+            (void)o_rhs;
             if (16 * cb + r < LW) {
                 vstore<S, 4>(&sSw[0][c][16 * I + 4 * g], o_pz);
                 vstore<S, 4>(&sSw[1][c][16 * I + 4 * g], o_sr);
                 vstore<S, 4>(&sSw[2][c][16 * I + 4 * g], o_st);
                 vstore<S, 4>(&sSw[3][c][16 * I + 4 * g], o_z);
-                vstore<S, 4>(&sSw[4][c][16 * I + 4 * g], o_rhs);
+                if constexpr (!DUAL) vstore<S, 4>(&sSw[4][c][16 * I + 4 * g], o_rhs);
             }
         }
         }   // column batches
+        // dual scan: the transposed Jacobian in A-operand layout, a[i][I][K][v] = J[16K + 4g + v][16I + r]: the
+        // row factors come four at a time, the weights are read down a column
+        if constexpr (DUAL) {
+            // the diagonal as arithmetic (a select on the lane's own indices would become a branch around the read)
+            S dsel[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) dsel[v] = (4 * g + v == r) ? S(1) : S(0);
+#pragma unroll
+            for (int i = 0; i < LW; ++i) {
+                const long long e = e0 + i;
+                const S live = (e >= p.T || e == 0) ? S(0) : S(1);   // no matrix at position 0 (zero) and past the end
+                const S unit = (e >= p.T) ? S(1) : S(0);             // ... where the pair is the identity
+#pragma unroll
+                for (int K = 0; K < NB; ++K) {
+                    S pz[4], sr[4], st[4], zz[4];
+                    vload<S, 4>(pz, &sSw[0][i][16 * K + 4 * g]);
+                    vload<S, 4>(sr, &sSw[1][i][16 * K + 4 * g]);
+                    vload<S, 4>(st, &sSw[2][i][16 * K + 4 * g]);
+                    vload<S, 4>(zz, &sSw[3][i][16 * K + 4 * g]);
+#pragma unroll
+                    for (int I = 0; I < NB; ++I) {
+                        const int col = 16 * I + r;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int row = 16 * K + 4 * g + v;
+                            S jv = pz[v] * sU[1][row][col] + (sr[v] * sU[2][row][col] + st[v] * sU[0][row][col]);
+                            if (I == K) jv += dsel[v] * zz[v];
+                            jv *= live;
+                            if (I == K) jv += dsel[v] * unit;
+                            a[i][I][K][v] = jv;
+                        }
+                    }
+                }
+            }
+        }
         // J of every position in A-operand layout from its row's three factors (weights from LDS in that layout)
 #pragma unroll
-        for (int i = 0; i < LW; ++i) {
+        for (int i = 0; i < (DUAL ? 0 : LW); ++i) {
             const bool past = e0 + i >= p.T;
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
@@ -645,7 +705,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
                 S wv = yr[I];
-                if (oldb) {
+                if (!DUAL && oldb) {
                     const S dq = abs_or_inf<S>(p.delta ? yr[I] : yr[I] - yo[i][I]);
                     emax = dq > emax ? dq : emax;
                     if (p.delta) wv += yo[i][I];
@@ -692,7 +752,12 @@ template <int N>
 hipError_t launch_fused_n(const ScanParams& p, const GruFeed& gf, hipStream_t s) {
     constexpr int LW = MfmaFusedShape<N>::LW, WAVES = MfmaFusedShape<N>::WAVES;
     dim3 grid((unsigned)((long long)p.B * p.tiles));
-    hipLaunchKernelGGL((scan_mfma_kernel<float, N, LW, WAVES, false, true>), grid, dim3(64 * WAVES), 0, s, p, gf);
+    if (p.reverse)   // the dual scan runs on the tile shape of the plain scan (n = 16: three wavefronts per SIMD; 24 positions
+                     // per wavefront measured 10 % slower)
+        hipLaunchKernelGGL((scan_mfma_kernel<float, N, MfmaShape<float, N>::LW, MfmaShape<float, N>::WAVES, true, true>), grid,
+                           dim3(64 * MfmaShape<float, N>::WAVES), 0, s, p, gf);
+    else
+        hipLaunchKernelGGL((scan_mfma_kernel<float, N, LW, WAVES, false, true>), grid, dim3(64 * WAVES), 0, s, p, gf);
     return hipGetLastError();
 }
 
@@ -712,7 +777,7 @@ int scan_mfma_fused_tile(int n) {
 bool scan_mfma_fused_supported(int dtype, int n, int d) { return dtype == 0 && (n == 16 || n == 32) && d >= 1 && d <= 16; }
 
 hipError_t launch_scan_mfma_fused(int n, const ScanParams& p, const void* theta, const void* x, int d, hipStream_t s) {
-    if (!scan_mfma_fused_supported(0, n, d) || p.reverse || p.delta || !p.yold) return hipErrorInvalidValue;
+    if (!scan_mfma_fused_supported(0, n, d) || p.delta || !p.yold) return hipErrorInvalidValue;
     const GruFeed gf{theta, x, d};
     return n == 16 ? launch_fused_n<16>(p, gf, s) : launch_fused_n<32>(p, gf, s);
 }

@@ -40,11 +40,13 @@ def test_small_shapes(n, d, dtype):
         check_grad(w, g.astype(np.float32).astype(np.float64), dtype)
 
 
+@pytest.mark.parametrize("knob", ["DEER_VJP_MFMA", "DEER_GRAD_FUSED"])
 @pytest.mark.parametrize("n,d", [(16, 6), (32, 16)])
-def test_vector_alu_kernel_at_the_matrix_core_sizes(n, d, monkeypatch):
-    # fp32 with n = 16, 32 goes to the matrix-core VJP by default; the vector-ALU kernel stays selectable
-    monkeypatch.setenv("DEER_VJP_MFMA", "0")
-    for k, (B, T) in enumerate([(2, 9), (3, 700)]):
+def test_unfused_kernels_at_the_matrix_core_sizes(n, d, knob, monkeypatch):
+    # fp32 with n = 16, 32 computes the Jacobians inside the reverse scan and runs the VJP on the matrix cores by
+    # default; the Jacobian kernel + plain reverse scan and the vector-ALU VJP stay selectable
+    monkeypatch.setenv(knob, "0")
+    for k, (B, T) in enumerate([(2, 9), (3, 700), (1, 1)]):
         w = inputs.gru_workload("g_n%d_T%d" % (n, T), 70 * n + k, B=B, T=T, n=n, d=d)
         g = np.random.default_rng(k + 1).standard_normal((B, T, n)) / np.sqrt(T)
         check_grad(w, g.astype(np.float32).astype(np.float64), deer.DEER_F32)
