@@ -139,10 +139,11 @@ deer_status deer_eval(deer_ctx* ctx, const void* d_theta, const void* d_x, const
  *   d_dLdx     out [B,T,d], or NULL to skip    d_dLdtheta out [theta_count] (overwritten, not accumulated)
  *   d_dLdy0    out [B,n], or NULL to skip
  * The parameter gradient is summed in a fixed order: two calls with the same inputs return the same bits.
- * For the GRU in fp32 with n = 16, 32 and d <= 16 the transposed Jacobians are computed inside the reverse
- * scan and the vector-Jacobian product runs on the matrix cores; DEER_GRAD_FUSED=0 and DEER_VJP_MFMA=0 (read
- * at each call; for tests and measurements) select the Jacobian kernel + plain reverse scan and the vector-ALU
- * product instead. */
+ * For the GRU the transposed Jacobians are computed inside the reverse scan wherever deer_eval() evaluates the
+ * cell inside the forward scan (n <= 8 with d <= 8; fp32 n = 16, 32 with d <= 16), and in fp32 with n = 16, 32
+ * the vector-Jacobian product runs on the matrix cores; DEER_GRAD_FUSED=0 and DEER_VJP_MFMA=0 (read at each
+ * call; for tests and measurements) select the Jacobian kernel + plain reverse scan and the vector-ALU product
+ * instead. */
 deer_status deer_grad(deer_ctx* ctx, const void* d_theta, const void* d_x, const void* d_y0,
                       const void* d_y, const void* d_dLdy, void* d_dLdx, void* d_dLdtheta,
                       void* d_dLdy0);

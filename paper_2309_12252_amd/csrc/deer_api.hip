@@ -310,7 +310,8 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
         p.W = c->plan.fused_W;
         p.tiles = c->plan.fused_tiles;
         prof_begin(c, KIND_FUSED, iter);
-        e = launch_scan_gru_fused(g.dtype, g.n, p, fused_theta, fused_x, g.d, c->stream);
+        e = reverse ? launch_scan_gru_dual(g.dtype, g.n, p, fused_theta, fused_x, g.d, c->stream)
+                    : launch_scan_gru_fused(g.dtype, g.n, p, fused_theta, fused_x, g.d, c->stream);
     } else {
         prof_begin(c, KIND_SCAN, iter);
         e = c->plan.mfma ? launch_scan_mfma(g.dtype, g.n, p, c->stream) : launch_scan_valu(g.dtype, g.n, p, c->stream);
@@ -729,7 +730,9 @@ deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const v
 
     deer_status st = zero_ctl(c);
     if (st != DEER_OK) return st;
-    if (c->plan.mfma && c->plan.fused && env_int("DEER_GRAD_FUSED", 1) != 0) {
+    const bool dual_fused = c->plan.fused && env_int("DEER_GRAD_FUSED", 1) != 0 &&
+                            (c->plan.mfma || scan_gru_dual_supported(g.dtype, g.n, g.d, c->plan.fused_L, c->plan.fused_W));
+    if (dual_fused) {
         // lam = (dL/dy) L_G^{-1} with the transposed Jacobians computed inside the reverse scan (they never reach memory)
         HIPCHK(c, run_scan(c, nullptr, d_dLdy, nullptr, lam, d_y, 0, (long long)(T * n), (long long)(T * n), 1, 0, false, 0,
                            Gate{nullptr, 0.0}, -1, d_theta, d_x));

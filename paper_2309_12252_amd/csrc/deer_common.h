@@ -288,6 +288,10 @@ int gru_newton_capacity(int dtype, int n, int d, int L);
 hipError_t launch_gru_newton(int dtype, int n, const NewtonParams& q, hipStream_t s);
 hipError_t launch_scan_gru_fused(int dtype, int n, const ScanParams& p, const void* theta, const void* x, int d,
                                  hipStream_t s);
+// the same for the dual scan of the backward derivative (p.reverse set, p.yold = trajectory, p.bv = cotangent)
+bool scan_gru_dual_supported(int dtype, int n, int d, int L, int W);
+hipError_t launch_scan_gru_dual(int dtype, int n, const ScanParams& p, const void* theta, const void* x, int d,
+                                hipStream_t s);
 int scan_mfma_tile(int dtype, int n);
 hipError_t launch_gru_funceval(int dtype, const GruParams& p, hipStream_t s);
 hipError_t launch_gru_vjp(int dtype, const GruVjpParams& p, hipStream_t s);

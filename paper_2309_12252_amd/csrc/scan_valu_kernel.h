@@ -333,6 +333,81 @@ __device__ __forceinline__ void gru_pairs(const GruFeed& gf, const S* __restrict
     gru_rows<S, N, L, DP, FULL>(w, pr, pq, pc, h, yo, T, e0, Ar, be);
 }
 
+// slot s of row i of the transposed Jacobian: J[c][i] with c the column slot s refers to, i.e. the row factors of
+// lane c times column i of the weights (Tz, Tc, Tr: that column, rows in swizzled order)
+template <typename S, int N, int s = 0>
+struct DualRow {
+    static __device__ __forceinline__ void run(const S* Tz, const S* Tc, const S* Tr, const S* E, S pz, S pzm, S sr, S srm,
+                                               S st, S stm, S z, S* out) {
+        out[s] = fetch<S, N, s>(pz, pzm) * Tz[s] + (fetch<S, N, s>(sr, srm) * Tc[s] + (fetch<S, N, s>(st, stm) * Tr[s] + z * E[s]));
+        if constexpr (s + 1 < N) DualRow<S, N, s + 1>::run(Tz, Tc, Tr, E, pz, pzm, sr, srm, st, stm, z, out);
+    }
+};
+
+// Matrices of the dual scan (Sec. 3.1.1 eq. 7) from the GRU cell: scan position e carries time T-1-e and the
+// transpose of the Jacobian at time T-e, a function of the state at time T-1-e (yv: entry i at the L positions, in
+// scan order) and the input at time T-e.  Position 0 has no matrix (zero); positions past the end get the identity.
+// Must be called by whole wavefronts.
+template <typename S, int N, int L, int DP, bool FULL>
+__device__ __forceinline__ void gru_pairs_dual(const GruFeed& gf, int b, long long T, long long e0, int i, const S* yv,
+                                               S (*Ar)[N]) {
+    GruRow<S, N, DP> w;
+    load_gru_row<S, N, DP>(gf, i, w);
+    const int d = gf.d;
+    const S* __restrict__ U = reinterpret_cast<const S*>(gf.theta) + 3 * N * d;
+    S Tr[N], Tz[N], Tc[N];
+#pragma unroll
+    for (int s = 0; s < N; ++s) {
+        const int c = swz_col<N>(s, i);
+        Tr[s] = U[c * N + i];
+        Tz[s] = U[(N + c) * N + i];
+        Tc[s] = U[(2 * N + c) * N + i];
+    }
+    const S* __restrict__ xb = reinterpret_cast<const S*>(gf.x) + (long long)b * T * d;
+    S pr[L], pq[L], pc[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        long long tj = T - (e0 + l);
+        if constexpr (!FULL) {
+            tj = tj > T - 1 ? T - 1 : tj;
+            tj = tj < 0 ? 0 : tj;
+        }
+        S ar = w.br, az = w.bz, ac = w.bc;
+#pragma unroll
+        for (int k = 0; k < DP; ++k) {
+            const S xv = xb[tj * d + (k < d ? k : d - 1)];
+            ar += w.Wr[k] * xv;
+            az += w.Wz[k] * xv;
+            ac += w.Wc[k] * xv;
+        }
+        pr[l] = ar; pq[l] = az; pc[l] = ac;
+    }
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        S h = yv[l];
+        S ar = pr[l], az = pq[l], ac = pc[l], q = w.bh;
+        row_dots<S, N, 1>(w.Ur, &h, &ar);
+        row_dots<S, N, 1>(w.Uz, &h, &az);
+        row_dots<S, N, 1>(w.Uc, &h, &q);
+        const S r = feed_sigmoid(ar), z = feed_sigmoid(az);
+        const S c = feed_tanh(ac + r * q);
+        const S pz = (h - c) * z * (S(1) - z);
+        const S sc = (S(1) - z) * (S(1) - c * c);
+        const S sr = sc * r;
+        const S st = sc * q * r * (S(1) - r);
+        S row[N];
+        DualRow<S, N>::run(Tz, Tc, Tr, w.E, pz, mirror<S, N>(pz), sr, mirror<S, N>(sr), st, mirror<S, N>(st), z, row);
+        if constexpr (FULL) {
+#pragma unroll
+            for (int s = 0; s < N; ++s) Ar[l][s] = row[s];
+        } else {
+            const long long e = e0 + l;
+#pragma unroll
+            for (int s = 0; s < N; ++s) Ar[l][s] = (e >= T) ? w.E[s] : (e == 0 ? S(0) : row[s]);
+        }
+    }
+}
+
 // Inclusive log-step scan over the groups of a wavefront.  (M | v): this group's pair, lane i holds
 // row i.  Afterwards group g holds pair_g o ... o pair_0.
 template <typename S, int N>
@@ -745,12 +820,13 @@ __device__ __forceinline__ S tile_start_state(const TileShared<S, N, W>& sh, con
     return y;
 }
 
-// DP = 0: pairs are read from p.A / p.bv.  DP > 0: pairs come from the GRU cell (forward scans only),
-// DP being the input width the x loops are unrolled for.  ADDI: the stored matrices are A - I (the identity
+// DP = 0: pairs are read from p.A / p.bv.  DP > 0: pairs come from the GRU cell, DP being the input width the x
+// loops are unrolled for: forward, the Newton step at the previous iterate p.yold; with REV, the dual scan with
+// the transposed Jacobians at the trajectory p.yold and the vectors from p.bv (no convergence measure).  ADDI: the stored matrices are A - I (the identity
 // is added on load; used by the dual recurrence of the ODE form, whose matrices are I + O(dt)).
 template <typename S, int N, int L, int W, bool REV, int DP, bool ADDI = false>
 __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed gf) {
-    static_assert(DP == 0 || !REV, "the fused cell feeds forward scans only");
+    constexpr bool DUAL = DP > 0 && REV;
     static_assert(!ADDI || DP == 0, "only stored matrices can lack their identity");
     constexpr int NG = 64 / N;        // groups per wavefront
     constexpr int TILE = W * NG * L;  // scan positions per tile
@@ -790,11 +866,21 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     if (full) {
         if constexpr (DP == 0) load_pairs<S, N, L, REV, true, ADDI>(Ab, bb, T, e0, i, Ar, be);
         load_previous<S, N, L, REV, true>(oldb ? oldb : bb, T, e0, i, yo);
-        if constexpr (DP > 0) gru_pairs<S, N, L, DP, true>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
+        if constexpr (DP > 0 && !REV) gru_pairs<S, N, L, DP, true>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
+        if constexpr (DUAL) {
+            load_previous<S, N, L, true, true>(bb, T, e0, i, be);
+            gru_pairs_dual<S, N, L, DP, true>(gf, b, T, e0, i, yo, Ar);
+        }
     } else {
         if constexpr (DP == 0) load_pairs<S, N, L, REV, false, ADDI>(Ab, bb, T, e0, i, Ar, be);
         load_previous<S, N, L, REV, false>(oldb ? oldb : bb, T, e0, i, yo);
-        if constexpr (DP > 0) gru_pairs<S, N, L, DP, false>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
+        if constexpr (DP > 0 && !REV) gru_pairs<S, N, L, DP, false>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
+        if constexpr (DUAL) {
+            load_previous<S, N, L, true, false>(bb, T, e0, i, be);
+#pragma unroll
+            for (int l = 0; l < L; ++l) be[l] = (e0 + l < T) ? be[l] : S(0);
+            gru_pairs_dual<S, N, L, DP, false>(gf, b, T, e0, i, yo, Ar);
+        }
     }
     S Pex[N], pex;
     // plain scans of n <= 4 look back on wavefront 1 while wavefront 0 scans the wavefront totals (measured on
@@ -812,7 +898,7 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
         if (full || e < T) {
             const long long oi = (REV ? (T - 1 - e) : e) * N + i;
             S w = y;
-            if (oldb) {
+            if (!DUAL && oldb) {
                 const S dq = abs_or_inf<S>(p.delta ? y : y - yo[l]);
                 emax = dq > emax ? dq : emax;
                 if (p.delta) w += yo[l];

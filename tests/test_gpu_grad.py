@@ -41,15 +41,17 @@ def test_small_shapes(n, d, dtype):
 
 
 @pytest.mark.parametrize("knob", ["DEER_VJP_MFMA", "DEER_GRAD_FUSED"])
-@pytest.mark.parametrize("n,d", [(16, 6), (32, 16)])
-def test_unfused_kernels_at_the_matrix_core_sizes(n, d, knob, monkeypatch):
-    # fp32 with n = 16, 32 computes the Jacobians inside the reverse scan and runs the VJP on the matrix cores by
-    # default; the Jacobian kernel + plain reverse scan and the vector-ALU VJP stay selectable
+@pytest.mark.parametrize("dtype", [deer.DEER_F32, deer.DEER_F64])
+@pytest.mark.parametrize("n,d", [(2, 2), (8, 4), (16, 6), (32, 16)])
+def test_separate_kernels_stay_selectable(n, d, dtype, knob, monkeypatch):
+    # by default the transposed Jacobians are computed inside the reverse scan (n <= 8; fp32 n = 16, 32) and the
+    # fp32 VJP at n = 16, 32 runs on the matrix cores; the Jacobian kernel + plain reverse scan and the vector-ALU
+    # VJP are the same computation in separate kernels
     monkeypatch.setenv(knob, "0")
     for k, (B, T) in enumerate([(2, 9), (3, 700), (1, 1)]):
         w = inputs.gru_workload("g_n%d_T%d" % (n, T), 70 * n + k, B=B, T=T, n=n, d=d)
         g = np.random.default_rng(k + 1).standard_normal((B, T, n)) / np.sqrt(T)
-        check_grad(w, g.astype(np.float32).astype(np.float64), deer.DEER_F32)
+        check_grad(w, g.astype(np.float32).astype(np.float64), dtype)
 
 
 def test_config4_training_step_gradients():
