@@ -141,7 +141,8 @@ deer_status deer_eval(deer_ctx* ctx, const void* d_theta, const void* d_x, const
  * The parameter gradient is summed in a fixed order: two calls with the same inputs return the same bits.
  * For the GRU the transposed Jacobians are computed inside the reverse scan wherever deer_eval() evaluates the
  * cell inside the forward scan (n <= 8 with d <= 8; fp32 n = 16, 32 with d <= 16), and in fp32 with n = 16, 32
- * the vector-Jacobian product runs on the matrix cores; DEER_GRAD_FUSED=0 and DEER_VJP_MFMA=0 (read at each
+ * the vector-Jacobian product runs on the matrix cores (so does the MLP field's for fp32, n = 8 and width 16,
+ * 32 or 64); DEER_GRAD_FUSED=0 and DEER_VJP_MFMA=0 (read at each
  * call; for tests and measurements) select the Jacobian kernel + plain reverse scan and the vector-ALU product
  * instead. */
 deer_status deer_grad(deer_ctx* ctx, const void* d_theta, const void* d_x, const void* d_y0,

@@ -709,7 +709,13 @@ static deer_status grad_ode(deer_ctx* c, const void* d_theta, const void* d_y, c
     prof_end(c);
     MlpVjpParams vp{d_theta, d_y, u, c->ws + c->plan.off_partial, d_dLdtheta, g.B, g.T, g.n, g.mlp_width, c->plan.vjp_blocks};
     prof_begin(c, KIND_VJP);
-    HIPCHK(c, launch_mlp_vjp(g.dtype, vp, c->stream));
+    if (mlp_vjp_mfma_supported(g.dtype, g.n, g.mlp_width) && env_int("DEER_VJP_MFMA", 1) != 0) {
+        if (vp.blocks > 512) vp.blocks = 512;   // two wavefronts per SIMD by registers: 512 blocks of four fill the chip once
+        HIPCHK(c, launch_mlp_vjp_mfma(vp, c->stream));
+        HIPCHK(c, launch_partial_reduce(g.dtype, vp.partial, d_dLdtheta, (long long)theta_count(&g), vp.blocks * 4, c->stream));
+    } else {
+        HIPCHK(c, launch_mlp_vjp(g.dtype, vp, c->stream));
+    }
     prof_end(c);
     st = check_status(c);
     prof_collect(c);

@@ -309,6 +309,10 @@ hipError_t launch_ode_dual_residual(int dtype, const void* D, const void* g, con
 // VJP of the MLP field with the parameter-gradient reduction; blocks from mlp_vjp_blocks()
 int mlp_vjp_blocks(int dtype, int n, int width, long long points);
 hipError_t launch_mlp_vjp(int dtype, const MlpVjpParams& p, hipStream_t s);
+// the same sums on the matrix cores (fp32, n = 8, width 16, 32 or 64); writes p.blocks * 4 partial rows and leaves
+// their addition (launch_partial_reduce) to the caller
+bool mlp_vjp_mfma_supported(int dtype, int n, int width);
+hipError_t launch_mlp_vjp_mfma(const MlpVjpParams& p, hipStream_t s);
 // fixed-order sum of partial rows [rows][P] into out[P]
 hipError_t launch_partial_reduce(int dtype, const void* partial, void* out, long long P, int rows, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);

@@ -76,6 +76,17 @@ def test_grad_small_ode_shapes(n, width, dtype):
         check_grad(w, dtype, seed=k)
 
 
+@pytest.mark.parametrize("width", [16, 32, 64])
+def test_grad_vector_alu_vjp_at_the_matrix_core_sizes(width, monkeypatch):
+    # fp32 with n = 8 runs the field's vector-Jacobian product on the matrix cores by default; the vector-ALU
+    # kernel (which serves the other sizes and fp64) stays selectable
+    monkeypatch.setenv("DEER_VJP_MFMA", "0")
+    for k, (B, T, t1) in enumerate([(2, 50, 1.0), (3, 1300, 2.0)]):
+        w = inputs.mlp_ode_workload("odeg_n8_T%d" % T, 400 + width + k, B=B, T=T, n=8, width=width, nhid=2,
+                                    t0=0.0, t1=t1, tol=1e-7)
+        check_grad(w, deer.DEER_F32, seed=k)
+
+
 def test_grad_coarse_grid():
     w = inputs.mlp_ode_workload("coarse_g", 78, B=2, T=12, n=4, width=16, nhid=2, t0=0.0, t1=6.0, tol=1e-7)
     w.theta = (w.theta * 2.0).astype(np.float32)
