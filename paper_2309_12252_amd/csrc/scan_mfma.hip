@@ -85,6 +85,16 @@ __device__ __forceinline__ double plus_lane16(double x) {
            __longlong_as_double((long long)(((unsigned long long)b[1] << 32) | a[1]));
 }
 
+// sum over the 16 lanes of a row (lanes with the same g); every lane of the row gets the total.  DPP only:
+// neighbours in a quad, the other pair of the quad, the other quad of the half row, the other half row.
+__device__ __forceinline__ float row_sum16(float x) {
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, true));    // quad_perm 1,0,3,2
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, true));    // quad_perm 2,3,0,1
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, true));   // row_half_mirror
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, true));   // row_mirror
+    return x;
+}
+
 // sum over the four lane groups g (lanes r, r+16, r+32, r+48)
 template <typename S>
 __device__ __forceinline__ S sum_groups(S v) {
@@ -102,6 +112,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     static_assert(!FUSE || sizeof(S) == 4, "the fused cell feeds fp32 scans only");
     constexpr bool DUAL = FUSE && REV;
     constexpr int NB = N / 16;
+    // fp32: the composition leaves the running pair of every position in the registers of its factor, so the second
+    // walk is L independent products with the carry instead of a chain through cross-lane gathers
+    constexpr bool PAR = sizeof(S) == 4;
     constexpr int LD = N + 1;   // LDS row stride of a wavefront total
     constexpr int TILE = LW * WAVES;
     using Acc = typename Mfma<S>::Acc;
@@ -434,6 +447,17 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
         for (int I = 0; I < NB; ++I)
 #pragma unroll
             for (int J = 0; J < NB; ++J) P[I][J] = Pn[I][J];
+        if constexpr (PAR) {
+            // the factor is not needed again: keep the running pair (accumulator layout: rows 4g + v, column r) in its place
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+#pragma unroll
+                for (int J = 0; J < NB; ++J)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) a[i][I][J][v] = Pn[I][J][v];
+                bel[i][I] = vr[I];
+            }
+        }
     }
 
     // wavefront total -> LDS (row-major)
@@ -681,15 +705,51 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
         }
         if (lane < N) sC[wave][lane] = s;
     }
+    S emax = S(0);
+    if constexpr (PAR) {
+        // y_e = (running matrix of e) carry + (running vector of e): lane (g, r) multiplies its column r of rows 4g + v
+        // with entry r of the carry; the sums over the row's 16 lanes leave y[16 I + 4g + v] in every lane of row g, and
+        // the four lanes r = 4g .. 4g+3 of each row own the 16 entries in memory order
+        S cr[NB];
+#pragma unroll
+        for (int J = 0; J < NB; ++J) cr[J] = sC[wave][16 * J + r];
+        const bool owner = (r >> 2) == g;
+#pragma unroll
+        for (int i = 0; i < LW; ++i) {
+            const long long e = e0 + i;
+            const long long oi = (REV ? ((long long)p.T - 1 - e) : e) * N;
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+                S t[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    S q = S(0);
+#pragma unroll
+                    for (int J = 0; J < NB; ++J) q += a[i][I][J][v] * cr[J];
+                    t[v] = row_sum16(q);
+                }
+                const S lo = (r & 1) ? t[1] : t[0], hi = (r & 1) ? t[3] : t[2];
+                const S y = ((r & 2) ? hi : lo) + bel[i][I];
+                if (e < p.T && owner) {
+                    S wv = y;
+                    if (!DUAL && oldb) {
+                        const S dq = abs_or_inf<S>(p.delta ? y : y - yo[i][I]);
+                        emax = dq > emax ? dq : emax;
+                        if (p.delta) wv += yo[i][I];
+                    }
+                    ob[oi + 16 * I + r] = wv;
+                }
+            }
+        }
+    }
     S yc[NB][4], yr[NB];
 #pragma unroll
     for (int K = 0; K < NB; ++K)
 #pragma unroll
         for (int v = 0; v < 4; ++v) yc[K][v] = sC[wave][16 * K + Lay<S>::idx(g, v)];
 
-    S emax = S(0);
 #pragma unroll
-    for (int i = 0; i < LW; ++i) {
+    for (int i = 0; i < (PAR ? 0 : LW); ++i) {
         const long long e = e0 + i;
 #pragma unroll
         for (int I = 0; I < NB; ++I) {
