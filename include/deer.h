@@ -78,7 +78,8 @@ typedef struct {
                                                        /* the residual and the dual discretisation       */
     double scan_ms;       int64_t scan_launches;       /* inverse linear operator (+ fused max|dy|)  */
     double vjp_ms;        int64_t vjp_launches;        /* VJP of f + parameter-gradient reduction    */
-    double fused_ms;      int64_t fused_launches;      /* GRU: cell + scan + max|dy| in one launch    */
+    double fused_ms;      int64_t fused_launches;      /* GRU: cell + scan + max|dy| in one launch;   */
+                                                       /* in deer_grad: cell inside the reverse scan  */
     double newton_ms;     int64_t newton_launches;     /* GRU, small problems: a whole solve in one   */
     int64_t newton_iterations;                         /* Newton iterations inside those launches     */
 } deer_profile;

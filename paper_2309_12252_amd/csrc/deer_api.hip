@@ -190,7 +190,7 @@ Plan make_plan(const deer_config* c) {
     // slots of the one-launch solve's grid barrier (two banks, one tagged scalar per workgroup)
     p.off_barrier = take(p.fused ? 2 * (B * (size_t)p.fused_tiles + 4) * (p.esz / 4) * 8 : 0);   // (+4: test hook)
     p.off_ctl = take((size_t)kSlots * 4 + (size_t)kSlots * 8 + 16);   // tickets, err bits, status
-    // partial rows of dL/dtheta: four per block (GRU: one per wavefront), two per block (MLP: one per thread group)
+    // partial rows of dL/dtheta: four per block (one per wavefront), two per block in the vector-ALU MLP kernel (one per thread group)
     p.off_partial = take((size_t)p.vjp_blocks * 4 * theta_count(c) * p.esz);
     p.total = off;
     return p;
@@ -606,7 +606,7 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
             } else {
                 char* Gbar = c->ws + c->plan.off_Gbar;
                 char* zbar = c->ws + c->plan.off_zbar;
-                MlpParams mp{d_theta, src, J, rhs, g.B, g.T, g.n, g.mlp_width, gate};
+                MlpParams mp{d_theta, src, J, rhs, g.B, g.T, g.n, g.mlp_width, gate, 0};
                 prof_begin(c, KIND_FUNCEVAL, k);
                 HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
                 prof_end(c);
@@ -679,7 +679,7 @@ static deer_status grad_ode(deer_ctx* c, const void* d_theta, const void* d_y, c
 
     deer_status st = zero_ctl(c);
     if (st != DEER_OK) return st;
-    MlpParams mp{d_theta, d_y, G, z, g.B, g.T, g.n, g.mlp_width, open};
+    MlpParams mp{d_theta, d_y, G, z, g.B, g.T, g.n, g.mlp_width, open, 1};   // the backward pass needs G only
     prof_begin(c, KIND_FUNCEVAL);
     HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
     prof_end(c);

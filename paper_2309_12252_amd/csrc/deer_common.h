@@ -243,6 +243,7 @@ struct MlpParams {
     void* G; void* z;                     // outputs: G = -df/dy [B,T,n,n], z = f + G y [B,T,n]
     int B, T, n, width;
     Gate gate;
+    int jac_only;                         // != 0: only G is wanted (the backward pass); kernels may write zeros to z
 };
 
 struct OdeDiscParams {

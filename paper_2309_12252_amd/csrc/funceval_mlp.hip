@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kThreads) void mlp_funceval_kernel(MlpParams p) {
 // Rows 8..15 of the W3 products are padding (n = 8).
 typedef float mlp_acc __attribute__((ext_vector_type(4)));
 
-template <int WB>   // hidden width / 16
+template <int WB, bool JONLY>   // hidden width / 16; JONLY: Jacobians only (z is written as zeros)
 __global__ __launch_bounds__(kThreads) void mlp_funceval_mfma_kernel(MlpParams p) {
     if (gate_closed<float>(p.gate)) return;
     constexpr int W = 16 * WB, N = 8;
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(kThreads) void mlp_funceval_mfma_kernel(MlpParams p
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w2a[I][K][v], a1[K][v], acc, 0, 0, 0);
-                    accq = __builtin_amdgcn_mfma_f32_16x16x4f32(w2a[I][K][v], q1[K][v], accq, 0, 0, 0);
+                    if constexpr (!JONLY) accq = __builtin_amdgcn_mfma_f32_16x16x4f32(w2a[I][K][v], q1[K][v], accq, 0, 0, 0);
                 }
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
@@ -229,13 +229,17 @@ __global__ __launch_bounds__(kThreads) void mlp_funceval_mfma_kernel(MlpParams p
         }
         {
             mlp_acc f = b3c, jy = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (JONLY) {
+                f = mlp_acc{0.f, 0.f, 0.f, 0.f};
+            } else {
 #pragma unroll
-            for (int K = 0; K < WB; ++K)
+                for (int K = 0; K < WB; ++K)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    f = __builtin_amdgcn_mfma_f32_16x16x4f32(w3a[K][v], a2[K][v], f, 0, 0, 0);
-                    jy = __builtin_amdgcn_mfma_f32_16x16x4f32(w3a[K][v], q2[K][v], jy, 0, 0, 0);
-                }
+                    for (int v = 0; v < 4; ++v) {
+                        f = __builtin_amdgcn_mfma_f32_16x16x4f32(w3a[K][v], a2[K][v], f, 0, 0, 0);
+                        jy = __builtin_amdgcn_mfma_f32_16x16x4f32(w3a[K][v], q2[K][v], jy, 0, 0, 0);
+                    }
+            }
             // z = f + G y = f - J y at point s0 + c, rows 4g + v < 8
             if (g < 2 && s0 + c < total) {
 #pragma unroll
@@ -617,9 +621,15 @@ hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s) {
         if (blocks > 256 * 4) blocks = 256 * 4;
         if (blocks < 1) blocks = 1;
         dim3 grid((unsigned)blocks), blk(kThreads);
-        if (p.width == 16) hipLaunchKernelGGL((mlp_funceval_mfma_kernel<1>), grid, blk, 0, s, p);
-        else if (p.width == 32) hipLaunchKernelGGL((mlp_funceval_mfma_kernel<2>), grid, blk, 0, s, p);
-        else hipLaunchKernelGGL((mlp_funceval_mfma_kernel<4>), grid, blk, 0, s, p);
+        if (p.jac_only) {
+            if (p.width == 16) hipLaunchKernelGGL((mlp_funceval_mfma_kernel<1, true>), grid, blk, 0, s, p);
+            else if (p.width == 32) hipLaunchKernelGGL((mlp_funceval_mfma_kernel<2, true>), grid, blk, 0, s, p);
+            else hipLaunchKernelGGL((mlp_funceval_mfma_kernel<4, true>), grid, blk, 0, s, p);
+        } else {
+            if (p.width == 16) hipLaunchKernelGGL((mlp_funceval_mfma_kernel<1, false>), grid, blk, 0, s, p);
+            else if (p.width == 32) hipLaunchKernelGGL((mlp_funceval_mfma_kernel<2, false>), grid, blk, 0, s, p);
+            else hipLaunchKernelGGL((mlp_funceval_mfma_kernel<4, false>), grid, blk, 0, s, p);
+        }
         return hipGetLastError();
     }
     return dtype == 0 ? launch_mlp_s<float>(p, s) : launch_mlp_s<double>(p, s);
