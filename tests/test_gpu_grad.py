@@ -84,3 +84,13 @@ def test_gradient_at_the_deer_trajectory():
         ctx.close()
     assert conv
     assert rel_err(host(dth), dth_o) <= 1e-4 and rel_err(host(dx), dx_o) <= 1e-4 and rel_err(host(dy0), dy0_o) <= 1e-4
+
+
+@pytest.mark.parametrize("k", [2, 3])
+def test_gradient_at_full_benchmark_sizes(k):
+    # cfg 2 (n = 8, T = 10,000, B = 16) and cfg 3 (n = 32, T = 100,000, B = 16) in the launch configuration the bench
+    # times: hundreds to thousands of tiles per sequence in the reverse scan with the cell inside
+    w = inputs.config(k)
+    print("gradient at %s" % w.name, flush=True)
+    g = np.random.default_rng(5).standard_normal((w.B, w.T, w.n)) / np.sqrt(w.T)
+    check_grad(w, g.astype(np.float32).astype(np.float64), deer.DEER_F32)
