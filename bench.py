@@ -162,6 +162,8 @@ def main():
                     help="time deer_grad (Jacobians at the solution, transposed reverse scan, VJP + parameter "
                          "reduction; for the ODE cell: field Jacobians, discretisation, reverse scan with one refinement, "
                          "dual discretisation, MLP VJP) on the chosen configuration and exit")
+    ap.add_argument("--train", action="store_true",
+                    help="time one training step per step: deer_eval to convergence, then deer_grad at that trajectory")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -199,6 +201,29 @@ def main():
     def step():
         return ctx.eval(th, x, y0, tol=w.tol, max_iter=w.max_iter, out=y)
 
+    if args.train:
+        torch.manual_seed(2)
+        g = torch.randn_like(y) / (w.B * w.T)
+        gx = None if w.cell != inputs.CELL_GRU else x
+
+        def train_step():
+            yy, iters, err, conv, _ = step()
+            ctx.grad(th, gx, y0, yy, g)
+            return iters, conv
+
+        for _ in range(args.warmup):
+            train_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            iters, conv = train_step()
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        print(json.dumps({"deer_train_step": w.name, "ms_per_step": ms, "sequence_steps_per_s": w.B * w.T / (ms * 1e-3),
+                          "newton_iterations": int(iters), "converged": bool(conv),
+                          "what": "deer_eval to convergence + deer_grad of a random cotangent at that trajectory"}))
+        ctx.close()
+        return
     if args.grad:
         y, iters, err, conv, _ = step()
         torch.manual_seed(2)
