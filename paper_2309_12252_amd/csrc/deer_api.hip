@@ -610,7 +610,7 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
                 prof_begin(c, KIND_FUNCEVAL, k);
                 HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
                 prof_end(c);
-                OdeDiscParams dp{J, rhs, src, Gbar, zbar, g.B, g.T, g.n, (g.t1 - g.t0) / (double)(g.T - 1), gate};
+                OdeDiscParams dp{J, rhs, src, Gbar, zbar, g.B, g.T, g.n, (g.t1 - g.t0) / (double)(g.T - 1), gate, 0, 0};
                 prof_begin(c, KIND_DISC, k);
                 HIPCHK(c, launch_ode_discretise(g.dtype, dp, c->stream));
                 prof_end(c);
@@ -683,8 +683,8 @@ static deer_status grad_ode(deer_ctx* c, const void* d_theta, const void* d_y, c
     prof_begin(c, KIND_FUNCEVAL);
     HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
     prof_end(c);
-    // D_i = Gbar_i - I (the residual output lands in lam and is overwritten below)
-    OdeDiscParams dp{G, z, d_y, Dm, lam, g.B, g.T, g.n, dt, open, 1};
+    // D_i = Gbar_i - I, the matrices alone
+    OdeDiscParams dp{G, z, d_y, Dm, lam, g.B, g.T, g.n, dt, open, 1, 1};
     prof_begin(c, KIND_DISC);
     HIPCHK(c, launch_ode_discretise(g.dtype, dp, c->stream));
     prof_end(c);

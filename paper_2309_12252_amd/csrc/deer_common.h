@@ -254,6 +254,7 @@ struct OdeDiscParams {
     double dt;
     Gate gate;
     int minus_identity;                   // 1: Gbar holds exp(-Gc dt) - I (nothing of size dt is rounded against 1)
+    int matrix_only;                      // 1: only Gbar is wanted (the backward pass): z, y and res are not touched
 };
 
 struct OdeDualParams {

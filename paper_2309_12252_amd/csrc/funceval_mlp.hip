@@ -301,7 +301,7 @@ template <> struct SeriesTol<double> { static constexpr double v = 1e-19; };
 
 // D = exp(X) - I and pv = phi1(X) v for one n x n matrix held in registers (X is overwritten by its scaled
 // copy): scaling so that the max-row-sum norm is at most 1/2, Taylor series, then the doublings undone.
-template <typename S, int N>
+template <typename S, int N, bool VEC = true>
 __device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
     S norm = S(0);
 #pragma unroll
@@ -350,7 +350,7 @@ __device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
             for (int c = 0; c < N; ++c) D[r * N + c] = nr[c];
         }
     }
-    {
+    if constexpr (VEC) {
         S wv[N];
 #pragma unroll
         for (int k = 0; k < N; ++k) { pv[k] = zc[k]; wv[k] = zc[k]; }
@@ -372,16 +372,18 @@ __device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
     // undo the scaling: phi1(2X) v = (exp(X) + I) phi1(X) v / 2 = phi1(X) v + D phi1(X) v / 2,
     // exp(2X) - I = 2D + D^2
     for (int sstep = 0; sstep < sq; ++sstep) {
-        S nv[N];
+        if constexpr (VEC) {
+            S nv[N];
 #pragma unroll
-        for (int r = 0; r < N; ++r) {
-            S s = S(0);
+            for (int r = 0; r < N; ++r) {
+                S s = S(0);
 #pragma unroll
-            for (int c = 0; c < N; ++c) s += D[r * N + c] * pv[c];
-            nv[r] = pv[r] + S(0.5) * s;
+                for (int c = 0; c < N; ++c) s += D[r * N + c] * pv[c];
+                nv[r] = pv[r] + S(0.5) * s;
+            }
+#pragma unroll
+            for (int r = 0; r < N; ++r) pv[r] = nv[r];
         }
-#pragma unroll
-        for (int r = 0; r < N; ++r) pv[r] = nv[r];
         // (X is dead by now: it holds the copy of D that the update needs)
 #pragma unroll
         for (int e = 0; e < N * N; ++e) X[e] = D[e];
@@ -398,7 +400,8 @@ __device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
 }
 
 // (two wavefronts per SIMD wanted: for n = 8 in fp32 the matrices of a thread just fit 256 registers)
-template <typename S, int N>
+// MATONLY: the backward pass wants the matrices alone (no vector series, no residual; z, y and res are not touched)
+template <typename S, int N, bool MATONLY>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(sizeof(S) == 4 ? 2 : 1)))
 void ode_discretise_kernel(OdeDiscParams p) {
     if (gate_closed<S>(p.gate)) return;
@@ -417,18 +420,29 @@ void ode_discretise_kernel(OdeDiscParams p) {
     // X = -Gc dt / 2^sq with max-row-sum norm at most 1/2
     S X[N * N], zc[N];
     {
-        S G0[N * N], G1[N * N], z0[N], z1[N];
+        S G0[N * N], G1[N * N];
         vload<S, N * N>(G0, G);
         vload<S, N * N>(G1, G + N * N);
-        vload<S, N>(z0, z);
-        vload<S, N>(z1, z + N);
 #pragma unroll
         for (int k = 0; k < N * N; ++k) X[k] = S(-0.5) * (G0[k] + G1[k]) * dt;
+        if constexpr (!MATONLY) {
+            S z0[N], z1[N];
+            vload<S, N>(z0, z);
+            vload<S, N>(z1, z + N);
 #pragma unroll
-        for (int k = 0; k < N; ++k) zc[k] = S(0.5) * (z0[k] + z1[k]);
+            for (int k = 0; k < N; ++k) zc[k] = S(0.5) * (z0[k] + z1[k]);
+        }
     }
     S D[N * N], pv[N];
-    expm1_phi1v<S, N>(X, zc, D, pv);
+    expm1_phi1v<S, N, !MATONLY>(X, zc, D, pv);
+    if constexpr (MATONLY) {
+        if (!p.minus_identity) {
+#pragma unroll
+            for (int e = 0; e < N * N; ++e) D[e] += ((e / N) == (e % N)) ? S(1) : S(0);
+        }
+        vstore<S, N * N>(Gbar, D);
+        return;
+    }
     // residual of the current iterate in the discretised recurrence (Sec. 3.3 eq. 9):
     // res = Gbar y_i + zbar - y_{i+1} = D y_i + dt phi1 zc - (y_{i+1} - y_i)
     S y0v[N], y1v[N], rv[N];
@@ -591,9 +605,18 @@ hipError_t launch_disc_s(const OdeDiscParams& p, hipStream_t s) {
     const long long nint = (long long)p.B * (p.T - 1);
     dim3 grid((unsigned)((nint + kThreads - 1) / kThreads));
     switch (p.n) {
-        case 2: hipLaunchKernelGGL((ode_discretise_kernel<S, 2>), grid, dim3(kThreads), 0, s, p); break;
-        case 4: hipLaunchKernelGGL((ode_discretise_kernel<S, 4>), grid, dim3(kThreads), 0, s, p); break;
-        case 8: hipLaunchKernelGGL((ode_discretise_kernel<S, 8>), grid, dim3(kThreads), 0, s, p); break;
+        case 2:
+            if (p.matrix_only) hipLaunchKernelGGL((ode_discretise_kernel<S, 2, true>), grid, dim3(kThreads), 0, s, p);
+            else hipLaunchKernelGGL((ode_discretise_kernel<S, 2, false>), grid, dim3(kThreads), 0, s, p);
+            break;
+        case 4:
+            if (p.matrix_only) hipLaunchKernelGGL((ode_discretise_kernel<S, 4, true>), grid, dim3(kThreads), 0, s, p);
+            else hipLaunchKernelGGL((ode_discretise_kernel<S, 4, false>), grid, dim3(kThreads), 0, s, p);
+            break;
+        case 8:
+            if (p.matrix_only) hipLaunchKernelGGL((ode_discretise_kernel<S, 8, true>), grid, dim3(kThreads), 0, s, p);
+            else hipLaunchKernelGGL((ode_discretise_kernel<S, 8, false>), grid, dim3(kThreads), 0, s, p);
+            break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
