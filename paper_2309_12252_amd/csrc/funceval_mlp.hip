@@ -302,7 +302,7 @@ template <> struct SeriesTol<double> { static constexpr double v = 1e-19; };
 // D = exp(X) - I and pv = phi1(X) v for one n x n matrix held in registers (X is overwritten by its scaled
 // copy): scaling so that the max-row-sum norm is at most 1/2, Taylor series, then the doublings undone.
 template <typename S, int N, bool VEC = true>
-__device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
+__device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv, bool need_matrix = true) {
     S norm = S(0);
 #pragma unroll
     for (int r = 0; r < N; ++r) {
@@ -329,12 +329,15 @@ __device__ __forceinline__ void expm1_phi1v(S* X, const S* zc, S* D, S* pv) {
         S bound = norm;
         while (K < 24 && !(bound < SeriesTol<S>::v)) { ++K; bound *= norm / (S)K; }
     }
-    {
+    // (a caller that wants the vector alone passes need_matrix = false: the matrix is then formed only where the
+    // scaling has to be undone, which takes it)
+    const bool with_matrix = need_matrix || sq > 0;
+    if (with_matrix) {
         const S invK = S(1) / (S)K;
 #pragma unroll
         for (int e = 0; e < N * N; ++e) D[e] = X[e] * invK;
     }
-    for (int k = K - 1; k >= 1; --k) {
+    for (int k = K - 1; with_matrix && k >= 1; --k) {
         const S invk = S(1) / (S)k;
 #pragma unroll
         for (int r = 0; r < N; ++r) {
@@ -491,12 +494,13 @@ void ode_dual_kernel(OdeDualParams p) {
             for (int c = 0; c < N; ++c) X[r * N + c] = S(-0.5) * (G0[c * N + r] + G1[c * N + r]) * dt;
     }
     S D[N * N], pv[N];
-    expm1_phi1v<S, N>(X, lv, D, pv);
+    const bool first = i == 0 && p.dy0;   // the first interval also yields dL/dy0, which takes the matrix
+    expm1_phi1v<S, N>(X, lv, D, pv, first);
     S uv[N];
 #pragma unroll
     for (int r = 0; r < N; ++r) uv[r] = dt * pv[r];
     vstore<S, N>(u, uv);
-    if (i == 0 && p.dy0) {
+    if (first) {
         const S* __restrict__ g0 = reinterpret_cast<const S*>(p.g) + bi * p.T * N;
         S* __restrict__ out = reinterpret_cast<S*>(p.dy0) + bi * N;
 #pragma unroll
