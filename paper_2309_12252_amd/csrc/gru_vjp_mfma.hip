@@ -86,9 +86,10 @@ __global__ __launch_bounds__(kThreads) void gru_vjp_mfma_kernel(GruVjpParams p) 
     const long long total = (long long)p.B * p.T;
     const long long tiles = (total + 15) / 16;
     // state in front of position s (y0 at the first position of a sequence); positions past the end read position 0
+    const bool narrow = total < (1LL << 31);   // 32-bit division is several times cheaper than the 64-bit one
     auto hrow = [&](long long s) -> const float* {
         const long long sc = s < total ? s : 0;
-        const long long bi = sc / p.T;
+        const long long bi = narrow ? (long long)((unsigned)sc / (unsigned)p.T) : sc / p.T;
         return (sc - bi * p.T == 0) ? (y0 + bi * N) : (y + (sc - 1) * N);
     };
 
