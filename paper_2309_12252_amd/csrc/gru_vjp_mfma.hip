@@ -32,7 +32,7 @@ typedef float acc4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ acc4 mfma(float a, float b, acc4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
 
 template <int N>
-__global__ __launch_bounds__(kThreads) void gru_vjp_mfma_kernel(GruVjpParams p) {
+__global__ __launch_bounds__(kThreads, N == 32 ? 2 : 1) void gru_vjp_mfma_kernel(GruVjpParams p) {
     constexpr int NB = N / 16;   // 16-row blocks
     constexpr int KH = N / 4;    // k-steps over the state
     extern __shared__ __align__(16) unsigned char smem_raw[];
