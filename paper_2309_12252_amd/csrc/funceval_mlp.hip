@@ -141,7 +141,9 @@ __global__ __launch_bounds__(kThreads) void mlp_funceval_kernel(MlpParams p) {
 typedef float mlp_acc __attribute__((ext_vector_type(4)));
 
 template <int WB, bool JONLY>   // hidden width / 16; JONLY: Jacobians only (z is written as zeros)
-__global__ __launch_bounds__(kThreads) void mlp_funceval_mfma_kernel(MlpParams p) {
+// (width 16 and 32: four wavefronts per SIMD through the launch bounds -- the compiler's own choice of three,
+// with part of the operands in accumulation registers, measured 8 % slower, five with spills 10 % slower)
+__global__ __launch_bounds__(kThreads, WB <= 2 ? 4 : 1) void mlp_funceval_mfma_kernel(MlpParams p) {
     if (gate_closed<float>(p.gate)) return;
     constexpr int W = 16 * WB, N = 8;
     const int lane = threadIdx.x & 63;
