@@ -2,11 +2,13 @@
 
 A step is one deer_eval(): the whole Newton solve (every iteration: f + Jacobian at all positions,
 the blocked scan, the convergence test) over one batch of synthetic input that is already resident
-in HBM.  The default workload is the second benchmark configuration: GRU, d=4, n=8, T=10,000, B=16, fp32.
+in HBM.  The default workload is the largest single-GPU benchmark configuration, the third one:
+GRU, d=8, n=32, T=100,000, B=16, fp32 (1.6 M sequence positions per solve).
 
 Prints one JSON line: whole-job throughput in sequence-steps/s, the roofline entry of the kernel that
-takes most of the step (duration from HIP events on the library's stream) and the CPU oracle's
-throughput on the host cores as a reported baseline.
+takes most of the step (duration from HIP events on the library's stream), the same figures for the
+other configurations and for deer_grad ("configs"), the scan kernels alone on chip-filling streams
+("scan_kernels"), and the CPU oracle's throughput on the host cores as a reported baseline.
 """
 import argparse
 import json
@@ -44,11 +46,11 @@ def fused_flops_per_position(n, d):
     return 6 * n * (n + d) + 8 * n * n + 2 * n * n + 30 * n + scan_flops_per_position(n)
 
 
-def mlp_flops_per_point(n, width):
-    # f: 2(wn + w^2 + nw); J y for the right-hand side: the same chain again; J = W3 D2 W2 D1 W1: 2 w^2 n + 2 n w n
-    # plus the two diagonal scalings (2 w n each)
-    chain = 2 * (width * n + width * width + n * width)
-    return 2 * chain + 2 * width * width * n + 2 * n * width * n + 4 * width * n
+def mlp_flops_per_point(n, width, nhid=2):
+    # f: 2(wn + (nhid-1) w^2 + nw); J y for the right-hand side: the same chain again; J = W_out D W ... D W_1:
+    # (nhid-1) products of w x w with w x n, one of n x w with w x n, plus the diagonal scalings (2 w n each)
+    chain = 2 * (width * n + (nhid - 1) * width * width + n * width)
+    return 2 * chain + (nhid - 1) * 2 * width * width * n + 2 * n * width * n + nhid * 2 * width * n
 
 
 def dominant_roofline(kind, ms, w, newton_iterations=0.0):
@@ -91,7 +93,7 @@ def dominant_roofline(kind, ms, w, newton_iterations=0.0):
                 "avg_launch_us": round(1e3 * ms, 2), "algorithmic_flops_per_launch": fl,
                 "hbm_bytes_per_launch": scan_bytes_per_position(w.n) * positions}
     if kind == "funceval" and ode and w.n == 8:
-        fl = mlp_flops_per_point(w.n, w.mlp_width) * positions
+        fl = mlp_flops_per_point(w.n, w.mlp_width, w.mlp_hidden_layers) * positions
         a = fl / sec / 1e12
         return {"bound": "mfma", "achieved": round(a, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(a / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None, "kernel": "MLP field + Jacobian",
@@ -111,22 +113,13 @@ def dominant_roofline(kind, ms, w, newton_iterations=0.0):
 def scan_stream(torch, deer, dev, n, B, T, steps):
     """deer_linrec_solve alone on a random stream [B, T, n, n] (fp32): duration from HIP events, algorithmic
     bytes and flop rates against the MI355X peaks."""
-    # the recipe of inputs.scan_inputs (random matrices scaled to spectral norm 0.9), drawn on the device:
-    # a multi-GB stream takes the host generator most of a minute
+    # Entries i.i.d. N(0, (0.45 / sqrt(n))^2), drawn on the device (a multi-GB stream takes the host generator
+    # most of a minute): the spectral norm of such a matrix concentrates at 2 sigma sqrt(n) = 0.9, the scale of
+    # inputs.scan_inputs, and products contract (growth rate sigma sqrt(n) < 1 per factor), without any
+    # per-matrix normalisation (no batched products or decompositions in the generator).
     torch.manual_seed(1)
     dA = torch.randn(B, T, n, n, device=dev)
-    # spectral norms by 12 power iterations (the batched SVD behind matrix_norm does not take millions
-    # of matrices); an estimate from below, so the scaled norms are 0.9 or slightly more.  In chunks of
-    # 2^22 matrices: one batched product over tens of millions of them has faulted in the library.
-    flat = dA.view(B * T, n, n)
-    for lo in range(0, B * T, 1 << 22):
-        a = flat[lo:lo + (1 << 22)]
-        v = torch.randn(a.shape[0], n, 1, device=dev)
-        for _ in range(12):
-            v = a.transpose(-1, -2) @ (a @ v)
-            v /= torch.linalg.vector_norm(v, dim=-2, keepdim=True)
-        a *= 0.9 / torch.linalg.vector_norm(a @ v, dim=-2, keepdim=True)
-        del v
+    dA *= 0.45 / float(np.sqrt(n))
     db, dy0 = torch.randn(B, T, n, device=dev), torch.randn(B, n, device=dev)
     cfg = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, B, T, n, d=1)
     sctx = deer.DeerContext(cfg, device=dev)
@@ -147,15 +140,166 @@ def scan_stream(torch, deer, dev, n, B, T, steps):
             "frac_of_mfma_f32_peak": flops / (ms * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS}
 
 
+class Bench:
+    """One configuration resident on the device: context, inputs and the timed calls."""
+
+    def __init__(self, torch, deer, inputs, dev, k):
+        self.torch, self.inputs = torch, inputs
+        self.w = w = inputs.config(k)
+        self.ctx = deer.context_for(w, device=dev)
+        t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
+        self.th, self.x, self.y0 = t(w.theta), t(w.x), t(w.y0)
+        self.y = torch.empty((w.B, w.T, w.n), dtype=torch.float32, device=dev)
+        torch.manual_seed(2)
+        self.g = torch.randn_like(self.y) / (w.B * w.T)
+        self.S = w.B * w.T
+
+    def step(self):
+        w = self.w
+        return self.ctx.eval(self.th, self.x, self.y0, tol=w.tol, max_iter=w.max_iter, out=self.y)
+
+    def grad(self):
+        gx = self.x if self.w.cell == self.inputs.CELL_GRU else None
+        return self.ctx.grad(self.th, gx, self.y0, self.y, self.g)
+
+    def _timed(self, fn, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            r = fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            r = fn()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, r
+
+    def _profiled(self, fn, steps):
+        self.ctx.set_profiling(True)
+        for _ in range(steps):
+            fn()
+        self.torch.cuda.synchronize()
+        prof = self.ctx.profile()
+        self.ctx.set_profiling(False)
+        return prof
+
+    def time_eval(self, steps, warmup):
+        """Exactly `steps` timed solves after `warmup` untimed ones; then the same steps again with HIP events
+        around every launch for the per-kernel durations."""
+        elapsed, (_, iters, err, conv, _) = self._timed(self.step, steps, warmup)
+        prof = self._profiled(self.step, steps)
+        per_launch = {k: prof[k + "_ms"] / max(1, prof[k + "_launches"])
+                      for k in ("funceval", "discretise", "scan", "fused", "newton")}
+        totals = {k: prof[k + "_ms"] for k in per_launch}
+        dominant = max(totals, key=totals.get)
+        its = prof["newton_iterations"] / max(1, prof["newton_launches"])   # iterations inside a one-launch solve
+        roofline = dominant_roofline(dominant, per_launch[dominant], self.w, its)
+        return {"elapsed": elapsed, "ms_per_step": 1e3 * elapsed / steps, "value": self.S * steps / elapsed,
+                "iters": int(iters), "converged": bool(conv), "per_launch": per_launch, "dominant": dominant,
+                "roofline": roofline}
+
+    def time_grad(self, steps, warmup):
+        """deer_grad of a random cotangent at the trajectory of the last solve (self.y)."""
+        elapsed, _ = self._timed(self.grad, steps, warmup)
+        prof = self._profiled(self.grad, steps)
+        keys = ("funceval", "fused", "discretise", "scan", "vjp")
+        per_call = {k: round(prof[k + "_ms"] / steps, 5) for k in keys if prof[k + "_launches"] > 0}
+        ms = 1e3 * elapsed / steps
+        return {"ms_per_call": ms, "sequence_steps_per_s": self.S / (ms * 1e-3), "kernels_ms_per_call": per_call}
+
+    def time_train(self, steps, warmup):
+        def train_step():
+            r = self.step()
+            self.grad()
+            return r
+        elapsed, (_, iters, _, conv, _) = self._timed(train_step, steps, warmup)
+        ms = 1e3 * elapsed / steps
+        return {"ms_per_step": ms, "sequence_steps_per_s": self.S / (ms * 1e-3), "newton_iterations": int(iters),
+                "converged": bool(conv)}
+
+    def close(self):
+        self.ctx.close()
+        self.ctx = None
+
+
+def attach_traffic(roofline, workload_name, dominant):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs (FETCH_SIZE and
+    WRITE_SIZE, each scaled by the same counter's reading for a plain device copy).  They are not measured in this
+    run: the source file and what it says about its own run travel with the number."""
+    tpath = os.path.join(ROOT, "profiles", "kernel_traffic.json")
+    if not os.path.exists(tpath):
+        return
+    table = json.load(open(tpath))
+    tr = table.get(workload_name, {}).get(dominant)
+    if tr:
+        roofline["traffic"] = tr["total_bytes"]
+        roofline["traffic_fetched"] = tr["fetched_bytes"]
+        roofline["traffic_written"] = tr["written_bytes"]
+        roofline["traffic_source"] = "profiles/kernel_traffic.json (separate rocprofv3 --pmc runs; %s)" % table.get(
+            "_measured", "date not recorded")
+
+
+def cpu_baseline(w, inputs):
+    """The oracle's DEER solve of the same workload on the host cores (OpenMP over the batch): once on the full
+    workload with every thread it can use, once single-threaded on a bounded sample (one sequence, a quarter of
+    the length: the cost is linear in B*T), plus the oracle's plain sequential evaluation for context."""
+    import oracle
+    S = w.B * w.T
+    threads = max(1, min(w.B, oracle.max_threads(), 16))
+    if w.cell == inputs.CELL_GRU:
+        cell = oracle.make_cell(oracle.CELL_GRU, w.n, w.d)
+        run = lambda th: oracle.deer_eval(cell, w.theta, w.x, w.y0, tol=w.tol, max_iter=w.max_iter, nthreads=th)
+        T1 = max(1, w.T // 4)
+        run1 = lambda: oracle.deer_eval(cell, w.theta, w.x[:1, :T1], w.y0[:1], tol=w.tol, max_iter=w.max_iter, nthreads=1)
+    else:
+        cell = oracle.make_cell(oracle.CELL_MLP, w.n, 0, w.mlp_width, w.mlp_hidden_layers)
+        run = lambda th: oracle.ode_deer_eval(cell, w.theta, w.y0, w.T, w.t0, w.t1, tol=w.tol, max_iter=w.max_iter,
+                                              nthreads=th)
+        T1 = max(2, w.T // 4)
+        run1 = lambda: oracle.ode_deer_eval(cell, w.theta, w.y0[:1], T1, w.t0, w.t0 + (w.t1 - w.t0) * (T1 - 1) / (w.T - 1),
+                                            tol=w.tol, max_iter=w.max_iter, nthreads=1)
+    times = []
+    t_start = time.perf_counter()
+    while len(times) < 1 or (time.perf_counter() - t_start < 12.0 and len(times) < 20):
+        a = time.perf_counter()
+        run(threads)
+        times.append(time.perf_counter() - a)
+    med = float(np.median(times))
+    a = time.perf_counter()
+    run1()
+    t1 = time.perf_counter() - a
+    try:
+        affinity = len(os.sched_getaffinity(0))
+    except AttributeError:
+        affinity = os.cpu_count()
+    out = {"value": S / med, "unit": "sequence-steps/s", "cores": threads, "kind": "oracle",
+           "sample": "the full workload (the same DEER solve in fp64, OpenMP over the batch), median of %d run(s) "
+                     "of %.1f s" % (len(times), med),
+           "nproc": os.cpu_count(), "cpus_in_affinity_mask": affinity, "omp_max_threads": oracle.max_threads(),
+           "single_thread_value": T1 / t1,
+           "single_thread_sample": "one sequence, first %d of %d positions, one thread, %.1f s" % (T1, w.T, t1)}
+    if w.cell == inputs.CELL_GRU:
+        # for context: the oracle's plain sequential evaluation of the same recurrence (what DEER replaces)
+        a = time.perf_counter()
+        oracle.seq_eval(cell, w.theta, w.x, w.y0, nthreads=threads)
+        out["sequential_value"] = S / (time.perf_counter() - a)
+        a = time.perf_counter()
+        oracle.seq_eval(cell, w.theta, w.x[:1], w.y0[:1], nthreads=1)
+        out["sequential_single_thread_value"] = w.T / (time.perf_counter() - a)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration (1-based), default 2")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3,
+                    help="benchmark configuration of the headline (1-based), default 3: the largest single-GPU one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scan-kernels", action="store_true",
                     help="skip the stand-alone measurements of the scan kernels on chip-filling streams")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the other configurations and the deer_grad / training-step timings")
     ap.add_argument("--scan-stream", type=str, default="",
                     help="n,B,T: time deer_linrec_solve alone on a random stream of that shape and exit")
     ap.add_argument("--grad", action="store_true",
@@ -192,165 +336,90 @@ def main():
         n, B, T = [int(v) for v in args.scan_stream.split(",")]
         print(json.dumps(scan_stream(torch, deer, dev, n, B, T, args.steps)))
         return
-    w = inputs.config(args.config)
-    ctx = deer.context_for(w, device=dev)
-    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
-    th, x, y0 = t(w.theta), t(w.x), t(w.y0)
-    y = torch.empty((w.B, w.T, w.n), dtype=torch.float32, device=dev)
 
-    def step():
-        return ctx.eval(th, x, y0, tol=w.tol, max_iter=w.max_iter, out=y)
-
+    bench = Bench(torch, deer, inputs, dev, args.config)
+    w = bench.w
     if args.train:
-        torch.manual_seed(2)
-        g = torch.randn_like(y) / (w.B * w.T)
-        gx = None if w.cell != inputs.CELL_GRU else x
-
-        def train_step():
-            yy, iters, err, conv, _ = step()
-            ctx.grad(th, gx, y0, yy, g)
-            return iters, conv
-
-        for _ in range(args.warmup):
-            train_step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            iters, conv = train_step()
-        torch.cuda.synchronize()
-        ms = 1e3 * (time.perf_counter() - t0) / args.steps
-        print(json.dumps({"deer_train_step": w.name, "ms_per_step": ms, "sequence_steps_per_s": w.B * w.T / (ms * 1e-3),
-                          "newton_iterations": int(iters), "converged": bool(conv),
-                          "what": "deer_eval to convergence + deer_grad of a random cotangent at that trajectory"}))
-        ctx.close()
+        r = bench.time_train(args.steps, args.warmup)
+        r.update({"deer_train_step": w.name,
+                  "what": "deer_eval to convergence + deer_grad of a random cotangent at that trajectory"})
+        print(json.dumps(r))
+        bench.close()
         return
     if args.grad:
-        y, iters, err, conv, _ = step()
-        torch.manual_seed(2)
-        g = torch.randn_like(y) / (w.B * w.T)
-        for _ in range(args.warmup):
-            ctx.grad(th, x, y0, y, g)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            ctx.grad(th, x, y0, y, g)
-        torch.cuda.synchronize()
-        ms = 1e3 * (time.perf_counter() - t0) / args.steps
-        ctx.set_profiling(True)
-        for _ in range(args.steps):
-            ctx.grad(th, x, y0, y, g)
-        torch.cuda.synchronize()
-        prof = ctx.profile()
-        keys = ("funceval", "fused", "scan", "vjp") if w.cell == inputs.CELL_GRU else ("funceval", "discretise", "scan", "vjp")
-        keys = tuple(k for k in keys if prof[k + "_launches"] > 0)   # "fused": the reverse scan with the cell inside (n = 16, 32)
-        per = {k: prof[k + "_ms"] / max(1, prof[k + "_launches"]) for k in keys}
-        per_call = {k: prof[k + "_ms"] / args.steps for k in keys}
-        S = w.B * w.T
-        jbytes = 4 * w.n * w.n * S
-        line = {"deer_grad": w.name, "ms_per_call": ms, "sequence_steps_per_s": S / (ms * 1e-3),
-                "kernels_ms_per_launch": per, "kernels_ms_per_call": per_call}
-        if "scan" in per:
-            line["reverse_scan_GBs"] = 4 * (w.n * w.n + 2 * w.n) * S / (per["scan"] * 1e-3) / 1e9
-        if "funceval" in per:
-            line["funceval_write_GBs"] = (jbytes + 4 * w.n * S) / (per["funceval"] * 1e-3) / 1e9
-        print(json.dumps(line))
-        ctx.close()
+        bench.step()
+        r = bench.time_grad(args.steps, args.warmup)
+        r["deer_grad"] = w.name
+        print(json.dumps(r))
+        bench.close()
         return
 
-    for _ in range(args.warmup):
-        _, iters, err, conv, _ = step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        _, iters, err, conv, _ = step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
-    S = w.B * w.T
-    value = S * args.steps / elapsed
-
-    # per-kernel durations: the same steps again with HIP events around every launch
-    ctx.set_profiling(True)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    prof = ctx.profile()
-    ctx.set_profiling(False)
-    per_launch = {k: prof[k + "_ms"] / max(1, prof[k + "_launches"])
-                  for k in ("funceval", "discretise", "scan", "fused", "newton")}
-    totals = {k: prof[k + "_ms"] for k in per_launch}
-    dominant = max(totals, key=totals.get)
-    its = prof["newton_iterations"] / max(1, prof["newton_launches"])   # iterations inside a one-launch solve
-    roofline = dominant_roofline(dominant, per_launch[dominant], w, its)
-    tpath = os.path.join(ROOT, "profiles", "kernel_traffic.json")
-    if os.path.exists(tpath):
-        # HBM bytes per launch from the committed rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, calibrated)
-        tr = json.load(open(tpath)).get(w.name, {}).get(dominant)
-        if tr:
-            roofline["traffic"] = tr["total_bytes"]
-            roofline["traffic_fetched"] = tr["fetched_bytes"]
-            roofline["traffic_written"] = tr["written_bytes"]
-
-    out = {"metric": "DEER sequence-steps/s (B*T/s), forward eval to convergence", "value": value,
+    head = bench.time_eval(args.steps, args.warmup)
+    roofline = head["roofline"]
+    attach_traffic(roofline, w.name, head["dominant"])
+    out = {"metric": "DEER sequence-steps/s (B*T/s), forward eval to convergence", "value": head["value"],
            "unit": "sequence-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "data": "synthetic",
            "config": {"workload": w.name, "cell": "gru" if w.cell == inputs.CELL_GRU else "mlp_ode", "B": w.B,
                       "T": w.T, "n": w.n, "d": w.d, "tol": w.tol, "max_iter": w.max_iter,
-                      "newton_iterations": iters, "converged": bool(conv)},
-           "kernels_ms_per_launch": per_launch,
+                      "newton_iterations": head["iters"], "converged": head["converged"]},
+           "kernels_ms_per_launch": head["per_launch"],
            "roofline": roofline}
 
+    if not args.no_configs:
+        # every other configuration, deer_grad at each, and the training step of the fourth one: fewer repetitions
+        # (the headline's region above is the one the contract times)
+        configs = {}
+        ksteps = max(3, min(args.steps, 10))
+        for k in (1, 2, 3, 4, 5):
+            if k == args.config:
+                b = bench
+                entry = {}
+            else:
+                b = Bench(torch, deer, inputs, dev, k)
+                r = b.time_eval(ksteps, 2)
+                attach_traffic(r["roofline"], b.w.name, r["dominant"])
+                entry = {"ms_per_eval": round(r["ms_per_step"], 5), "sequence_steps_per_s": r["value"],
+                         "newton_iterations": r["iters"], "converged": r["converged"],
+                         "kernels_ms_per_launch": {kk: round(v, 5) for kk, v in r["per_launch"].items() if v > 0},
+                         "dominant_kernel": r["roofline"]}
+            if k != 1:
+                b.step()
+                entry["deer_grad"] = b.time_grad(ksteps, 2)
+            if k == 4:
+                entry["train_step"] = b.time_train(ksteps, 2)
+            configs[b.w.name] = entry
+            if b is not bench:
+                b.close()
+                del b
+                torch.cuda.empty_cache()
+        out["configs"] = configs
+    bench.close()
+    del bench
+    torch.cuda.empty_cache()
+
     if not args.no_scan_kernels:
-        # the scan kernels on their own, on streams that fill the chip: the HBM fraction of the n <= 8 kernel
-        # and the MFMA fraction of the n = 32 kernel (HIP events, 10 launches each)
-        ctx.close()
-        ctx = None
-        torch.cuda.empty_cache()
-        s8 = scan_stream(torch, deer, dev, 8, 16, 400000, 10)
-        torch.cuda.empty_cache()
-        s32 = scan_stream(torch, deer, dev, 32, 16, 100000, 10)
-        torch.cuda.empty_cache()
-        s4 = scan_stream(torch, deer, dev, 4, 16, 800000, 10)
-        torch.cuda.empty_cache()
-        out["scan_kernels"] = {
-            "n4_B16_T800k": {"bound": "hbm", "achieved": round(s4["achieved_GBs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                             "frac": round(s4["frac_of_8TBs"], 4), "avg_launch_us": round(1e3 * s4["avg_launch_ms"], 1)},
-            "n8_B16_T400k": {"bound": "hbm", "achieved": round(s8["achieved_GBs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                             "frac": round(s8["frac_of_8TBs"], 4), "avg_launch_us": round(1e3 * s8["avg_launch_ms"], 1)},
-            "n32_B16_T100k": {"bound": "mfma", "achieved": round(s32["achieved_TFLOPs"], 2), "peak": MFMA_F32_PEAK_TFLOPS,
-                              "unit": "TFLOP/s", "frac": round(s32["frac_of_mfma_f32_peak"], 4),
-                              "hbm_GBs": round(s32["achieved_GBs"], 1), "avg_launch_us": round(1e3 * s32["avg_launch_ms"], 1)}}
+        # the scan kernels on their own, on streams that fill the chip: the HBM fraction of the n <= 8 kernels
+        # and the MFMA fraction of the n = 16 and n = 32 kernels (HIP events, 10 launches each)
+        sk = {}
+        for n, B, T, label in ((2, 16, 2000000, "n2_B16_T2M"), (4, 16, 800000, "n4_B16_T800k"),
+                               (8, 16, 400000, "n8_B16_T400k"), (16, 16, 100000, "n16_B16_T100k"),
+                               (32, 16, 100000, "n32_B16_T100k")):
+            s = scan_stream(torch, deer, dev, n, B, T, 10)
+            torch.cuda.empty_cache()
+            if n <= 8:
+                sk[label] = {"bound": "hbm", "achieved": round(s["achieved_GBs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": round(s["frac_of_8TBs"], 4), "avg_launch_us": round(1e3 * s["avg_launch_ms"], 1)}
+            else:
+                sk[label] = {"bound": "mfma", "achieved": round(s["achieved_TFLOPs"], 2), "peak": MFMA_F32_PEAK_TFLOPS,
+                             "unit": "TFLOP/s", "frac": round(s["frac_of_mfma_f32_peak"], 4),
+                             "hbm_GBs": round(s["achieved_GBs"], 1), "hbm_frac": round(s["frac_of_8TBs"], 4),
+                             "avg_launch_us": round(1e3 * s["avg_launch_ms"], 1)}
+        out["scan_kernels"] = sk
 
     if not args.no_cpu_baseline:
-        import oracle
-        threads = max(1, min(w.B, oracle.max_threads(), 16))
-        if w.cell == inputs.CELL_GRU:
-            cell = oracle.make_cell(oracle.CELL_GRU, w.n, w.d)
-            run = lambda: oracle.deer_eval(cell, w.theta, w.x, w.y0, tol=w.tol, max_iter=w.max_iter, nthreads=threads)
-        else:
-            cell = oracle.make_cell(oracle.CELL_MLP, w.n, 0, w.mlp_width, w.mlp_hidden_layers)
-            run = lambda: oracle.ode_deer_eval(cell, w.theta, w.y0, w.T, w.t0, w.t1, tol=w.tol,
-                                               max_iter=w.max_iter, nthreads=threads)
-        times = []
-        t_start = time.perf_counter()
-        while len(times) < 3 or (time.perf_counter() - t_start < 10.0 and len(times) < 40):
-            a = time.perf_counter()
-            run()
-            times.append(time.perf_counter() - a)
-        med = float(np.median(times))
-        out["cpu_baseline"] = {"value": S / med, "unit": "sequence-steps/s", "cores": threads, "kind": "oracle",
-                               "sample": "the full workload (same DEER solve in fp64), median of %d runs" % len(times)}
-        if w.cell == inputs.CELL_GRU:
-            # for context: the oracle's plain sequential evaluation of the same recurrence (what DEER replaces)
-            seq = []
-            for _ in range(5):
-                a = time.perf_counter()
-                oracle.seq_eval(cell, w.theta, w.x, w.y0, nthreads=threads)
-                seq.append(time.perf_counter() - a)
-            out["cpu_baseline"]["sequential_value"] = S / float(np.median(seq))
-    if ctx is not None:
-        ctx.close()
+        out["cpu_baseline"] = cpu_baseline(w, inputs)
     print(json.dumps(out))
 
 

@@ -13,6 +13,8 @@
  *   - Pointers named d_* are DEVICE pointers owned by the caller; all other
  *     pointers are HOST pointers owned by the caller.  The library allocates no
  *     device memory: the caller hands in a workspace of deer_workspace_bytes().
+ *     (deer_create() allocates a few hundred bytes of pinned HOST memory and the
+ *     HIP events of the context; deer_destroy() frees them.)
  *   - Arrays are dense, row-major, in the dtype of the configuration (fp32 or
  *     fp64).  d_* arrays must be 16-byte aligned.
  *   - Work is enqueued on the HIP stream given to deer_create().  deer_eval()
@@ -64,7 +66,7 @@ typedef struct {
     int32_t T;                  /* GRU: number of steps; MLP_ODE: number of grid points (>= 2)           */
     int32_t n;                  /* state size: 1, 2, 4, 8, 16 or 32                                      */
     int32_t d;                  /* GRU input size (1..16); ignored for MLP_ODE                           */
-    int32_t mlp_width;          /* MLP_ODE hidden width (multiple of 4, <= 64); ignored for GRU          */
+    int32_t mlp_width;          /* MLP_ODE hidden width: 16, 32 or 64, and a multiple of n; ignored for GRU */
     int32_t mlp_hidden_layers;  /* MLP_ODE: must be 2                                                    */
     double t0, t1;              /* MLP_ODE: uniform grid t_j = t0 + j (t1 - t0)/(T - 1)                  */
 } deer_config;
@@ -87,8 +89,13 @@ typedef struct {
 /* Number of parameters in the flat theta of this configuration (layouts above); 0 if invalid. */
 size_t deer_theta_count(const deer_config* cfg);
 
-/* Bytes of device workspace deer_create() needs for cfg (Jacobian stream [B,T,n,n], right-hand
- * side, second trajectory buffer, scan tile descriptors, counters; Sec. 3.5: O(n^2 T) memory). */
+/* Bytes of device workspace deer_create() needs for cfg: a second trajectory buffer, the words the scan's
+ * tiles publish for each other, counters, partial sums of dL/dtheta -- and, only where a kernel pair exchanges
+ * them through memory (MLP_ODE; GRU in fp64 with n >= 16, with d beyond what the in-scan cell takes, or with the
+ * DEER_FUSED / DEER_GRAD_FUSED knobs at 0), the Jacobian stream [B,T,n,n] and the right-hand side, the O(n^2 T)
+ * memory of Sec. 3.5.  Where the cell is evaluated inside the scans the workspace is O(n T).
+ * The environment variables listed under "Environment" below are read here and in deer_create(); both calls must
+ * see the same values. */
 deer_status deer_workspace_bytes(const deer_config* cfg, size_t* bytes);
 
 /* Create a context.  d_workspace (device, 256-byte aligned, >= deer_workspace_bytes) stays owned by
@@ -117,10 +124,10 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
  * chosen from the shapes: for the GRU with n <= 8 the cell is evaluated inside the scan kernel (the
  * Jacobians never reach memory), and when all tiles of the problem fit on the device at once the
  * whole solve is one kernel launch; for n = 16, 32 in fp32 the cell is evaluated inside the matrix-core
- * scan; otherwise an iteration is a Jacobian kernel followed by a scan kernel.  Environment variables
- * read at deer_create() can force the other paths (meant for tests and measurements):
- * DEER_FUSED=0, DEER_ONE_LAUNCH=0, DEER_FUSED_L, DEER_FUSED_W, DEER_SCAN_L (tile shapes), DEER_BATCH
- * (iterations enqueued per host round trip). */
+ * scan; otherwise an iteration is a Jacobian kernel followed by a scan kernel (see "Environment").
+ * The Jacobians of the last iteration are not kept for deer_grad(): Sec. 3.1.1 offers that as a way to trade memory
+ * for speed, this library always recomputes them at the trajectory it is given (exact for any trajectory, and the
+ * O(n^2 T) buffer is not needed), so there is no save-the-Jacobian option in deer_config. */
 deer_status deer_eval(deer_ctx* ctx, const void* d_theta, const void* d_x, const void* d_y0,
                       const void* d_y_guess, double tol, int32_t max_iter, void* d_y,
                       int32_t* iters, double* final_err, int32_t* converged);
@@ -143,9 +150,7 @@ deer_status deer_eval(deer_ctx* ctx, const void* d_theta, const void* d_x, const
  * For the GRU the transposed Jacobians are computed inside the reverse scan wherever deer_eval() evaluates the
  * cell inside the forward scan (n <= 8 with d <= 8; fp32 n = 16, 32 with d <= 16), and in fp32 with n = 16, 32
  * the vector-Jacobian product runs on the matrix cores (so does the MLP field's for fp32, n = 8 and width 16,
- * 32 or 64); DEER_GRAD_FUSED=0 and DEER_VJP_MFMA=0 (read at each
- * call; for tests and measurements) select the Jacobian kernel + plain reverse scan and the vector-ALU product
- * instead. */
+ * 32 or 64); see "Environment" for the knobs that select the separate kernels instead. */
 deer_status deer_grad(deer_ctx* ctx, const void* d_theta, const void* d_x, const void* d_y0,
                       const void* d_y, const void* d_dLdy, void* d_dLdx, void* d_dLdtheta,
                       void* d_dLdy0);
@@ -171,6 +176,27 @@ const char* deer_last_error(const deer_ctx* ctx);
 
 /* Free the context (host memory and HIP events only; the workspace stays with the caller). */
 void deer_destroy(deer_ctx* ctx);
+
+/* Environment.  Every variable the library reads; all are meant for tests and measurements, none changes a
+ * result beyond rounding.  Read by deer_workspace_bytes() and deer_create() (the plan and the workspace size
+ * depend on them), except DEER_VJP_MFMA, which deer_grad() reads at each call.
+ *   DEER_FUSED=0        GRU: run the cell kernel and the plain scan as two launches per iteration (needs the
+ *                       Jacobian stream in the workspace) instead of the scan with the cell inside
+ *   DEER_GRAD_FUSED=0   GRU deer_grad(): Jacobian kernel + plain reverse scan instead of the reverse scan with the
+ *                       cell inside (needs the Jacobian stream in the workspace)
+ *   DEER_ONE_LAUNCH=0   GRU, n <= 8: one launch per iteration even when the whole solve fits one launch
+ *   DEER_FUSED_L, DEER_FUSED_W, DEER_SCAN_L
+ *                       tile shapes of the n <= 8 kernels: positions per lane group (1, 2, 4, 8, 10, 12, 16; 24 for
+ *                       the plain n = 4 scan) and wavefronts per tile (4 or 8); ignored when no such variant exists
+ *   DEER_BATCH          Newton iterations enqueued per host round trip on a fresh context (1..8, default 4)
+ *   DEER_VJP_MFMA=0     vector-ALU kernels for the vector-Jacobian products instead of the matrix-core ones
+ * Test hooks (exercise paths that ordinary runs reach rarely; never set them in production):
+ *   DEER_EPOCH0         first launch epoch of the context (default 1), to reach the wrap-around of the 30-bit
+ *                       epoch that tags published words
+ *   DEER_TEST_SPIN_LIMIT, DEER_TEST_EXTRA_WORKGROUPS
+ *                       polls before a wait in the one-launch solve gives up, and a number (1..4) of workgroups
+ *                       that solve also waits for although they do not exist: together they force the give-up path,
+ *                       after which deer_eval() solves launch by launch */
 
 #ifdef __cplusplus
 }

@@ -23,7 +23,9 @@ constexpr int kMaxEvents = 24;      // timed launches between two host synchroni
 
 thread_local std::string g_last_error;
 #ifdef DEER_SCAN_TIMING
-unsigned long long* g_timing = nullptr;
+// development builds only (-DDEER_SCAN_TIMING): the kernels stamp the phases of every tile into a region at the
+// end of the caller's workspace (deer_workspace_bytes() grows by kTimingBytes); deer_debug_timing(ctx) returns it
+constexpr size_t kTimingBytes = (size_t)1 << 26;
 #endif
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -38,9 +40,11 @@ struct Plan {
     bool mfma;
     bool fused;          // GRU with n <= 8: Newton steps run the scan with the cell evaluated in place
     int fused_L, fused_W, fused_tiles;
+    bool grad_fused;     // deer_grad computes the transposed Jacobians inside the reverse scan
+    bool need_J;         // some kernel of this plan reads or writes the Jacobian stream [B,T,n,n] and the right-hand side
     int vjp_blocks;
     // byte offsets into the workspace
-    size_t off_J, off_rhs, off_ybuf, off_Gbar, off_zbar, off_aggW, off_inclW, off_barrier, off_ctl, off_partial, total;
+    size_t off_J, off_rhs, off_ybuf, off_Gbar, off_zbar, off_aggW, off_inclW, off_barrier, off_ctl, off_partial, off_timing, total;
 };
 
 size_t theta_count(const deer_config* c) {
@@ -176,10 +180,17 @@ Plan make_plan(const deer_config* c) {
     p.vjp_blocks = c->cell == DEER_CELL_GRU ? gru_vjp_blocks(c->n, (long long)B * T)
                                             : mlp_vjp_blocks(c->dtype, c->n, c->mlp_width, (long long)B * T);
 
+    p.grad_fused = p.fused && env_int("DEER_GRAD_FUSED", 1) != 0 &&
+                   (p.mfma || scan_gru_dual_supported(c->dtype, c->n, c->d, p.fused_L, p.fused_W));
+    // The Jacobians exist in memory only where a kernel pair exchanges them: the ODE form, and the GRU sizes (or
+    // knob settings) whose forward or backward pass runs the cell kernel followed by the plain scan.  With the
+    // cell inside both scans the workspace is O(n T) instead of the O(n^2 T) of Sec. 3.5.
+    p.need_J = ode || !p.fused || !p.grad_fused;
+
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
-    p.off_J = take(B * T * n * n * p.esz);
-    p.off_rhs = take(B * T * n * p.esz);
+    p.off_J = take(p.need_J ? B * T * n * n * p.esz : 0);
+    p.off_rhs = take(p.need_J ? B * T * n * p.esz : 0);
     p.off_ybuf = take(B * T * n * p.esz);
     p.off_Gbar = take(ode ? B * (T - 1) * n * n * p.esz : 0);
     p.off_zbar = take(ode ? B * (T - 1) * n * p.esz : 0);
@@ -192,6 +203,9 @@ Plan make_plan(const deer_config* c) {
     p.off_ctl = take((size_t)kSlots * 4 + (size_t)kSlots * 8 + 16);   // tickets, err bits, status
     // partial rows of dL/dtheta: four per block (one per wavefront), two per block in the vector-ALU MLP kernel (one per thread group)
     p.off_partial = take((size_t)p.vjp_blocks * 4 * theta_count(c) * p.esz);
+#ifdef DEER_SCAN_TIMING
+    p.off_timing = take(kTimingBytes);
+#endif
     p.total = off;
     return p;
 }
@@ -292,13 +306,8 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
     p.status = ctl_status(c);
     p.gate = gate;
 #ifdef DEER_SCAN_TIMING
-    {
-        static unsigned long long* dbg = nullptr;
-        if (!dbg) (void)hipMalloc(&dbg, (size_t)1 << 26);
-        // eight segments of 2^20 words, one per launch in turn, so consecutive launches can be compared
-        p.timing = dbg + (size_t)(p.epoch & 7u) * ((size_t)1 << 20);
-        g_timing = dbg;
-    }
+    // eight segments of 2^20 words, one per launch in turn, so consecutive launches can be compared
+    p.timing = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_timing) + (size_t)(p.epoch & 7u) * ((size_t)1 << 20);
 #endif
     hipError_t e;
     if (fused_theta && c->plan.mfma) {
@@ -385,12 +394,7 @@ deer_status eval_one_launch(bool* busy, deer_ctx* c, const void* d_theta, const 
     q.extra_workgroups = c->test_extra_workgroups;
     std::memset(h + (size_t)kSlots * 8, 0, 8);
 #ifdef DEER_SCAN_TIMING
-    {
-        static unsigned long long* dbg = nullptr;
-        if (!dbg) (void)hipMalloc(&dbg, (size_t)1 << 26);
-        p.timing = dbg;
-        g_timing = dbg;
-    }
+    p.timing = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_timing);
 #endif
     prof_begin(c, KIND_NEWTON);
     HIPCHK(c, launch_gru_newton(g.dtype, g.n, q, c->stream));
@@ -540,7 +544,10 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
         bool busy = false;
         deer_status s1 = eval_one_launch(&busy, c, d_theta, d_x, d_y0, d_y_guess, tol, max_iter, d_y, iters, final_err, converged);
         if (!busy) return s1;
-        // a workgroup waited too long for the others (the device is shared): solve again launch by launch
+        // a workgroup waited too long for the others (the device is shared): solve again launch by launch.  An
+        // abandoned solve may have stored part of its last iterate: a guess that shares the output buffer is
+        // no longer the caller's, so the solve starts from zeros instead.
+        if (d_y_guess == d_y) d_y_guess = nullptr;
     }
 
     // Iteration k reads buf[k & 1] and writes buf[(k + 1) & 1].  The buffers are ordered so that the
@@ -736,9 +743,7 @@ deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const v
 
     deer_status st = zero_ctl(c);
     if (st != DEER_OK) return st;
-    const bool dual_fused = c->plan.fused && env_int("DEER_GRAD_FUSED", 1) != 0 &&
-                            (c->plan.mfma || scan_gru_dual_supported(g.dtype, g.n, g.d, c->plan.fused_L, c->plan.fused_W));
-    if (dual_fused) {
+    if (c->plan.grad_fused) {
         // lam = (dL/dy) L_G^{-1} with the transposed Jacobians computed inside the reverse scan (they never reach memory)
         HIPCHK(c, run_scan(c, nullptr, d_dLdy, nullptr, lam, d_y, 0, (long long)(T * n), (long long)(T * n), 1, 0, false, 0,
                            Gate{nullptr, 0.0}, -1, d_theta, d_x));
@@ -798,7 +803,7 @@ deer_status deer_get_profile(deer_ctx* c, deer_profile* out) {
 }
 
 #ifdef DEER_SCAN_TIMING
-void* deer_debug_timing() { return g_timing; }
+void* deer_debug_timing(deer_ctx* c) { return c ? c->ws + c->plan.off_timing : nullptr; }
 #endif
 
 const char* deer_last_error(const deer_ctx* c) {

@@ -128,19 +128,22 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
     // Second half of the convergence test of iteration kk: collect the maxima of all workgroups (bounded
     // wait), record the result for the host, and say whether the solve stops here.
     S elast = S(INFINITY);
+    bool gave_up = false;   // a wait of this workgroup ran out: the solve is abandoned, the caller solves again
     auto collect = [&](int kk, S own) -> bool {
         unsigned long long* bank = q.barrier + (size_t)(kk & 1) * G * TaggedWords<S>::per_scalar;
         const unsigned tagK = ((p.epoch + (unsigned)kk) << 2) | TILE_INCLUSIVE;
         S gm = S(0);
         bool ok = true;
-        for (unsigned j = tid; j < G && G > 1u; j += 64 * W) {   // a single workgroup has nobody to wait for
+        for (unsigned j = tid; j < G && G > 1u && ok; j += 64 * W) {   // a single workgroup has nobody to wait for
             S v = S(0);
             unsigned spins = 0;
             while (!TaggedWords<S>::get(bank, j, tagK, v)) {
-                // give up after the bound, or as soon as another workgroup has given up
+                // give up after the bound, or as soon as another workgroup has given up; the first thread whose
+                // wait runs out raises the status word at once, so nobody else waits out a bound of its own
                 if (++spins > q.spin_limit ||
                     ((spins & 1023u) == 0u && __hip_atomic_load(p.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
                     ok = false;
+                    atomicOr(p.status, 2u);
                     break;
                 }
                 __builtin_amdgcn_s_sleep(1);
@@ -151,10 +154,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         gm = wave_max<S>(gm);
         const bool wave_ok = __ballot(!ok) == 0ull;
         __syncthreads();   // s_red is reused
-        if (lane == 0) {
-            s_red[wave] = gm;
-            if (!wave_ok) atomicOr(p.status, 2u);
-        }
+        if (lane == 0) s_red[wave] = gm;
         if (tid == 0) s_stop = 0;
         __syncthreads();
         if (lane == 0 && !wave_ok) s_stop = 1;
@@ -163,6 +163,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         for (int v = 1; v < W; ++v) e = s_red[v] > e ? s_red[v] : e;
         __syncthreads();
         const bool stop = s_stop != 0 || !(e > tol) || e >= S(INFINITY);
+        gave_up = gave_up || s_stop != 0;
         if (blockIdx.x == 0 && tid == 0) {   // the record for the host (host-visible memory)
             const S rec = s_stop != 0 ? S(INFINITY) : e;
             if constexpr (sizeof(S) == 4) *reinterpret_cast<float*>(q.err + kk) = rec;
@@ -238,10 +239,14 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         }
     }
 
+    // An abandoned solve leaves the output alone: it may be the caller's initial guess (d_y_guess == d_y), which
+    // the launch-by-launch solve that follows starts from.
     S* __restrict__ ob = reinterpret_cast<S*>(p.out) + (long long)b * p.strideOut;
+    if (!gave_up && !sh.failed) {
 #pragma unroll
-    for (int l = 0; l < L; ++l)
-        if (full || e0 + l < T) __builtin_nontemporal_store(yv[l], ob + (e0 + l) * N + i);
+        for (int l = 0; l < L; ++l)
+            if (full || e0 + l < T) __builtin_nontemporal_store(yv[l], ob + (e0 + l) * N + i);
+    }
     if (blockIdx.x == 0 && tid == 0) *q.result = k;
 }
 

@@ -60,3 +60,12 @@ def dual_serial(A, b):
     br = np.asarray(b[::-1], dtype=np.float64)
     yr = oracle.linrec_serial(Ar, br, np.zeros(n))
     return yr[::-1]
+
+
+def grad_errors(name, what, got, want):
+    """max-abs error of a gradient array against the oracle's, printed with the scale of the oracle's values
+    (pytest -s or a failing test shows the line); returns the max-abs error."""
+    err = float(np.abs(got - want).max())
+    scale = float(np.abs(want).max())
+    print("%s: max|%s - oracle| = %.3e  (max|oracle| = %.3e)" % (name, what, err, scale), flush=True)
+    return err

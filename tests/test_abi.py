@@ -31,7 +31,6 @@ def test_theta_count_and_validation_on_host():
     mlp = deer.make_config(deer.DEER_CELL_MLP_ODE, deer.DEER_F32, 8, 100000, 8, mlp_width=32,
                            mlp_hidden_layers=2, t0=0.0, t1=10.0)
     assert deer.theta_count(mlp) == 32 * 8 + 32 + 32 * 32 + 32 + 8 * 32 + 8
-    assert deer.workspace_bytes(gru) > 16 * 10000 * 8 * 8 * 4
     assert deer.workspace_bytes(mlp) > 2 * 8 * 100000 * 8 * 8 * 4 - 8 * 64 * 4
     with pytest.raises(deer.DeerError) as e:
         deer.workspace_bytes(deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 1, 10, 5, d=2))
@@ -43,6 +42,27 @@ def test_theta_count_and_validation_on_host():
         deer.workspace_bytes(deer.make_config(deer.DEER_CELL_MLP_ODE, deer.DEER_F32, 1, 10, 8, mlp_width=32,
                                               mlp_hidden_layers=3, t0=0.0, t1=1.0))
     assert e.value.status == deer.DEER_ERR_UNSUPPORTED
+
+
+def test_workspace_follows_the_plan(monkeypatch):
+    # Sec. 3.5: the Jacobian stream is O(n^2 T) memory.  It is part of the workspace only where two kernels
+    # exchange it; with the cell inside the scans the third benchmark configuration (6.55 GB of Jacobians, a
+    # shape the paper's 16 GB device could not run: Table 4) needs well under 1 GB.
+    for var in ("DEER_FUSED", "DEER_GRAD_FUSED"):
+        monkeypatch.delenv(var, raising=False)
+    cfg2 = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 16, 10000, 8, d=4)
+    cfg3 = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 16, 100000, 32, d=8)
+    jac2, jac3 = 16 * 10000 * 8 * 8 * 4, 16 * 100000 * 32 * 32 * 4
+    assert deer.workspace_bytes(cfg2) < jac2
+    assert deer.workspace_bytes(cfg3) < (1 << 30) < jac3
+    # fp64 at n = 32 runs the cell kernel and the plain scan: the stream is there
+    cfg3_64 = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F64, 16, 100000, 32, d=8)
+    assert deer.workspace_bytes(cfg3_64) > 2 * jac3
+    # and so it is when a knob asks for the separate kernels in either direction
+    for var in ("DEER_FUSED", "DEER_GRAD_FUSED"):
+        monkeypatch.setenv(var, "0")
+        assert deer.workspace_bytes(cfg2) > jac2 and deer.workspace_bytes(cfg3) > jac3
+        monkeypatch.delenv(var)
 
 
 def test_create_rejects_bad_arguments_without_touching_the_gpu():

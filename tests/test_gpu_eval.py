@@ -147,12 +147,26 @@ def test_repeated_calls_on_one_context():
             torch.cuda.synchronize()
             ref, ito, erro, _ = oracle_eval(w, tol=tol, max_iter=max_iter, guess=guess)
             assert st == deer.DEER_OK and abs(it - ito) <= 1, (tol, max_iter, it, ito)
-            if it == ito:
-                assert np.abs(host(y) - ref).max() <= 1e-4, (tol, max_iter, guess is not None)
-            seen.append(it)
-        assert len(set(seen)) > 1
+            if it != ito:
+                # one iteration more or less than the oracle (allowed): compare with the oracle's iterate of
+                # the same count, which is what the buffer order and the iteration memory must hand back
+                ref, _, _, _ = oracle_eval(w, tol=0.0, max_iter=it, guess=guess)
+            assert np.abs(host(y) - ref).max() <= 1e-4, (tol, max_iter, guess is not None, it, ito)
+            seen.append((it, it == ito))
+        assert len(set(s[0] for s in seen)) > 1 and sum(s[1] for s in seen) >= 5
     finally:
         ctx.close()
+
+
+def test_longer_than_the_jacobian_stream_would_allow():
+    # n = 32, T = 1,000,000, B = 2: the Jacobians of this solve would fill 8.2 GB, more than the whole device of the
+    # paper's benchmark held beside its working copies (Table 4 has no entry for n = 32 beyond 10k samples); with the
+    # cell inside the scan the workspace stays below 1 GB and the solve matches the oracle, which stores no Jacobians
+    w = inputs.gru_workload("long_n32", 33, B=2, T=1000000, n=32, d=8, x_kind="sinusoid")
+    cfg = deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, w.B, w.T, w.n, d=w.d)
+    assert deer.workspace_bytes(cfg) < (1 << 30) < w.B * w.T * w.n * w.n * 4
+    print("oracle on 2 x 1,000,000 positions at n = 32", flush=True)
+    check(w, deer.DEER_F32)
 
 
 def test_more_tiles_than_the_chip_holds():
@@ -205,7 +219,7 @@ def test_epoch_counter_wraps(one_launch, monkeypatch):
             assert st == deer.DEER_OK and conv and abs(it - ito) <= 1
             assert np.abs(host(y) - ref).max() <= 1e-4
             dth, _, _ = ctx.grad(th, x, y0, dev(ref, deer.DEER_F32), dev(g, deer.DEER_F32))
-            assert np.abs(host(dth) - dth_o).max() <= 1e-4 * max(1.0, np.abs(dth_o).max())
+            assert np.abs(host(dth) - dth_o).max() <= 1e-4
     finally:
         ctx.close()
 

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 from paper_2309_12252_amd import deer, inputs
-from helpers import DEV, TOL_ABS, dev, gpu_eval, host, oracle_cell, oracle_eval
+from helpers import DEV, TOL_ABS, dev, gpu_eval, grad_errors, host, oracle_cell, oracle_eval
 
 pytestmark = pytest.mark.gpu
 
@@ -44,11 +44,7 @@ def test_config5_full_size():
 
 # ---- backward derivative (Sec. 3.1.1 eq. 7 on the discretised operator) ----
 
-def rel_err(got, want):
-    return np.abs(got - want).max() / max(1.0, np.abs(want).max())
-
-
-def check_grad(w, dtype, seed=0):
+def check_grad(w, dtype, seed=0, bar_theta=None):
     cell = oracle_cell(w)
     y, _, _, _ = oracle_eval(w, tol=1e-9)
     y = y.astype(np.float32).astype(np.float64)          # what the device sees in either precision
@@ -62,8 +58,9 @@ def check_grad(w, dtype, seed=0):
     finally:
         ctx.close()
     assert dx is None and none0 is None
-    assert rel_err(host(dth), dth_o) <= TOL_ABS[dtype], (w.name, dtype, rel_err(host(dth), dth_o))
-    assert rel_err(host(dy0), dy0_o) <= TOL_ABS[dtype], (w.name, dtype, rel_err(host(dy0), dy0_o))
+    # plain max-abs against the oracle, the same bar as for the trajectory
+    assert grad_errors(w.name, "dL/dtheta", host(dth), dth_o) <= (bar_theta or TOL_ABS[dtype])
+    assert grad_errors(w.name, "dL/dy0", host(dy0), dy0_o) <= TOL_ABS[dtype]
     assert np.array_equal(host(dth), host(dth2))   # fixed reduction order: run-to-run identical
 
 
@@ -96,4 +93,8 @@ def test_grad_coarse_grid():
 
 def test_config5_grad_full_size():
     print("config 5 gradient: oracle on 800k grid points", flush=True)
-    check_grad(inputs.config(5), deer.DEER_F32)
+    # The one gradient whose plain max-abs error exceeds 1e-4 in fp32: measured 3.2e-4 on entries of dL/dtheta up to
+    # 32.8 in magnitude (1e-5 relative, about 160 units in the last place of the largest entries).  Each entry is a sum
+    # over 800,000 grid points of a cotangent that went through a 100,000-step dual recurrence with matrices I + O(dt);
+    # the bar for this case is 5e-4 absolute (1.5e-5 of the largest entry), dL/dy0 keeps 1e-4.
+    check_grad(inputs.config(5), deer.DEER_F32, bar_theta=5e-4)
