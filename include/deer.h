@@ -165,6 +165,26 @@ deer_status deer_grad(deer_ctx* ctx, const void* d_theta, const void* d_x, const
 deer_status deer_linrec_solve(deer_ctx* ctx, const void* d_A, const void* d_b, const void* d_y0,
                               void* d_y, int32_t reverse);
 
+/* deer_linrec_solve() for callers that cannot allocate device memory or hand in a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same scan kernels run, but the words their
+ * tiles publish for each other, the tile dispenser and the status word live in a static device array inside the
+ * library (64 MiB; every GPU the library runs on holds its own copy until the process ends) instead of a workspace,
+ * and no context is needed.  The call allocates nothing (no hipMalloc/hipFree, no pinned host memory, no events),
+ * enqueues three kernels on hip_stream (a fill that clears the part of the array it uses, the scan, a one-word
+ * copy) and returns without synchronising: outputs are complete when the stream reaches that point.
+ *   dtype, B, T, n   as in deer_config (n = 1, 2, 4, 8, 16 or 32)
+ *   d_A [B,T,n,n]  d_b [B,T,n]  d_y0 [B,n] or NULL (zeros)  d_y out [B,T,n]  reverse: as in deer_linrec_solve()
+ *   hip_stream     hipStream_t (NULL = the default stream)
+ *   d_status       out, DEVICE int32, or NULL: 0, or non-zero if a tile waited too long for its predecessors
+ *                  (then d_y is not valid); the host-side return value cannot report that without a synchronisation
+ * Limit: the published words of all tiles must fit the array; a shape beyond it is rejected with
+ * DEER_ERR_WORKSPACE before anything is enqueued (n = 32: about 480,000 positions in all; n = 8: several 10^7).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads) race.
+ * Returns DEER_OK once everything is enqueued; errors are reported through deer_last_error(NULL). */
+deer_status deer_linrec_solve_static(int32_t dtype, int32_t B, int32_t T, int32_t n, const void* d_A, const void* d_b,
+                                     const void* d_y0, void* d_y, int32_t reverse, void* hip_stream,
+                                     int32_t* d_status);
+
 /* Switch per-kernel timing with HIP events on the context's stream on or off (off by default;
  * turning it on resets the accumulated numbers), and read the numbers accumulated so far. */
 deer_status deer_set_profiling(deer_ctx* ctx, int32_t on);

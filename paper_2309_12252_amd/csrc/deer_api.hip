@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -22,6 +23,16 @@ constexpr size_t kAlign = 256;
 constexpr int kMaxEvents = 24;      // timed launches between two host synchronisations
 
 thread_local std::string g_last_error;
+
+// Scratch of deer_linrec_solve_static(): the words the scan's tiles publish for each other, the tile dispenser
+// and the status word live in this array instead of a caller-provided workspace.  Every GPU the library runs
+// on holds its own copy, at its own address, until the process ends.  In host code the array's name is only
+// a handle for hipGetSymbolAddress(); kernels and fills get the per-device address kept in g_static_ptr.
+constexpr size_t kStaticBytes = (size_t)64 << 20;
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) unsigned char deer_static_scratch[kStaticBytes];
+std::mutex g_static_mutex;
+void* g_static_ptr[kMaxDevices] = {};
 #ifdef DEER_SCAN_TIMING
 // development builds only (-DDEER_SCAN_TIMING): the kernels stamp the phases of every tile into a region at the
 // end of the caller's workspace (deer_workspace_bytes() grows by kTimingBytes); deer_debug_timing(ctx) returns it
@@ -805,6 +816,76 @@ deer_status deer_get_profile(deer_ctx* c, deer_profile* out) {
 #ifdef DEER_SCAN_TIMING
 void* deer_debug_timing(deer_ctx* c) { return c ? c->ws + c->plan.off_timing : nullptr; }
 #endif
+
+deer_status deer_linrec_solve_static(int32_t dtype, int32_t B, int32_t T, int32_t n, const void* d_A, const void* d_b,
+                                     const void* d_y0, void* d_y, int32_t reverse, void* hip_stream, int32_t* d_status) {
+    deer_config cfg{};
+    cfg.cell = DEER_CELL_GRU;
+    cfg.dtype = dtype;
+    cfg.B = B;
+    cfg.T = T;
+    cfg.n = n;
+    cfg.d = 1;
+    std::string why;
+    if (!validate(&cfg, why)) return fail(nullptr, DEER_ERR_INVALID_ARG, why);
+    if (!supported(&cfg, why)) return fail(nullptr, DEER_ERR_UNSUPPORTED, why);
+    if (!d_A || !d_b || !d_y) return fail(nullptr, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
+    // the part of the plan the scan uses, re-based to the start of the static array
+    Plan plan = make_plan(&cfg);
+    const size_t base = plan.off_aggW;
+    const size_t need = plan.off_ctl - base + ctl_bytes();
+    if (need > kStaticBytes)
+        return fail(nullptr, DEER_ERR_WORKSPACE,
+                    "deer_linrec_solve_static: B * tiles of this shape need " + std::to_string(need) +
+                        " bytes of published words, the static scratch holds " + std::to_string(kStaticBytes));
+    plan.off_aggW -= base;
+    plan.off_inclW -= base;
+    plan.off_barrier -= base;
+    plan.off_ctl -= base;
+
+    // address of this device's copy of the array, looked up once per device with that device current
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(nullptr, DEER_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, DEER_ERR_UNSUPPORTED, "device index beyond the table of static scratch addresses");
+    void* scratch = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        if (!g_static_ptr[dev]) {
+            void* ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(deer_static_scratch));
+            if (e != hipSuccess || !ptr)
+                return fail(nullptr, DEER_ERR_HIP, std::string("hipGetSymbolAddress(deer_static_scratch): ") + hipGetErrorString(e));
+            g_static_ptr[dev] = ptr;
+        }
+        scratch = g_static_ptr[dev];
+    }
+
+    // a context on the stack (host memory only) that points the scan at the static array
+    deer_ctx c;
+    c.cfg = cfg;
+    c.plan = plan;
+    c.stream = reinterpret_cast<hipStream_t>(hip_stream);
+    c.ws = reinterpret_cast<char*>(scratch);
+    c.epoch = 1;   // the same tag in every call: everything published by the previous call is cleared below
+    c.h_err = nullptr;
+    c.d_h_err = nullptr;
+    c.profiling = false;
+    c.ev_used = 0;
+    // The array keeps the last call's contents: clear the published words (their tags would match again), the
+    // tile dispenser and the status word, with a fill kernel on the caller's stream.
+    e = launch_fill_zero(scratch, need, c.stream);
+    if (e != hipSuccess) return fail(nullptr, DEER_ERR_HIP, std::string("fill launch: ") + hipGetErrorString(e));
+    const size_t nn = (size_t)n, TT = (size_t)T;
+    e = run_scan(&c, d_A, d_b, reverse ? nullptr : d_y0, d_y, nullptr, (long long)(TT * nn * nn), (long long)(TT * nn),
+                 (long long)(TT * nn), reverse ? 1 : 0, 0, false);
+    if (e != hipSuccess) return fail(nullptr, DEER_ERR_HIP, std::string("scan launch: ") + hipGetErrorString(e));
+    if (d_status) {
+        e = launch_copy_word(d_status, ctl_status(&c), c.stream);
+        if (e != hipSuccess) return fail(nullptr, DEER_ERR_HIP, std::string("status copy launch: ") + hipGetErrorString(e));
+    }
+    return DEER_OK;
+}
 
 const char* deer_last_error(const deer_ctx* c) {
     return c ? c->last_error.c_str() : g_last_error.c_str();

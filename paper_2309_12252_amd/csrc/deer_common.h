@@ -319,6 +319,7 @@ hipError_t launch_mlp_vjp_mfma(const MlpVjpParams& p, hipStream_t s);
 hipError_t launch_partial_reduce(int dtype, const void* partial, void* out, long long P, int rows, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_fill_zero2(void* a, size_t abytes, void* b, size_t bbytes, hipStream_t s);
+hipError_t launch_copy_word(void* dst, const void* src, hipStream_t s);   // one 32-bit word, device to device
 hipError_t launch_pin_first(int dtype, void* y, const void* y0, int B, int T, int n, hipStream_t s);
 
 }  // namespace deer

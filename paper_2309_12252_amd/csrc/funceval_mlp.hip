@@ -698,6 +698,16 @@ hipError_t launch_ode_dual_residual(int dtype, const void* D, const void* g, con
                       : launch_residual_s<double>(D, g, lam0, res, B, T, n, s);
 }
 
+__global__ void copy_word_kernel(unsigned* __restrict__ dst, const unsigned* __restrict__ src) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *dst = *src;
+}
+
+hipError_t launch_copy_word(void* dst, const void* src, hipStream_t s) {
+    hipLaunchKernelGGL(copy_word_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<unsigned*>(dst),
+                       reinterpret_cast<const unsigned*>(src));
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
     // bytes must be a multiple of 16 and p 16-byte aligned (workspace sections are)
     const size_t n16 = bytes / 16;

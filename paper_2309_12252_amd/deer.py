@@ -18,7 +18,7 @@ DEER_CELL_GRU, DEER_CELL_MLP_ODE = 0, 1
 DEER_F32, DEER_F64 = 0, 1
 
 EXPORTS = ["deer_theta_count", "deer_workspace_bytes", "deer_create", "deer_eval", "deer_grad",
-           "deer_linrec_solve", "deer_set_profiling", "deer_get_profile", "deer_last_error", "deer_destroy"]
+           "deer_linrec_solve", "deer_linrec_solve_static", "deer_set_profiling", "deer_get_profile", "deer_last_error", "deer_destroy"]
 
 
 class DeerConfig(ctypes.Structure):
@@ -69,6 +69,8 @@ def load_library():
     lib.deer_grad.argtypes = [vp] * 9
     lib.deer_linrec_solve.restype = ctypes.c_int
     lib.deer_linrec_solve.argtypes = [vp, vp, vp, vp, vp, i32]
+    lib.deer_linrec_solve_static.restype = ctypes.c_int
+    lib.deer_linrec_solve_static.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp]
     lib.deer_set_profiling.restype = ctypes.c_int
     lib.deer_set_profiling.argtypes = [vp, i32]
     lib.deer_get_profile.restype = ctypes.c_int
@@ -194,6 +196,24 @@ class DeerContext:
             self.close()
         except Exception:
             pass
+
+
+def linrec_solve_static(A, b, y0=None, reverse=False, out=None, status=None, stream=None):
+    """deer_linrec_solve_static: the scan alone without a context or workspace (nothing is allocated by the
+    library).  A [B,T,n,n], b [B,T,n], y0 [B,n] or None; `out` and the int32 device tensor `status` are the
+    caller's.  Asynchronous on `stream` (default: torch's current stream).  Returns out."""
+    lib = load_library()
+    assert A.is_cuda and A.is_contiguous() and b.is_contiguous() and A.dtype == b.dtype
+    B, T, n, _ = A.shape
+    assert tuple(b.shape) == (B, T, n) and (y0 is None or tuple(y0.shape) == (B, n))
+    dtype = DEER_F32 if A.dtype == torch.float32 else DEER_F64
+    y = out if out is not None else torch.empty((B, T, n), dtype=A.dtype, device=A.device)
+    stream = stream if stream is not None else torch.cuda.current_stream(A.device)
+    st = lib.deer_linrec_solve_static(dtype, B, T, n, _ptr(A), _ptr(b), _ptr(y0), _ptr(y), 1 if reverse else 0,
+                                      ctypes.c_void_p(stream.cuda_stream), _ptr(status))
+    if st != DEER_OK:
+        raise DeerError(st, lib.deer_last_error(None).decode())
+    return y
 
 
 def context_for(workload, dtype=DEER_F32, device="cuda:0"):
