@@ -143,6 +143,13 @@ Plan make_plan(const deer_config* c) {
             const bool fills = (long long)B * ((p.scan_T + tile24 - 1) / tile24) >= 256;
             if (forced == 24 || (forced == 0 && L == 16 && fills)) L = 24;
         }
+        // n = 2 in fp32: 32 positions per group (three registers each) once the launch still gives every
+        // compute unit a tile; the fixed per-tile latencies are most of a tile's life at this size
+        if (c->dtype == DEER_F32 && c->n == 2) {
+            const long long tile32 = scan_valu_tile(2, 32, W);
+            const bool fills = (long long)B * ((p.scan_T + tile32 - 1) / tile32) >= 256;
+            if (forced == 32 || (forced == 0 && L == 16 && fills)) L = 32;
+        }
         p.L = L;
         p.tile = scan_valu_tile(c->n, p.L, p.W);
     }

@@ -67,6 +67,7 @@ hipError_t launch_n(const ScanParams& p, hipStream_t s) {
         case 12: if constexpr (sizeof(S) == 4) return launch_nl<S, N, 12>(p, s); else return hipErrorInvalidValue;
         case 16: if constexpr (sizeof(S) == 4) return launch_nl<S, N, 16>(p, s); else return hipErrorInvalidValue;
         case 24: if constexpr (sizeof(S) == 4 && N == 4) return launch_nl<S, N, 24>(p, s); else return hipErrorInvalidValue;
+        case 32: if constexpr (sizeof(S) == 4 && N == 2) return launch_nl<S, N, 32>(p, s); else return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }

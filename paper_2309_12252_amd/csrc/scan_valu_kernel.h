@@ -135,7 +135,7 @@ __device__ __forceinline__ S group_matvec(const S* Lr, S add, S y) {
 // past the end read the last valid one and are then replaced by the identity pair): with
 // straight-line code the compiler keeps the loads in order and lets the first products start while
 // later positions are still in flight.
-template <typename S, int N, int L, bool REV, bool FULL, bool ADDI = false>
+template <typename S, int N, int L, bool REV, bool FULL, bool ADDI = false, bool SKIPB = false>
 __device__ __forceinline__ void load_pairs(const S* __restrict__ Ab, const S* __restrict__ bb, long long T,
                                            long long e0, int i, S (*Ar)[N], S* be) {
     constexpr S addI = ADDI ? S(1) : S(0);   // ADDI: the stored matrices are A - I
@@ -153,7 +153,7 @@ __device__ __forceinline__ void load_pairs(const S* __restrict__ Ab, const S* __
             } else {
                 vload<S, N>(Ar[l], rowa + l * (N * N));
             }
-            be[l] = bp[l * N];
+            if constexpr (!SKIPB) be[l] = bp[l * N];   // (SKIPB: the vectors come through the staged loads)
         }
     } else if constexpr (FULL && REV) {
         // column i of the matrix stored at index T - e, rows in swizzled order
@@ -204,6 +204,114 @@ __device__ __forceinline__ void load_pairs(const S* __restrict__ Ab, const S* __
         for (int l = 0; l < L; ++l)
 #pragma unroll
             for (int s = 0; s < N; ++s) Ar[l][s] += (swz_col<N>(s, i) == i) ? S(1) : S(0);
+    }
+}
+
+
+// Staged loads and stores for n = 2 (fp32, forward, tiles inside the sequence; the code also handles n = 4 and
+// n = 8, see the measurements below).  A group's rows are short (8 bytes), so a lane-per-row load instruction
+// touches one cache line per group and every line
+// is visited by many instructions; with eight wavefronts in flight the lines do not survive in the
+// first-level cache between visits.  Here every lane loads contiguous 16-byte pieces of the wavefront's
+// chunk instead (each line is touched by one instruction), the pieces cross a wavefront-private LDS region
+// (one 16-byte pad per group run keeps the reads off each other's banks), and every lane reads its own
+// rows back.  LC positions per group and pass.
+template <int N, int L>
+struct Staged {
+    // Measured on chip-filling streams: n = 2 goes from 2.2 to 4.2 TB/s (with 32 positions per group); n = 4 and
+    // n = 8, whose rows are whole 16-byte loads, lose with any part staged (matrices at n = 4: 3.9 against 4.2 TB/s;
+    // vectors and results only: 4.0 against 4.2 at n = 4, 3.1 against 3.45 at n = 8), so they stay with direct accesses.
+    static constexpr bool use = N == 2 && (L % 8 == 0);   // vectors in, results out
+    static constexpr bool useA = use && N == 2;           // matrices too
+    static constexpr int NG = 64 / N;
+    static constexpr int LC = (N == 2) ? ((L % 16 == 0) ? 16 : 8) : 8;   // positions per group and pass
+    static constexpr int MU = N * N / 4;            // 16-byte pieces per matrix
+    static constexpr int RUNA = LC * MU;            // pieces per group and pass, matrices
+    static constexpr int RUNB = LC * N / 4;         // pieces per group and pass, vectors
+    static constexpr int TOTA = NG * RUNA, TOTB = NG * RUNB;
+    static constexpr int IN4 = (useA ? TOTA + NG : 0) + TOTB + NG, OUT4 = NG * (L * N / 4) + NG;
+    static constexpr int U4 = use ? (IN4 > OUT4 ? IN4 : OUT4) : 1;   // pieces of LDS per wavefront
+};
+
+// (the staging region is written as 16-byte pieces and read as scalars: both through types that may alias
+// anything, so the compiler keeps the reads behind the writes)
+typedef uint4 __attribute__((may_alias)) staged_piece;
+typedef float __attribute__((may_alias)) staged_scalar;
+
+template <int N, int L>
+__device__ __forceinline__ void load_pairs_staged(const float* __restrict__ Ab, const float* __restrict__ bb,
+                                                  long long ew, int lane, staged_piece* st, float (*Ar)[N], float* be) {
+    using P = Staged<N, L>;
+    constexpr int NG = P::NG, LC = P::LC, MU = P::MU, RUNA = P::RUNA, RUNB = P::RUNB;
+    static_assert((!P::useA || P::TOTA % 64 == 0) && P::TOTB % 64 == 0, "whole load instructions");
+    constexpr int KA = P::useA ? P::TOTA / 64 : 0;
+    const int group = lane / N, i = lane % N;
+    staged_piece* stA = st;
+    staged_piece* stB = st + (P::useA ? P::TOTA + NG : 0);
+#pragma unroll
+    for (int l0 = 0; l0 < L; l0 += LC) {
+        uint4 va[KA > 0 ? KA : 1], vb[P::TOTB / 64];
+#pragma unroll
+        for (int k = 0; k < KA; ++k) {
+            const int u = k * 64 + lane, g = u / RUNA, o = u % RUNA;
+            va[k] = reinterpret_cast<const uint4*>(Ab + (ew + (long long)g * L + l0) * (N * N))[o];
+        }
+#pragma unroll
+        for (int k = 0; k < P::TOTB / 64; ++k) {
+            const int u = k * 64 + lane, g = u / RUNB, o = u % RUNB;
+            vb[k] = reinterpret_cast<const uint4*>(bb + (ew + (long long)g * L + l0) * N)[o];
+        }
+        if (l0 > 0) __builtin_amdgcn_wave_barrier();   // the previous pass has been read
+#pragma unroll
+        for (int k = 0; k < KA; ++k) {
+            const int u = k * 64 + lane;
+            stA[u + u / RUNA] = va[k];
+        }
+#pragma unroll
+        for (int k = 0; k < P::TOTB / 64; ++k) {
+            const int u = k * 64 + lane;
+            stB[u + u / RUNB] = vb[k];
+        }
+        __builtin_amdgcn_wave_barrier();
+        const staged_scalar* rowsA = reinterpret_cast<const staged_scalar*>(stA + group * (RUNA + 1)) + i * N;
+        const staged_scalar* rowsB = reinterpret_cast<const staged_scalar*>(stB + group * (RUNB + 1)) + i;
+#pragma unroll
+        for (int l = 0; l < LC; ++l) {
+            if constexpr (P::useA) {
+#pragma unroll
+                for (int c = 0; c < N; ++c) Ar[l0 + l][c] = rowsA[l * (N * N) + c];
+            }
+            float bv = rowsB[l * N];
+            // The vectors come back from LDS two to a register pair, and the composition's assembly blocks
+            // accumulate into a copy of each vector: with the pair's halves used directly the compiler (ROCm
+            // 7.2) dropped that copy for every second position and the block overwrote the vector the
+            // second walk still needs.  Passing each value through an opaque statement gives it a register
+            // of its own.
+            asm volatile("" : "+v"(bv));
+            be[l0 + l] = bv;
+        }
+    }
+}
+
+// The other direction for the results: every lane leaves entry i of its L positions in the wavefront's LDS region
+// and the wavefront writes its chunk of the output as contiguous 16-byte pieces.
+template <int N, int L>
+__device__ __forceinline__ void store_staged(float* __restrict__ ob, long long ew, int lane, staged_piece* st, const float* w) {
+    constexpr int NG = 64 / N;
+    constexpr int RUN = L * N / 4;        // pieces per group
+    constexpr int TOT = NG * RUN;
+    static_assert(TOT % 64 == 0 && TOT + NG <= Staged<N, L>::U4, "whole store instructions inside the region");
+    const int group = lane / N, i = lane % N;
+    __builtin_amdgcn_wave_barrier();
+    staged_scalar* mine = reinterpret_cast<staged_scalar*>(st + group * (RUN + 1)) + i;
+#pragma unroll
+    for (int l = 0; l < L; ++l) mine[l * N] = w[l];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int k = 0; k < TOT / 64; ++k) {
+        const int u = k * 64 + lane;
+        const staged_piece v = st[u + u / RUN];
+        reinterpret_cast<uint4*>(ob + ew * N)[u] = v;
     }
 }
 
@@ -833,6 +941,8 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
 
     __shared__ unsigned s_ticket;
     __shared__ TileShared<S, N, W> sh;
+    constexpr bool STAGED = DP == 0 && !REV && !ADDI && sizeof(S) == 4 && Staged<N, L>::use;
+    __shared__ uint4 s_stage[STAGED ? W : 1][Staged<N, L>::U4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -864,8 +974,22 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     const bool full = (long long)(t + 1) * TILE <= T && (!REV || t > 0);
     S Ar[L][N], be[L], yo[L];
     if (full) {
-        if constexpr (DP == 0) load_pairs<S, N, L, REV, true, ADDI>(Ab, bb, T, e0, i, Ar, be);
-        load_previous<S, N, L, REV, true>(oldb ? oldb : bb, T, e0, i, yo);
+        if constexpr (STAGED) {
+            if constexpr (!Staged<N, L>::useA) load_pairs<S, N, L, REV, true, ADDI, true>(Ab, bb, T, e0, i, Ar, be);
+            load_pairs_staged<N, L>(Ab, bb, (long long)t * TILE + (long long)wave * (NG * L), lane, reinterpret_cast<staged_piece*>(s_stage[wave]), Ar, be);
+        } else if constexpr (DP == 0) {
+            load_pairs<S, N, L, REV, true, ADDI>(Ab, bb, T, e0, i, Ar, be);
+        }
+        if constexpr (STAGED) {
+            // (without a previous iterate nothing is loaded: the lane-per-entry loads are the slow kind here)
+            if (oldb) load_previous<S, N, L, REV, true>(oldb, T, e0, i, yo);
+            else {
+#pragma unroll
+                for (int l = 0; l < L; ++l) yo[l] = S(0);
+            }
+        } else {
+            load_previous<S, N, L, REV, true>(oldb ? oldb : bb, T, e0, i, yo);
+        }
         if constexpr (DP > 0 && !REV) gru_pairs<S, N, L, DP, true>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
         if constexpr (DUAL) {
             load_previous<S, N, L, true, true>(bb, T, e0, i, be);
@@ -891,6 +1015,7 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     S y = tile_start_state<S, N, W>(sh, Pex, pex, wave, i);
 
     S emax = S(0);
+    S wout[STAGED ? L : 1];
 #pragma unroll
     for (int l = 0; l < L; ++l) {
         const long long e = e0 + l;
@@ -903,8 +1028,18 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
                 emax = dq > emax ? dq : emax;
                 if (p.delta) w += yo[l];
             }
-            ob[oi] = w;
+            if constexpr (STAGED) {
+                if (full) wout[l] = w;
+                else ob[oi] = w;
+            } else {
+                ob[oi] = w;
+            }
         }
+    }
+    if constexpr (STAGED) {
+        if (full)
+            store_staged<N, L>(ob, (long long)t * TILE + (long long)wave * (NG * L), lane,
+                               reinterpret_cast<staged_piece*>(s_stage[wave]), wout);
     }
     if (p.err) {
         emax = wave_max<S>(emax);

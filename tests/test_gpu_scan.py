@@ -49,6 +49,18 @@ def test_many_tiles_per_sequence(n, B, T):
     run_case(n, B, T, deer.DEER_F32, True, 9 * n)
 
 
+@pytest.mark.parametrize("n,L", [(2, 8), (2, 16), (2, 32), (4, 8), (4, 16), (4, 24), (8, 16)])
+def test_tile_shapes_of_the_small_state_scan(n, L, monkeypatch):
+    # positions per lane group through the knob; for n = 2 and 4 the longer runs take the loads that are staged
+    # through LDS (tiles inside the sequence) next to the lane-per-row loads of the ragged last tile, and an odd
+    # batch index puts a sequence at an address that is not a multiple of 16 bytes
+    monkeypatch.setenv("DEER_SCAN_L", str(L))
+    tile = 8 * (64 // n) * L
+    for k, (B, T) in enumerate([(3, 2 * tile + 77), (2, tile), (1, 5 * tile - 1)]):
+        run_case(n, B, T, deer.DEER_F32, False, 300 * n + L + k)
+        run_case(n, B, T, deer.DEER_F32, True, 400 * n + L + k)
+
+
 def test_identity_matrices_give_a_prefix_sum():
     n, B, T = 4, 2, 3000
     rng = np.random.default_rng(0)
