@@ -251,7 +251,7 @@ def cpu_baseline(w, inputs):
         T1 = max(1, w.T // 4)
         run1 = lambda: oracle.deer_eval(cell, w.theta, w.x[:1, :T1], w.y0[:1], tol=w.tol, max_iter=w.max_iter, nthreads=1)
     else:
-        cell = oracle.make_cell(oracle.CELL_MLP, w.n, 0, w.mlp_width, w.mlp_hidden_layers)
+        cell = oracle.make_cell(oracle.CELL_MLP, w.n, 0, w.mlp_width, w.mlp_hidden_layers, w.mlp_activation)
         run = lambda th: oracle.ode_deer_eval(cell, w.theta, w.y0, w.T, w.t0, w.t1, tol=w.tol, max_iter=w.max_iter,
                                               nthreads=th)
         T1 = max(2, w.T // 4)

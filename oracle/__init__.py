@@ -22,7 +22,7 @@ CELL_GRU, CELL_MLP, CELL_AFFINE = 0, 1, 2
 
 class _Cell(ctypes.Structure):
     _fields_ = [("cell", ctypes.c_int), ("n", ctypes.c_int), ("d", ctypes.c_int),
-                ("width", ctypes.c_int), ("nhid", ctypes.c_int)]
+                ("width", ctypes.c_int), ("nhid", ctypes.c_int), ("act", ctypes.c_int)]
 
 
 def build(force=False):
@@ -57,8 +57,11 @@ def _p(a):
     return a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
 
 
-def make_cell(cell, n, d=0, width=0, nhid=0):
-    return _Cell(int(cell), int(n), int(d), int(width), int(nhid))
+ACT_TANH, ACT_SOFTPLUS = 0, 1
+
+
+def make_cell(cell, n, d=0, width=0, nhid=0, act=ACT_TANH):
+    return _Cell(int(cell), int(n), int(d), int(width), int(nhid), int(act))
 
 
 def theta_count(cell):

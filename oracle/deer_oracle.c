@@ -30,8 +30,10 @@
  *         q = U_c h + b_hc                  c = tanh(W_c x + b_c + r*q)
  *         h' = (1 - z)*c + z*h
  *     theta = W[3n,d] (rows r|z|c), U[3n,n] (rows r|z|c), b[3n], b_hc[n].
- *   - MLP field: f(y) = W_out tanh(... tanh(W_1 y + b_1) ...) + b_out with
- *     nhid hidden layers of equal width; theta = W_1[w,n], b_1[w],
+ *   - MLP field: f(y) = W_out s(... s(W_1 y + b_1) ...) + b_out with
+ *     nhid hidden layers of equal width and activation s = tanh, or softplus
+ *     s(a) = log(1 + exp(a)) (the activation of the paper's two-body network,
+ *     App. B.2: six linear layers, softplus on all but the last); theta = W_1[w,n], b_1[w],
  *     (W_k[w,w], b_k[w]) for k = 2..nhid, W_out[n,w], b_out[n]; nhid = 0 is
  *     the linear field W_out[n,n] y + b_out.
  *   - affine RNN cell (a test hook, used to pin "Newton is exact for linear
@@ -63,6 +65,7 @@ typedef struct {
     int d;      /* input size (GRU, AFFINE); ignored for MLP */
     int width;  /* MLP hidden width */
     int nhid;   /* MLP number of hidden layers */
+    int act;    /* MLP activation: 0 tanh, 1 softplus */
 } oracle_cell;
 
 static double sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
@@ -174,8 +177,19 @@ static void gru_vjp(int n, int d, const double* th, const double* h, const doubl
 
 /* ------------------------------------------------------------------ MLP -- */
 
-/* forward pass keeping every layer's activations: act[l] (l = 0..nhid-1), width w */
-static void mlp_forward(const oracle_cell* c, const double* th, const double* y, double* act, double* out) {
+/* activation and its derivative at pre-activation a */
+static double mlp_act(int kind, double a) {
+    if (kind == 0) return tanh(a);
+    return a > 0.0 ? a + log1p(exp(-a)) : log1p(exp(a));   /* log(1 + e^a) without overflow */
+}
+static double mlp_dact(int kind, double a) {
+    if (kind == 0) { double t = tanh(a); return 1.0 - t * t; }
+    return sigmoid(a);
+}
+
+/* forward pass keeping every layer's activations: act[l] (l = 0..nhid-1), width w, and (when dact is
+ * not NULL) the derivative of the activation at every unit */
+static void mlp_forward_d(const oracle_cell* c, const double* th, const double* y, double* act, double* dact, double* out) {
     int n = c->n, w = c->width, L = c->nhid;
     const double* p = th;
     const double* in = y;
@@ -186,7 +200,8 @@ static void mlp_forward(const oracle_cell* c, const double* th, const double* y,
         for (int i = 0; i < w; i++) {
             double a = bl[i];
             for (int j = 0; j < nin; j++) a += Wl[i * nin + j] * in[j];
-            act[l * w + i] = tanh(a);
+            act[l * w + i] = mlp_act(c->act, a);
+            if (dact) dact[l * w + i] = mlp_dact(c->act, a);
         }
         p += w * nin + w;
         in = act + l * w;
@@ -201,13 +216,17 @@ static void mlp_forward(const oracle_cell* c, const double* th, const double* y,
     }
 }
 
+static void mlp_forward(const oracle_cell* c, const double* th, const double* y, double* act, double* out) {
+    mlp_forward_d(c, th, y, act, NULL, out);
+}
+
 static void mlp_f(const oracle_cell* c, const double* th, const double* y, double* out) {
     double* act = malloc((size_t)(c->nhid * c->width + 1) * sizeof(double));
     mlp_forward(c, th, y, act, out);
     free(act);
 }
 
-/* J = W_out D_L W_L ... D_1 W_1, D_l = diag(1 - act_l^2): propagate the n
+/* J = W_out D_L W_L ... D_1 W_1, D_l = diag(s'(pre-activation of layer l)): propagate the n
  * columns of the identity through the layers (forward mode). */
 static void mlp_jac(const oracle_cell* c, const double* th, const double* y, double* J) {
     int n = c->n, w = c->width, L = c->nhid;
@@ -216,7 +235,8 @@ static void mlp_jac(const oracle_cell* c, const double* th, const double* y, dou
     double* out = malloc((size_t)n * sizeof(double));
     double* S = malloc((size_t)big * n * sizeof(double));   /* d(layer input)/dy, [nin, n] */
     double* S2 = malloc((size_t)big * n * sizeof(double));
-    mlp_forward(c, th, y, act, out);
+    double* dac = malloc((size_t)(L * w + 1) * sizeof(double));
+    mlp_forward_d(c, th, y, act, dac, out);
     for (int i = 0; i < n; i++)
         for (int j = 0; j < n; j++) S[i * n + j] = (i == j ? 1.0 : 0.0);
     const double* p = th;
@@ -224,7 +244,7 @@ static void mlp_jac(const oracle_cell* c, const double* th, const double* y, dou
     for (int l = 0; l < L; l++) {
         const double* Wl = p;
         for (int i = 0; i < w; i++) {
-            double dact = 1.0 - act[l * w + i] * act[l * w + i];
+            double dact = dac[l * w + i];
             for (int j = 0; j < n; j++) {
                 double s = 0.0;
                 for (int k = 0; k < nin; k++) s += Wl[i * nin + k] * S[k * n + j];
@@ -242,7 +262,7 @@ static void mlp_jac(const oracle_cell* c, const double* th, const double* y, dou
             for (int k = 0; k < nin; k++) s += Wo[i * nin + k] * S[k * n + j];
             J[i * n + j] = s;
         }
-    free(act); free(out); free(S); free(S2);
+    free(act); free(out); free(S); free(S2); free(dac);
 }
 
 /* --------------------------------------------------------------- affine -- */
@@ -610,7 +630,8 @@ static void mlp_vjp(const oracle_cell* c, const double* th, const double* y, con
     double* out = malloc((size_t)n * sizeof(double));
     double* up = malloc((size_t)big * sizeof(double));     /* dL/d(output of the current layer) */
     double* down = malloc((size_t)big * sizeof(double));   /* dL/d(input of the current layer) */
-    mlp_forward(c, th, y, act, out);
+    double* dac = malloc((size_t)(L * wd + 1) * sizeof(double));
+    mlp_forward_d(c, th, y, act, dac, out);
     /* offsets of the layers inside theta */
     size_t* off = malloc((size_t)(L + 1) * sizeof(size_t));
     size_t o = 0;
@@ -633,7 +654,7 @@ static void mlp_vjp(const oracle_cell* c, const double* th, const double* y, con
             up[j] = sacc;
         }
     }
-    /* hidden layers, last to first: act_l = tanh(W_l in + b_l) */
+    /* hidden layers, last to first: act_l = s(W_l in + b_l) */
     for (int l = L - 1; l >= 0; l--) {
         int lin = (l == 0 ? n : wd);
         const double* in = (l == 0 ? y : act + (l - 1) * wd);
@@ -642,7 +663,7 @@ static void mlp_vjp(const oracle_cell* c, const double* th, const double* y, con
         double* dbl = dWl + (size_t)wd * lin;
         for (int j = 0; j < lin; j++) down[j] = 0.0;
         for (int i = 0; i < wd; i++) {
-            double dpre = up[i] * (1.0 - act[l * wd + i] * act[l * wd + i]);
+            double dpre = up[i] * dac[l * wd + i];
             for (int j = 0; j < lin; j++) {
                 dWl[i * lin + j] += dpre * in[j];
                 down[j] += Wl[i * lin + j] * dpre;
@@ -652,7 +673,7 @@ static void mlp_vjp(const oracle_cell* c, const double* th, const double* y, con
         memcpy(up, down, (size_t)lin * sizeof(double));
     }
     memcpy(dy, up, (size_t)n * sizeof(double));
-    free(act); free(out); free(up); free(down); free(off);
+    free(act); free(out); free(up); free(down); free(off); free(dac);
 }
 
 void oracle_mlp_vjp(const oracle_cell* c, const double* th, const double* y, const double* w,

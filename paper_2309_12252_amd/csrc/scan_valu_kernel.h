@@ -980,8 +980,9 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
         } else if constexpr (DP == 0) {
             load_pairs<S, N, L, REV, true, ADDI>(Ab, bb, T, e0, i, Ar, be);
         }
-        if constexpr (STAGED) {
-            // (without a previous iterate nothing is loaded: the lane-per-entry loads are the slow kind here)
+        if constexpr (DP == 0 && N <= 4) {
+            // (without a previous iterate nothing is loaded; measured +6 % at n = 4, while the n = 8 kernel, at
+            // its register limit, is a few per cent slower with the branch and keeps the unconditional loads)
             if (oldb) load_previous<S, N, L, REV, true>(oldb, T, e0, i, yo);
             else {
 #pragma unroll

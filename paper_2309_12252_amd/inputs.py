@@ -26,6 +26,7 @@ class Workload:
     d: int = 0
     mlp_width: int = 0
     mlp_hidden_layers: int = 0
+    mlp_activation: int = 0    # 0 tanh, 1 softplus
     t0: float = 0.0
     t1: float = 0.0
     tol: float = 1e-4
@@ -71,13 +72,16 @@ def gru_workload(name, seed, B, T, n, d, tol=1e-4, max_iter=50, x_kind="normal",
                     theta=theta, x=x, y0=y0)
 
 
-def mlp_ode_workload(name, seed, B, T, n, width, nhid, t0, t1, tol=1e-4, max_iter=50):
+ACT_TANH, ACT_SOFTPLUS = 0, 1
+
+
+def mlp_ode_workload(name, seed, B, T, n, width, nhid, t0, t1, tol=1e-4, max_iter=50, act=ACT_TANH):
     """dy/dt = MLP(y): weights and biases ~ N(0, 1/width); y0 ~ N(0,1); uniform grid of T points."""
     rng = np.random.default_rng(seed)
     theta = _normal(rng, mlp_theta_count(n, width, nhid), 1.0 / np.sqrt(width))
     y0 = _normal(rng, (B, n), 1.0)
     return Workload(name=name, cell=CELL_MLP_ODE, B=B, T=T, n=n, mlp_width=width, mlp_hidden_layers=nhid,
-                    t0=t0, t1=t1, tol=tol, max_iter=max_iter, theta=theta, y0=y0)
+                    mlp_activation=act, t0=t0, t1=t1, tol=tol, max_iter=max_iter, theta=theta, y0=y0)
 
 
 def config(k, rep=0, T=None, B=None):

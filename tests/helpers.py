@@ -23,7 +23,7 @@ def host(t):
 def oracle_cell(w):
     if w.cell == inputs.CELL_GRU:
         return oracle.make_cell(oracle.CELL_GRU, w.n, w.d)
-    return oracle.make_cell(oracle.CELL_MLP, w.n, 0, w.mlp_width, w.mlp_hidden_layers)
+    return oracle.make_cell(oracle.CELL_MLP, w.n, 0, w.mlp_width, w.mlp_hidden_layers, w.mlp_activation)
 
 
 def oracle_eval(w, tol=None, max_iter=None, guess=None, nthreads=8):

@@ -27,7 +27,7 @@ def torch_gru_cell(n, d, theta):
     return cell
 
 
-def torch_mlp(n, width, nhid, theta):
+def torch_mlp(n, width, nhid, theta, act=torch.tanh):
     th = torch.tensor(np.asarray(theta, dtype=np.float64))
     mats = []
     o, nin = 0, n
@@ -42,7 +42,7 @@ def torch_mlp(n, width, nhid, theta):
     def f(y):
         a = y
         for W, b in mats:
-            a = torch.tanh(W @ a + b)
+            a = act(W @ a + b)
         return Wo @ a + bo
     return f
 
@@ -124,6 +124,50 @@ def test_mlp_f_and_jacobian_match_autograd(n, width, nhid):
     np.testing.assert_allclose(oracle.cell_f(cell, theta, y), f(torch.tensor(y)).numpy(), atol=1e-14)
     Jt = torch.autograd.functional.jacobian(f, torch.tensor(y)).numpy()
     np.testing.assert_allclose(oracle.cell_jac(cell, theta, y), Jt, atol=1e-13)
+
+
+@pytest.mark.parametrize("n,width,nhid", [(8, 64, 5), (8, 16, 1), (4, 12, 3), (2, 8, 4)])
+@pytest.mark.parametrize("act", [oracle.ACT_TANH, oracle.ACT_SOFTPLUS])
+def test_mlp_of_any_depth_and_activation_matches_autograd(n, width, nhid, act):
+    # the general field (App. B.2 uses six linear layers with softplus): f, Jacobian and the vector-Jacobian
+    # product of every parameter block against the library's own softplus / tanh and autograd
+    rng = np.random.default_rng(10 * n + width + nhid + act)
+    theta = rng.standard_normal(inputs.mlp_theta_count(n, width, nhid)) / np.sqrt(width)
+    cell = oracle.make_cell(oracle.CELL_MLP, n, 0, width, nhid, act)
+    fun = torch.tanh if act == oracle.ACT_TANH else torch.nn.functional.softplus
+    tht = torch.tensor(theta, requires_grad=True)
+
+    def f_of(th, y):
+        o, nin, a = 0, n, y
+        for _ in range(nhid):
+            W = th[o:o + width * nin].reshape(width, nin); o += width * nin
+            b = th[o:o + width]; o += width
+            a = fun(W @ a + b)
+            nin = width
+        Wo = th[o:o + n * nin].reshape(n, nin); o += n * nin
+        return Wo @ a + th[o:o + n]
+
+    y = rng.standard_normal(n) * 3.0        # softplus is exercised on both of its branches
+    yt = torch.tensor(y, requires_grad=True)
+    out = f_of(tht, yt)
+    np.testing.assert_allclose(oracle.cell_f(cell, theta, y), out.detach().numpy(), atol=1e-13)
+    Jt = torch.autograd.functional.jacobian(lambda yy: f_of(tht.detach(), yy), torch.tensor(y)).numpy()
+    np.testing.assert_allclose(oracle.cell_jac(cell, theta, y), Jt, atol=1e-12)
+    w = rng.standard_normal(n)
+    (out * torch.tensor(w)).sum().backward()
+    dth, dy = oracle.mlp_vjp(cell, theta, y, w)
+    np.testing.assert_allclose(dth, tht.grad.numpy(), atol=1e-12)
+    np.testing.assert_allclose(dy, yt.grad.numpy(), atol=1e-12)
+
+
+def test_softplus_limits():
+    # log(1 + e^a) must not overflow and must approach a (large a) and e^a (very negative a)
+    cell = oracle.make_cell(oracle.CELL_MLP, 1, 0, 1, 1, oracle.ACT_SOFTPLUS)
+    theta = np.array([1.0, 0.0, 1.0, 0.0])     # f(y) = softplus(y)
+    for a, want in [(800.0, 800.0), (-800.0, 0.0), (0.0, np.log(2.0)), (40.0, 40.0), (-40.0, np.exp(-40.0))]:
+        got = oracle.cell_f(cell, theta, np.array([a]))[0]
+        assert np.isfinite(got) and abs(got - want) <= 1e-15 * max(1.0, abs(want)) + 1e-30
+    assert abs(oracle.cell_jac(cell, theta, np.array([0.0]))[0, 0] - 0.5) < 1e-15
 
 
 def test_affine_cell():

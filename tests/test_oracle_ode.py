@@ -71,7 +71,7 @@ def test_linear_field_is_integrated_exactly_in_two_iterations():
             np.testing.assert_allclose(y[b, j], want, atol=1e-11)
 
 
-def mlp_numpy(n, width, nhid, theta):
+def mlp_numpy(n, width, nhid, theta, act=0):
     o, nin, mats = 0, n, []
     for _ in range(nhid):
         W = theta[o:o + width * nin].reshape(width, nin); o += width * nin
@@ -83,24 +83,26 @@ def mlp_numpy(n, width, nhid, theta):
     def f(y):
         a = y
         for W, b in mats:
-            a = np.tanh(W @ a + b)
+            a = np.tanh(W @ a + b) if act == 0 else np.logaddexp(0.0, W @ a + b)
         return Wo @ a + bo
     return f
 
 
-def small_ode(seed=3, n=3, width=6, nhid=2, B=2):
-    w = inputs.mlp_ode_workload("t", seed, B=B, T=2, n=n, width=width, nhid=nhid, t0=0.0, t1=1.5)
-    return w, oracle.make_cell(oracle.CELL_MLP, n, 0, width, nhid)
+def small_ode(seed=3, n=3, width=6, nhid=2, B=2, act=0):
+    w = inputs.mlp_ode_workload("t", seed, B=B, T=2, n=n, width=width, nhid=nhid, t0=0.0, t1=1.5, act=act)
+    return w, oracle.make_cell(oracle.CELL_MLP, n, 0, width, nhid, act)
 
 
-def test_converged_iterate_satisfies_the_discretised_equation():
+@pytest.mark.parametrize("nhid,act", [(2, 0), (5, 1), (1, 1), (3, 0)])
+def test_converged_iterate_satisfies_the_discretised_equation(nhid, act):
     # at the fixed point, y_{i+1} = Gbar_i y_i + zbar_i with G = -df/dy and z = f + G y taken at
     # the iterate itself; rebuilt here with SciPy's expm, a linear solve and a finite-difference Jacobian
-    w, cell = small_ode()
+    # (tanh and softplus fields of one to five hidden layers)
+    w, cell = small_ode(nhid=nhid, act=act)
     T = 40
     y, it, err, _ = oracle.ode_deer_eval(cell, w.theta, w.y0, T, w.t0, w.t1, tol=1e-12, max_iter=50)
     assert it < 50
-    f = mlp_numpy(w.n, w.mlp_width, w.mlp_hidden_layers, w.theta.astype(np.float64))
+    f = mlp_numpy(w.n, w.mlp_width, w.mlp_hidden_layers, w.theta.astype(np.float64), act)
     dt = (w.t1 - w.t0) / (T - 1)
     n = w.n
 
