@@ -33,9 +33,12 @@
  *       q = U_c h + b_hc                     c = tanh(W_c x + b_c + r * q)
  *       f(h, x) = (1 - z) * c + z * h
  *     theta (flat): W[3n,d] (rows r|z|c), U[3n,n] (rows r|z|c), b[3n] (r|z|c), b_hc[n].
- *   MLP vector field (autonomous):
- *       f(y) = W_3 tanh(W_2 tanh(W_1 y + b_1) + b_2) + b_3
- *     theta (flat): W_1[w,n], b_1[w], W_2[w,w], b_2[w], W_3[n,w], b_3[n].
+ *   MLP vector field (autonomous), L hidden layers of width w with activation s = tanh or softplus
+ *   (s(a) = log(1 + exp(a)); App. B.2 uses six linear layers with softplus on all but the last):
+ *       f(y) = W_out s(W_L s(... s(W_1 y + b_1) ...) + b_L) + b_out
+ *     theta (flat): W_1[w,n], b_1[w], then W_l[w,w], b_l[w] for l = 2..L, then W_out[n,w], b_out[n].
+ *   Two tanh layers of width 16, 32 or 64 (a multiple of n) have kernels of their own (fp32 with n = 8: on
+ *   the matrix cores); every other depth, width and the softplus activation run general kernels.
  */
 #ifndef DEER_H
 #define DEER_H
@@ -58,6 +61,7 @@ typedef enum {
 
 typedef enum { DEER_CELL_GRU = 0, DEER_CELL_MLP_ODE = 1 } deer_cell;
 typedef enum { DEER_F32 = 0, DEER_F64 = 1 } deer_dtype;
+typedef enum { DEER_ACT_TANH = 0, DEER_ACT_SOFTPLUS = 1 } deer_activation;
 
 typedef struct {
     int32_t cell;               /* deer_cell                                                             */
@@ -66,9 +70,11 @@ typedef struct {
     int32_t T;                  /* GRU: number of steps; MLP_ODE: number of grid points (>= 2)           */
     int32_t n;                  /* state size: 1, 2, 4, 8, 16 or 32                                      */
     int32_t d;                  /* GRU input size (1..16); ignored for MLP_ODE                           */
-    int32_t mlp_width;          /* MLP_ODE hidden width: 16, 32 or 64, and a multiple of n; ignored for GRU */
-    int32_t mlp_hidden_layers;  /* MLP_ODE: must be 2                                                    */
+    int32_t mlp_width;          /* MLP_ODE hidden width w: a multiple of 4, 4..64; ignored for GRU       */
+    int32_t mlp_hidden_layers;  /* MLP_ODE: hidden layers L, 1..5 (L + 1 linear layers)                  */
     double t0, t1;              /* MLP_ODE: uniform grid t_j = t0 + j (t1 - t0)/(T - 1)                  */
+    int32_t mlp_activation;     /* MLP_ODE: deer_activation of the hidden layers (0 = tanh)              */
+    int32_t reserved;           /* must be 0                                                             */
 } deer_config;
 
 typedef struct deer_ctx deer_ctx; /* opaque, host memory owned by the library */

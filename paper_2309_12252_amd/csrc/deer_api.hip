@@ -62,7 +62,15 @@ size_t theta_count(const deer_config* c) {
     const size_t n = (size_t)c->n;
     if (c->cell == DEER_CELL_GRU) return 3 * n * (size_t)c->d + 3 * n * n + 4 * n;
     const size_t w = (size_t)c->mlp_width;
-    return (w * n + w) + (w * w + w) + (n * w + n);
+    const size_t L = c->mlp_hidden_layers >= 1 ? (size_t)c->mlp_hidden_layers : 1;
+    return (w * n + w) + (L - 1) * (w * w + w) + (n * w + n);
+}
+
+// the two-hidden-layer tanh field has kernels of its own (on the matrix cores for fp32, n = 8); every other depth
+// and the softplus activation run the general kernels
+bool mlp_fast_path(const deer_config* c) {
+    const int w = c->mlp_width;
+    return c->mlp_hidden_layers == 2 && c->mlp_activation == DEER_ACT_TANH && (w == 16 || w == 32 || w == 64) && w % c->n == 0;
 }
 
 bool validate(const deer_config* c, std::string& why) {
@@ -84,10 +92,12 @@ bool supported(const deer_config* c, std::string& why) {
         if (c->d < 1 || c->d > 16) { why = "GRU input size must be 1..16"; return false; }
     } else {
         if (!(n == 2 || n == 4 || n == 8)) { why = "MLP_ODE state size must be 2, 4 or 8"; return false; }
-        if (c->mlp_hidden_layers != 2) { why = "MLP_ODE needs exactly 2 hidden layers"; return false; }
+        if (c->mlp_activation != DEER_ACT_TANH && c->mlp_activation != DEER_ACT_SOFTPLUS) { why = "unknown MLP activation"; return false; }
+        if (c->mlp_hidden_layers < 1 || c->mlp_hidden_layers > 5) { why = "MLP_ODE needs 1 to 5 hidden layers"; return false; }
         const int w = c->mlp_width;
-        if (!(w == 16 || w == 32 || w == 64) || w % n != 0) {
-            why = "MLP_ODE hidden width must be 16, 32 or 64 and a multiple of n";
+        if (w < 4 || w > 64 || (w & 3) != 0) { why = "MLP_ODE hidden width must be a multiple of 4 between 4 and 64"; return false; }
+        if (!mlp_fast_path(c) && !mlp_general_supported(n, w, c->mlp_hidden_layers, c->mlp_activation)) {
+            why = "MLP_ODE: no kernel for this width, depth and activation";
             return false;
         }
         if (c->T < 2) { why = "MLP_ODE needs at least 2 grid points"; return false; }
@@ -196,7 +206,8 @@ Plan make_plan(const deer_config* c) {
         if (p.fused_tiles < 1) p.fused_tiles = 1;
     }
     p.vjp_blocks = c->cell == DEER_CELL_GRU ? gru_vjp_blocks(c->n, (long long)B * T)
-                                            : mlp_vjp_blocks(c->dtype, c->n, c->mlp_width, (long long)B * T);
+                   : mlp_fast_path(c)       ? mlp_vjp_blocks(c->dtype, c->n, c->mlp_width, (long long)B * T)
+                                            : mlp_general_vjp_blocks(c->dtype, c->n, c->mlp_width, c->mlp_hidden_layers, (long long)B * T);
 
     p.grad_fused = p.fused && env_int("DEER_GRAD_FUSED", 1) != 0 &&
                    (p.mfma || scan_gru_dual_supported(c->dtype, c->n, c->d, p.fused_L, p.fused_W));
@@ -631,9 +642,10 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
             } else {
                 char* Gbar = c->ws + c->plan.off_Gbar;
                 char* zbar = c->ws + c->plan.off_zbar;
-                MlpParams mp{d_theta, src, J, rhs, g.B, g.T, g.n, g.mlp_width, gate, 0};
+                MlpParams mp{d_theta, src, J, rhs, g.B, g.T, g.n, g.mlp_width, gate, 0, g.mlp_hidden_layers, g.mlp_activation};
                 prof_begin(c, KIND_FUNCEVAL, k);
-                HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
+                HIPCHK(c, mlp_fast_path(&g) ? launch_mlp_funceval(g.dtype, mp, c->stream)
+                                            : launch_mlp_general_funceval(g.dtype, mp, c->stream));
                 prof_end(c);
                 OdeDiscParams dp{J, rhs, src, Gbar, zbar, g.B, g.T, g.n, (g.t1 - g.t0) / (double)(g.T - 1), gate, 0, 0};
                 prof_begin(c, KIND_DISC, k);
@@ -704,9 +716,9 @@ static deer_status grad_ode(deer_ctx* c, const void* d_theta, const void* d_y, c
 
     deer_status st = zero_ctl(c);
     if (st != DEER_OK) return st;
-    MlpParams mp{d_theta, d_y, G, z, g.B, g.T, g.n, g.mlp_width, open, 1};   // the backward pass needs G only
+    MlpParams mp{d_theta, d_y, G, z, g.B, g.T, g.n, g.mlp_width, open, 1, g.mlp_hidden_layers, g.mlp_activation};   // the backward pass needs G only
     prof_begin(c, KIND_FUNCEVAL);
-    HIPCHK(c, launch_mlp_funceval(g.dtype, mp, c->stream));
+    HIPCHK(c, mlp_fast_path(&g) ? launch_mlp_funceval(g.dtype, mp, c->stream) : launch_mlp_general_funceval(g.dtype, mp, c->stream));
     prof_end(c);
     // D_i = Gbar_i - I, the matrices alone
     OdeDiscParams dp{G, z, d_y, Dm, lam, g.B, g.T, g.n, dt, open, 1, 1};
@@ -732,9 +744,12 @@ static deer_status grad_ode(deer_ctx* c, const void* d_theta, const void* d_y, c
     prof_begin(c, KIND_DISC);
     HIPCHK(c, launch_ode_dual(g.dtype, up, c->stream));
     prof_end(c);
-    MlpVjpParams vp{d_theta, d_y, u, c->ws + c->plan.off_partial, d_dLdtheta, g.B, g.T, g.n, g.mlp_width, c->plan.vjp_blocks};
+    MlpVjpParams vp{d_theta, d_y, u, c->ws + c->plan.off_partial, d_dLdtheta, g.B, g.T, g.n, g.mlp_width, c->plan.vjp_blocks,
+                    g.mlp_hidden_layers, g.mlp_activation};
     prof_begin(c, KIND_VJP);
-    if (mlp_vjp_mfma_supported(g.dtype, g.n, g.mlp_width) && env_int("DEER_VJP_MFMA", 1) != 0) {
+    if (!mlp_fast_path(&g)) {
+        HIPCHK(c, launch_mlp_general_vjp(g.dtype, vp, c->stream));
+    } else if (mlp_vjp_mfma_supported(g.dtype, g.n, g.mlp_width) && env_int("DEER_VJP_MFMA", 1) != 0) {
         if (vp.blocks > 512) vp.blocks = 512;   // two wavefronts per SIMD by registers: 512 blocks of four fill the chip once
         HIPCHK(c, launch_mlp_vjp_mfma(vp, c->stream));
         HIPCHK(c, launch_partial_reduce(g.dtype, vp.partial, d_dLdtheta, (long long)theta_count(&g), vp.blocks * 4, c->stream));

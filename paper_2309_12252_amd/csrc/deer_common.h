@@ -244,6 +244,7 @@ struct MlpParams {
     int B, T, n, width;
     Gate gate;
     int jac_only;                         // != 0: only G is wanted (the backward pass); kernels may write zeros to z
+    int nhid, act;                        // hidden layers and activation (0 tanh, 1 softplus): read by the general kernels only
 };
 
 struct OdeDiscParams {
@@ -274,6 +275,7 @@ struct MlpVjpParams {
     void* dtheta;                         // [theta_count]
     int B, T, n, width;
     int blocks;
+    int nhid, act;                        // as in MlpParams
 };
 
 hipError_t launch_scan_valu(int dtype, int n, const ScanParams& p, hipStream_t s);
@@ -315,6 +317,12 @@ hipError_t launch_mlp_vjp(int dtype, const MlpVjpParams& p, hipStream_t s);
 // their addition (launch_partial_reduce) to the caller
 bool mlp_vjp_mfma_supported(int dtype, int n, int width);
 hipError_t launch_mlp_vjp_mfma(const MlpVjpParams& p, hipStream_t s);
+// MLP field of any depth (1..5 hidden layers) and activation (tanh, softplus): field + Jacobian, and the
+// vector-Jacobian product with its reduction (partial rows = p.blocks, from mlp_general_vjp_blocks())
+bool mlp_general_supported(int n, int width, int nhid, int act);
+int mlp_general_vjp_blocks(int dtype, int n, int width, int nhid, long long points);
+hipError_t launch_mlp_general_funceval(int dtype, const MlpParams& p, hipStream_t s);
+hipError_t launch_mlp_general_vjp(int dtype, const MlpVjpParams& p, hipStream_t s);
 // fixed-order sum of partial rows [rows][P] into out[P]
 hipError_t launch_partial_reduce(int dtype, const void* partial, void* out, long long P, int rows, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);

@@ -1,0 +1,485 @@
+// MLP vector field of any depth and either activation (Sec. 3.3; the two-body network of App. B.2 has six
+// linear layers with softplus on all but the last): the field kernel and the vector-Jacobian product for
+// every shape the two-hidden-layer tanh kernels do not take.
+//
+//   f(y) = W_out s(W_L s(... s(W_1 y + b_1) ...) + b_L) + b_out,   s = tanh or softplus,
+//   theta = W_1[w,n], b_1[w], (W_l[w,w], b_l[w]) for l = 2..L, W_out[n,w], b_out[n].
+//
+// mlp_gen_funceval_kernel: f and J = df/dy = W_out D_L W_L ... D_1 W_1 (D_l = diag s'(pre-activation)) by
+// carrying S_l = d(a_l)/dy, a w x n matrix, through the layers next to the activations (forward mode: one
+// pass, nothing of the earlier layers is kept); output G = -J and z = f + G y (Sec. 3.1 eq. 5, Sec. 3.3 eq. 8).
+// mlp_gen_vjp_kernel: the reverse sweep at every grid point and the sums over the grid points of the outer
+// products that make dL/dtheta (Sec. 3.1.1 eq. 7, outer bracket), as in the two-layer kernel: phase A leaves
+// every point's activations and pre-activation cotangents as a row in LDS, phase B sums 4 x 4 blocks of
+// (cotangent) x (layer input) over the points in registers; one partial row per block, added by the
+// fixed-order reduction.
+//
+// Both kernels take the shape at run time.  A block of 256 threads handles `pts` grid points at a time with
+// 256 / pts threads per point, which share the hidden units of a layer; a point's state is a row in LDS
+// (row length = 4 mod 32 words, so that the 16-byte reads of consecutive points fall on different banks).
+// The weights are read from memory as they are (rows by 16-byte loads, the same address in all lanes of a
+// point group); the reverse sweep reads them down a column.
+#include "deer_common.h"
+
+namespace deer {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__host__ __device__ inline int ceil4(int v) { return (v + 3) & ~3; }
+
+template <typename S> struct Act;
+template <> struct Act<float> {
+    static __device__ __forceinline__ float tanh_(float a) { return feed_tanh(a); }
+    static __device__ __forceinline__ float softplus(float a) { return fmaxf(a, 0.0f) + log1pf(expf(-fabsf(a))); }
+    static __device__ __forceinline__ float sigmoid(float a) { return 1.0f / (1.0f + expf(-a)); }
+    static __device__ __forceinline__ float one_minus_exp_neg(float a) { return -expm1f(-a); }
+};
+template <> struct Act<double> {
+    static __device__ __forceinline__ double tanh_(double a) { return tanh(a); }
+    static __device__ __forceinline__ double softplus(double a) { return fmax(a, 0.0) + log1p(exp(-fabs(a))); }
+    static __device__ __forceinline__ double sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
+    static __device__ __forceinline__ double one_minus_exp_neg(double a) { return -expm1(-a); }
+};
+
+// activation and its derivative at pre-activation `pre`
+template <typename S>
+__device__ __forceinline__ void act_both(int kind, S pre, S& a, S& da) {
+    if (kind == 0) {
+        a = Act<S>::tanh_(pre);
+        da = S(1) - a * a;
+    } else {
+        a = Act<S>::softplus(pre);
+        da = Act<S>::sigmoid(pre);
+    }
+}
+// derivative from the activation's value: tanh' = 1 - a^2, softplus' = sigmoid(pre) = 1 - exp(-a)
+template <typename S>
+__device__ __forceinline__ S dact_from_value(int kind, S a) {
+    return kind == 0 ? S(1) - a * a : Act<S>::one_minus_exp_neg(a);
+}
+
+// offset of layer l (0-based hidden layers 0..L-1, L = the output layer) inside theta
+__host__ __device__ inline long long layer_offset(int n, int w, int l) {
+    if (l == 0) return 0;
+    return (long long)w * n + w + (long long)(l - 1) * ((long long)w * w + w);
+}
+__host__ __device__ inline long long gen_theta_len(int n, int w, int L) { return layer_offset(n, w, L) + (long long)n * w + n; }
+
+// ---------------------------------------------------------------------------------------------------------
+// field + Jacobian
+// ---------------------------------------------------------------------------------------------------------
+struct FeRow {
+    int a[2], S[2], y, len, np;
+    __host__ __device__ FeRow(int n, int w) {
+        np = ceil4(n);
+        a[0] = 0; a[1] = w; S[0] = 2 * w; S[1] = 2 * w + w * np; y = 2 * w + 2 * w * np;
+        len = y + np;
+        while ((len & 31) != 4) len += 4;
+    }
+};
+
+template <typename S>
+__global__ __launch_bounds__(kThreads) void mlp_gen_funceval_kernel(MlpParams p, int pts) {
+    if (gate_closed<S>(p.gate)) return;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    S* rows = reinterpret_cast<S*>(smem_raw);
+    const int n = p.n, w = p.width, L = p.nhid, kind = p.act;
+    const FeRow rl(n, w);
+    const int np = rl.np;
+    const int tid = threadIdx.x;
+    const int split = kThreads / pts;
+    const int pt = tid % pts, part = tid / pts;
+    const S* __restrict__ th = reinterpret_cast<const S*>(p.theta);
+    const S* __restrict__ yg = reinterpret_cast<const S*>(p.y);
+    S* __restrict__ Gg = reinterpret_cast<S*>(p.G);
+    S* __restrict__ zg = reinterpret_cast<S*>(p.z);
+    const long long total = (long long)p.B * p.T;
+    const long long chunks = (total + pts - 1) / pts;
+    S* R = rows + (size_t)pt * rl.len;
+
+    for (long long ch = blockIdx.x; ch < chunks; ch += gridDim.x) {
+        const long long gp = ch * pts + pt;
+        const bool valid = gp < total;
+        if (part == 0) {
+            for (int k = 0; k < np; ++k) R[rl.y + k] = (valid && k < n) ? yg[gp * n + k] : S(0);
+        }
+        __syncthreads();
+        // layer 1: a = s(W_1 y + b_1), S = D_1 W_1
+        {
+            const S* __restrict__ W1 = th;
+            const S* __restrict__ b1 = th + (long long)w * n;
+            for (int h = part; h < w; h += split) {
+                S pre = b1[h];
+                for (int k = 0; k < n; ++k) pre += W1[h * n + k] * R[rl.y + k];
+                S a, da;
+                act_both<S>(kind, pre, a, da);
+                R[rl.a[0] + h] = a;
+                for (int k = 0; k < np; ++k) R[rl.S[0] + h * np + k] = (k < n) ? da * W1[h * n + k] : S(0);
+            }
+        }
+        __syncthreads();
+        // layers 2..L: a' = s(W a + b), S' = D (W S)
+        int cur = 0;
+        for (int l = 1; l < L; ++l) {
+            const S* __restrict__ Wl = th + layer_offset(n, w, l);
+            const S* __restrict__ bl = Wl + (long long)w * w;
+            const S* ain = R + rl.a[cur];
+            const S* Sin = R + rl.S[cur];
+            for (int h = part; h < w; h += split) {
+                S pre = bl[h];
+                S t[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) t[j] = S(0);
+                for (int k = 0; k < w; k += 4) {
+                    S wv[4], av[4];
+                    vload<S, 4>(wv, Wl + (long long)h * w + k);
+                    vload<S, 4>(av, ain + k);
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) {
+                        pre += wv[kk] * av[kk];
+                        S sv[8];
+                        vload<S, 4>(sv, Sin + (k + kk) * np);
+                        if (np > 4) vload<S, 4>(sv + 4, Sin + (k + kk) * np + 4);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) t[j] += wv[kk] * sv[j];
+                        if (np > 4) {
+#pragma unroll
+                            for (int j = 4; j < 8; ++j) t[j] += wv[kk] * sv[j];
+                        }
+                    }
+                }
+                S a, da;
+                act_both<S>(kind, pre, a, da);
+                R[rl.a[cur ^ 1] + h] = a;
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (j < np) R[rl.S[cur ^ 1] + h * np + j] = da * t[j];
+            }
+            cur ^= 1;
+            __syncthreads();
+        }
+        // output layer: f = W_out a + b_out, J = W_out S; G = -J, z = f - J y
+        {
+            const S* __restrict__ Wo = th + layer_offset(n, w, L);
+            const S* __restrict__ bo = Wo + (long long)n * w;
+            const S* ain = R + rl.a[cur];
+            const S* Sin = R + rl.S[cur];
+            for (int i = part; i < n; i += split) {
+                S f = bo[i];
+                S t[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) t[j] = S(0);
+                for (int k = 0; k < w; k += 4) {
+                    S wv[4], av[4];
+                    vload<S, 4>(wv, Wo + (long long)i * w + k);
+                    vload<S, 4>(av, ain + k);
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) {
+                        f += wv[kk] * av[kk];
+                        S sv[8];
+                        vload<S, 4>(sv, Sin + (k + kk) * np);
+                        if (np > 4) vload<S, 4>(sv + 4, Sin + (k + kk) * np + 4);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) t[j] += wv[kk] * sv[j];
+                        if (np > 4) {
+#pragma unroll
+                            for (int j = 4; j < 8; ++j) t[j] += wv[kk] * sv[j];
+                        }
+                    }
+                }
+                if (valid) {
+                    S jy = S(0);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (j < n) {
+                            jy += t[j] * R[rl.y + j];
+                            Gg[(gp * n + i) * n + j] = -t[j];
+                        }
+                    zg[gp * n + i] = p.jac_only ? S(0) : f - jy;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <typename S>
+int fe_points(int n, int w, size_t* bytes) {
+    const FeRow rl(n, w);
+    int pts = 64;
+    while (pts > 4 && (size_t)pts * rl.len * sizeof(S) > (size_t)48 * 1024) pts >>= 1;
+    *bytes = (size_t)pts * rl.len * sizeof(S);
+    return pts;
+}
+
+template <typename S>
+hipError_t launch_fe(const MlpParams& p, hipStream_t s) {
+    size_t bytes = 0;
+    const int pts = fe_points<S>(p.n, p.width, &bytes);
+    if (bytes > (size_t)150 * 1024) return hipErrorInvalidValue;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_gen_funceval_kernel<S>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+    const long long total = (long long)p.B * p.T;
+    long long blocks = (total + pts - 1) / pts;
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((mlp_gen_funceval_kernel<S>), dim3((unsigned)blocks), dim3(kThreads), bytes, s, p, pts);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// vector-Jacobian product with the parameter-gradient sums
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kMaxTasks = 5;   // 4 x 4 blocks per thread (width 64, five hidden layers, n = 8: 1,170 tasks over 256 threads)
+
+// a point's row: a_1..a_L | d_1..d_L (cotangents of the pre-activations) | y | w | 1
+struct VjRow {
+    int a, d, y, w, one, len;
+    __host__ __device__ VjRow(int n, int width, int L) {
+        a = 0; d = L * width; y = 2 * L * width; w = y + ceil4(n); one = w + ceil4(n);
+        len = one + 4;
+        while ((len & 31) != 4) len += 4;
+    }
+};
+
+struct Task {
+    int uo, vo, out, rs, nr, nc;
+};
+
+__host__ __device__ inline int gen_task_count(int n, int w, int L) {
+    const int wb = w / 4, nb = ceil4(n) / 4;
+    return wb * nb + wb + (L - 1) * (wb * wb + wb) + nb * wb + nb;
+}
+
+// task number q: four entries of one field of the row (rows of the block) times four entries of another
+__device__ __forceinline__ bool make_task(int q, int n, int w, int L, const VjRow& rl, Task& t) {
+    const int wb = w / 4, nb = ceil4(n) / 4;
+    int r = q;
+    if (r < wb * nb) {   // dW_1[h][k] = sum d_1[h] y[k]
+        const int hb = r / nb, kb = r % nb;
+        t = Task{rl.d + 4 * hb, rl.y + 4 * kb, 4 * hb * n + 4 * kb, n, 4, (n - 4 * kb) < 4 ? (n - 4 * kb) : 4};
+        return true;
+    }
+    r -= wb * nb;
+    if (r < wb) {        // db_1
+        t = Task{rl.d + 4 * r, rl.one, w * n + 4 * r, 1, 4, 1};
+        return true;
+    }
+    r -= wb;
+    for (int l = 1; l < L; ++l) {
+        const int base = (int)layer_offset(n, w, l);
+        if (r < wb * wb) {   // dW_{l+1}[h][k] = sum d_{l+1}[h] a_l[k]
+            const int hb = r / wb, kb = r % wb;
+            t = Task{rl.d + l * w + 4 * hb, rl.a + (l - 1) * w + 4 * kb, base + 4 * hb * w + 4 * kb, w, 4, 4};
+            return true;
+        }
+        r -= wb * wb;
+        if (r < wb) {
+            t = Task{rl.d + l * w + 4 * r, rl.one, base + w * w + 4 * r, 1, 4, 1};
+            return true;
+        }
+        r -= wb;
+    }
+    const int base = (int)layer_offset(n, w, L);
+    if (r < nb * wb) {   // dW_out[i][h] = sum w[i] a_L[h]
+        const int rb = r / wb, hb = r % wb;
+        t = Task{rl.w + 4 * rb, rl.a + (L - 1) * w + 4 * hb, base + 4 * rb * w + 4 * hb, w, (n - 4 * rb) < 4 ? (n - 4 * rb) : 4, 4};
+        return true;
+    }
+    r -= nb * wb;
+    if (r < nb) {        // db_out
+        t = Task{rl.w + 4 * r, rl.one, base + n * w + 4 * r, 1, (n - 4 * r) < 4 ? (n - 4 * r) : 4, 1};
+        return true;
+    }
+    return false;
+}
+
+template <typename S>
+__global__ __launch_bounds__(kThreads) void mlp_gen_vjp_kernel(MlpVjpParams p, int pts) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    S* rows = reinterpret_cast<S*>(smem_raw);
+    const int n = p.n, w = p.width, L = p.nhid, kind = p.act;
+    const VjRow rl(n, w, L);
+    const int tid = threadIdx.x;
+    const S* __restrict__ th = reinterpret_cast<const S*>(p.theta);
+    const int split = kThreads / pts;
+    const int pt = tid % pts, part = tid / pts;
+
+    S acc[kMaxTasks][16];
+    Task task[kMaxTasks];
+    bool has[kMaxTasks];
+#pragma unroll
+    for (int k = 0; k < kMaxTasks; ++k) {
+        has[k] = make_task(tid + kThreads * k, n, w, L, rl, task[k]);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[k][e] = S(0);
+    }
+
+    const long long total = (long long)p.B * p.T;
+    const long long chunks = (total + pts - 1) / pts;
+    const S* __restrict__ yg = reinterpret_cast<const S*>(p.y);
+    const S* __restrict__ ug = reinterpret_cast<const S*>(p.u);
+    S* R = rows + (size_t)pt * rl.len;
+
+    for (long long ch = blockIdx.x; ch < chunks; ch += gridDim.x) {
+        // ---- phase A: forward and reverse sweep at every point of the chunk ----
+        const long long gp = ch * pts + pt;
+        const bool valid = gp < total;
+        if (part == 0) {
+            const long long b = valid ? gp / p.T : 0, j = valid ? gp % p.T : 0;
+            for (int k = 0; k < ceil4(n); ++k) {
+                S yv = S(0), wv = S(0);
+                if (valid && k < n) {
+                    yv = yg[gp * n + k];
+                    const S ua = (j + 1 < p.T) ? ug[(b * (p.T - 1) + j) * n + k] : S(0);
+                    const S ub = (j > 0) ? ug[(b * (p.T - 1) + j - 1) * n + k] : S(0);
+                    wv = S(0.5) * (ua + ub);
+                }
+                R[rl.y + k] = yv;
+                R[rl.w + k] = wv;
+            }
+            for (int k = 0; k < 4; ++k) R[rl.one + k] = (valid && k == 0) ? S(1) : S(0);
+        }
+        __syncthreads();
+        {
+            const S* __restrict__ W1 = th;
+            const S* __restrict__ b1 = th + (long long)w * n;
+            for (int h = part; h < w; h += split) {
+                S pre = b1[h];
+                for (int k = 0; k < n; ++k) pre += W1[h * n + k] * R[rl.y + k];
+                S a, da;
+                act_both<S>(kind, pre, a, da);
+                R[rl.a + h] = a;
+            }
+        }
+        __syncthreads();
+        for (int l = 1; l < L; ++l) {
+            const S* __restrict__ Wl = th + layer_offset(n, w, l);
+            const S* __restrict__ bl = Wl + (long long)w * w;
+            const S* ain = R + rl.a + (l - 1) * w;
+            for (int h = part; h < w; h += split) {
+                S pre = bl[h];
+                for (int k = 0; k < w; k += 4) {
+                    S wv[4], av[4];
+                    vload<S, 4>(wv, Wl + (long long)h * w + k);
+                    vload<S, 4>(av, ain + k);
+                    pre += wv[0] * av[0] + wv[1] * av[1] + wv[2] * av[2] + wv[3] * av[3];
+                }
+                S a, da;
+                act_both<S>(kind, pre, a, da);
+                R[rl.a + l * w + h] = a;
+            }
+            __syncthreads();
+        }
+        // d_L = (W_out^T w) s'(.), then d_l = (W_{l+1}^T d_{l+1}) s'(.) down to l = 1
+        {
+            const S* __restrict__ Wo = th + layer_offset(n, w, L);
+            for (int h = part; h < w; h += split) {
+                S s = S(0);
+                for (int r = 0; r < n; ++r) s += Wo[(long long)r * w + h] * R[rl.w + r];
+                R[rl.d + (L - 1) * w + h] = s * dact_from_value<S>(kind, R[rl.a + (L - 1) * w + h]);
+            }
+        }
+        __syncthreads();
+        for (int l = L - 1; l >= 1; --l) {
+            const S* __restrict__ Wn = th + layer_offset(n, w, l);   // weights of hidden layer l + 1 (0-based l)
+            const S* dn = R + rl.d + l * w;
+            for (int h = part; h < w; h += split) {
+                S s = S(0);
+                for (int m = 0; m < w; m += 4) {
+                    S dv[4];
+                    vload<S, 4>(dv, dn + m);
+                    s += Wn[(long long)m * w + h] * dv[0] + Wn[(long long)(m + 1) * w + h] * dv[1] +
+                         Wn[(long long)(m + 2) * w + h] * dv[2] + Wn[(long long)(m + 3) * w + h] * dv[3];
+                }
+                R[rl.d + (l - 1) * w + h] = s * dact_from_value<S>(kind, R[rl.a + (l - 1) * w + h]);
+            }
+            __syncthreads();
+        }
+
+        // ---- phase B: outer products summed over the points of the chunk ----
+#pragma unroll
+        for (int k = 0; k < kMaxTasks; ++k) {
+            if (has[k]) {
+                for (int q = 0; q < pts; ++q) {
+                    const S* Rq = rows + (size_t)q * rl.len;
+                    S uv[4], vv[4];
+                    vload<S, 4>(uv, Rq + task[k].uo);
+                    vload<S, 4>(vv, Rq + task[k].vo);
+#pragma unroll
+                    for (int a = 0; a < 4; ++a)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) acc[k][a * 4 + c] += uv[a] * vv[c];
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    S* __restrict__ out = reinterpret_cast<S*>(p.partial) + (size_t)blockIdx.x * (size_t)gen_theta_len(n, w, L);
+#pragma unroll
+    for (int k = 0; k < kMaxTasks; ++k) {
+        if (has[k]) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (a < task[k].nr && c < task[k].nc) out[task[k].out + a * task[k].rs + c] = acc[k][a * 4 + c];
+        }
+    }
+}
+
+template <typename S>
+int vj_points(int n, int w, int L, size_t* bytes) {
+    const VjRow rl(n, w, L);
+    int pts = 64;
+    while (pts > 8 && (size_t)pts * rl.len * sizeof(S) > (size_t)64 * 1024) pts >>= 1;
+    *bytes = (size_t)pts * rl.len * sizeof(S);
+    return pts;
+}
+
+template <typename S>
+hipError_t launch_vj(const MlpVjpParams& p, hipStream_t s) {
+    size_t bytes = 0;
+    const int pts = vj_points<S>(p.n, p.width, p.nhid, &bytes);
+    if (bytes > (size_t)150 * 1024) return hipErrorInvalidValue;
+    if (gen_task_count(p.n, p.width, p.nhid) > kThreads * kMaxTasks) return hipErrorInvalidValue;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_gen_vjp_kernel<S>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((mlp_gen_vjp_kernel<S>), dim3((unsigned)p.blocks), dim3(kThreads), bytes, s, p, pts);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_partial_reduce(sizeof(S) == 4 ? 0 : 1, p.partial, p.dtheta, gen_theta_len(p.n, p.width, p.nhid), p.blocks, s);
+}
+
+}  // namespace
+
+bool mlp_general_supported(int n, int width, int nhid, int act) {
+    return n >= 1 && n <= 8 && width >= 4 && width <= 64 && (width & 3) == 0 && nhid >= 1 && nhid <= 5 &&
+           (act == 0 || act == 1) && gen_task_count(n, width, nhid) <= kThreads * kMaxTasks;
+}
+
+int mlp_general_vjp_blocks(int dtype, int n, int width, int nhid, long long points) {
+    size_t bytes = 0;
+    const int pts = dtype == 0 ? vj_points<float>(n, width, nhid, &bytes) : vj_points<double>(n, width, nhid, &bytes);
+    long long chunks = (points + pts - 1) / pts;
+    if (chunks > 512) chunks = 512;
+    if (chunks < 1) chunks = 1;
+    return (int)chunks;
+}
+
+hipError_t launch_mlp_general_funceval(int dtype, const MlpParams& p, hipStream_t s) {
+    if (!mlp_general_supported(p.n, p.width, p.nhid, p.act)) return hipErrorInvalidValue;
+    return dtype == 0 ? launch_fe<float>(p, s) : launch_fe<double>(p, s);
+}
+
+hipError_t launch_mlp_general_vjp(int dtype, const MlpVjpParams& p, hipStream_t s) {
+    if (!mlp_general_supported(p.n, p.width, p.nhid, p.act) || p.T < 2) return hipErrorInvalidValue;
+    return dtype == 0 ? launch_vj<float>(p, s) : launch_vj<double>(p, s);
+}
+
+}  // namespace deer

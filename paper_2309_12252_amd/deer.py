@@ -24,7 +24,8 @@ EXPORTS = ["deer_theta_count", "deer_workspace_bytes", "deer_create", "deer_eval
 class DeerConfig(ctypes.Structure):
     _fields_ = [("cell", ctypes.c_int32), ("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("T", ctypes.c_int32),
                 ("n", ctypes.c_int32), ("d", ctypes.c_int32), ("mlp_width", ctypes.c_int32),
-                ("mlp_hidden_layers", ctypes.c_int32), ("t0", ctypes.c_double), ("t1", ctypes.c_double)]
+                ("mlp_hidden_layers", ctypes.c_int32), ("t0", ctypes.c_double), ("t1", ctypes.c_double),
+                ("mlp_activation", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class DeerProfile(ctypes.Structure):
@@ -87,9 +88,12 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
 
 
-def make_config(cell, dtype, B, T, n, d=0, mlp_width=0, mlp_hidden_layers=0, t0=0.0, t1=0.0):
+DEER_ACT_TANH, DEER_ACT_SOFTPLUS = 0, 1
+
+
+def make_config(cell, dtype, B, T, n, d=0, mlp_width=0, mlp_hidden_layers=0, t0=0.0, t1=0.0, mlp_activation=0):
     return DeerConfig(int(cell), int(dtype), int(B), int(T), int(n), int(d), int(mlp_width),
-                      int(mlp_hidden_layers), float(t0), float(t1))
+                      int(mlp_hidden_layers), float(t0), float(t1), int(mlp_activation), 0)
 
 
 def theta_count(cfg):
@@ -219,5 +223,5 @@ def linrec_solve_static(A, b, y0=None, reverse=False, out=None, status=None, str
 def context_for(workload, dtype=DEER_F32, device="cuda:0"):
     """Context for an ``inputs.Workload``."""
     cfg = make_config(workload.cell, dtype, workload.B, workload.T, workload.n, workload.d, workload.mlp_width,
-                      workload.mlp_hidden_layers, workload.t0, workload.t1)
+                      workload.mlp_hidden_layers, workload.t0, workload.t1, workload.mlp_activation)
     return DeerContext(cfg, device=device)

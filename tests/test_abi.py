@@ -40,8 +40,13 @@ def test_theta_count_and_validation_on_host():
     assert e.value.status == deer.DEER_ERR_INVALID_ARG
     with pytest.raises(deer.DeerError) as e:
         deer.workspace_bytes(deer.make_config(deer.DEER_CELL_MLP_ODE, deer.DEER_F32, 1, 10, 8, mlp_width=32,
-                                              mlp_hidden_layers=3, t0=0.0, t1=1.0))
+                                              mlp_hidden_layers=6, t0=0.0, t1=1.0))
     assert e.value.status == deer.DEER_ERR_UNSUPPORTED
+    # the two-body network's shape (App. B.2): five hidden layers of width 64, softplus
+    hnn = deer.make_config(deer.DEER_CELL_MLP_ODE, deer.DEER_F32, 4, 10000, 8, mlp_width=64, mlp_hidden_layers=5,
+                           t0=0.0, t1=10.0, mlp_activation=deer.DEER_ACT_SOFTPLUS)
+    assert deer.theta_count(hnn) == 64 * 8 + 64 + 4 * (64 * 64 + 64) + 8 * 64 + 8
+    assert deer.workspace_bytes(hnn) > 0
 
 
 def test_workspace_follows_the_plan(monkeypatch):

@@ -42,6 +42,33 @@ def test_config5_full_size():
     check(inputs.config(5), deer.DEER_F32)
 
 
+GENERAL = [(8, 64, 5, inputs.ACT_SOFTPLUS), (8, 32, 3, inputs.ACT_TANH), (4, 20, 1, inputs.ACT_SOFTPLUS),
+           (2, 8, 4, inputs.ACT_SOFTPLUS), (8, 24, 2, inputs.ACT_TANH), (8, 32, 2, inputs.ACT_SOFTPLUS),
+           (4, 64, 5, inputs.ACT_TANH)]
+
+
+@pytest.mark.parametrize("n,width,nhid,act", GENERAL)
+@pytest.mark.parametrize("dtype", [deer.DEER_F32, deer.DEER_F64])
+def test_fields_of_other_depths_and_activations(n, width, nhid, act, dtype):
+    # one to five hidden layers, tanh or softplus, widths that are not 16/32/64: the general field kernel
+    tol = 1e-4 if dtype == deer.DEER_F32 else 1e-7
+    for k, (B, T, t1) in enumerate([(1, 2, 0.1), (2, 50, 1.0), (3, 1300, 2.0), (2, 4000, 3.0)]):
+        w = inputs.mlp_ode_workload("gen_n%d_w%d_L%d_T%d" % (n, width, nhid, T), 900 + 7 * n + width + nhid + k, B=B, T=T,
+                                    n=n, width=width, nhid=nhid, t0=0.0, t1=t1, tol=tol, act=act)
+        check(w, dtype)
+
+
+def two_body_shaped(B, T):
+    # the shape of the paper's two-body network (Sec. 4.2, App. B.2): state 8, six linear layers (five hidden
+    # ones of width 64), softplus, 10,000 grid points on [0, 10]; random weights stand in for the trained ones
+    return inputs.mlp_ode_workload("two_body_shape", 4242, B=B, T=T, n=8, width=64, nhid=5, t0=0.0, t1=10.0, tol=1e-4,
+                                   act=inputs.ACT_SOFTPLUS)
+
+
+def test_two_body_network_shape_forward():
+    check(two_body_shaped(4, 10000), deer.DEER_F32)
+
+
 # ---- backward derivative (Sec. 3.1.1 eq. 7 on the discretised operator) ----
 
 def check_grad(w, dtype, seed=0, bar_theta=None):
@@ -82,6 +109,19 @@ def test_grad_vector_alu_vjp_at_the_matrix_core_sizes(width, monkeypatch):
         w = inputs.mlp_ode_workload("odeg_n8_T%d" % T, 400 + width + k, B=B, T=T, n=8, width=width, nhid=2,
                                     t0=0.0, t1=t1, tol=1e-7)
         check_grad(w, deer.DEER_F32, seed=k)
+
+
+@pytest.mark.parametrize("n,width,nhid,act", GENERAL)
+@pytest.mark.parametrize("dtype", [deer.DEER_F32, deer.DEER_F64])
+def test_grad_fields_of_other_depths_and_activations(n, width, nhid, act, dtype):
+    for k, (B, T, t1) in enumerate([(1, 2, 0.1), (2, 50, 1.0), (3, 1300, 2.0)]):
+        w = inputs.mlp_ode_workload("geng_n%d_w%d_L%d_T%d" % (n, width, nhid, T), 950 + 7 * n + width + nhid + k, B=B, T=T,
+                                    n=n, width=width, nhid=nhid, t0=0.0, t1=t1, tol=1e-7, act=act)
+        check_grad(w, dtype, seed=k)
+
+
+def test_two_body_network_shape_gradient():
+    check_grad(two_body_shaped(4, 10000), deer.DEER_F32)
 
 
 def test_grad_coarse_grid():
