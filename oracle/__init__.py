@@ -45,6 +45,7 @@ def lib():
         _lib.oracle_theta_count.restype = ctypes.c_long
         _lib.oracle_deer_eval.restype = ctypes.c_int
         _lib.oracle_ode_deer_eval.restype = ctypes.c_int
+        _lib.oracle_mh_deer_eval.restype = ctypes.c_int
         _lib.oracle_max_threads.restype = ctypes.c_int
     return _lib
 
@@ -162,6 +163,40 @@ def gru_grad(n, d, theta, x, y0, y, g):
     dy0 = np.empty((B, n))
     lib().oracle_gru_grad(n, d, _p(theta), ctypes.c_long(B), ctypes.c_long(T), _p(x), _p(y0), _p(y), _p(g),
                           _p(dtheta), _p(dx), _p(dy0))
+    return dtheta, dx, dy0
+
+
+def mh_seq_eval(n, d, H, K, theta, x, y0, nthreads=1):
+    """Multi-head strided GRU, sequential.  theta [H, P], x [B,T,H,d], y0 [B,H,n] -> y [B,T,H,n]."""
+    theta, x, y0 = _f64(theta), _f64(x), _f64(y0)
+    B, T = x.shape[0], x.shape[1]
+    y = np.empty((B, T, H, n))
+    lib().oracle_mh_seq_eval(n, d, H, K, _p(theta), ctypes.c_long(B), ctypes.c_long(T), _p(x), _p(y0), _p(y), int(nthreads))
+    return y
+
+
+def mh_deer_eval(n, d, H, K, theta, x, y0, guess=None, tol=1e-7, max_iter=100, nthreads=1):
+    """DEER for the multi-head strided GRU.  Returns (y [B,T,H,n], iterations, final err, err history)."""
+    theta, x, y0 = _f64(theta), _f64(x), _f64(y0)
+    B, T = x.shape[0], x.shape[1]
+    guess = _f64(guess) if guess is not None else None
+    y = np.empty((B, T, H, n))
+    err = ctypes.c_double(0.0)
+    hist = np.full(max_iter, np.nan)
+    it = lib().oracle_mh_deer_eval(n, d, H, K, _p(theta), ctypes.c_long(B), ctypes.c_long(T), _p(x), _p(y0), _p(guess),
+                                   ctypes.c_double(tol), int(max_iter), _p(y), ctypes.byref(err), _p(hist), int(nthreads))
+    return y, int(it), float(err.value), hist[:it]
+
+
+def mh_gru_grad(n, d, H, K, theta, x, y0, y, g):
+    """Backward derivative of the multi-head strided GRU.  Returns (dtheta [H,P], dx [B,T,H,d], dy0 [B,H,n])."""
+    theta, x, y0, y, g = _f64(theta), _f64(x), _f64(y0), _f64(y), _f64(g)
+    B, T = x.shape[0], x.shape[1]
+    dtheta = np.empty(theta.size).reshape(H, -1)
+    dx = np.empty((B, T, H, d))
+    dy0 = np.empty((B, H, n))
+    lib().oracle_mh_gru_grad(n, d, H, K, _p(theta), ctypes.c_long(B), ctypes.c_long(T), _p(x), _p(y0), _p(y), _p(g),
+                             _p(dtheta), _p(dx), _p(dy0))
     return dtheta, dx, dy0
 
 

@@ -467,6 +467,129 @@ void oracle_gru_grad(int n, int d, const double* th, long B, long T, const doubl
     free(lam); free(G); free(dh);
 }
 
+/* ----------------------------------------- multi-head GRU with strides -- */
+
+/* Sec. 4.4 / App. B.4: the state is split into H heads of n channels, every head a GRU of its own
+ * (parameters th[h], inputs x[b,i,h,:]), and head h looks back s_h = 2^(h mod K) steps instead of one
+ * (K stride levels dealt out to the heads in turn):
+ *     y[b,i,h] = f_h( y[b,i-s_h,h], x[b,i,h] ),   y[b,i-s_h,h] = y0[b,h] for i < s_h
+ * (0-based i).  Layouts: x [B,T,H,d], y0 [B,H,n], y [B,T,H,n], th [H][theta_count]. */
+static long mh_stride(int h, int K) { return 1L << (h % K); }
+
+void oracle_mh_seq_eval(int n, int d, int H, int K, const double* th, long B, long T, const double* x,
+                        const double* y0, double* y, int nthreads) {
+    long P = 3L * n * d + 3L * n * n + 4L * n;
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for num_threads(nthreads) schedule(static)
+    for (long bh = 0; bh < B * H; bh++) {
+        long b = bh / H;
+        int h = (int)(bh % H);
+        long s = mh_stride(h, K);
+        for (long i = 0; i < T; i++) {
+            const double* prev = (i >= s ? y + ((b * T + i - s) * H + h) * n : y0 + (b * H + h) * n);
+            gru_f(n, d, th + h * P, prev, x + ((b * T + i) * H + h) * d, y + ((b * T + i) * H + h) * n);
+        }
+    }
+}
+
+/* DEER for the same recurrence: the shifter hands f the previous iterate s_h steps back, the linear
+ * operator is (L y)_i = y_i + G_i y_{i-s_h} (Sec. 3.4 eq. 11 with that delay), solved serially; one
+ * convergence test over batch, time, heads and channels (App. B.1). */
+int oracle_mh_deer_eval(int n, int d, int H, int K, const double* th, long B, long T, const double* x,
+                        const double* y0, const double* guess, double tol, int max_iter,
+                        double* y, double* final_err, double* err_hist, int nthreads) {
+    long P = 3L * n * d + 3L * n * n + 4L * n;
+    size_t total = (size_t)B * T * H * n;
+    double* ynew = malloc(total * sizeof(double));
+    if (guess) memcpy(y, guess, total * sizeof(double));
+    else memset(y, 0, total * sizeof(double));
+    if (nthreads < 1) nthreads = 1;
+    double err = 1e10;
+    int iter = 0;
+    while (err > tol && iter < max_iter) {
+        double errmax = 0.0;
+        int bad = 0;
+#pragma omp parallel for num_threads(nthreads) schedule(static) reduction(max : errmax) reduction(| : bad)
+        for (long bh = 0; bh < B * H; bh++) {
+            long b = bh / H;
+            int h = (int)(bh % H);
+            long s = mh_stride(h, K);
+            const double* thh = th + h * P;
+            double* f = malloc((size_t)(2 * n + n * n) * sizeof(double));
+            double *zv = f + n, *G = zv + n;
+            for (long i = 0; i < T; i++) {
+                const double* hs = (i >= s ? y + ((b * T + i - s) * H + h) * n : y0 + (b * H + h) * n);
+                const double* xi = x + ((b * T + i) * H + h) * d;
+                gru_f(n, d, thh, hs, xi, f);
+                gru_jac(n, d, thh, hs, xi, G);
+                for (int k = 0; k < n * n; k++) G[k] = -G[k];
+                for (int r = 0; r < n; r++) {
+                    double a = f[r];
+                    for (int k = 0; k < n; k++) a += G[r * n + k] * hs[k];
+                    zv[r] = a;
+                }
+                const double* hp = (i >= s ? ynew + ((b * T + i - s) * H + h) * n : y0 + (b * H + h) * n);
+                for (int r = 0; r < n; r++) {
+                    double a = zv[r];
+                    for (int k = 0; k < n; k++) a -= G[r * n + k] * hp[k];
+                    size_t at = (size_t)((b * T + i) * H + h) * n + r;
+                    ynew[at] = a;
+                    double dlt = fabs(a - y[at]);
+                    if (dlt > errmax) errmax = dlt;
+                    if (!(dlt == dlt) || isinf(dlt)) bad = 1;
+                }
+            }
+            free(f);
+        }
+        err = bad ? NAN : errmax;
+        memcpy(y, ynew, total * sizeof(double));
+        if (err_hist) err_hist[iter] = err;
+        iter++;
+    }
+    if (final_err) *final_err = err;
+    free(ynew);
+    return iter;
+}
+
+/* Backward derivative (Sec. 3.1.1 eq. 7) for the strided operator: lam_i = g_i + J_{i+s}^T lam_{i+s}
+ * (no term when i + s >= T), J_{i+s} evaluated at h = y_i and x_{i+s}; then the vector-Jacobian product
+ * of f_h at every position; the first s positions of a head all start from y0, so dL/dy0 collects s terms.
+ * Outputs: dtheta [H][theta_count] (overwritten), dx [B,T,H,d], dy0 [B,H,n]. */
+void oracle_mh_gru_grad(int n, int d, int H, int K, const double* th, long B, long T, const double* x,
+                        const double* y0, const double* y, const double* g,
+                        double* dtheta, double* dx, double* dy0) {
+    long P = 3L * n * d + 3L * n * n + 4L * n;
+    memset(dtheta, 0, (size_t)H * P * sizeof(double));
+    memset(dy0, 0, (size_t)B * H * n * sizeof(double));
+    double* lam = malloc((size_t)T * n * sizeof(double));
+    double* G = malloc((size_t)n * n * sizeof(double));
+    double* dh = malloc((size_t)n * sizeof(double));
+    for (long b = 0; b < B; b++)
+        for (int h = 0; h < H; h++) {
+            long s = mh_stride(h, K);
+            const double* thh = th + h * P;
+            for (long i = T - 1; i >= 0; i--) {
+                for (int r = 0; r < n; r++) lam[i * n + r] = g[((b * T + i) * H + h) * n + r];
+                if (i + s < T) {
+                    gru_jac(n, d, thh, y + ((b * T + i) * H + h) * n, x + ((b * T + i + s) * H + h) * d, G);
+                    for (int r = 0; r < n; r++) {
+                        double a = 0.0;
+                        for (int k = 0; k < n; k++) a += G[k * n + r] * lam[(i + s) * n + k];
+                        lam[i * n + r] += a;
+                    }
+                }
+            }
+            for (long i = 0; i < T; i++) {
+                const double* hs = (i >= s ? y + ((b * T + i - s) * H + h) * n : y0 + (b * H + h) * n);
+                gru_vjp(n, d, thh, hs, x + ((b * T + i) * H + h) * d, lam + i * n, dtheta + h * P,
+                        dx + ((b * T + i) * H + h) * d, dh);
+                if (i < s)
+                    for (int r = 0; r < n; r++) dy0[(b * H + h) * n + r] += dh[r];
+            }
+        }
+    free(lam); free(G); free(dh);
+}
+
 /* ------------------------------------------- matrix exponential and phi1 -- */
 
 static void matmul(int n, const double* A, const double* Bm, double* C) {

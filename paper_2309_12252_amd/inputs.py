@@ -31,6 +31,8 @@ class Workload:
     t1: float = 0.0
     tol: float = 1e-4
     max_iter: int = 50
+    heads: int = 1             # GRU: heads (each a GRU of its own on its own input slice)
+    stride_levels: int = 1     # GRU multi-head: head h looks back 2^(h mod stride_levels) steps
     theta: np.ndarray = None   # flat fp32
     x: np.ndarray = None       # [B,T,d] fp32 or None
     y0: np.ndarray = None      # [B,n] fp32
@@ -73,6 +75,17 @@ def gru_workload(name, seed, B, T, n, d, tol=1e-4, max_iter=50, x_kind="normal",
 
 
 ACT_TANH, ACT_SOFTPLUS = 0, 1
+
+
+def mh_gru_workload(name, seed, B, T, n, d, H, K, tol=1e-4, max_iter=50):
+    """Multi-head GRU with strides: H heads of n channels, head h with its own parameters (~ N(0, 1/n)), its own
+    d input channels (x [B,T,H,d] ~ N(0,1)) and stride 2^(h mod K); y0 [B,H,n] = 0."""
+    rng = np.random.default_rng(seed)
+    theta = _normal(rng, (H, gru_theta_count(n, d)), 1.0 / np.sqrt(n))
+    x = _normal(rng, (B, T, H, d), 1.0)
+    y0 = np.zeros((B, H, n), dtype=np.float32)
+    return Workload(name=name, cell=CELL_GRU, B=B, T=T, n=n, d=d, heads=H, stride_levels=K, tol=tol, max_iter=max_iter,
+                    theta=theta, x=x, y0=y0)
 
 
 def mlp_ode_workload(name, seed, B, T, n, width, nhid, t0, t1, tol=1e-4, max_iter=50, act=ACT_TANH):
