@@ -33,6 +33,14 @@
  *       q = U_c h + b_hc                     c = tanh(W_c x + b_c + r * q)
  *       f(h, x) = (1 - z) * c + z * h
  *     theta (flat): W[3n,d] (rows r|z|c), U[3n,n] (rows r|z|c), b[3n] (r|z|c), b_hc[n].
+ *   Multi-head GRU with strides (Sec. 4.4, App. B.4; heads > 1 or stride_levels > 1): the state is H heads of n
+ *   channels, every head a GRU cell of its own on its own d input channels, and head h looks back
+ *   s_h = 2^(h mod K) steps instead of one (the K stride levels are dealt out to the heads in turn):
+ *       y[b,i,h,:] = f_h(y[b,i-s_h,h,:], x[b,i,h,:]),  with y0[b,h,:] in place of y[b,i-s_h,h,:] while i < s_h.
+ *     Arrays: x [B,T,H,d], y0 [B,H,n], y / guess / dL/dy [B,T,H,n], dL/dx [B,T,H,d], dL/dy0 [B,H,n];
+ *     theta and dL/dtheta [H][theta of one cell]; deer_theta_count() returns the total.  n = 2, 4 or 8, d <= 8,
+ *     H <= 64, K <= 8.  A head that takes all input channels is obtained by projecting the inputs beforehand
+ *     (a plain matrix product outside this library).
  *   MLP vector field (autonomous), L hidden layers of width w with activation s = tanh or softplus
  *   (s(a) = log(1 + exp(a)); App. B.2 uses six linear layers with softplus on all but the last):
  *       f(y) = W_out s(W_L s(... s(W_1 y + b_1) ...) + b_L) + b_out
@@ -74,6 +82,8 @@ typedef struct {
     int32_t mlp_hidden_layers;  /* MLP_ODE: hidden layers L, 1..5 (L + 1 linear layers)                  */
     double t0, t1;              /* MLP_ODE: uniform grid t_j = t0 + j (t1 - t0)/(T - 1)                  */
     int32_t mlp_activation;     /* MLP_ODE: deer_activation of the hidden layers (0 = tanh)              */
+    int32_t heads;              /* GRU: number of heads H (0 or 1: the plain cell); see "multi-head GRU"  */
+    int32_t stride_levels;      /* GRU: stride levels K (0 or 1: every head has stride 1)                */
     int32_t reserved;           /* must be 0                                                             */
 } deer_config;
 

@@ -51,6 +51,9 @@ struct Plan {
     bool mfma;
     bool fused;          // GRU with n <= 8: Newton steps run the scan with the cell evaluated in place
     int fused_L, fused_W, fused_tiles;
+    bool mh;             // multi-head GRU with strides: the scan's sequences are the heads' strided recurrences
+    int mh_H, mh_K, mh_Sper;   // heads, stride levels, recurrences per batch entry
+    size_t off_dy0parts;
     bool grad_fused;     // deer_grad computes the transposed Jacobians inside the reverse scan
     bool need_J;         // some kernel of this plan reads or writes the Jacobian stream [B,T,n,n] and the right-hand side
     int vjp_blocks;
@@ -60,7 +63,7 @@ struct Plan {
 
 size_t theta_count(const deer_config* c) {
     const size_t n = (size_t)c->n;
-    if (c->cell == DEER_CELL_GRU) return 3 * n * (size_t)c->d + 3 * n * n + 4 * n;
+    if (c->cell == DEER_CELL_GRU) return (size_t)(c->heads > 1 ? c->heads : 1) * (3 * n * (size_t)c->d + 3 * n * n + 4 * n);
     const size_t w = (size_t)c->mlp_width;
     const size_t L = c->mlp_hidden_layers >= 1 ? (size_t)c->mlp_hidden_layers : 1;
     return (w * n + w) + (L - 1) * (w * w + w) + (n * w + n);
@@ -73,17 +76,35 @@ bool mlp_fast_path(const deer_config* c) {
     return c->mlp_hidden_layers == 2 && c->mlp_activation == DEER_ACT_TANH && (w == 16 || w == 32 || w == 64) && w % c->n == 0;
 }
 
+int env_int(const char* name, int dflt) {
+    const char* s = std::getenv(name);
+    if (!s || !*s) return dflt;
+    return std::atoi(s);
+}
+
 bool validate(const deer_config* c, std::string& why) {
     if (!c) { why = "config is NULL"; return false; }
     if (c->cell != DEER_CELL_GRU && c->cell != DEER_CELL_MLP_ODE) { why = "unknown cell"; return false; }
     if (c->dtype != DEER_F32 && c->dtype != DEER_F64) { why = "unknown dtype"; return false; }
     if (c->B < 1 || c->T < 1 || c->n < 1) { why = "B, T and n must be positive"; return false; }
     if ((long long)c->B * c->T > (1LL << 31) - 1) { why = "B*T must fit 31 bits"; return false; }
+    if (c->heads < 0 || c->stride_levels < 0 || c->reserved != 0) { why = "heads and stride_levels must be >= 0 and reserved 0"; return false; }
+    if (c->cell != DEER_CELL_GRU && (c->heads > 1 || c->stride_levels > 1)) { why = "heads and strides exist for the GRU only"; return false; }
     return true;
 }
 
+bool is_multihead(const deer_config* c) { return c->cell == DEER_CELL_GRU && (c->heads > 1 || c->stride_levels > 1); }
+
 bool supported(const deer_config* c, std::string& why) {
     const int n = c->n;
+    if (is_multihead(c)) {
+        const int H = c->heads > 1 ? c->heads : 1, K = c->stride_levels > 1 ? c->stride_levels : 1;
+        if (!(n == 2 || n == 4 || n == 8) || c->d < 1 || c->d > 8) { why = "multi-head GRU: state size per head must be 2, 4 or 8 and input size per head 1..8"; return false; }
+        if (H > 64 || K > 8) { why = "multi-head GRU: at most 64 heads and 8 stride levels"; return false; }
+        if ((long long)c->B * c->T * H > (1LL << 31) - 1) { why = "B*T*heads must fit 31 bits"; return false; }
+        if (env_int("DEER_FUSED", 1) == 0 || env_int("DEER_GRAD_FUSED", 1) == 0) { why = "multi-head GRU runs only with the cell inside the scans"; return false; }
+        return true;
+    }
     if (c->cell == DEER_CELL_GRU) {
         if (!(n == 1 || n == 2 || n == 4 || n == 8 || n == 16 || n == 32)) {
             why = "GRU state size must be 1, 2, 4, 8, 16 or 32";
@@ -106,18 +127,59 @@ bool supported(const deer_config* c, std::string& why) {
     return true;
 }
 
-int env_int(const char* name, int dflt) {
-    const char* s = std::getenv(name);
-    if (!s || !*s) return dflt;
-    return std::atoi(s);
-}
-
 Plan make_plan(const deer_config* c) {
     Plan p{};
     p.esz = c->dtype == DEER_F32 ? 4 : 8;
     const size_t n = (size_t)c->n, B = (size_t)c->B, T = (size_t)c->T;
     const bool ode = c->cell == DEER_CELL_MLP_ODE;
     p.scan_T = ode ? c->T - 1 : c->T;
+    p.mh = is_multihead(c);
+    if (p.mh) {
+        // every head's strided recurrences are sequences of the fused small-n kernel (eight wavefronts per tile);
+        // positions per lane group from the same kind of estimate as below, over the real tiles of all recurrences
+        const int H = c->heads > 1 ? c->heads : 1, K = c->stride_levels > 1 ? c->stride_levels : 1;
+        p.mh_H = H; p.mh_K = K; p.mh_Sper = 0;
+        for (int h = 0; h < H; ++h) p.mh_Sper += 1 << (h % K);
+        p.mfma = false; p.W = 8; p.L = 1; p.fused = true; p.fused_W = 8;
+        static const int kLm[] = {1, 2, 4};
+        double best = 1e300;
+        int forced = env_int("DEER_FUSED_L", 0);
+        for (int q = 0; q < 3; ++q) {
+            const long long tile = scan_valu_tile(c->n, kLm[q], 8);
+            long long tiles = 0;
+            for (int h = 0; h < H; ++h) {
+                const long long s = 1LL << (h % K);
+                for (long long r = 0; r < s && r < (long long)T; ++r) tiles += (((long long)T - r + s - 1) / s + tile - 1) / tile;
+            }
+            tiles *= (long long)B;
+            double est = (double)((tiles + 255) / 256) * (5.0 + 1.6 * kLm[q]);
+            if (forced == kLm[q]) est = -1.0;
+            if (est < best) { best = est; p.fused_L = kLm[q]; }
+        }
+        const int tile = scan_valu_tile(c->n, p.fused_L, 8);
+        p.fused_tiles = (int)((T + tile - 1) / tile);
+        p.tile = tile; p.tiles = p.fused_tiles;
+        p.grad_fused = true; p.need_J = false;
+        long long vb = ((long long)B * (long long)T + 31) / 32;
+        p.vjp_blocks = (int)(vb > 128 ? 128 : (vb < 1 ? 1 : vb));
+        size_t off = 0;
+        auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+        p.off_J = take(0); p.off_rhs = take(0);
+        p.off_ybuf = take(B * T * (size_t)H * n * p.esz);
+        p.off_Gbar = take(0); p.off_zbar = take(0);
+        const size_t nt = B * (size_t)p.mh_Sper * (size_t)p.fused_tiles;
+        p.off_aggW = take(nt * (n * n + n) * (p.esz / 4) * 8);
+        p.off_inclW = take(nt * n * (p.esz / 4) * 8);
+        p.off_barrier = take(0);
+        p.off_ctl = take((size_t)kSlots * 4 + (size_t)kSlots * 8 + 16);
+        p.off_partial = take((size_t)H * p.vjp_blocks * 4 * (theta_count(c) / H) * p.esz);
+        p.off_dy0parts = take(B * (size_t)H * ((size_t)1 << (K - 1)) * n * p.esz);
+#ifdef DEER_SCAN_TIMING
+        p.off_timing = take(kTimingBytes);
+#endif
+        p.total = off;
+        return p;
+    }
     p.mfma = c->n >= 16;
     if (p.mfma) {
         p.L = 0;
@@ -339,7 +401,16 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
     p.timing = reinterpret_cast<unsigned long long*>(c->ws + c->plan.off_timing) + (size_t)(p.epoch & 7u) * ((size_t)1 << 20);
 #endif
     hipError_t e;
-    if (fused_theta && c->plan.mfma) {
+    if (fused_theta && c->plan.mh) {
+        p.B = g.B * c->plan.mh_Sper;
+        p.L = c->plan.fused_L;
+        p.W = 8;
+        p.tiles = c->plan.fused_tiles;
+        p.mh_H = c->plan.mh_H; p.mh_K = c->plan.mh_K; p.mh_Sper = c->plan.mh_Sper;
+        p.mh_P = (long long)(theta_count(&g) / (size_t)c->plan.mh_H);
+        prof_begin(c, KIND_FUSED, iter);
+        e = launch_scan_gru_mh(g.dtype, g.n, p, fused_theta, fused_x, g.d, c->stream);
+    } else if (fused_theta && c->plan.mfma) {
         p.tiles = reverse ? c->plan.tiles : c->plan.fused_tiles;   // the dual scan keeps the plain scan's tile shape
         prof_begin(c, KIND_FUSED, iter);
         e = launch_scan_mfma_fused(g.n, p, fused_theta, fused_x, g.d, c->stream);
@@ -545,7 +616,7 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
         c->test_extra_workgroups = (xw > 0 && xw <= 4) ? (unsigned)xw : 0u;
     }
     c->one_launch = false;
-    if (plan.fused && plan.fused_W == 8 && env_int("DEER_ONE_LAUNCH", 1) != 0) {
+    if (plan.fused && !plan.mh && plan.fused_W == 8 && env_int("DEER_ONE_LAUNCH", 1) != 0) {
         const long long grid = (long long)cfg->B * plan.fused_tiles;
         c->one_launch = grid <= (long long)gru_newton_capacity(cfg->dtype, cfg->n, cfg->d, plan.fused_L);
     }
@@ -565,7 +636,7 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
 
     const size_t esz = c->plan.esz;
     const size_t n = (size_t)g.n, B = (size_t)g.B, T = (size_t)g.T;
-    const size_t ybytes = B * T * n * esz;
+    const size_t ybytes = B * T * n * esz * (size_t)(c->plan.mh ? c->plan.mh_H : 1);
     char* J = c->ws + c->plan.off_J;
     char* rhs = c->ws + c->plan.off_rhs;
 
@@ -791,9 +862,10 @@ deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const v
                            (long long)(T * n), 1, 0, false));
     }
     GruVjpParams vp{d_theta, d_x, d_y0, d_y, lam, d_dLdx, d_dLdy0, c->ws + c->plan.off_partial, d_dLdtheta,
-                    g.B, g.T, g.n, g.d, c->plan.vjp_blocks};
+                    g.B, g.T, g.n, g.d, c->plan.vjp_blocks, c->plan.mh ? c->plan.mh_H : 0, c->plan.mh ? c->plan.mh_K : 0,
+                    c->plan.mh ? c->ws + c->plan.off_dy0parts : nullptr};
     prof_begin(c, KIND_VJP);
-    if (gru_vjp_mfma_supported(g.dtype, g.n, g.d) && env_int("DEER_VJP_MFMA", 1) != 0) {
+    if (!c->plan.mh && gru_vjp_mfma_supported(g.dtype, g.n, g.d) && env_int("DEER_VJP_MFMA", 1) != 0) {
         HIPCHK(c, launch_gru_vjp_mfma(vp, c->stream));
         HIPCHK(c, launch_partial_reduce(g.dtype, vp.partial, d_dLdtheta, (long long)theta_count(&g), vp.blocks * 4, c->stream));
     } else {
@@ -810,7 +882,7 @@ deer_status deer_linrec_solve(deer_ctx* c, const void* d_A, const void* d_b, con
     if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
     const deer_config& g = c->cfg;
     if (!d_A || !d_b || !d_y) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
-    if (g.cell != DEER_CELL_GRU) return fail(c, DEER_ERR_UNSUPPORTED, "deer_linrec_solve needs a GRU-shaped context");
+    if (g.cell != DEER_CELL_GRU || c->plan.mh) return fail(c, DEER_ERR_UNSUPPORTED, "deer_linrec_solve needs a plain GRU-shaped context");
     const size_t n = (size_t)g.n, T = (size_t)g.T;
     deer_status st = zero_ctl(c);
     if (st != DEER_OK) return st;

@@ -49,6 +49,10 @@ struct ScanParams {
     void* err;           // max |out - yold| as raw bits of a non-negative scalar, or nullptr
     unsigned* status;    // set non-zero when a bounded wait ran out
     Gate gate;
+    // multi-head GRU with strides (kernels instantiated with MH only): heads, stride levels, recurrences per batch
+    // entry (sum over the heads of their strides), parameters per head
+    int mh_H, mh_K, mh_Sper;
+    long long mh_P;
 #ifdef DEER_SCAN_TIMING
     unsigned long long* timing;   // development builds only: [B * tiles][8] timestamps of the tile's phases
 #endif
@@ -236,6 +240,9 @@ struct GruVjpParams {
     void* dtheta;      // [theta_count]
     int B, T, n, d;
     int blocks;
+    int H, K;          // multi-head GRU with strides: heads and stride levels (0 or 1: the plain GRU); arrays are then
+                       // [B][T][H][.], theta and dtheta [H][theta_count], partial [H][blocks * 4][theta_count]
+    void* dy0_parts;   // multi-head: [B][H][2^(K-1)][n] scratch for the terms of dL/dy0
 };
 
 struct MlpParams {
@@ -296,6 +303,9 @@ hipError_t launch_scan_gru_fused(int dtype, int n, const ScanParams& p, const vo
 bool scan_gru_dual_supported(int dtype, int n, int d, int L, int W);
 hipError_t launch_scan_gru_dual(int dtype, int n, const ScanParams& p, const void* theta, const void* x, int d,
                                 hipStream_t s);
+// the fused step and its dual for the strided heads of a multi-head GRU (p.mh_* set; p.B = batch * p.mh_Sper)
+bool scan_gru_mh_supported(int dtype, int n, int d, int L);
+hipError_t launch_scan_gru_mh(int dtype, int n, const ScanParams& p, const void* theta, const void* x, int d, hipStream_t s);
 int scan_mfma_tile(int dtype, int n);
 hipError_t launch_gru_funceval(int dtype, const GruParams& p, hipStream_t s);
 hipError_t launch_gru_vjp(int dtype, const GruVjpParams& p, hipStream_t s);

@@ -185,8 +185,12 @@ __device__ __forceinline__ S reduce_scatter_position(const S* v, int i) {
     return r;
 }
 
-// DP: the input width the x loops are unrolled for (d <= DP)
-template <typename S, int N, int DP>
+// DP: the input width the x loops are unrolled for (d <= DP).
+// MH: multi-head GRU with strides (Sec. 4.4, App. B.4).  Arrays are [batch][time][head][channel]; blockIdx.y is the
+// head, which has its own parameters and partial rows and looks back st = 2^(head mod K) steps.  The first st positions
+// of a head all start from y0, so dL/dy0 collects st terms: each goes to p.dy0_parts[batch][head][time] and a second
+// kernel adds them in order.
+template <typename S, int N, int DP, bool MH = false>
 __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     S* sW = reinterpret_cast<S*>(smem_raw);
@@ -202,7 +206,13 @@ __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
     const S* __restrict__ y = reinterpret_cast<const S*>(p.y);
     const S* __restrict__ lam = reinterpret_cast<const S*>(p.lam);
     S* __restrict__ dx = reinterpret_cast<S*>(p.dx);
-    S* __restrict__ dy0 = reinterpret_cast<S*>(p.dy0);
+    S* __restrict__ dy0 = reinterpret_cast<S*>(MH ? p.dy0_parts : p.dy0);
+    const long long P = 3LL * N * d + 3LL * N * N + 4LL * N;
+    const int hd = MH ? (int)blockIdx.y : 0;
+    const int H = MH ? p.H : 1;
+    const int st = MH ? (1 << (hd % p.K)) : 1;
+    const int smax = MH ? (1 << (p.K - 1)) : 1;
+    if constexpr (MH) theta += (long long)hd * P;
 
     RowWeights<S, N> w;
     load_row_weights<S, N>(theta, d, i, w, sW, ds, tid);
@@ -228,12 +238,13 @@ __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
         const long long sc_ = live ? s : 0;
         const long long bi = sc_ / p.T;
         const int ti = (int)(sc_ - bi * p.T);
-        const S* hp = (ti == 0) ? (y0 + bi * N) : (y + (sc_ - 1) * N);
+        const long long at = MH ? (sc_ * H + hd) : sc_;   // element index of this position in the [batch][time][head] grid
+        const S* hp = (ti < st) ? (y0 + (MH ? bi * H + hd : bi) * N) : (y + (at - (long long)st * H) * N);
         vload<S, N>(hn, hp);
         hin = hp[i];
 #pragma unroll
-        for (int k = 0; k < DP; ++k) xn[k] = (k < d) ? x[sc_ * d + k] : S(0);
-        lmn = live ? lam[sc_ * N + i] : S(0);
+        for (int k = 0; k < DP; ++k) xn[k] = (k < d) ? x[at * d + k] : S(0);
+        lmn = live ? lam[at * N + i] : S(0);
     };
     if (passes > 0) fetch(0);
     for (long long it = 0; it < passes; ++it) {
@@ -242,6 +253,7 @@ __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
         const long long sc_ = live ? s : 0;
         const long long bi = sc_ / p.T;
         const int ti = (int)(sc_ - bi * p.T);
+        const long long at = MH ? (sc_ * H + hd) : sc_;
         S h[N], xp[DP];
 #pragma unroll
         for (int j = 0; j < N; ++j) h[j] = hn[j];
@@ -300,32 +312,33 @@ __global__ __launch_bounds__(kThreads) void gru_vjp_kernel(GruVjpParams p) {
             if constexpr (DP <= N) {
                 const S tot = reduce_scatter_position<S, N, DP>(dxp, i);
                 const int k = i / (N / DP);
-                if (live && (i % (N / DP)) == 0 && k < d) dx[sc_ * d + k] = tot;
+                if (live && (i % (N / DP)) == 0 && k < d) dx[at * d + k] = tot;
             } else {
 #pragma unroll
                 for (int k = 0; k < DP; ++k) {
                     if (k < d) {
                         const S part = sum_position<S, N>(dxp[k]);
-                        if (live && i == (k % N)) dx[sc_ * d + k] = part;
+                        if (live && i == (k % N)) dx[at * d + k] = part;
                     }
                 }
             }
         }
-        if (dy0 && ti == 0) {
+        if (dy0 && ti < st) {
             // dL/dy0 = J_1^T lam_1, row j: z_j lam_j + sum_i (U_r[i][j] dar_i + U_z[i][j] daz_i + U_c[i][j] dq_i)
+            // (strided heads: one such term for each of the first st positions)
 #pragma unroll
             for (int j = 0; j < N; ++j) {
                 S part = w.Ur[j] * dar + w.Uz[j] * daz + w.Uc[j] * dq;
                 part += (j == i) ? g.z * lm : S(0);
                 part = sum_position<S, N>(part);
-                if (live && i == j) dy0[bi * N + j] = part;
+                if (live && i == j) dy0[(MH ? ((bi * H + hd) * smax + ti) : bi) * N + j] = part;
             }
         }
     }
 
-    // per-wavefront partial sums, written without atomics: row (block * 4 + wave) of p.partial
-    const long long P = 3LL * N * d + 3LL * N * N + 4LL * N;
-    S* __restrict__ prow = reinterpret_cast<S*>(p.partial) + ((long long)blockIdx.x * (kThreads / 64) + (tid >> 6)) * P;
+    // per-wavefront partial sums, written without atomics: row (block * 4 + wave) of p.partial (of this head's rows)
+    S* __restrict__ prow = reinterpret_cast<S*>(p.partial) +
+                           (((long long)hd * gridDim.x + blockIdx.x) * (kThreads / 64) + (tid >> 6)) * P;
     const bool writer = lane < N;   // the first position group of the wavefront holds the totals
 #pragma unroll
     for (int k = 0; k < DP; ++k) {
@@ -371,6 +384,9 @@ __global__ __launch_bounds__(256) void gru_vjp_reduce_kernel(const S* __restrict
     __shared__ S part[16][17];
     const int ql = threadIdx.x & 15, g = threadIdx.x >> 4;
     const long long q = (long long)blockIdx.x * 16 + ql;
+    // (blockIdx.y: one set of rows and one output vector per head of a multi-head GRU)
+    partial += (long long)blockIdx.y * rows * P;
+    dtheta += (long long)blockIdx.y * P;
     S acc = S(0);
     if (q < P) {
         int r = g;
@@ -433,6 +449,50 @@ hipError_t launch_vjp(const GruVjpParams& p, hipStream_t s) {
     return hipGetLastError();
 }
 
+// dL/dy0 of a multi-head GRU: the terms of the first st positions of every head, added in time order
+template <typename S>
+__global__ __launch_bounds__(256) void gru_dy0_mh_kernel(const S* __restrict__ parts, S* __restrict__ dy0, int B, int T, int H,
+                                                         int K, int n) {
+    const long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= (long long)B * H * n) return;
+    const int j = (int)(q % n);
+    const long long bh = q / n;
+    const int hd = (int)(bh % H);
+    const int smax = 1 << (K - 1);
+    int st = 1 << (hd % K);
+    if (st > T) st = T;
+    S acc = S(0);
+    for (int t = 0; t < st; ++t) acc += parts[(bh * smax + t) * n + j];
+    dy0[q] = acc;
+}
+
+template <typename S, int N>
+hipError_t launch_vjp_mh(const GruVjpParams& p, hipStream_t s) {
+    const size_t shmem = (size_t)3 * N * (p.d | 1) * sizeof(S);
+    hipLaunchKernelGGL((gru_vjp_kernel<S, N, 8, true>), dim3((unsigned)p.blocks, (unsigned)p.H), dim3(kThreads), shmem, s, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const long long P = 3LL * N * p.d + 3LL * N * N + 4LL * N;
+    hipLaunchKernelGGL((gru_vjp_reduce_kernel<S>), dim3((unsigned)((P + 15) / 16), (unsigned)p.H), dim3(256), 0, s,
+                       reinterpret_cast<const S*>(p.partial), reinterpret_cast<S*>(p.dtheta), P, p.blocks * (kThreads / 64));
+    e = hipGetLastError();
+    if (e != hipSuccess || !p.dy0) return e;
+    const long long q = (long long)p.B * p.H * N;
+    hipLaunchKernelGGL((gru_dy0_mh_kernel<S>), dim3((unsigned)((q + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<const S*>(p.dy0_parts), reinterpret_cast<S*>(p.dy0), p.B, p.T, p.H, p.K, N);
+    return hipGetLastError();
+}
+
+template <typename S>
+hipError_t launch_vjp_mh_s(const GruVjpParams& p, hipStream_t s) {
+    switch (p.n) {
+        case 2: return launch_vjp_mh<S, 2>(p, s);
+        case 4: return launch_vjp_mh<S, 4>(p, s);
+        case 8: return launch_vjp_mh<S, 8>(p, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 template <typename S>
 hipError_t launch_vjp_s(const GruVjpParams& p, hipStream_t s) {
     switch (p.n) {
@@ -476,6 +536,10 @@ hipError_t launch_gru_funceval(int dtype, const GruParams& p, hipStream_t s) {
 
 hipError_t launch_gru_vjp(int dtype, const GruVjpParams& p, hipStream_t s) {
     if (p.d < 1 || p.d > kMaxD) return hipErrorInvalidValue;
+    if (p.H > 1 || p.K > 1) {   // multi-head GRU with strides
+        if (p.d > 8 || p.H < 1 || p.K < 1 || !p.dy0_parts) return hipErrorInvalidValue;
+        return dtype == 0 ? launch_vjp_mh_s<float>(p, s) : launch_vjp_mh_s<double>(p, s);
+    }
     return dtype == 0 ? launch_vjp_s<float>(p, s) : launch_vjp_s<double>(p, s);
 }
 

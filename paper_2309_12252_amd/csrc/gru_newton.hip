@@ -193,7 +193,8 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         // loop, where they would occupy registers for the whole solve.
         ScanParams pk = p;
         asm volatile("" : "+v"(pk.aggW), "+v"(pk.inclW));
-        tile_lookback<S, N, W>(pk, sh, b, t, p.epoch + (unsigned)k, Mt, vt);
+        tile_lookback<S, N, W>(pk, sh, b, t, p.epoch + (unsigned)k, Mt, vt,
+                               p.y0 ? reinterpret_cast<const S*>(p.y0) + (long long)b * N : nullptr);
         S y = tile_start_state<S, N, W>(sh, Pex, pex, wave, i);
         h0 = y;   // the new iterate in front of this group's first position
         S emax = S(0);

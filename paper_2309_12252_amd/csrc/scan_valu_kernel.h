@@ -316,17 +316,19 @@ __device__ __forceinline__ void store_staged(float* __restrict__ ob, long long e
 }
 
 // entry i of the previous iterate (or any array laid out like the output) at positions e0 .. e0+L-1
+// (psy: scalars between consecutive positions of the sequence, N unless the sequence is a strided head)
 template <typename S, int N, int L, bool REV, bool FULL>
-__device__ __forceinline__ void load_previous(const S* __restrict__ src, long long T, long long e0, int i, S* yo) {
+__device__ __forceinline__ void load_previous(const S* __restrict__ src, long long T, long long e0, int i, S* yo,
+                                              long long psy = N) {
     if constexpr (FULL) {
-        const S* bp = src + (REV ? (T - 1 - e0) : e0) * N + i;
+        const S* bp = src + (REV ? (T - 1 - e0) : e0) * psy + i;
 #pragma unroll
-        for (int l = 0; l < L; ++l) yo[l] = bp[REV ? -l * N : l * N];
+        for (int l = 0; l < L; ++l) yo[l] = bp[REV ? -l * psy : l * psy];
     } else {
 #pragma unroll
         for (int l = 0; l < L; ++l) {
             const long long e = (e0 + l < T) ? e0 + l : T - 1;
-            yo[l] = src[(REV ? (T - 1 - e) : e) * N + i];
+            yo[l] = src[(REV ? (T - 1 - e) : e) * psy + i];
         }
     }
 }
@@ -365,14 +367,15 @@ __device__ __forceinline__ void load_gru_row(const GruFeed& gf, int i, GruRow<S,
 // input projections W x + b of row i at positions e0 .. e0+L-1 (xb: inputs of the sequence)
 template <typename S, int N, int L, int DP, bool FULL>
 __device__ __forceinline__ void gru_project(const GruRow<S, N, DP>& w, const S* __restrict__ xb, int d, long long T,
-                                            long long e0, S* pr, S* pq, S* pc) {
+                                            long long e0, S* pr, S* pq, S* pc, long long psx = -1) {
+    if (psx < 0) psx = d;   // scalars between the inputs of consecutive positions
 #pragma unroll
     for (int l = 0; l < L; ++l) {
         const long long e = (FULL || e0 + l < T) ? e0 + l : T - 1;
         S ar = w.br, az = w.bz, ac = w.bc;
 #pragma unroll
         for (int k = 0; k < DP; ++k) {
-            const S xv = xb[e * d + (k < d ? k : d - 1)];
+            const S xv = xb[e * psx + (k < d ? k : d - 1)];
             ar += w.Wr[k] * xv;
             az += w.Wz[k] * xv;
             ac += w.Wc[k] * xv;
@@ -420,24 +423,26 @@ __device__ __forceinline__ void gru_rows(const GruRow<S, N, DP>& w, const S* pr,
 
 // The pairs of positions e0 .. e0+L-1 from the GRU cell.  yo: previous iterate at these positions
 // (already requested); oldb: previous iterate of the sequence; DP: input width the x loops are unrolled for.
+// (gf.theta: this sequence's parameters; xb: its inputs; y0row: its initial state or nullptr; psy, psx: scalars between
+// consecutive positions of the trajectory and of the inputs)
 template <typename S, int N, int L, int DP, bool FULL>
-__device__ __forceinline__ void gru_pairs(const GruFeed& gf, const S* __restrict__ y0p, const S* __restrict__ oldb,
-                                          int b, long long T, long long e0, int i, const S* yo, S (*Ar)[N], S* be) {
+__device__ __forceinline__ void gru_pairs(const GruFeed& gf, const S* __restrict__ xb, const S* __restrict__ y0row,
+                                          const S* __restrict__ oldb, long long T, long long e0, int i, const S* yo,
+                                          S (*Ar)[N], S* be, long long psy, long long psx) {
     GruRow<S, N, DP> w;
     load_gru_row<S, N, DP>(gf, i, w);
-    const S* __restrict__ xb = reinterpret_cast<const S*>(gf.x) + (long long)b * T * gf.d;
     // state in front of the first position of this group
     S h;
     {
         const long long ef = e0 < T ? e0 : T;
-        const S a = oldb[(ef > 0 ? ef - 1 : 0) * N + i];
-        const S c0 = y0p ? y0p[(long long)b * N + i] : S(0);
+        const S a = oldb[(ef > 0 ? ef - 1 : 0) * psy + i];
+        const S c0 = y0row ? y0row[i] : S(0);
         h = ef > 0 ? a : c0;
     }
     // input projections of all positions first: their loads are all in flight before the
     // cross-lane products start (those are opaque to the scheduler, loads do not move across them)
     S pr[L], pq[L], pc[L];
-    gru_project<S, N, L, DP, FULL>(w, xb, gf.d, T, e0, pr, pq, pc);
+    gru_project<S, N, L, DP, FULL>(w, xb, gf.d, T, e0, pr, pq, pc, psx);
     gru_rows<S, N, L, DP, FULL>(w, pr, pq, pc, h, yo, T, e0, Ar, be);
 }
 
@@ -457,8 +462,8 @@ struct DualRow {
 // scan order) and the input at time T-e.  Position 0 has no matrix (zero); positions past the end get the identity.
 // Must be called by whole wavefronts.
 template <typename S, int N, int L, int DP, bool FULL>
-__device__ __forceinline__ void gru_pairs_dual(const GruFeed& gf, int b, long long T, long long e0, int i, const S* yv,
-                                               S (*Ar)[N]) {
+__device__ __forceinline__ void gru_pairs_dual(const GruFeed& gf, const S* __restrict__ xb, long long T, long long e0, int i,
+                                               const S* yv, S (*Ar)[N], long long psx) {
     GruRow<S, N, DP> w;
     load_gru_row<S, N, DP>(gf, i, w);
     const int d = gf.d;
@@ -471,7 +476,6 @@ __device__ __forceinline__ void gru_pairs_dual(const GruFeed& gf, int b, long lo
         Tz[s] = U[(N + c) * N + i];
         Tc[s] = U[(2 * N + c) * N + i];
     }
-    const S* __restrict__ xb = reinterpret_cast<const S*>(gf.x) + (long long)b * T * d;
     S pr[L], pq[L], pc[L];
 #pragma unroll
     for (int l = 0; l < L; ++l) {
@@ -483,7 +487,7 @@ __device__ __forceinline__ void gru_pairs_dual(const GruFeed& gf, int b, long lo
         S ar = w.br, az = w.bz, ac = w.bc;
 #pragma unroll
         for (int k = 0; k < DP; ++k) {
-            const S xv = xb[tj * d + (k < d ? k : d - 1)];
+            const S xv = xb[tj * psx + (k < d ? k : d - 1)];
             ar += w.Wr[k] * xv;
             az += w.Wz[k] * xv;
             ac += w.Wc[k] * xv;
@@ -626,7 +630,7 @@ __device__ __forceinline__ void tile_local(const ScanParams& p, TileShared<S, N,
 // entering the tile.  (Mt | vt): the tile total as left by tile_local.
 template <typename S, int N, int W>
 __device__ __forceinline__ void tile_lookback(const ScanParams& p, TileShared<S, N, W>& sh, int b, int t, unsigned epoch,
-                                              const S* Mt, S vt) {
+                                              const S* Mt, S vt, const S* y0row) {   // y0row: initial state of this sequence or nullptr (zeros)
     constexpr int NG = 64 / N;
     constexpr int WS = TaggedWords<S>::per_scalar;
     constexpr int AGG_WORDS = (N * N + N) * WS;   // words of one published tile total
@@ -686,7 +690,7 @@ __device__ __forceinline__ void tile_lookback(const ScanParams& p, TileShared<S,
             const int far = t - 1 - k;   // tile whose inclusive carry is known (-1: the initial state)
             if (group == 0) {
                 if (far >= 0) ok = tagged_get_wait<S>(inclSeq + (long long)far * (N * WS), i, tagI, y);
-                else if (p.y0) y = reinterpret_cast<const S*>(p.y0)[(long long)b * N + i];
+                else if (y0row) y = y0row[i];
             }
             // fold the totals of tiles far+1 .. t-1 forward, NG of them per round: group g fetches
             // tile q0 + g, then the running value walks through the groups in order
@@ -759,7 +763,7 @@ __device__ __forceinline__ void tile_lookback(const ScanParams& p, TileShared<S,
 // polls, then one fetch).  Called by all threads after tile_local; ends like tile_lookback.
 template <typename S, int N, int W>
 __device__ __forceinline__ void tile_lookback_split(const ScanParams& p, TileShared<S, N, W>& sh, int b, int t,
-                                                    unsigned epoch, const S* Mt, S vt) {
+                                                    unsigned epoch, const S* Mt, S vt, const S* y0row) {
     static_assert(W >= 2, "one wavefront publishes while another looks back");
     constexpr int NG = 64 / N;
     constexpr int WS = TaggedWords<S>::per_scalar;
@@ -812,7 +816,7 @@ __device__ __forceinline__ void tile_lookback_split(const ScanParams& p, TileSha
                         gotI = TaggedWords<S>::get(inclSeq + (long long)qs * (N * WS), i, tagI, cv);
                     } else if (qs == -1) {
                         gotI = true;
-                        cv = p.y0 ? reinterpret_cast<const S*>(p.y0)[(long long)b * N + i] : S(0);
+                        cv = y0row ? y0row[i] : S(0);
                     }
                 }
                 const unsigned long long incl_mask = __ballot(st == TILE_INCLUSIVE);
@@ -850,7 +854,7 @@ __device__ __forceinline__ void tile_lookback_split(const ScanParams& p, TileSha
             const int far = t - 1 - k;   // tile whose inclusive carry is known (-1: the initial state)
             if (group == 0) {
                 if (far >= 0) ok = tagged_get_wait<S>(inclSeq + (long long)far * (N * WS), i, tagI, y);
-                else if (p.y0) y = reinterpret_cast<const S*>(p.y0)[(long long)b * N + i];
+                else if (y0row) y = y0row[i];
             }
             for (int q0 = far + 1; q0 <= t - 1; q0 += NG) {
                 const int q = q0 + group;
@@ -904,13 +908,13 @@ __device__ __forceinline__ void tile_lookback_split(const ScanParams& p, TileSha
 // Steps 1b-4 in one go (see tile_local, tile_lookback and tile_lookback_split).
 template <typename S, int N, int L, int W, bool SPLIT = false>
 __device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N, W>& sh, const S (*Ar)[N], const S* be,
-                                           int b, int t, unsigned epoch, S* Pex, S& pex) {
+                                           int b, int t, unsigned epoch, S* Pex, S& pex, const S* y0row) {
     S Mt[N], vt = S(0);
 #pragma unroll
     for (int c = 0; c < N; ++c) Mt[c] = S(0);
     tile_local<S, N, L, W>(p, sh, Ar, be, b, t, Pex, pex, Mt, vt);
-    if constexpr (SPLIT) tile_lookback_split<S, N, W>(p, sh, b, t, epoch, Mt, vt);
-    else tile_lookback<S, N, W>(p, sh, b, t, epoch, Mt, vt);
+    if constexpr (SPLIT) tile_lookback_split<S, N, W>(p, sh, b, t, epoch, Mt, vt, y0row);
+    else tile_lookback<S, N, W>(p, sh, b, t, epoch, Mt, vt, y0row);
 }
 
 // Step 5a: the state in front of this group's first position (entry i), from the tile's carry
@@ -932,10 +936,16 @@ __device__ __forceinline__ S tile_start_state(const TileShared<S, N, W>& sh, con
 // loops are unrolled for: forward, the Newton step at the previous iterate p.yold; with REV, the dual scan with
 // the transposed Jacobians at the trajectory p.yold and the vectors from p.bv (no convergence measure).  ADDI: the stored matrices are A - I (the identity
 // is added on load; used by the dual recurrence of the ODE form, whose matrices are I + O(dt)).
-template <typename S, int N, int L, int W, bool REV, int DP, bool ADDI = false>
+// MH (with DP > 0): the launch's sequences are the strided heads of a multi-head GRU (Sec. 4.4, App. B.4).  Arrays are
+// [batch][time][head][channel]; head h has its own parameters (gf.theta + h * p.mh_P) and looks back s = 2^(h mod p.mh_K)
+// steps, so it falls into s independent recurrences over the times r, r + s, r + 2s, ...  Sequence number q of the
+// launch (p.B of them: p.mh_Sper per batch entry) is one such recurrence: its positions lie s * H * N scalars apart, its
+// length is ceil((T - r) / s), and tiles past that length return at once.
+template <typename S, int N, int L, int W, bool REV, int DP, bool ADDI = false, bool MH = false>
 __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed gf) {
     constexpr bool DUAL = DP > 0 && REV;
     static_assert(!ADDI || DP == 0, "only stored matrices can lack their identity");
+    static_assert(!MH || DP > 0, "strided heads exist for the GRU feed only");
     constexpr int NG = 64 / N;        // groups per wavefront
     constexpr int TILE = W * NG * L;  // scan positions per tile
 
@@ -963,7 +973,36 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     S* __restrict__ ob = reinterpret_cast<S*>(p.out) + (long long)b * p.strideOut;
     const S* __restrict__ oldb =
         p.yold ? reinterpret_cast<const S*>(p.yold) + (long long)b * p.strideOld : nullptr;
-    const long long T = p.T;
+    long long T = p.T;
+    long long psy = N, psx = gf.d;   // scalars between consecutive positions of the trajectory and of the inputs
+    const S* __restrict__ xb = nullptr;
+    const S* __restrict__ y0row = nullptr;
+    if constexpr (!MH) {
+        if constexpr (DP > 0) xb = reinterpret_cast<const S*>(gf.x) + (long long)b * T * gf.d;
+        if (p.y0) y0row = reinterpret_cast<const S*>(p.y0) + (long long)b * N;
+    }
+    if constexpr (MH) {
+        const int H = p.mh_H;
+        const long long bi = b / p.mh_Sper;
+        int r = b % p.mh_Sper, h = 0;
+        while (r >= (1 << (h % p.mh_K))) {   // heads in order, 2^(h mod K) recurrences each
+            r -= 1 << (h % p.mh_K);
+            ++h;
+        }
+        const long long s = 1LL << (h % p.mh_K);
+        const long long Tfull = p.T;
+        T = (Tfull - r + s - 1) / s;
+        if ((long long)t * TILE >= T) return;   // (also an empty recurrence: r >= Tfull)
+        psy = s * H * N;
+        psx = s * H * (long long)gf.d;
+        const long long first = ((bi * Tfull + r) * H + h);
+        ob = reinterpret_cast<S*>(p.out) + first * N;
+        oldb = reinterpret_cast<const S*>(p.yold) + first * N;
+        bb = reinterpret_cast<const S*>(p.bv) + first * N;
+        xb = reinterpret_cast<const S*>(gf.x) + first * gf.d;
+        if (p.y0) y0row = reinterpret_cast<const S*>(p.y0) + (bi * H + h) * N;
+        gf.theta = reinterpret_cast<const S*>(gf.theta) + (long long)h * p.mh_P;
+    }
     const long long e0 = (long long)t * TILE + (long long)(wave * NG + group) * L;
     const long long slot = (long long)b * p.tiles + t;
     DEER_STAMP(p, slot, 0, tid == 0);
@@ -989,28 +1028,28 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
                 for (int l = 0; l < L; ++l) yo[l] = S(0);
             }
         } else {
-            load_previous<S, N, L, REV, true>(oldb ? oldb : bb, T, e0, i, yo);
+            load_previous<S, N, L, REV, true>(oldb ? oldb : bb, T, e0, i, yo, psy);
         }
-        if constexpr (DP > 0 && !REV) gru_pairs<S, N, L, DP, true>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
+        if constexpr (DP > 0 && !REV) gru_pairs<S, N, L, DP, true>(gf, xb, y0row, oldb, T, e0, i, yo, Ar, be, psy, psx);
         if constexpr (DUAL) {
-            load_previous<S, N, L, true, true>(bb, T, e0, i, be);
-            gru_pairs_dual<S, N, L, DP, true>(gf, b, T, e0, i, yo, Ar);
+            load_previous<S, N, L, true, true>(bb, T, e0, i, be, psy);
+            gru_pairs_dual<S, N, L, DP, true>(gf, xb, T, e0, i, yo, Ar, psx);
         }
     } else {
         if constexpr (DP == 0) load_pairs<S, N, L, REV, false, ADDI>(Ab, bb, T, e0, i, Ar, be);
-        load_previous<S, N, L, REV, false>(oldb ? oldb : bb, T, e0, i, yo);
-        if constexpr (DP > 0 && !REV) gru_pairs<S, N, L, DP, false>(gf, reinterpret_cast<const S*>(p.y0), oldb, b, T, e0, i, yo, Ar, be);
+        load_previous<S, N, L, REV, false>(oldb ? oldb : bb, T, e0, i, yo, psy);
+        if constexpr (DP > 0 && !REV) gru_pairs<S, N, L, DP, false>(gf, xb, y0row, oldb, T, e0, i, yo, Ar, be, psy, psx);
         if constexpr (DUAL) {
-            load_previous<S, N, L, true, false>(bb, T, e0, i, be);
+            load_previous<S, N, L, true, false>(bb, T, e0, i, be, psy);
 #pragma unroll
             for (int l = 0; l < L; ++l) be[l] = (e0 + l < T) ? be[l] : S(0);
-            gru_pairs_dual<S, N, L, DP, false>(gf, b, T, e0, i, yo, Ar);
+            gru_pairs_dual<S, N, L, DP, false>(gf, xb, T, e0, i, yo, Ar, psx);
         }
     }
     S Pex[N], pex;
     // plain scans of n <= 4 look back on wavefront 1 while wavefront 0 scans the wavefront totals (measured on
     // chip-filling streams: +5 % at n = 4, +12 % at n = 2; at n = 8 the extra registers cost more than it gains)
-    tile_carry<S, N, L, W, DP == 0 && N <= 4>(p, sh, Ar, be, b, t, p.epoch, Pex, pex);
+    tile_carry<S, N, L, W, DP == 0 && N <= 4>(p, sh, Ar, be, b, t, p.epoch, Pex, pex, y0row);
 
     // ---- 5. starting state of this group, then the second walk over the resident pairs ----
     S y = tile_start_state<S, N, W>(sh, Pex, pex, wave, i);
@@ -1022,7 +1061,7 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
         const long long e = e0 + l;
         y = group_matvec<S, N>(Ar[l], be[l], y);
         if (full || e < T) {
-            const long long oi = (REV ? (T - 1 - e) : e) * N + i;
+            const long long oi = (REV ? (T - 1 - e) : e) * psy + i;
             S w = y;
             if (!DUAL && oldb) {
                 const S dq = abs_or_inf<S>(p.delta ? y : y - yo[l]);

@@ -25,7 +25,8 @@ class DeerConfig(ctypes.Structure):
     _fields_ = [("cell", ctypes.c_int32), ("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("T", ctypes.c_int32),
                 ("n", ctypes.c_int32), ("d", ctypes.c_int32), ("mlp_width", ctypes.c_int32),
                 ("mlp_hidden_layers", ctypes.c_int32), ("t0", ctypes.c_double), ("t1", ctypes.c_double),
-                ("mlp_activation", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("mlp_activation", ctypes.c_int32), ("heads", ctypes.c_int32), ("stride_levels", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 class DeerProfile(ctypes.Structure):
@@ -91,9 +92,10 @@ def _ptr(t):
 DEER_ACT_TANH, DEER_ACT_SOFTPLUS = 0, 1
 
 
-def make_config(cell, dtype, B, T, n, d=0, mlp_width=0, mlp_hidden_layers=0, t0=0.0, t1=0.0, mlp_activation=0):
+def make_config(cell, dtype, B, T, n, d=0, mlp_width=0, mlp_hidden_layers=0, t0=0.0, t1=0.0, mlp_activation=0,
+                heads=0, stride_levels=0):
     return DeerConfig(int(cell), int(dtype), int(B), int(T), int(n), int(d), int(mlp_width),
-                      int(mlp_hidden_layers), float(t0), float(t1), int(mlp_activation), 0)
+                      int(mlp_hidden_layers), float(t0), float(t1), int(mlp_activation), int(heads), int(stride_levels), 0)
 
 
 def theta_count(cfg):
@@ -142,16 +144,26 @@ class DeerContext:
             assert tuple(t.shape) == tuple(shape), (tuple(t.shape), tuple(shape))
         return t
 
+    def _shapes(self):
+        """(trajectory, inputs, initial state) shapes: with heads, arrays carry a head axis in front of the channels"""
+        c = self.cfg
+        if c.cell == DEER_CELL_GRU and (c.heads > 1 or c.stride_levels > 1):
+            H = max(1, c.heads)
+            return (c.B, c.T, H, c.n), (c.B, c.T, H, c.d), (c.B, H, c.n)
+        return (c.B, c.T, c.n), (c.B, c.T, c.d), (c.B, c.n)
+
     def eval(self, theta, x, y0, y_guess=None, tol=1e-4, max_iter=100, out=None, allow_nonfinite=False):
         """deer_eval.  Returns (y, iters, final_err, converged, status)."""
         c = self.cfg
-        y = out if out is not None else torch.empty((c.B, c.T, c.n), dtype=self.torch_dtype, device=self.device)
-        self._tensor(theta, (theta_count(c),))
+        ys, xs, y0s = self._shapes()
+        y = out if out is not None else torch.empty(ys, dtype=self.torch_dtype, device=self.device)
+        assert theta.numel() == theta_count(c)
+        self._tensor(theta)
         if c.cell == DEER_CELL_GRU:
-            self._tensor(x, (c.B, c.T, c.d))
-        self._tensor(y0, (c.B, c.n))
-        self._tensor(y_guess, (c.B, c.T, c.n))
-        self._tensor(y, (c.B, c.T, c.n))
+            self._tensor(x, xs)
+        self._tensor(y0, y0s)
+        self._tensor(y_guess, ys)
+        self._tensor(y, ys)
         iters, conv, err = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_double(0.0)
         st = self.lib.deer_eval(self.handle, _ptr(theta), _ptr(x), _ptr(y0), _ptr(y_guess), float(tol),
                                 int(max_iter), _ptr(y), ctypes.byref(iters), ctypes.byref(err), ctypes.byref(conv))
@@ -164,9 +176,10 @@ class DeerContext:
         ode = c.cell == DEER_CELL_MLP_ODE   # autonomous field: no inputs, hence no dL/dx; x and y0 may be None
         for t in (theta, x, y0, y, dLdy):
             self._tensor(t)
+        ys, xs, y0s = self._shapes()
         dtheta = torch.empty(theta_count(c), dtype=self.torch_dtype, device=self.device)
-        dx = torch.empty((c.B, c.T, c.d), dtype=self.torch_dtype, device=self.device) if (want_dx and not ode) else None
-        dy0 = torch.empty((c.B, c.n), dtype=self.torch_dtype, device=self.device) if want_dy0 else None
+        dx = torch.empty(xs, dtype=self.torch_dtype, device=self.device) if (want_dx and not ode) else None
+        dy0 = torch.empty(y0s, dtype=self.torch_dtype, device=self.device) if want_dy0 else None
         st = self.lib.deer_grad(self.handle, _ptr(theta), _ptr(x), _ptr(y0), _ptr(y), _ptr(dLdy), _ptr(dx),
                                 _ptr(dtheta), _ptr(dy0))
         self._check(st)
@@ -223,5 +236,6 @@ def linrec_solve_static(A, b, y0=None, reverse=False, out=None, status=None, str
 def context_for(workload, dtype=DEER_F32, device="cuda:0"):
     """Context for an ``inputs.Workload``."""
     cfg = make_config(workload.cell, dtype, workload.B, workload.T, workload.n, workload.d, workload.mlp_width,
-                      workload.mlp_hidden_layers, workload.t0, workload.t1, workload.mlp_activation)
+                      workload.mlp_hidden_layers, workload.t0, workload.t1, workload.mlp_activation,
+                      workload.heads, workload.stride_levels)
     return DeerContext(cfg, device=device)
