@@ -76,8 +76,10 @@ typedef struct {
     int32_t dtype;              /* deer_dtype                                                            */
     int32_t B;                  /* batch: independent sequences                                          */
     int32_t T;                  /* GRU: number of steps; MLP_ODE: number of grid points (>= 2)           */
-    int32_t n;                  /* state size: 1, 2, 4, 8, 16 or 32                                      */
-    int32_t d;                  /* GRU input size (1..16); ignored for MLP_ODE                           */
+    int32_t n;                  /* state size.  GRU: 1..32 (1, 2, 4, 8, 16, 32 have kernels of their own; any other */
+                                /* size runs embedded in the next of those, with identical results);     */
+                                /* MLP_ODE: 2, 4 or 8; multi-head GRU: 2, 4 or 8 per head                */
+    int32_t d;                  /* GRU input size (1..32); ignored for MLP_ODE                           */
     int32_t mlp_width;          /* MLP_ODE hidden width w: a multiple of 4, 4..64; ignored for GRU       */
     int32_t mlp_hidden_layers;  /* MLP_ODE: hidden layers L, 1..5 (L + 1 linear layers)                  */
     double t0, t1;              /* MLP_ODE: uniform grid t_j = t0 + j (t1 - t0)/(T - 1)                  */
@@ -174,6 +176,7 @@ deer_status deer_grad(deer_ctx* ctx, const void* d_theta, const void* d_x, const
 /* The inverse linear operator alone (Sec. 3.3 eq. 9-10, Sec. 3.4 eq. 11):
  * y_i = A_i y_{i-1} + b_i for i = 1..T from y_0, for B independent sequences, by the blocked
  * associative scan.  Shapes come from the context (B, T, n, dtype).
+ * (plain GRU-shaped contexts with n = 1, 2, 4, 8, 16 or 32 only).
  *   d_A [B,T,n,n]   d_b [B,T,n]   d_y0 [B,n] (NULL = zeros)   d_y out [B,T,n]
  *   reverse != 0 applies the dual (transposed, time-reversed) operator of Sec. 3.1.1 eq. 7 instead:
  *   y_T = b_T, y_i = b_i + A_{i+1}^T y_{i+1}; d_y0 is ignored.  A is read as stored and transposed

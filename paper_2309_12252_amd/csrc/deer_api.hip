@@ -93,6 +93,24 @@ bool validate(const deer_config* c, std::string& why) {
     return true;
 }
 
+// smallest state size with kernels of its own that holds n channels (0: none)
+int native_n(int n) {
+    for (int v = 1; v <= 32; v <<= 1)
+        if (n <= v) return v;
+    return 0;
+}
+
+bool is_multihead(const deer_config* c);
+
+// The configuration the kernels run: a plain GRU whose state size has no kernels of its own is embedded in the next
+// size that has (zero rows and columns in every weight: the extra channels stay at zero and the real ones never see
+// them, so iterates, iteration counts and gradients are those of the original cell).
+deer_config internal_config(const deer_config* user) {
+    deer_config c = *user;
+    if (c.cell == DEER_CELL_GRU && !is_multihead(user) && native_n(c.n) > 0) c.n = native_n(c.n);
+    return c;
+}
+
 bool is_multihead(const deer_config* c) { return c->cell == DEER_CELL_GRU && (c->heads > 1 || c->stride_levels > 1); }
 
 bool supported(const deer_config* c, std::string& why) {
@@ -106,11 +124,9 @@ bool supported(const deer_config* c, std::string& why) {
         return true;
     }
     if (c->cell == DEER_CELL_GRU) {
-        if (!(n == 1 || n == 2 || n == 4 || n == 8 || n == 16 || n == 32)) {
-            why = "GRU state size must be 1, 2, 4, 8, 16 or 32";
-            return false;
-        }
-        if (c->d < 1 || c->d > 16) { why = "GRU input size must be 1..16"; return false; }
+        // 1, 2, 4, 8, 16 and 32 have kernels; the sizes in between run embedded in the next one of those
+        if (n > 32) { why = "GRU state size must be at most 32"; return false; }
+        if (c->d < 1 || c->d > 32) { why = "GRU input size must be 1..32"; return false; }
     } else {
         if (!(n == 2 || n == 4 || n == 8)) { why = "MLP_ODE state size must be 2, 4 or 8"; return false; }
         if (c->mlp_activation != DEER_ACT_TANH && c->mlp_activation != DEER_ACT_SOFTPLUS) { why = "unknown MLP activation"; return false; }
@@ -303,7 +319,35 @@ Plan make_plan(const deer_config* c) {
 
 }  // namespace
 
+// Regions behind the kernels' own workspace that hold the embedded copies of a padded configuration
+struct PadPlan {
+    bool on;
+    size_t off_theta, off_y0, off_y, off_g, off_dtheta, off_dy0, total;
+};
+
+static PadPlan make_pad_plan(const deer_config* user, const deer_config* in, size_t base) {
+    PadPlan q{};
+    q.on = in->n != user->n;
+    q.total = base;
+    if (!q.on) return q;
+    const size_t esz = in->dtype == DEER_F32 ? 4 : 8;
+    const size_t B = (size_t)in->B, T = (size_t)in->T, np = (size_t)in->n;
+    size_t off = base;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    const size_t P = theta_count(in);
+    q.off_theta = take(P * esz);
+    q.off_y0 = take(B * np * esz);
+    q.off_y = take(B * T * np * esz);
+    q.off_g = take(B * T * np * esz);
+    q.off_dtheta = take(P * esz);
+    q.off_dy0 = take(B * np * esz);
+    q.total = off;
+    return q;
+}
+
 struct deer_ctx {
+    deer_config user;    // the configuration as the caller gave it
+    PadPlan pad;
     deer_config cfg;
     Plan plan;
     hipStream_t stream;
@@ -558,7 +602,8 @@ deer_status deer_workspace_bytes(const deer_config* cfg, size_t* bytes) {
     if (!bytes) return fail(nullptr, DEER_ERR_INVALID_ARG, "bytes is NULL");
     if (!validate(cfg, why)) return fail(nullptr, DEER_ERR_INVALID_ARG, why);
     if (!supported(cfg, why)) return fail(nullptr, DEER_ERR_UNSUPPORTED, why);
-    *bytes = make_plan(cfg).total;
+    const deer_config in = internal_config(cfg);
+    *bytes = make_pad_plan(cfg, &in, make_plan(&in).total).total;
     return DEER_OK;
 }
 
@@ -569,11 +614,17 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
     std::string why;
     if (!validate(cfg, why)) return fail(nullptr, DEER_ERR_INVALID_ARG, why);
     if (!supported(cfg, why)) return fail(nullptr, DEER_ERR_UNSUPPORTED, why);
+    const deer_config user_cfg = *cfg;
+    const deer_config in_cfg = internal_config(cfg);
+    cfg = &in_cfg;   // from here on: the configuration the kernels run
     Plan plan = make_plan(cfg);
-    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0 || workspace_bytes < plan.total)
+    const PadPlan pad = make_pad_plan(&user_cfg, cfg, plan.total);
+    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) % kAlign) != 0 || workspace_bytes < pad.total)
         return fail(nullptr, DEER_ERR_WORKSPACE, "workspace is NULL, misaligned or too small");
     deer_ctx* c = new (std::nothrow) deer_ctx();
     if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "out of host memory");
+    c->user = user_cfg;
+    c->pad = pad;
     c->cfg = *cfg;
     c->plan = plan;
     c->stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -624,10 +675,35 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
     return DEER_OK;
 }
 
+static deer_status eval_impl(deer_ctx* c, const void* d_theta, const void* d_x, const void* d_y0, const void* d_y_guess,
+                             double tol, int32_t max_iter, void* d_y, int32_t* iters, double* final_err, int32_t* converged);
+
 deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const void* d_y0, const void* d_y_guess,
                       double tol, int32_t max_iter, void* d_y, int32_t* iters, double* final_err,
                       int32_t* converged) {
     if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
+    if (!c->pad.on) return eval_impl(c, d_theta, d_x, d_y0, d_y_guess, tol, max_iter, d_y, iters, final_err, converged);
+    // embedded state size: zero-padded copies of the parameters, the initial state and the guess go in, the real
+    // channels of the result come out
+    if (!d_theta || !d_y0 || !d_y || !d_x) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
+    const deer_config& g = c->cfg;
+    const int n = c->user.n, np = g.n;
+    const long long rows = (long long)g.B * g.T;
+    char* pth = c->ws + c->pad.off_theta;
+    char* py0 = c->ws + c->pad.off_y0;
+    char* py = c->ws + c->pad.off_y;
+    HIPCHK(c, launch_pad_gru_theta(g.dtype, d_theta, pth, n, np, g.d, 0, c->stream));
+    HIPCHK(c, launch_pad_rows(g.dtype, d_y0, py0, g.B, n, np, 0, c->stream));
+    if (d_y_guess) HIPCHK(c, launch_pad_rows(g.dtype, d_y_guess, py, rows, n, np, 0, c->stream));
+    const deer_status st = eval_impl(c, pth, d_x, py0, d_y_guess ? py : nullptr, tol, max_iter, py, iters, final_err, converged);
+    if (st != DEER_OK && st != DEER_ERR_NONFINITE) return st;
+    HIPCHK(c, launch_pad_rows(g.dtype, py, d_y, rows, n, np, 1, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return st;
+}
+
+static deer_status eval_impl(deer_ctx* c, const void* d_theta, const void* d_x, const void* d_y0, const void* d_y_guess,
+                             double tol, int32_t max_iter, void* d_y, int32_t* iters, double* final_err, int32_t* converged) {
     const deer_config& g = c->cfg;
     const bool ode = g.cell == DEER_CELL_MLP_ODE;
     if (!d_theta || !d_y0 || !d_y || (!ode && !d_x)) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
@@ -833,8 +909,39 @@ static deer_status grad_ode(deer_ctx* c, const void* d_theta, const void* d_y, c
     return st;
 }
 
+static deer_status grad_impl(deer_ctx* c, const void* d_theta, const void* d_x, const void* d_y0, const void* d_y,
+                             const void* d_dLdy, void* d_dLdx, void* d_dLdtheta, void* d_dLdy0);
+
 deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const void* d_y0, const void* d_y,
                       const void* d_dLdy, void* d_dLdx, void* d_dLdtheta, void* d_dLdy0) {
+    if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
+    if (!c->pad.on) return grad_impl(c, d_theta, d_x, d_y0, d_y, d_dLdy, d_dLdx, d_dLdtheta, d_dLdy0);
+    // embedded state size: padded copies in, the real entries of the gradients out (the cotangent of the extra
+    // channels is zero and stays zero through the dual recurrence)
+    if (!d_theta || !d_x || !d_y0 || !d_y || !d_dLdy || !d_dLdtheta) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
+    const deer_config& g = c->cfg;
+    const int n = c->user.n, np = g.n;
+    const long long rows = (long long)g.B * g.T;
+    char* pth = c->ws + c->pad.off_theta;
+    char* py0 = c->ws + c->pad.off_y0;
+    char* py = c->ws + c->pad.off_y;
+    char* pg = c->ws + c->pad.off_g;
+    char* pdth = c->ws + c->pad.off_dtheta;
+    char* pdy0 = c->ws + c->pad.off_dy0;
+    HIPCHK(c, launch_pad_gru_theta(g.dtype, d_theta, pth, n, np, g.d, 0, c->stream));
+    HIPCHK(c, launch_pad_rows(g.dtype, d_y0, py0, g.B, n, np, 0, c->stream));
+    HIPCHK(c, launch_pad_rows(g.dtype, d_y, py, rows, n, np, 0, c->stream));
+    HIPCHK(c, launch_pad_rows(g.dtype, d_dLdy, pg, rows, n, np, 0, c->stream));
+    const deer_status st = grad_impl(c, pth, d_x, py0, py, pg, d_dLdx, pdth, d_dLdy0 ? pdy0 : nullptr);
+    if (st != DEER_OK) return st;
+    HIPCHK(c, launch_pad_gru_theta(g.dtype, pdth, d_dLdtheta, n, np, g.d, 1, c->stream));
+    if (d_dLdy0) HIPCHK(c, launch_pad_rows(g.dtype, pdy0, d_dLdy0, g.B, n, np, 1, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return DEER_OK;
+}
+
+static deer_status grad_impl(deer_ctx* c, const void* d_theta, const void* d_x, const void* d_y0, const void* d_y,
+                             const void* d_dLdy, void* d_dLdx, void* d_dLdtheta, void* d_dLdy0) {
     if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
     const deer_config& g = c->cfg;
     if (g.cell == DEER_CELL_MLP_ODE) return grad_ode(c, d_theta, d_y, d_dLdy, d_dLdtheta, d_dLdy0);
@@ -882,7 +989,8 @@ deer_status deer_linrec_solve(deer_ctx* c, const void* d_A, const void* d_b, con
     if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
     const deer_config& g = c->cfg;
     if (!d_A || !d_b || !d_y) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
-    if (g.cell != DEER_CELL_GRU || c->plan.mh) return fail(c, DEER_ERR_UNSUPPORTED, "deer_linrec_solve needs a plain GRU-shaped context");
+    if (g.cell != DEER_CELL_GRU || c->plan.mh || c->pad.on)
+        return fail(c, DEER_ERR_UNSUPPORTED, "deer_linrec_solve needs a plain GRU-shaped context of state size 1, 2, 4, 8, 16 or 32");
     const size_t n = (size_t)g.n, T = (size_t)g.T;
     deer_status st = zero_ctl(c);
     if (st != DEER_OK) return st;
@@ -923,6 +1031,7 @@ deer_status deer_linrec_solve_static(int32_t dtype, int32_t B, int32_t T, int32_
     std::string why;
     if (!validate(&cfg, why)) return fail(nullptr, DEER_ERR_INVALID_ARG, why);
     if (!supported(&cfg, why)) return fail(nullptr, DEER_ERR_UNSUPPORTED, why);
+    if (native_n(n) != n) return fail(nullptr, DEER_ERR_UNSUPPORTED, "the scan alone needs a state size of 1, 2, 4, 8, 16 or 32");
     if (!d_A || !d_b || !d_y) return fail(nullptr, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
     // the part of the plan the scan uses, re-based to the start of the static array
     Plan plan = make_plan(&cfg);
@@ -957,6 +1066,8 @@ deer_status deer_linrec_solve_static(int32_t dtype, int32_t B, int32_t T, int32_
 
     // a context on the stack (host memory only) that points the scan at the static array
     deer_ctx c;
+    c.user = cfg;
+    c.pad = PadPlan{};
     c.cfg = cfg;
     c.plan = plan;
     c.stream = reinterpret_cast<hipStream_t>(hip_stream);

@@ -335,6 +335,9 @@ hipError_t launch_mlp_general_funceval(int dtype, const MlpParams& p, hipStream_
 hipError_t launch_mlp_general_vjp(int dtype, const MlpVjpParams& p, hipStream_t s);
 // fixed-order sum of partial rows [rows][P] into out[P]
 hipError_t launch_partial_reduce(int dtype, const void* partial, void* out, long long P, int rows, hipStream_t s);
+// zero-padding of the channel axis (rows of n scalars <-> rows of np) and of the GRU parameters, both directions
+hipError_t launch_pad_rows(int dtype, const void* src, void* dst, long long rows, int n, int np, int unpack, hipStream_t s);
+hipError_t launch_pad_gru_theta(int dtype, const void* src, void* dst, int n, int np, int d, int unpack, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_fill_zero2(void* a, size_t abytes, void* b, size_t bbytes, hipStream_t s);
 hipError_t launch_copy_word(void* dst, const void* src, hipStream_t s);   // one 32-bit word, device to device

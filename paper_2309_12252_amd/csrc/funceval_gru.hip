@@ -23,7 +23,7 @@ namespace deer {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxD = 16;
+constexpr int kMaxD = 32;   // largest input size (the kernels are instantiated for unroll widths 16 and 32)
 
 // fp32: hardware exp2 and reciprocal (absolute error below 3e-7), as in the fused step
 __device__ __forceinline__ float sigmoid_(float a) { return feed_sigmoid(a); }
@@ -57,8 +57,8 @@ struct Gates {
     S r, z, q, c, hi;
 };
 
-// gates of row i at (h, x)
-template <typename S, int N>
+// gates of row i at (h, x); DX: the input width the x loops are unrolled for (d <= DX)
+template <typename S, int N, int DX>
 __global__ __launch_bounds__(kThreads) void gru_funceval_kernel(GruParams p) {
     if (gate_closed<S>(p.gate)) return;
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void gru_funceval_kernel(GruParams p) {
     const long long stride = (long long)gridDim.x * SPB;
     // Software pipeline: the operands of the next position are requested before the current one is
     // computed, so the loop does not expose a memory round trip per position.
-    S hn[N], hin = S(0), xn[kMaxD];
+    S hn[N], hin = S(0), xn[DX];
     auto fetch = [&](long long s) {
         const long long bi = s / p.T;
         const int ti = (int)(s - bi * p.T);
@@ -91,21 +91,21 @@ __global__ __launch_bounds__(kThreads) void gru_funceval_kernel(GruParams p) {
         vload<S, N>(hn, hp);
         hin = hp[i];
 #pragma unroll
-        for (int k = 0; k < kMaxD; ++k) xn[k] = (k < d) ? x[s * d + k] : S(0);
+        for (int k = 0; k < DX; ++k) xn[k] = (k < d) ? x[s * d + k] : S(0);
     };
     long long s = (long long)blockIdx.x * SPB + sg;
     if (s < total) fetch(s);
     for (; s < total; s += stride) {
-        S h[N], xv[kMaxD];
+        S h[N], xv[DX];
 #pragma unroll
         for (int j = 0; j < N; ++j) h[j] = hn[j];
 #pragma unroll
-        for (int k = 0; k < kMaxD; ++k) xv[k] = xn[k];
+        for (int k = 0; k < DX; ++k) xv[k] = xn[k];
         const S hi = hin;
         if (s + stride < total) fetch(s + stride);
         S ar = w.br, az = w.bz, ac = w.bc, q = w.bh;
 #pragma unroll
-        for (int k = 0; k < kMaxD; ++k) {
+        for (int k = 0; k < DX; ++k) {
             if (k < d) {
                 ar += sW[(i)*ds + k] * xv[k];
                 az += sW[(N + i) * ds + k] * xv[k];
@@ -417,7 +417,8 @@ hipError_t launch_fe(const GruParams& p, hipStream_t s) {
     if (blocks > 256 * 8) blocks = 256 * 8;
     if (blocks < 1) blocks = 1;
     const size_t shmem = (size_t)3 * N * (p.d | 1) * sizeof(S);
-    hipLaunchKernelGGL((gru_funceval_kernel<S, N>), dim3((unsigned)blocks), dim3(kThreads), shmem, s, p);
+    if (p.d <= 16) hipLaunchKernelGGL((gru_funceval_kernel<S, N, 16>), dim3((unsigned)blocks), dim3(kThreads), shmem, s, p);
+    else hipLaunchKernelGGL((gru_funceval_kernel<S, N, 32>), dim3((unsigned)blocks), dim3(kThreads), shmem, s, p);
     return hipGetLastError();
 }
 
@@ -439,7 +440,8 @@ hipError_t launch_vjp(const GruVjpParams& p, hipStream_t s) {
     const size_t shmem = (size_t)3 * N * (p.d | 1) * sizeof(S);
     if (p.d <= 4) hipLaunchKernelGGL((gru_vjp_kernel<S, N, 4>), dim3((unsigned)p.blocks), dim3(kThreads), shmem, s, p);
     else if (p.d <= 8) hipLaunchKernelGGL((gru_vjp_kernel<S, N, 8>), dim3((unsigned)p.blocks), dim3(kThreads), shmem, s, p);
-    else hipLaunchKernelGGL((gru_vjp_kernel<S, N, 16>), dim3((unsigned)p.blocks), dim3(kThreads), shmem, s, p);
+    else if (p.d <= 16) hipLaunchKernelGGL((gru_vjp_kernel<S, N, 16>), dim3((unsigned)p.blocks), dim3(kThreads), shmem, s, p);
+    else hipLaunchKernelGGL((gru_vjp_kernel<S, N, 32>), dim3((unsigned)p.blocks), dim3(kThreads), shmem, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const long long P = 3LL * N * p.d + 3LL * N * N + 4LL * N;
@@ -515,6 +517,81 @@ int gru_vjp_blocks(int n, long long steps) {
     if (blocks > (n == 16 ? 768 : 512)) blocks = (n == 16 ? 768 : 512);
     if (blocks < 1) blocks = 1;
     return (int)blocks;
+}
+
+// ---- embedding of a state size without kernels of its own into the next larger one ----
+// The cell with n channels is run as a cell with np >= n channels whose extra rows and columns of every weight and
+// bias are zero.  Extra channels then obey h' = h / 2 and stay at the zero they start from, and the real channels never
+// see them (their columns of U are zero): the recurrence, its Jacobians, the Newton iterates and the cotangents of
+// the real channels are exactly those of the n-channel cell.
+template <typename S>
+__global__ __launch_bounds__(256) void pad_rows_kernel(const S* __restrict__ src, S* __restrict__ dst, long long rows, int n, int np,
+                                                      int unpack) {
+    // pack: dst[rows][np] <- src[rows][n] with zeros behind; unpack: dst[rows][n] <- src[rows][np]
+    const long long total = rows * (unpack ? n : np);
+    for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += (long long)gridDim.x * blockDim.x) {
+        if (unpack) {
+            const long long r = q / n;
+            const int c = (int)(q % n);
+            dst[q] = src[r * np + c];
+        } else {
+            const long long r = q / np;
+            const int c = (int)(q % np);
+            dst[q] = c < n ? src[r * n + c] : S(0);
+        }
+    }
+}
+
+// theta of the GRU cell: W[3n,d] | U[3n,n] | b[3n] | b_hc[n]  <->  the same blocks for np channels
+template <typename S>
+__global__ __launch_bounds__(256) void pad_gru_theta_kernel(const S* __restrict__ src, S* __restrict__ dst, int n, int np, int d,
+                                                           int unpack) {
+    const long long Pp = 3LL * np * d + 3LL * np * np + 4LL * np;
+    for (long long q = (long long)blockIdx.x * blockDim.x + threadIdx.x; q < Pp; q += (long long)gridDim.x * blockDim.x) {
+        // position of entry q of the padded layout in the small one, or -1
+        long long at = -1, r = q;
+        if (r < 3LL * np * d) {
+            const int gate = (int)(r / ((long long)np * d)), row = (int)((r / d) % np), col = (int)(r % d);
+            if (row < n) at = ((long long)gate * n + row) * d + col;
+        } else if ((r -= 3LL * np * d) < 3LL * np * np) {
+            const int gate = (int)(r / ((long long)np * np)), row = (int)((r / np) % np), col = (int)(r % np);
+            if (row < n && col < n) at = 3LL * n * d + ((long long)gate * n + row) * n + col;
+        } else {
+            r -= 3LL * np * np;   // four bias vectors of np entries
+            const int which = (int)(r / np), row = (int)(r % np);
+            if (row < n) at = 3LL * n * d + 3LL * n * n + (long long)which * n + row;
+        }
+        if (unpack) {
+            if (at >= 0) dst[at] = src[q];
+        } else {
+            dst[q] = at >= 0 ? src[at] : S(0);
+        }
+    }
+}
+
+hipError_t launch_pad_rows(int dtype, const void* src, void* dst, long long rows, int n, int np, int unpack, hipStream_t s) {
+    if (rows < 1) return hipSuccess;
+    long long blocks = (rows * np + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (dtype == 0)
+        hipLaunchKernelGGL((pad_rows_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<const float*>(src),
+                           reinterpret_cast<float*>(dst), rows, n, np, unpack);
+    else
+        hipLaunchKernelGGL((pad_rows_kernel<double>), dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<const double*>(src),
+                           reinterpret_cast<double*>(dst), rows, n, np, unpack);
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_gru_theta(int dtype, const void* src, void* dst, int n, int np, int d, int unpack, hipStream_t s) {
+    const long long Pp = 3LL * np * d + 3LL * np * np + 4LL * np;
+    const unsigned blocks = (unsigned)((Pp + 255) / 256);
+    if (dtype == 0)
+        hipLaunchKernelGGL((pad_gru_theta_kernel<float>), dim3(blocks), dim3(256), 0, s, reinterpret_cast<const float*>(src),
+                           reinterpret_cast<float*>(dst), n, np, d, unpack);
+    else
+        hipLaunchKernelGGL((pad_gru_theta_kernel<double>), dim3(blocks), dim3(256), 0, s, reinterpret_cast<const double*>(src),
+                           reinterpret_cast<double*>(dst), n, np, d, unpack);
+    return hipGetLastError();
 }
 
 hipError_t launch_partial_reduce(int dtype, const void* partial, void* out, long long P, int rows, hipStream_t s) {
