@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "deer_oracle.c")
 _LIB = os.path.join(_HERE, "libdeer_oracle.so")
 
-CELL_GRU, CELL_MLP, CELL_AFFINE = 0, 1, 2
+CELL_GRU, CELL_MLP, CELL_AFFINE, CELL_LSTM = 0, 1, 2, 3
 
 
 class _Cell(ctypes.Structure):
@@ -96,6 +96,28 @@ def gru_vjp(n, d, theta, h, x, lam):
     dh = np.empty(n)
     lib().oracle_gru_vjp(n, d, _p(theta), _p(h), _p(x), _p(lam), _p(dtheta), _p(dx), _p(dh))
     return dtheta, dx, dh
+
+
+def cell_vjp(cell, theta, h, x, lam):
+    """GRU / LSTM: (dtheta, dx, dh) for an output cotangent lam (cell.n is the state size)."""
+    theta, h, x, lam = _f64(theta), _f64(h), _f64(x), _f64(lam)
+    dtheta = np.zeros(theta.size)
+    dx = np.empty(cell.d)
+    dh = np.empty(cell.n)
+    lib().oracle_cell_vjp(ctypes.byref(cell), _p(theta), _p(h), _p(x), _p(lam), _p(dtheta), _p(dx), _p(dh))
+    return dtheta, dx, dh
+
+
+def rnn_grad(cell, theta, x, y0, y, g):
+    """Backward derivative for a recurrent cell (GRU, LSTM).  Returns (dtheta, dx [B,T,d], dy0 [B,n])."""
+    theta, x, y0, y, g = _f64(theta), _f64(x), _f64(y0), _f64(y), _f64(g)
+    B, T, _ = x.shape
+    dtheta = np.empty(theta.size)
+    dx = np.empty((B, T, cell.d))
+    dy0 = np.empty((B, cell.n))
+    lib().oracle_rnn_grad(ctypes.byref(cell), _p(theta), ctypes.c_long(B), ctypes.c_long(T), _p(x), _p(y0), _p(y), _p(g),
+                          _p(dtheta), _p(dx), _p(dy0))
+    return dtheta, dx, dy0
 
 
 def affine_combine(Gi, zi, Gj, zj):

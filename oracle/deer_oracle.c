@@ -36,6 +36,12 @@
  *     App. B.2: six linear layers, softplus on all but the last); theta = W_1[w,n], b_1[w],
  *     (W_k[w,w], b_k[w]) for k = 2..nhid, W_out[n,w], b_out[n]; nhid = 0 is
  *     the linear field W_out[n,n] y + b_out.
+ *   - LSTM cell (Sec. 3.4 names it as an instance of the recurrence): u units, state y = (h | c) of 2u
+ *     entries, gates in the order input, forget, candidate, output:
+ *         i = sig(W_i x + U_i h + b_i)   f = sig(W_f x + U_f h + b_f)
+ *         g = tanh(W_g x + U_g h + b_g)  o = sig(W_o x + U_o h + b_o)
+ *         c' = f*c + i*g                 h' = o*tanh(c')
+ *     theta = W[4u,d], U[4u,u], b[4u].  (The cell torch.nn.LSTMCell computes with its second bias at zero.)
  *   - affine RNN cell (a test hook, used to pin "Newton is exact for linear
  *     f"): f(h, x) = A h + Bm x + c, theta = A[n,n], Bm[n,d], c[n].
  *   - one global convergence test over batch, time and state; the returned
@@ -58,6 +64,7 @@
 #define ORACLE_CELL_GRU 0
 #define ORACLE_CELL_MLP 1
 #define ORACLE_CELL_AFFINE 2
+#define ORACLE_CELL_LSTM 3
 
 typedef struct {
     int cell;   /* ORACLE_CELL_* */
@@ -74,6 +81,7 @@ long oracle_theta_count(const oracle_cell* c) {
     long n = c->n, d = c->d, w = c->width;
     if (c->cell == ORACLE_CELL_GRU) return 3 * n * d + 3 * n * n + 3 * n + n;
     if (c->cell == ORACLE_CELL_AFFINE) return n * n + n * d + n;
+    if (c->cell == ORACLE_CELL_LSTM) { long u = n / 2; return 4 * u * d + 4 * u * u + 4 * u; }
     if (c->nhid == 0) return n * n + n;
     return (w * n + w) + (long)(c->nhid - 1) * (w * w + w) + (n * w + n);
 }
@@ -265,6 +273,106 @@ static void mlp_jac(const oracle_cell* c, const double* th, const double* y, dou
     free(act); free(out); free(S); free(S2); free(dac);
 }
 
+/* ----------------------------------------------------------------- LSTM -- */
+
+/* gate values at (y = (h | c), x); each output has u entries; cn = c', tc = tanh(c') */
+static void lstm_gates(int u, int d, const double* th, const double* y, const double* x,
+                       double* gi, double* gf, double* gg, double* go, double* cn, double* tc) {
+    const double* W = th;                 /* [4u, d] */
+    const double* U = W + 4 * u * d;      /* [4u, u] */
+    const double* b = U + 4 * u * u;      /* [4u]    */
+    const double* h = y;
+    const double* c = y + u;
+    for (int j = 0; j < u; j++) {
+        double a[4];
+        for (int q = 0; q < 4; q++) {
+            a[q] = b[q * u + j];
+            for (int k = 0; k < d; k++) a[q] += W[(q * u + j) * d + k] * x[k];
+            for (int k = 0; k < u; k++) a[q] += U[(q * u + j) * u + k] * h[k];
+        }
+        gi[j] = sigmoid(a[0]);
+        gf[j] = sigmoid(a[1]);
+        gg[j] = tanh(a[2]);
+        go[j] = sigmoid(a[3]);
+        cn[j] = gf[j] * c[j] + gi[j] * gg[j];
+        tc[j] = tanh(cn[j]);
+    }
+}
+
+static void lstm_f(int u, int d, const double* th, const double* y, const double* x, double* out) {
+    double* g = malloc(6 * u * sizeof(double));
+    lstm_gates(u, d, th, y, x, g, g + u, g + 2 * u, g + 3 * u, g + 4 * u, g + 5 * u);
+    for (int j = 0; j < u; j++) {
+        out[j] = g[3 * u + j] * g[5 * u + j];   /* h' = o tanh(c') */
+        out[u + j] = g[4 * u + j];              /* c'              */
+    }
+    free(g);
+}
+
+/* J = d(h' | c') / d(h | c), 2u x 2u, row-major */
+static void lstm_jac(int u, int d, const double* th, const double* y, const double* x, double* J) {
+    const double* U = th + 4 * u * d;
+    const double* c = y + u;
+    int n = 2 * u;
+    double* g = malloc(6 * u * sizeof(double));
+    double *gi = g, *gf = g + u, *gg = g + 2 * u, *go = g + 3 * u, *tc = g + 5 * u;
+    lstm_gates(u, d, th, y, x, gi, gf, gg, go, g + 4 * u, tc);
+    memset(J, 0, (size_t)n * n * sizeof(double));
+    for (int j = 0; j < u; j++) {
+        double dti = gi[j] * (1.0 - gi[j]), dtf = gf[j] * (1.0 - gf[j]);
+        double dtg = 1.0 - gg[j] * gg[j], dto = go[j] * (1.0 - go[j]);
+        double dtc = 1.0 - tc[j] * tc[j];
+        for (int k = 0; k < u; k++) {
+            /* dc'_j/dh_k */
+            double dc = c[j] * dtf * U[(u + j) * u + k] + gg[j] * dti * U[(j)*u + k] + gi[j] * dtg * U[(2 * u + j) * u + k];
+            J[(u + j) * n + k] = dc;
+            /* dh'_j/dh_k */
+            J[j * n + k] = tc[j] * dto * U[(3 * u + j) * u + k] + go[j] * dtc * dc;
+        }
+        J[(u + j) * n + u + j] = gf[j];                 /* dc'_j/dc_j */
+        J[j * n + u + j] = go[j] * dtc * gf[j];         /* dh'_j/dc_j */
+    }
+    free(g);
+}
+
+/* vector-Jacobian products for an output cotangent lam = (lam_h | lam_c): dtheta += ..., dx, dy overwritten */
+static void lstm_vjp(int u, int d, const double* th, const double* y, const double* x,
+                     const double* lam, double* dtheta, double* dx, double* dy) {
+    const double* W = th;
+    const double* U = W + 4 * u * d;
+    double* dW = dtheta;
+    double* dU = dW + 4 * u * d;
+    double* db = dU + 4 * u * u;
+    const double* h = y;
+    const double* c = y + u;
+    double* g = malloc(6 * u * sizeof(double));
+    double *gi = g, *gf = g + u, *gg = g + 2 * u, *go = g + 3 * u, *tc = g + 5 * u;
+    lstm_gates(u, d, th, y, x, gi, gf, gg, go, g + 4 * u, tc);
+    for (int k = 0; k < d; k++) dx[k] = 0.0;
+    for (int k = 0; k < 2 * u; k++) dy[k] = 0.0;
+    for (int j = 0; j < u; j++) {
+        double dcn = lam[u + j] + lam[j] * go[j] * (1.0 - tc[j] * tc[j]);   /* dL/dc'_j */
+        double da[4];
+        da[0] = dcn * gg[j] * gi[j] * (1.0 - gi[j]);           /* input gate, pre-sigmoid   */
+        da[1] = dcn * c[j] * gf[j] * (1.0 - gf[j]);            /* forget gate               */
+        da[2] = dcn * gi[j] * (1.0 - gg[j] * gg[j]);           /* candidate, pre-tanh       */
+        da[3] = lam[j] * tc[j] * go[j] * (1.0 - go[j]);        /* output gate               */
+        dy[u + j] += dcn * gf[j];                              /* direct path c -> c'       */
+        for (int q = 0; q < 4; q++) {
+            for (int k = 0; k < d; k++) {
+                dW[(q * u + j) * d + k] += da[q] * x[k];
+                dx[k] += W[(q * u + j) * d + k] * da[q];
+            }
+            for (int k = 0; k < u; k++) {
+                dU[(q * u + j) * u + k] += da[q] * h[k];
+                dy[k] += U[(q * u + j) * u + k] * da[q];
+            }
+            db[q * u + j] += da[q];
+        }
+    }
+    free(g);
+}
+
 /* --------------------------------------------------------------- affine -- */
 
 static void affine_f(int n, int d, const double* th, const double* h, const double* x, double* out) {
@@ -283,12 +391,14 @@ static void affine_f(int n, int d, const double* th, const double* h, const doub
 
 void oracle_cell_f(const oracle_cell* c, const double* th, const double* h, const double* x, double* out) {
     if (c->cell == ORACLE_CELL_GRU) gru_f(c->n, c->d, th, h, x, out);
+    else if (c->cell == ORACLE_CELL_LSTM) lstm_f(c->n / 2, c->d, th, h, x, out);
     else if (c->cell == ORACLE_CELL_MLP) mlp_f(c, th, h, out);
     else affine_f(c->n, c->d, th, h, x, out);
 }
 
 void oracle_cell_jac(const oracle_cell* c, const double* th, const double* h, const double* x, double* J) {
     if (c->cell == ORACLE_CELL_GRU) gru_jac(c->n, c->d, th, h, x, J);
+    else if (c->cell == ORACLE_CELL_LSTM) lstm_jac(c->n / 2, c->d, th, h, x, J);
     else if (c->cell == ORACLE_CELL_MLP) mlp_jac(c, th, h, J);
     else memcpy(J, th, (size_t)c->n * c->n * sizeof(double));
 }
@@ -297,6 +407,13 @@ void oracle_cell_jac(const oracle_cell* c, const double* th, const double* h, co
 void oracle_gru_vjp(int n, int d, const double* th, const double* h, const double* x,
                     const double* lam, double* dtheta, double* dx, double* dh) {
     gru_vjp(n, d, th, h, x, lam, dtheta, dx, dh);
+}
+
+/* GRU and LSTM: vector-Jacobian products of the cell; dtheta is accumulated into, dx and dh overwritten */
+void oracle_cell_vjp(const oracle_cell* c, const double* th, const double* h, const double* x,
+                     const double* lam, double* dtheta, double* dx, double* dh) {
+    if (c->cell == ORACLE_CELL_GRU) gru_vjp(c->n, c->d, th, h, x, lam, dtheta, dx, dh);
+    else lstm_vjp(c->n / 2, c->d, th, h, x, lam, dtheta, dx, dh);
 }
 
 /* --------------------------------------------- affine pairs and the scan -- */
@@ -465,6 +582,38 @@ void oracle_gru_grad(int n, int d, const double* th, long B, long T, const doubl
         }
     }
     free(lam); free(G); free(dh);
+}
+
+/* The same backward derivative (Sec. 3.1.1 eq. 7) for any recurrent cell with a vector-Jacobian product
+ * (GRU, LSTM); c->n is the state size. */
+void oracle_rnn_grad(const oracle_cell* c, const double* th, long B, long T, const double* x,
+                     const double* y0, const double* y, const double* g,
+                     double* dtheta, double* dx, double* dy0) {
+    int n = c->n, d = c->d;
+    long P = oracle_theta_count(c);
+    memset(dtheta, 0, (size_t)P * sizeof(double));
+    double* lam = malloc((size_t)T * n * sizeof(double));
+    double* J = malloc((size_t)n * n * sizeof(double));
+    double* dh = malloc((size_t)n * sizeof(double));
+    for (long b = 0; b < B; b++) {
+        for (long i = T - 1; i >= 0; i--) {
+            for (int r = 0; r < n; r++) lam[i * n + r] = g[(b * T + i) * n + r];
+            if (i < T - 1) {
+                oracle_cell_jac(c, th, y + (b * T + i) * n, x + (b * T + i + 1) * d, J);   /* J_{i+1} at h = y_i */
+                for (int r = 0; r < n; r++) {
+                    double a = 0.0;
+                    for (int k = 0; k < n; k++) a += J[k * n + r] * lam[(i + 1) * n + k];
+                    lam[i * n + r] += a;
+                }
+            }
+        }
+        for (long i = 0; i < T; i++) {
+            const double* h = (i == 0 ? y0 + b * n : y + (b * T + i - 1) * n);
+            oracle_cell_vjp(c, th, h, x + (b * T + i) * d, lam + i * n, dtheta, dx + (b * T + i) * d, dh);
+            if (i == 0) memcpy(dy0 + b * n, dh, (size_t)n * sizeof(double));
+        }
+    }
+    free(lam); free(J); free(dh);
 }
 
 /* ----------------------------------------- multi-head GRU with strides -- */

@@ -14,6 +14,7 @@ import numpy as np
 
 CELL_GRU = 0
 CELL_MLP_ODE = 1
+CELL_LSTM = 2
 
 
 @dataclass
@@ -75,6 +76,20 @@ def gru_workload(name, seed, B, T, n, d, tol=1e-4, max_iter=50, x_kind="normal",
 
 
 ACT_TANH, ACT_SOFTPLUS = 0, 1
+
+
+def lstm_theta_count(u, d):
+    return 4 * u * d + 4 * u * u + 4 * u
+
+
+def lstm_workload(name, seed, B, T, units, d, tol=1e-4, max_iter=50):
+    """LSTM cell with `units` units (state (h | c) of 2 units entries; Workload.n holds the units): weights and biases
+    ~ N(0, 1/units), x ~ N(0,1), y0 = 0."""
+    rng = np.random.default_rng(seed)
+    theta = _normal(rng, lstm_theta_count(units, d), 1.0 / np.sqrt(units))
+    x = _normal(rng, (B, T, d), 1.0)
+    y0 = np.zeros((B, 2 * units), dtype=np.float32)
+    return Workload(name=name, cell=CELL_LSTM, B=B, T=T, n=units, d=d, tol=tol, max_iter=max_iter, theta=theta, x=x, y0=y0)
 
 
 def mh_gru_workload(name, seed, B, T, n, d, H, K, tol=1e-4, max_iter=50):
