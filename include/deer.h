@@ -33,6 +33,14 @@
  *       q = U_c h + b_hc                     c = tanh(W_c x + b_c + r * q)
  *       f(h, x) = (1 - z) * c + z * h
  *     theta (flat): W[3n,d] (rows r|z|c), U[3n,n] (rows r|z|c), b[3n] (r|z|c), b_hc[n].
+ *   LSTM cell (Sec. 3.4 names it as an instance of the recurrence; cell = DEER_CELL_LSTM, n = number of units u,
+ *   1..16, d = 1..8).  The state is y = (h | c) with 2u entries, so y0 is [B,2u] and y, the guess and dL/dy are
+ *   [B,T,2u]; gates in the order input, forget, candidate, output:
+ *       i = sigmoid(W_i x + U_i h + b_i)   f = sigmoid(W_f x + U_f h + b_f)
+ *       g = tanh(W_g x + U_g h + b_g)      o = sigmoid(W_o x + U_o h + b_o)
+ *       c' = f * c + i * g                 h' = o * tanh(c')
+ *     theta (flat): W[4u,d], U[4u,u], b[4u].  An iteration is a Jacobian kernel followed by the scan over the 2u x 2u
+ *     Jacobians (embedded in the next state size with a scan kernel).
  *   Multi-head GRU with strides (Sec. 4.4, App. B.4; heads > 1 or stride_levels > 1): the state is H heads of n
  *   channels, every head a GRU cell of its own on its own d input channels, and head h looks back
  *   s_h = 2^(h mod K) steps instead of one (the K stride levels are dealt out to the heads in turn):
@@ -67,7 +75,7 @@ typedef enum {
     DEER_ERR_NONFINITE = 5     /* the iteration produced a NaN/Inf; outputs hold the last iterate        */
 } deer_status;
 
-typedef enum { DEER_CELL_GRU = 0, DEER_CELL_MLP_ODE = 1 } deer_cell;
+typedef enum { DEER_CELL_GRU = 0, DEER_CELL_MLP_ODE = 1, DEER_CELL_LSTM = 2 } deer_cell;
 typedef enum { DEER_F32 = 0, DEER_F64 = 1 } deer_dtype;
 typedef enum { DEER_ACT_TANH = 0, DEER_ACT_SOFTPLUS = 1 } deer_activation;
 

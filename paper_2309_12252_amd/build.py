@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdeer_hip.so")
-SOURCES = ["deer_api.hip", "scan_valu.hip", "scan_gru_fused.hip", "scan_gru_dual.hip", "scan_gru_mh.hip", "gru_newton.hip", "scan_mfma.hip", "funceval_gru.hip", "funceval_mlp.hip", "mlp_vjp.hip", "mlp_general.hip", "mlp_vjp_mfma.hip", "gru_vjp_mfma.hip"]
+SOURCES = ["deer_api.hip", "scan_valu.hip", "scan_gru_fused.hip", "scan_gru_dual.hip", "scan_gru_mh.hip", "gru_newton.hip", "scan_mfma.hip", "funceval_gru.hip", "cell_lstm.hip", "funceval_mlp.hip", "mlp_vjp.hip", "mlp_general.hip", "mlp_vjp_mfma.hip", "gru_vjp_mfma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 instructions are switched off on purpose: some of their forms have given wrong results on the target machines
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

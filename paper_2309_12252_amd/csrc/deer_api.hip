@@ -64,6 +64,10 @@ struct Plan {
 size_t theta_count(const deer_config* c) {
     const size_t n = (size_t)c->n;
     if (c->cell == DEER_CELL_GRU) return (size_t)(c->heads > 1 ? c->heads : 1) * (3 * n * (size_t)c->d + 3 * n * n + 4 * n);
+    if (c->cell == DEER_CELL_LSTM) {
+        const size_t u = c->reserved > 0 ? (size_t)c->reserved : n;   // (the configuration the kernels run keeps the units there)
+        return 4 * u * (size_t)c->d + 4 * u * u + 4 * u;
+    }
     const size_t w = (size_t)c->mlp_width;
     const size_t L = c->mlp_hidden_layers >= 1 ? (size_t)c->mlp_hidden_layers : 1;
     return (w * n + w) + (L - 1) * (w * w + w) + (n * w + n);
@@ -84,7 +88,7 @@ int env_int(const char* name, int dflt) {
 
 bool validate(const deer_config* c, std::string& why) {
     if (!c) { why = "config is NULL"; return false; }
-    if (c->cell != DEER_CELL_GRU && c->cell != DEER_CELL_MLP_ODE) { why = "unknown cell"; return false; }
+    if (c->cell != DEER_CELL_GRU && c->cell != DEER_CELL_MLP_ODE && c->cell != DEER_CELL_LSTM) { why = "unknown cell"; return false; }
     if (c->dtype != DEER_F32 && c->dtype != DEER_F64) { why = "unknown dtype"; return false; }
     if (c->B < 1 || c->T < 1 || c->n < 1) { why = "B, T and n must be positive"; return false; }
     if ((long long)c->B * c->T > (1LL << 31) - 1) { why = "B*T must fit 31 bits"; return false; }
@@ -108,6 +112,10 @@ bool is_multihead(const deer_config* c);
 deer_config internal_config(const deer_config* user) {
     deer_config c = *user;
     if (c.cell == DEER_CELL_GRU && !is_multihead(user) && native_n(c.n) > 0) c.n = native_n(c.n);
+    if (c.cell == DEER_CELL_LSTM) {   // state (h | c) of 2 units entries in the next state size with a scan kernel
+        c.reserved = user->n;
+        c.n = native_n(2 * user->n);
+    }
     return c;
 }
 
@@ -121,6 +129,10 @@ bool supported(const deer_config* c, std::string& why) {
         if (H > 64 || K > 8) { why = "multi-head GRU: at most 64 heads and 8 stride levels"; return false; }
         if ((long long)c->B * c->T * H > (1LL << 31) - 1) { why = "B*T*heads must fit 31 bits"; return false; }
         if (env_int("DEER_FUSED", 1) == 0 || env_int("DEER_GRAD_FUSED", 1) == 0) { why = "multi-head GRU runs only with the cell inside the scans"; return false; }
+        return true;
+    }
+    if (c->cell == DEER_CELL_LSTM) {
+        if (!lstm_supported(n, c->d)) { why = "LSTM: 1..16 units and input size 1..8"; return false; }
         return true;
     }
     if (c->cell == DEER_CELL_GRU) {
@@ -245,7 +257,8 @@ Plan make_plan(const deer_config* c) {
     if (p.tiles < 1) p.tiles = 1;
     p.fused = false;
     p.fused_tiles = 0;
-    if (!ode && !p.mfma && c->d <= 8 && env_int("DEER_FUSED", 1) != 0) {
+    const bool gru = c->cell == DEER_CELL_GRU;
+    if (gru && !p.mfma && c->d <= 8 && env_int("DEER_FUSED", 1) != 0) {
         // The fused step spends more time per position on arithmetic and none on loading matrices:
         // shorter serial runs than the plain scan, so that more tiles are in flight.
         static const int kLf[] = {1, 2, 4, 8, 10, 12, 16};
@@ -275,7 +288,7 @@ Plan make_plan(const deer_config* c) {
             if (p.fused_tiles < 1) p.fused_tiles = 1;
         }
     }
-    if (!ode && p.mfma && env_int("DEER_FUSED", 1) != 0 && scan_mfma_fused_supported(c->dtype, c->n, c->d)) {
+    if (gru && p.mfma && env_int("DEER_FUSED", 1) != 0 && scan_mfma_fused_supported(c->dtype, c->n, c->d)) {
         p.fused = true;   // the MFMA scan with the cell inside (its own tile shape)
         p.fused_L = 0;
         p.fused_W = 0;
@@ -283,7 +296,8 @@ Plan make_plan(const deer_config* c) {
         p.fused_tiles = (p.scan_T + ft - 1) / ft;
         if (p.fused_tiles < 1) p.fused_tiles = 1;
     }
-    p.vjp_blocks = c->cell == DEER_CELL_GRU ? gru_vjp_blocks(c->n, (long long)B * T)
+    p.vjp_blocks = c->cell == DEER_CELL_GRU    ? gru_vjp_blocks(c->n, (long long)B * T)
+                   : c->cell == DEER_CELL_LSTM ? lstm_vjp_blocks(c->reserved, (long long)B * T)
                    : mlp_fast_path(c)       ? mlp_vjp_blocks(c->dtype, c->n, c->mlp_width, (long long)B * T)
                                             : mlp_general_vjp_blocks(c->dtype, c->n, c->mlp_width, c->mlp_hidden_layers, (long long)B * T);
 
@@ -327,7 +341,8 @@ struct PadPlan {
 
 static PadPlan make_pad_plan(const deer_config* user, const deer_config* in, size_t base) {
     PadPlan q{};
-    q.on = in->n != user->n;
+    const int user_state = user->cell == DEER_CELL_LSTM ? 2 * user->n : user->n;
+    q.on = in->n != user_state;
     q.total = base;
     if (!q.on) return q;
     const size_t esz = in->dtype == DEER_F32 ? 4 : 8;
@@ -687,15 +702,16 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
     // channels of the result come out
     if (!d_theta || !d_y0 || !d_y || !d_x) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
     const deer_config& g = c->cfg;
-    const int n = c->user.n, np = g.n;
+    const bool lstm = g.cell == DEER_CELL_LSTM;   // its kernels take the parameters as they are
+    const int n = lstm ? 2 * c->user.n : c->user.n, np = g.n;
     const long long rows = (long long)g.B * g.T;
     char* pth = c->ws + c->pad.off_theta;
     char* py0 = c->ws + c->pad.off_y0;
     char* py = c->ws + c->pad.off_y;
-    HIPCHK(c, launch_pad_gru_theta(g.dtype, d_theta, pth, n, np, g.d, 0, c->stream));
+    if (!lstm) HIPCHK(c, launch_pad_gru_theta(g.dtype, d_theta, pth, n, np, g.d, 0, c->stream));
     HIPCHK(c, launch_pad_rows(g.dtype, d_y0, py0, g.B, n, np, 0, c->stream));
     if (d_y_guess) HIPCHK(c, launch_pad_rows(g.dtype, d_y_guess, py, rows, n, np, 0, c->stream));
-    const deer_status st = eval_impl(c, pth, d_x, py0, d_y_guess ? py : nullptr, tol, max_iter, py, iters, final_err, converged);
+    const deer_status st = eval_impl(c, lstm ? d_theta : pth, d_x, py0, d_y_guess ? py : nullptr, tol, max_iter, py, iters, final_err, converged);
     if (st != DEER_OK && st != DEER_ERR_NONFINITE) return st;
     HIPCHK(c, launch_pad_rows(g.dtype, py, d_y, rows, n, np, 1, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -780,9 +796,9 @@ static deer_status eval_impl(deer_ctx* c, const void* d_theta, const void* d_x, 
                 HIPCHK(c, run_scan(c, nullptr, nullptr, d_y0, dst, src, 0, 0, (long long)(T * n), 0, slot, true, 0, gate,
                                    k, d_theta, d_x));
             } else if (!ode) {
-                GruParams gp{d_theta, d_x, d_y0, src, J, rhs, g.B, g.T, g.n, g.d, gate};
+                GruParams gp{d_theta, d_x, d_y0, src, J, rhs, g.B, g.T, g.n, g.d, gate, g.cell == DEER_CELL_LSTM ? g.reserved : 0};
                 prof_begin(c, KIND_FUNCEVAL, k);
-                HIPCHK(c, launch_gru_funceval(g.dtype, gp, c->stream));
+                HIPCHK(c, g.cell == DEER_CELL_LSTM ? launch_lstm_funceval(g.dtype, gp, c->stream) : launch_gru_funceval(g.dtype, gp, c->stream));
                 prof_end(c);
                 HIPCHK(c, run_scan(c, J, rhs, d_y0, dst, src, (long long)(T * n * n), (long long)(T * n),
                                    (long long)(T * n), 0, slot, true, 0, gate, k));
@@ -920,7 +936,8 @@ deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const v
     // channels is zero and stays zero through the dual recurrence)
     if (!d_theta || !d_x || !d_y0 || !d_y || !d_dLdy || !d_dLdtheta) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
     const deer_config& g = c->cfg;
-    const int n = c->user.n, np = g.n;
+    const bool lstm = g.cell == DEER_CELL_LSTM;
+    const int n = lstm ? 2 * c->user.n : c->user.n, np = g.n;
     const long long rows = (long long)g.B * g.T;
     char* pth = c->ws + c->pad.off_theta;
     char* py0 = c->ws + c->pad.off_y0;
@@ -928,13 +945,13 @@ deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const v
     char* pg = c->ws + c->pad.off_g;
     char* pdth = c->ws + c->pad.off_dtheta;
     char* pdy0 = c->ws + c->pad.off_dy0;
-    HIPCHK(c, launch_pad_gru_theta(g.dtype, d_theta, pth, n, np, g.d, 0, c->stream));
+    if (!lstm) HIPCHK(c, launch_pad_gru_theta(g.dtype, d_theta, pth, n, np, g.d, 0, c->stream));
     HIPCHK(c, launch_pad_rows(g.dtype, d_y0, py0, g.B, n, np, 0, c->stream));
     HIPCHK(c, launch_pad_rows(g.dtype, d_y, py, rows, n, np, 0, c->stream));
     HIPCHK(c, launch_pad_rows(g.dtype, d_dLdy, pg, rows, n, np, 0, c->stream));
-    const deer_status st = grad_impl(c, pth, d_x, py0, py, pg, d_dLdx, pdth, d_dLdy0 ? pdy0 : nullptr);
+    const deer_status st = grad_impl(c, lstm ? d_theta : pth, d_x, py0, py, pg, d_dLdx, lstm ? d_dLdtheta : pdth, d_dLdy0 ? pdy0 : nullptr);
     if (st != DEER_OK) return st;
-    HIPCHK(c, launch_pad_gru_theta(g.dtype, pdth, d_dLdtheta, n, np, g.d, 1, c->stream));
+    if (!lstm) HIPCHK(c, launch_pad_gru_theta(g.dtype, pdth, d_dLdtheta, n, np, g.d, 1, c->stream));
     if (d_dLdy0) HIPCHK(c, launch_pad_rows(g.dtype, pdy0, d_dLdy0, g.B, n, np, 1, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
     return DEER_OK;
@@ -960,9 +977,9 @@ static deer_status grad_impl(deer_ctx* c, const void* d_theta, const void* d_x, 
                            Gate{nullptr, 0.0}, -1, d_theta, d_x));
     } else {
         // Jacobians at the given trajectory (the right-hand side output is not used)
-        GruParams gp{d_theta, d_x, d_y0, d_y, J, rhs, g.B, g.T, g.n, g.d, Gate{nullptr, 0.0}};
+        GruParams gp{d_theta, d_x, d_y0, d_y, J, rhs, g.B, g.T, g.n, g.d, Gate{nullptr, 0.0}, g.cell == DEER_CELL_LSTM ? g.reserved : 0};
         prof_begin(c, KIND_FUNCEVAL);
-        HIPCHK(c, launch_gru_funceval(g.dtype, gp, c->stream));
+        HIPCHK(c, g.cell == DEER_CELL_LSTM ? launch_lstm_funceval(g.dtype, gp, c->stream) : launch_gru_funceval(g.dtype, gp, c->stream));
         prof_end(c);
         // lam = (dL/dy) L_G^{-1}: reverse scan with transposed Jacobians
         HIPCHK(c, run_scan(c, J, d_dLdy, nullptr, lam, nullptr, (long long)(T * n * n), (long long)(T * n),
@@ -970,9 +987,11 @@ static deer_status grad_impl(deer_ctx* c, const void* d_theta, const void* d_x, 
     }
     GruVjpParams vp{d_theta, d_x, d_y0, d_y, lam, d_dLdx, d_dLdy0, c->ws + c->plan.off_partial, d_dLdtheta,
                     g.B, g.T, g.n, g.d, c->plan.vjp_blocks, c->plan.mh ? c->plan.mh_H : 0, c->plan.mh ? c->plan.mh_K : 0,
-                    c->plan.mh ? c->ws + c->plan.off_dy0parts : nullptr};
+                    c->plan.mh ? c->ws + c->plan.off_dy0parts : nullptr, g.cell == DEER_CELL_LSTM ? g.reserved : 0};
     prof_begin(c, KIND_VJP);
-    if (!c->plan.mh && gru_vjp_mfma_supported(g.dtype, g.n, g.d) && env_int("DEER_VJP_MFMA", 1) != 0) {
+    if (g.cell == DEER_CELL_LSTM) {
+        HIPCHK(c, launch_lstm_vjp(g.dtype, vp, c->stream));
+    } else if (!c->plan.mh && gru_vjp_mfma_supported(g.dtype, g.n, g.d) && env_int("DEER_VJP_MFMA", 1) != 0) {
         HIPCHK(c, launch_gru_vjp_mfma(vp, c->stream));
         HIPCHK(c, launch_partial_reduce(g.dtype, vp.partial, d_dLdtheta, (long long)theta_count(&g), vp.blocks * 4, c->stream));
     } else {
@@ -989,7 +1008,7 @@ deer_status deer_linrec_solve(deer_ctx* c, const void* d_A, const void* d_b, con
     if (!c) return fail(nullptr, DEER_ERR_INVALID_ARG, "ctx is NULL");
     const deer_config& g = c->cfg;
     if (!d_A || !d_b || !d_y) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
-    if (g.cell != DEER_CELL_GRU || c->plan.mh || c->pad.on)
+    if (g.cell != DEER_CELL_GRU || c->plan.mh || c->pad.on || c->user.cell != DEER_CELL_GRU)
         return fail(c, DEER_ERR_UNSUPPORTED, "deer_linrec_solve needs a plain GRU-shaped context of state size 1, 2, 4, 8, 16 or 32");
     const size_t n = (size_t)g.n, T = (size_t)g.T;
     deer_status st = zero_ctl(c);

@@ -230,6 +230,7 @@ struct GruParams {
     void* J; void* rhs;                                               // outputs [B,T,n,n], [B,T,n]
     int B, T, n, d;
     Gate gate;
+    int units;         // LSTM kernels: units of the cell (n is then the scan's state size, >= 2 units); 0 otherwise
 };
 
 struct GruVjpParams {
@@ -243,6 +244,7 @@ struct GruVjpParams {
     int H, K;          // multi-head GRU with strides: heads and stride levels (0 or 1: the plain GRU); arrays are then
                        // [B][T][H][.], theta and dtheta [H][theta_count], partial [H][blocks * 4][theta_count]
     void* dy0_parts;   // multi-head: [B][H][2^(K-1)][n] scratch for the terms of dL/dy0
+    int units;         // LSTM kernels: units of the cell (n: the scan's state size); 0 otherwise
 };
 
 struct MlpParams {
@@ -313,6 +315,12 @@ hipError_t launch_gru_vjp(int dtype, const GruVjpParams& p, hipStream_t s);
 bool gru_vjp_mfma_supported(int dtype, int n, int d);
 hipError_t launch_gru_vjp_mfma(const GruVjpParams& p, hipStream_t s);
 int gru_vjp_blocks(int n, long long steps);
+// LSTM cell (p.units units, state (h | c) in rows of p.n >= 2 units scalars): Jacobian + right-hand side, and the
+// vector-Jacobian product with its reduction (partial rows = blocks * 4)
+bool lstm_supported(int units, int d);
+int lstm_vjp_blocks(int units, long long steps);
+hipError_t launch_lstm_funceval(int dtype, const GruParams& p, hipStream_t s);
+hipError_t launch_lstm_vjp(int dtype, const GruVjpParams& p, hipStream_t s);
 hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s);
 hipError_t launch_ode_discretise(int dtype, const OdeDiscParams& p, hipStream_t s);
 hipError_t launch_ode_dual(int dtype, const OdeDualParams& p, hipStream_t s);
