@@ -145,21 +145,21 @@ class Bench:
 
     def __init__(self, torch, deer, inputs, dev, k):
         self.torch, self.inputs = torch, inputs
-        self.w = w = inputs.config(k)
+        self.w = w = inputs.config(k) if isinstance(k, int) else k   # a benchmark configuration or any workload
         self.ctx = deer.context_for(w, device=dev)
         t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
         self.th, self.x, self.y0 = t(w.theta), t(w.x), t(w.y0)
-        self.y = torch.empty((w.B, w.T, w.n), dtype=torch.float32, device=dev)
+        self.y = torch.empty(self.ctx._shapes()[0], dtype=torch.float32, device=dev)
         torch.manual_seed(2)
         self.g = torch.randn_like(self.y) / (w.B * w.T)
-        self.S = w.B * w.T
+        self.S = w.B * w.T * max(1, w.heads)   # sequence positions (of every head)
 
     def step(self):
         w = self.w
         return self.ctx.eval(self.th, self.x, self.y0, tol=w.tol, max_iter=w.max_iter, out=self.y)
 
     def grad(self):
-        gx = self.x if self.w.cell == self.inputs.CELL_GRU else None
+        gx = self.x if self.w.cell != self.inputs.CELL_MLP_ODE else None
         return self.ctx.grad(self.th, gx, self.y0, self.y, self.g)
 
     def _timed(self, fn, steps, warmup):
@@ -192,7 +192,7 @@ class Bench:
         totals = {k: prof[k + "_ms"] for k in per_launch}
         dominant = max(totals, key=totals.get)
         its = prof["newton_iterations"] / max(1, prof["newton_launches"])   # iterations inside a one-launch solve
-        roofline = dominant_roofline(dominant, per_launch[dominant], self.w, its)
+        roofline = None if self.w.extra.get("no_roofline") else dominant_roofline(dominant, per_launch[dominant], self.w, its)
         return {"elapsed": elapsed, "ms_per_step": 1e3 * elapsed / steps, "value": self.S * steps / elapsed,
                 "iters": int(iters), "converged": bool(conv), "per_launch": per_launch, "dominant": dominant,
                 "roofline": roofline}
@@ -394,6 +394,25 @@ def main():
                 b.close()
                 del b
                 torch.cuda.empty_cache()
+        # shapes of the paper's other experiments that the library also runs (random weights stand in for trained
+        # ones): the two-body network's field (App. B.2), the multi-head GRU with strides (App. B.4), an LSTM (Sec. 3.4)
+        extras = [inputs.mlp_ode_workload("two_body_shape_mlp_n8_w64_L5_softplus_T10k_B16", 4242, B=16, T=10000, n=8, width=64,
+                                          nhid=5, t0=0.0, t1=10.0, act=inputs.ACT_SOFTPLUS),
+                  inputs.mh_gru_workload("multihead_gru_32x8_strides8_T1024_B64", 4321, B=64, T=1024, n=8, d=8, H=32, K=8),
+                  inputs.lstm_workload("lstm_u8_d4_T50k_B16", 88, B=16, T=50000, units=8, d=4)]
+        for wx in extras:
+            wx.extra["no_roofline"] = True
+            b = Bench(torch, deer, inputs, dev, wx)
+            r = b.time_eval(ksteps, 2)
+            entry = {"ms_per_eval": round(r["ms_per_step"], 5), "sequence_steps_per_s": r["value"],
+                     "newton_iterations": r["iters"], "converged": r["converged"],
+                     "kernels_ms_per_launch": {kk: round(v, 5) for kk, v in r["per_launch"].items() if v > 0}}
+            b.step()
+            entry["deer_grad"] = b.time_grad(ksteps, 2)
+            configs[wx.name] = entry
+            b.close()
+            del b
+            torch.cuda.empty_cache()
         out["configs"] = configs
     bench.close()
     del bench

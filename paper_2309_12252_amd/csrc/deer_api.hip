@@ -10,6 +10,7 @@
 #include <mutex>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "../../include/deer.h"
 #include "deer_common.h"
@@ -52,8 +53,8 @@ struct Plan {
     bool fused;          // GRU with n <= 8: Newton steps run the scan with the cell evaluated in place
     int fused_L, fused_W, fused_tiles;
     bool mh;             // multi-head GRU with strides: the scan's sequences are the heads' strided recurrences
-    int mh_H, mh_K, mh_Sper;   // heads, stride levels, recurrences per batch entry
-    size_t off_dy0parts;
+    int mh_H, mh_K;      // heads, stride levels
+    size_t off_dy0parts, off_mhtable;
     bool grad_fused;     // deer_grad computes the transposed Jacobians inside the reverse scan
     bool need_J;         // some kernel of this plan reads or writes the Jacobian stream [B,T,n,n] and the right-hand side
     int vjp_blocks;
@@ -155,6 +156,21 @@ bool supported(const deer_config* c, std::string& why) {
     return true;
 }
 
+// Multi-head GRU: the tiles of one batch entry, head by head, recurrence by recurrence (first time index r < stride),
+// tile by tile: head << 26 | r << 19 | tile.  The kernels read this list instead of decoding a ticket.
+std::vector<unsigned> mh_table(const deer_config* c, int tile) {
+    const int H = c->heads > 1 ? c->heads : 1, K = c->stride_levels > 1 ? c->stride_levels : 1;
+    std::vector<unsigned> v;
+    for (int h = 0; h < H; ++h) {
+        const long long s = 1LL << (h % K);
+        for (long long r = 0; r < s && r < (long long)c->T; ++r) {
+            const long long len = ((long long)c->T - r + s - 1) / s;
+            for (long long t = 0; t * tile < len; ++t) v.push_back((unsigned)h << 26 | (unsigned)r << 19 | (unsigned)t);
+        }
+    }
+    return v;
+}
+
 Plan make_plan(const deer_config* c) {
     Plan p{};
     p.esz = c->dtype == DEER_F32 ? 4 : 8;
@@ -166,26 +182,19 @@ Plan make_plan(const deer_config* c) {
         // every head's strided recurrences are sequences of the fused small-n kernel (eight wavefronts per tile);
         // positions per lane group from the same kind of estimate as below, over the real tiles of all recurrences
         const int H = c->heads > 1 ? c->heads : 1, K = c->stride_levels > 1 ? c->stride_levels : 1;
-        p.mh_H = H; p.mh_K = K; p.mh_Sper = 0;
-        for (int h = 0; h < H; ++h) p.mh_Sper += 1 << (h % K);
+        p.mh_H = H; p.mh_K = K;
         p.mfma = false; p.W = 8; p.L = 1; p.fused = true; p.fused_W = 8;
         static const int kLm[] = {1, 2, 4};
         double best = 1e300;
         int forced = env_int("DEER_FUSED_L", 0);
         for (int q = 0; q < 3; ++q) {
-            const long long tile = scan_valu_tile(c->n, kLm[q], 8);
-            long long tiles = 0;
-            for (int h = 0; h < H; ++h) {
-                const long long s = 1LL << (h % K);
-                for (long long r = 0; r < s && r < (long long)T; ++r) tiles += (((long long)T - r + s - 1) / s + tile - 1) / tile;
-            }
-            tiles *= (long long)B;
+            const long long tiles = (long long)B * (long long)mh_table(c, scan_valu_tile(c->n, kLm[q], 8)).size();
             double est = (double)((tiles + 255) / 256) * (5.0 + 1.6 * kLm[q]);
             if (forced == kLm[q]) est = -1.0;
             if (est < best) { best = est; p.fused_L = kLm[q]; }
         }
         const int tile = scan_valu_tile(c->n, p.fused_L, 8);
-        p.fused_tiles = (int)((T + tile - 1) / tile);
+        p.fused_tiles = (int)mh_table(c, tile).size();   // tiles of one batch entry over all its recurrences
         p.tile = tile; p.tiles = p.fused_tiles;
         p.grad_fused = true; p.need_J = false;
         long long vb = ((long long)B * (long long)T + 31) / 32;
@@ -195,7 +204,8 @@ Plan make_plan(const deer_config* c) {
         p.off_J = take(0); p.off_rhs = take(0);
         p.off_ybuf = take(B * T * (size_t)H * n * p.esz);
         p.off_Gbar = take(0); p.off_zbar = take(0);
-        const size_t nt = B * (size_t)p.mh_Sper * (size_t)p.fused_tiles;
+        const size_t nt = B * (size_t)p.fused_tiles;
+        p.off_mhtable = take((size_t)p.fused_tiles * 4);
         p.off_aggW = take(nt * (n * n + n) * (p.esz / 4) * 8);
         p.off_inclW = take(nt * n * (p.esz / 4) * 8);
         p.off_barrier = take(0);
@@ -461,11 +471,11 @@ hipError_t run_scan(deer_ctx* c, const void* A, const void* bv, const void* y0, 
 #endif
     hipError_t e;
     if (fused_theta && c->plan.mh) {
-        p.B = g.B * c->plan.mh_Sper;
         p.L = c->plan.fused_L;
         p.W = 8;
         p.tiles = c->plan.fused_tiles;
-        p.mh_H = c->plan.mh_H; p.mh_K = c->plan.mh_K; p.mh_Sper = c->plan.mh_Sper;
+        p.mh_H = c->plan.mh_H; p.mh_K = c->plan.mh_K;
+        p.mh_table = reinterpret_cast<const unsigned*>(c->ws + c->plan.off_mhtable);
         p.mh_P = (long long)(theta_count(&g) / (size_t)c->plan.mh_H);
         prof_begin(c, KIND_FUSED, iter);
         e = launch_scan_gru_mh(g.dtype, g.n, p, fused_theta, fused_x, g.d, c->stream);
@@ -658,6 +668,11 @@ deer_status deer_create(const deer_config* cfg, void* d_workspace, size_t worksp
     c->last_iters = 0;
     if (c->batch < 1) c->batch = 1;
     if (c->batch > 8) c->batch = 8;
+    std::vector<unsigned> table;   // (lives until the synchronisation below)
+    if (e == hipSuccess && plan.mh) {
+        table = mh_table(cfg, plan.tile);
+        e = hipMemcpyAsync(c->ws + plan.off_mhtable, table.data(), table.size() * 4, hipMemcpyHostToDevice, c->stream);
+    }
     if (e == hipSuccess) e = launch_fill_zero(c->ws + plan.off_ctl, ctl_bytes(), c->stream);
     // tagged words must not carry a valid tag by accident: epochs start at 1, so zeros never match
     if (e == hipSuccess)

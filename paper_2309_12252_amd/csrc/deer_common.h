@@ -49,10 +49,11 @@ struct ScanParams {
     void* err;           // max |out - yold| as raw bits of a non-negative scalar, or nullptr
     unsigned* status;    // set non-zero when a bounded wait ran out
     Gate gate;
-    // multi-head GRU with strides (kernels instantiated with MH only): heads, stride levels, recurrences per batch
-    // entry (sum over the heads of their strides), parameters per head
-    int mh_H, mh_K, mh_Sper;
+    // multi-head GRU with strides (kernels instantiated with MH only): heads, stride levels, parameters per head, and
+    // the list of one batch entry's tiles (p.tiles entries: head << 26 | first time index << 19 | tile of its recurrence)
+    int mh_H, mh_K;
     long long mh_P;
+    const unsigned* mh_table;
 #ifdef DEER_SCAN_TIMING
     unsigned long long* timing;   // development builds only: [B * tiles][8] timestamps of the tile's phases
 #endif
@@ -198,11 +199,17 @@ __device__ __forceinline__ bool tagged_get_wait(const unsigned long long* base, 
 }
 
 // max-reduce a non-negative value (NaN mapped to +inf by the caller) into *err as raw bits
+// (the stored maximum only grows: a value that does not exceed what a plain load sees cannot change it, and skipping
+// its read-modify-write keeps a launch with hundreds of thousands of wavefronts from queueing on one address)
 __device__ __forceinline__ void err_atomic_max(void* err, float v) {
-    atomicMax(reinterpret_cast<unsigned*>(err), __float_as_uint(v));
+    unsigned* p = reinterpret_cast<unsigned*>(err);
+    const unsigned bits = __float_as_uint(v);
+    if (bits > __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(p, bits);
 }
 __device__ __forceinline__ void err_atomic_max(void* err, double v) {
-    atomicMax(reinterpret_cast<unsigned long long*>(err), (unsigned long long)__double_as_longlong(v));
+    unsigned long long* p = reinterpret_cast<unsigned long long*>(err);
+    const unsigned long long bits = (unsigned long long)__double_as_longlong(v);
+    if (bits > __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(p, bits);
 }
 
 template <typename S>

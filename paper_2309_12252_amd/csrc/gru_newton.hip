@@ -121,7 +121,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         }
         if (full) gru_rows<S, N, L, DP, true>(w, pr, pq, pc, h0, yv, T, e0, Ar, be);
         else gru_rows<S, N, L, DP, false>(w, pr, pq, pc, h0, yv, T, e0, Ar, be);
-        tile_local<S, N, L, W>(p, sh, Ar, be, b, t, Pex, pex, Mt, vt);
+        tile_local<S, N, L, W>(p, sh, Ar, be, (long long)b * p.tiles, t, Pex, pex, Mt, vt);
     };
 
     const unsigned G = gridDim.x + q.extra_workgroups;   // (extra: test hook, see NewtonParams)
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         // loop, where they would occupy registers for the whole solve.
         ScanParams pk = p;
         asm volatile("" : "+v"(pk.aggW), "+v"(pk.inclW));
-        tile_lookback<S, N, W>(pk, sh, b, t, p.epoch + (unsigned)k, Mt, vt,
+        tile_lookback<S, N, W>(pk, sh, (long long)b * p.tiles, t, p.epoch + (unsigned)k, Mt, vt,
                                p.y0 ? reinterpret_cast<const S*>(p.y0) + (long long)b * N : nullptr);
         S y = tile_start_state<S, N, W>(sh, Pex, pex, wave, i);
         h0 = y;   // the new iterate in front of this group's first position

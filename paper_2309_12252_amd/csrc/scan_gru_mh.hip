@@ -46,7 +46,7 @@ bool scan_gru_mh_supported(int dtype, int n, int d, int L) {
 }
 
 hipError_t launch_scan_gru_mh(int dtype, int n, const ScanParams& p, const void* theta, const void* x, int d, hipStream_t s) {
-    if (!scan_gru_mh_supported(dtype, n, d, p.L) || p.W != 8 || p.delta || !p.yold || p.mh_H < 1 || p.mh_K < 1 || p.mh_Sper < 1)
+    if (!scan_gru_mh_supported(dtype, n, d, p.L) || p.W != 8 || p.delta || !p.yold || p.mh_H < 1 || p.mh_K < 1 || !p.mh_table)
         return hipErrorInvalidValue;
     if (p.reverse && !p.bv) return hipErrorInvalidValue;
     const GruFeed gf{theta, x, d};

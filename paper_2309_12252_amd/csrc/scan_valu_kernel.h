@@ -563,7 +563,7 @@ struct TileShared {
 // prefixes in front of the wavefronts; in wavefront 0, group W-1: (Mt | vt) the tile total (natural order).
 template <typename S, int N, int L, int W>
 __device__ __forceinline__ void tile_local(const ScanParams& p, TileShared<S, N, W>& sh, const S (*Ar)[N], const S* be,
-                                           int b, int t, S* Pex, S& pex, S* Mt, S& vt) {
+                                           long long seq0, int t, S* Pex, S& pex, S* Mt, S& vt) {
     constexpr int NG = 64 / N;
     static_assert(NG >= W, "wavefront 0 scans one wavefront total per group");
     const int tid = threadIdx.x;
@@ -571,7 +571,7 @@ __device__ __forceinline__ void tile_local(const ScanParams& p, TileShared<S, N,
     const int wave = tid >> 6;
     const int group = lane / N;
     const int i = lane % N;
-    const long long slot = (long long)b * p.tiles + t;
+    const long long slot = seq0 + t;
     (void)slot;
     S M[N], v;
 #pragma unroll
@@ -629,7 +629,7 @@ __device__ __forceinline__ void tile_local(const ScanParams& p, TileShared<S, N,
 // tags carry `epoch`).  Called by all threads; ends with a barrier after which sh.carry holds the state
 // entering the tile.  (Mt | vt): the tile total as left by tile_local.
 template <typename S, int N, int W>
-__device__ __forceinline__ void tile_lookback(const ScanParams& p, TileShared<S, N, W>& sh, int b, int t, unsigned epoch,
+__device__ __forceinline__ void tile_lookback(const ScanParams& p, TileShared<S, N, W>& sh, long long seq0, int t, unsigned epoch,
                                               const S* Mt, S vt, const S* y0row) {   // y0row: initial state of this sequence or nullptr (zeros)
     constexpr int NG = 64 / N;
     constexpr int WS = TaggedWords<S>::per_scalar;
@@ -639,13 +639,13 @@ __device__ __forceinline__ void tile_lookback(const ScanParams& p, TileShared<S,
     const int wave = tid >> 6;
     const int group = lane / N;
     const int i = lane % N;
-    const long long slot = (long long)b * p.tiles + t;
+    const long long slot = seq0 + t;
     (void)tid;
     if (wave == 0) {
         const unsigned tagA = (epoch << 2) | TILE_AGGREGATE;
         const unsigned tagI = (epoch << 2) | TILE_INCLUSIVE;
-        const unsigned long long* aggSeq = p.aggW + (long long)b * p.tiles * AGG_WORDS;
-        const unsigned long long* inclSeq = p.inclW + (long long)b * p.tiles * (N * WS);
+        const unsigned long long* aggSeq = p.aggW + seq0 * AGG_WORDS;
+        const unsigned long long* inclSeq = p.inclW + seq0 * (N * WS);
         if (t > 0 && group == W - 1) {
             unsigned long long* mine = p.aggW + slot * AGG_WORDS;
 #pragma unroll
@@ -762,7 +762,7 @@ __device__ __forceinline__ void tile_lookback(const ScanParams& p, TileShared<S,
 // forward through the groups at once.  Otherwise the search goes on exactly as in tile_lookback (light
 // polls, then one fetch).  Called by all threads after tile_local; ends like tile_lookback.
 template <typename S, int N, int W>
-__device__ __forceinline__ void tile_lookback_split(const ScanParams& p, TileShared<S, N, W>& sh, int b, int t,
+__device__ __forceinline__ void tile_lookback_split(const ScanParams& p, TileShared<S, N, W>& sh, long long seq0, int t,
                                                     unsigned epoch, const S* Mt, S vt, const S* y0row) {
     static_assert(W >= 2, "one wavefront publishes while another looks back");
     constexpr int NG = 64 / N;
@@ -773,7 +773,7 @@ __device__ __forceinline__ void tile_lookback_split(const ScanParams& p, TileSha
     const int wave = tid >> 6;
     const int group = lane / N;
     const int i = lane % N;
-    const long long slot = (long long)b * p.tiles + t;
+    const long long slot = seq0 + t;
     (void)slot;
     const unsigned tagA = (epoch << 2) | TILE_AGGREGATE;
     const unsigned tagI = (epoch << 2) | TILE_INCLUSIVE;
@@ -786,8 +786,8 @@ __device__ __forceinline__ void tile_lookback_split(const ScanParams& p, TileSha
         }
         DEER_STAMP(p, slot, 2, lane == 0);
     } else if (wave == 1) {
-        const unsigned long long* aggSeq = p.aggW + (long long)b * p.tiles * AGG_WORDS;
-        const unsigned long long* inclSeq = p.inclW + (long long)b * p.tiles * (N * WS);
+        const unsigned long long* aggSeq = p.aggW + seq0 * AGG_WORDS;
+        const unsigned long long* inclSeq = p.inclW + seq0 * (N * WS);
         int k = -1;
         bool fast = false;
         S Lr[N], hv = S(0), cv = S(0);
@@ -908,13 +908,13 @@ __device__ __forceinline__ void tile_lookback_split(const ScanParams& p, TileSha
 // Steps 1b-4 in one go (see tile_local, tile_lookback and tile_lookback_split).
 template <typename S, int N, int L, int W, bool SPLIT = false>
 __device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N, W>& sh, const S (*Ar)[N], const S* be,
-                                           int b, int t, unsigned epoch, S* Pex, S& pex, const S* y0row) {
+                                           long long seq0, int t, unsigned epoch, S* Pex, S& pex, const S* y0row) {
     S Mt[N], vt = S(0);
 #pragma unroll
     for (int c = 0; c < N; ++c) Mt[c] = S(0);
-    tile_local<S, N, L, W>(p, sh, Ar, be, b, t, Pex, pex, Mt, vt);
-    if constexpr (SPLIT) tile_lookback_split<S, N, W>(p, sh, b, t, epoch, Mt, vt, y0row);
-    else tile_lookback<S, N, W>(p, sh, b, t, epoch, Mt, vt, y0row);
+    tile_local<S, N, L, W>(p, sh, Ar, be, seq0, t, Pex, pex, Mt, vt);
+    if constexpr (SPLIT) tile_lookback_split<S, N, W>(p, sh, seq0, t, epoch, Mt, vt, y0row);
+    else tile_lookback<S, N, W>(p, sh, seq0, t, epoch, Mt, vt, y0row);
 }
 
 // Step 5a: the state in front of this group's first position (entry i), from the tile's carry
@@ -938,9 +938,9 @@ __device__ __forceinline__ S tile_start_state(const TileShared<S, N, W>& sh, con
 // is added on load; used by the dual recurrence of the ODE form, whose matrices are I + O(dt)).
 // MH (with DP > 0): the launch's sequences are the strided heads of a multi-head GRU (Sec. 4.4, App. B.4).  Arrays are
 // [batch][time][head][channel]; head h has its own parameters (gf.theta + h * p.mh_P) and looks back s = 2^(h mod p.mh_K)
-// steps, so it falls into s independent recurrences over the times r, r + s, r + 2s, ...  Sequence number q of the
-// launch (p.B of them: p.mh_Sper per batch entry) is one such recurrence: its positions lie s * H * N scalars apart, its
-// length is ceil((T - r) / s), and tiles past that length return at once.
+// steps, so it falls into s independent recurrences over the times r, r + s, r + 2s, ...; each is a sequence of the scan:
+// its positions lie s * H * N scalars apart and its length is ceil((T - r) / s).  The launch's tiles are the tiles of all
+// recurrences of all p.B batch entries, listed in p.mh_table.
 template <typename S, int N, int L, int W, bool REV, int DP, bool ADDI = false, bool MH = false>
 __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed gf) {
     constexpr bool DUAL = DP > 0 && REV;
@@ -965,8 +965,9 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     __syncthreads();
     const unsigned tk = s_ticket;
     const int b = (int)(tk % (unsigned)p.B);
-    const int t = (int)(tk / (unsigned)p.B);
+    int t = (int)(tk / (unsigned)p.B);
     if (t >= p.tiles) return;
+    long long seq0 = (long long)b * p.tiles;   // slot of the sequence's first tile in the published-word regions
 
     const S* __restrict__ Ab = reinterpret_cast<const S*>(p.A) + (long long)b * p.strideA;
     const S* __restrict__ bb = reinterpret_cast<const S*>(p.bv) + (long long)b * p.strideb;
@@ -982,17 +983,19 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
         if (p.y0) y0row = reinterpret_cast<const S*>(p.y0) + (long long)b * N;
     }
     if constexpr (MH) {
+        // p.tiles counts the tiles of one batch entry over all its recurrences; the table lists them head by head,
+        // recurrence by recurrence, tile by tile: head (6 bits) | first time index r (7 bits) | tile (19 bits).  The
+        // tiles of a recurrence are consecutive entries, so its published words are consecutive slots.
         const int H = p.mh_H;
-        const long long bi = b / p.mh_Sper;
-        int r = b % p.mh_Sper, h = 0;
-        while (r >= (1 << (h % p.mh_K))) {   // heads in order, 2^(h mod K) recurrences each
-            r -= 1 << (h % p.mh_K);
-            ++h;
-        }
+        const int entry = t;
+        const unsigned ent = p.mh_table[entry];
+        const int h = (int)(ent >> 26), r = (int)((ent >> 19) & 127u);
+        t = (int)(ent & 0x7ffffu);
+        seq0 = (long long)b * p.tiles + entry - t;
+        const long long bi = b;
         const long long s = 1LL << (h % p.mh_K);
         const long long Tfull = p.T;
         T = (Tfull - r + s - 1) / s;
-        if ((long long)t * TILE >= T) return;   // (also an empty recurrence: r >= Tfull)
         psy = s * H * N;
         psx = s * H * (long long)gf.d;
         const long long first = ((bi * Tfull + r) * H + h);
@@ -1004,7 +1007,7 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
         gf.theta = reinterpret_cast<const S*>(gf.theta) + (long long)h * p.mh_P;
     }
     const long long e0 = (long long)t * TILE + (long long)(wave * NG + group) * L;
-    const long long slot = (long long)b * p.tiles + t;
+    const long long slot = seq0 + t;
     DEER_STAMP(p, slot, 0, tid == 0);
 
     // ---- 1. this group's pairs (kept for the second walk), then their composition ----
@@ -1049,7 +1052,7 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     S Pex[N], pex;
     // plain scans of n <= 4 look back on wavefront 1 while wavefront 0 scans the wavefront totals (measured on
     // chip-filling streams: +5 % at n = 4, +12 % at n = 2; at n = 8 the extra registers cost more than it gains)
-    tile_carry<S, N, L, W, DP == 0 && N <= 4>(p, sh, Ar, be, b, t, p.epoch, Pex, pex, y0row);
+    tile_carry<S, N, L, W, DP == 0 && N <= 4>(p, sh, Ar, be, seq0, t, p.epoch, Pex, pex, y0row);
 
     // ---- 5. starting state of this group, then the second walk over the resident pairs ----
     S y = tile_start_state<S, N, W>(sh, Pex, pex, wave, i);
