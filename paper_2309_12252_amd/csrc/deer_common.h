@@ -55,12 +55,12 @@ struct ScanParams {
     long long mh_P;
     const unsigned* mh_table;
 #ifdef DEER_SCAN_TIMING
-    unsigned long long* timing;   // development builds only: [B * tiles][8] timestamps of the tile's phases
+    unsigned long long* timing;   // development builds only: [B * tiles][16] timestamps of the tile's phases
 #endif
 };
 
 #ifdef DEER_SCAN_TIMING
-#define DEER_STAMP(p, slot, j, cond) do { if ((p).timing && (cond)) (p).timing[(slot) * 8 + (j)] = wall_clock64(); } while (0)
+#define DEER_STAMP(p, slot, j, cond) do { if ((p).timing && (cond)) (p).timing[(slot) * 16 + (j)] = wall_clock64(); } while (0)
 #else
 #define DEER_STAMP(p, slot, j, cond) do { } while (0)
 #endif

@@ -229,7 +229,7 @@ __global__ __launch_bounds__(64 * W) void gru_newton_kernel(NewtonParams q) {
         }
         ++k;
 #ifdef DEER_SCAN_TIMING
-        if (p.timing && tid == 0) p.timing[((long long)b * p.tiles + t) * 8 + 7] = wall_clock64();
+        if (p.timing && tid == 0) p.timing[((long long)b * p.tiles + t) * 16 + 7] = wall_clock64();
 #endif
         // After an error of e the next one is about e^2 (Newton): with the last known error above the
         // threshold one more iteration is expected and its local half runs before the collection.

@@ -247,6 +247,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
         }
     }
 
+    DEER_STAMP(p, slot, 8, tid == 0);
     if constexpr (FUSE) {
         // The cell at all LW positions of this wavefront at once.  Gate pre-activations are products on the
         // matrix cores with the positions as columns: S_gate = U_gate H, H[:, c] = state in front of position
@@ -337,6 +338,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
             }
         }
         }   // column batches
+        DEER_STAMP(p, slot, 9, tid == 0);
         // dual scan: the transposed Jacobian in A-operand layout, a[i][I][K][v] = J[16K + 4g + v][16I + r]: the
         // row factors come four at a time, the weights are read down a column
         if constexpr (DUAL) {
@@ -400,6 +402,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
         }
     }
 
+    DEER_STAMP(p, slot, 10, tid == 0);
     // ---- 1b. serial composition: P <- A_e P (MFMA), vec <- A_e vec + b_e (VALU) ----
     Acc P[NB][NB];
 #pragma unroll
@@ -460,6 +463,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
         }
     }
 
+    DEER_STAMP(p, slot, 11, tid == 0);
     // wavefront total -> LDS (row-major)
 #pragma unroll
     for (int I = 0; I < NB; ++I) {
@@ -680,7 +684,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
         if (wave == 0) {
             DEER_STAMP(p, slot, 4, lane == 0);
 #ifdef DEER_SCAN_TIMING
-            if (p.timing && lane == 0) p.timing[slot * 8 + 7] = (unsigned long long)(k < 0 ? 0 : k);
+            if (p.timing && lane == 0) p.timing[slot * 16 + 7] = (unsigned long long)(k < 0 ? 0 : k);
 #endif
             // inclusive carry of this tile = (tile total) applied to the carry
             if (lane < N) {

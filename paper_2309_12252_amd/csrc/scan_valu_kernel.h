@@ -737,7 +737,7 @@ __device__ __forceinline__ void tile_lookback(const ScanParams& p, TileShared<S,
         }
         DEER_STAMP(p, slot, 4, lane == 0);
 #ifdef DEER_SCAN_TIMING
-        if (p.timing && lane == 0) p.timing[slot * 8 + 7] = (unsigned long long)(k < 0 ? 0 : k);
+        if (p.timing && lane == 0) p.timing[slot * 16 + 7] = (unsigned long long)(k < 0 ? 0 : k);
 #endif
         if (group == 0) sh.carry[i] = y;
         // inclusive carry of this tile: (tile total) applied to the carry
