@@ -61,8 +61,11 @@ struct ScanParams {
 
 #ifdef DEER_SCAN_TIMING
 #define DEER_STAMP(p, slot, j, cond) do { if ((p).timing && (cond)) (p).timing[(slot) * 16 + (j)] = wall_clock64(); } while (0)
+// per wavefront (up to 8 per tile, two stamps each), in the upper half of the segment
+#define DEER_STAMPW(p, slot, wave, j, cond) do { if ((p).timing && (cond)) (p).timing[((size_t)1 << 19) + ((slot) * 8 + (wave)) * 2 + (j)] = wall_clock64(); } while (0)
 #else
 #define DEER_STAMP(p, slot, j, cond) do { } while (0)
+#define DEER_STAMPW(p, slot, wave, j, cond) do { } while (0)
 #endif
 
 // Source of the pairs when the GRU cell is evaluated inside the scan: the pair at position e is

@@ -85,15 +85,22 @@ __device__ __forceinline__ double plus_lane16(double x) {
            __longlong_as_double((long long)(((unsigned long long)b[1] << 32) | a[1]));
 }
 
-// sum over the 16 lanes of a row (lanes with the same g); every lane of the row gets the total.  DPP only:
-// neighbours in a quad, the other pair of the quad, the other quad of the half row, the other half row.
-__device__ __forceinline__ float row_sum16(float x) {
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, true));    // quad_perm 1,0,3,2
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, true));    // quad_perm 2,3,0,1
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, true));   // row_half_mirror
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, true));   // row_mirror
-    return x;
+// Four sums over the 16 lanes of a row at once: lane r ends with the total of q[r & 3].  Lanes first trade the values they
+// do not keep (with the neighbour, then with the other pair of the quad), the two rotations then add the four quads, which
+// hold the same selection.  11 instructions instead of the 19 of four separate sums and a select.
+__device__ __forceinline__ float row_sum16_select4(const float q[4], int r) {
+    const bool odd = r & 1, upper = r & 2;
+    const float k0 = odd ? q[1] : q[0], s0 = odd ? q[0] : q[1];
+    const float k1 = odd ? q[3] : q[2], s1 = odd ? q[2] : q[3];
+    const float u0 = k0 + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s0), 0xB1, 0xf, 0xf, true));   // quad_perm 1,0,3,2
+    const float u1 = k1 + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s1), 0xB1, 0xf, 0xf, true));
+    const float k = upper ? u1 : u0, s = upper ? u0 : u1;
+    float w = k + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x4E, 0xf, 0xf, true));             // quad_perm 2,3,0,1
+    w += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(w), 0x124, 0xf, 0xf, true));                     // row_ror 4
+    w += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(w), 0x128, 0xf, 0xf, true));                     // row_ror 8
+    return w;
 }
+__device__ __forceinline__ double row_sum16_select4(const double*, int) { return 0.0; }   // fp64 walks the chain instead
 
 // sum over the four lane groups g (lanes r, r+16, r+32, r+48)
 template <typename S>
@@ -127,8 +134,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     __shared__ S sT[N * LD];          // tile total
     __shared__ S sTv[N];
     __shared__ S sC[WAVES][N];        // carry entering each wavefront
-    constexpr int HOPS = (sizeof(S) == 4) ? 8 : 2;   // predecessor totals staged in LDS per round
-    __shared__ S sHop[HOPS][N * LD + N];
+    constexpr int HOPS = (sizeof(S) == 4) ? (WAVES < 8 ? 4 : 8) : 2;   // predecessor totals staged in LDS per round
     __shared__ int s_k;               // hops between this tile and the nearest known inclusive carry
     __shared__ int s_ok;
     // fused cell: rows of [U_gate | W_gate (16 columns, zero padded)] per gate, and the four bias vectors
@@ -136,7 +142,14 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     __shared__ __align__(16) S sU[FUSE ? 3 : 1][FUSE ? N : 1][FUSE ? LDU : 1];
     __shared__ __align__(16) S sB[FUSE ? 4 : 1][FUSE ? N : 1];
     // per wavefront: p_z, s_r, s_t, z and rhs of its LW positions, [scalar][position][row]
-    __shared__ __align__(16) S sS[FUSE ? WAVES : 1][DUAL ? 4 : 5][FUSE ? LW : 1][FUSE ? N : 1];
+    // The staged predecessor totals share their memory: the scalars are last read when the matrices are assembled, the
+    // totals are first staged after the barriers of the tree.
+    constexpr int NSC = DUAL ? 4 : 5;
+    constexpr int SS_ELEMS = FUSE ? WAVES * NSC * LW * N : 1;
+    constexpr int HOP_ELEMS = HOPS * (N * LD + N);
+    __shared__ __align__(16) S sRaw[SS_ELEMS > HOP_ELEMS ? SS_ELEMS : HOP_ELEMS];
+    S (*sHop)[N * LD + N] = reinterpret_cast<S (*)[N * LD + N]>(sRaw);
+    S (*sS)[NSC][FUSE ? LW : 1][FUSE ? N : 1] = reinterpret_cast<S (*)[NSC][FUSE ? LW : 1][FUSE ? N : 1]>(sRaw);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -152,15 +165,28 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
         const int d = gf.d;
         const S* __restrict__ U = th + 3 * N * d;
         const S* __restrict__ bias = U + 3 * N * N;
-        for (int q = tid; q < 3 * N * (N + 16); q += 64 * WAVES) {
-            const int gate = q / (N * (N + 16)), rem = q % (N * (N + 16));
-            const int row = rem / (N + 16), col = rem % (N + 16);
-            S val;
-            if (col < N) val = U[(gate * N + row) * N + col];
-            else val = (col - N < d) ? th[(gate * N + row) * d + (col - N)] : S(0);
-            sU[gate][row][col] = val;
+        // sixteen threads per row, four columns each (the last 16 - (N + 16) / 4 of them idle): one 16-byte load and
+        // store per gate for the U part, guarded scalars for the d input columns
+        const int c4 = tid & 15;
+        for (int row = tid >> 4; row < N; row += 4 * WAVES) {
+            if (c4 < (N + 16) / 4) {
+#pragma unroll
+                for (int gate = 0; gate < 3; ++gate) {
+                    S val[4];
+                    if (4 * c4 < N) {
+                        vload<S, 4>(val, U + (gate * N + row) * N + 4 * c4);
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int col = 4 * c4 + v - N;
+                            val[v] = (col < d) ? th[(gate * N + row) * d + col] : S(0);
+                        }
+                    }
+                    vstore<S, 4>(&sU[gate][row][4 * c4], val);
+                }
+            }
         }
-        for (int q = tid; q < 4 * N; q += 64 * WAVES) sB[q / N][q % N] = bias[q];
+        if (tid < 4 * N) sB[tid / N][tid % N] = bias[tid];
     }
     __syncthreads();
     const unsigned tk = s_ticket;
@@ -375,13 +401,19 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
             }
         }
         // J of every position in A-operand layout from its row's three factors (weights from LDS in that layout)
+        // (a position past the end takes the factors 0, 0, 0, 1 and the vector 0: the identity pair, at five selects a
+        // row instead of one per entry; the diagonal term is one multiply-add with the lane's own 0/1 indicator)
+        S dsel[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dsel[v] = (r == Lay<S>::idx(g, v)) ? S(1) : S(0);
 #pragma unroll
         for (int i = 0; i < (DUAL ? 0 : LW); ++i) {
             const bool past = e0 + i >= p.T;
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
                 const int row = 16 * I + r;
-                const S pz = sSw[0][i][row], sr = sSw[1][i][row], st = sSw[2][i][row], zz = sSw[3][i][row];
+                const S pz = past ? S(0) : sSw[0][i][row], sr = past ? S(0) : sSw[1][i][row];
+                const S st = past ? S(0) : sSw[2][i][row], zz = past ? S(1) : sSw[3][i][row];
                 const S rhs = sSw[4][i][row];
 #pragma unroll
                 for (int K = 0; K < NB; ++K) {
@@ -392,9 +424,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         S jv = pz * Uz[v] + (sr * Uc[v] + st * Ur[v]);
-                        const bool diag = (I == K) && (r == Lay<S>::idx(g, v));
-                        jv += diag ? zz : S(0);
-                        a[i][I][K][v] = past ? (diag ? S(1) : S(0)) : jv;
+                        if (I == K) jv += dsel[v] * zz;
+                        a[i][I][K][v] = jv;
                     }
                 }
                 bel[i][I] = past ? S(0) : rhs;
@@ -403,6 +434,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     }
 
     DEER_STAMP(p, slot, 10, tid == 0);
+    DEER_STAMPW(p, slot, wave, 0, lane == 0);
     // ---- 1b. serial composition: P <- A_e P (MFMA), vec <- A_e vec + b_e (VALU) ----
     Acc P[NB][NB];
 #pragma unroll
@@ -464,6 +496,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     }
 
     DEER_STAMP(p, slot, 11, tid == 0);
+    DEER_STAMPW(p, slot, wave, 1, lane == 0);
     // wavefront total -> LDS (row-major)
 #pragma unroll
     for (int I = 0; I < NB; ++I) {
@@ -712,7 +745,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     S emax = S(0);
     if constexpr (PAR) {
         // y_e = (running matrix of e) carry + (running vector of e): lane (g, r) multiplies its column r of rows 4g + v
-        // with entry r of the carry; the sums over the row's 16 lanes leave y[16 I + 4g + v] in every lane of row g, and
+        // with entry r of the carry; the sums over the row's 16 lanes leave y[16 I + 4g + (r & 3)] in lane r of row g, and
         // the four lanes r = 4g .. 4g+3 of each row own the 16 entries in memory order
         S cr[NB];
 #pragma unroll
@@ -730,10 +763,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
                     S q = S(0);
 #pragma unroll
                     for (int J = 0; J < NB; ++J) q += a[i][I][J][v] * cr[J];
-                    t[v] = row_sum16(q);
+                    t[v] = q;
                 }
-                const S lo = (r & 1) ? t[1] : t[0], hi = (r & 1) ? t[3] : t[2];
-                const S y = ((r & 2) ? hi : lo) + bel[i][I];
+                const S y = row_sum16_select4(t, r) + bel[i][I];
                 if (e < p.T && owner) {
                     S wv = y;
                     if (!DUAL && oldb) {
@@ -811,6 +843,13 @@ hipError_t launch_n(const ScanParams& p, hipStream_t s) {
 template <int N> struct MfmaFusedShape;
 template <> struct MfmaFusedShape<16> { static constexpr int LW = 24, WAVES = 4; };
 template <> struct MfmaFusedShape<32> { static constexpr int LW = 8, WAVES = 8; };
+// n = 32 on four wavefronts: two workgroups share a compute unit, each one's serial phases (tree, look-back, fold)
+// run under the other's compositions
+struct MfmaFusedShape32Half { static constexpr int LW = 8, WAVES = 4; };
+static int fused_waves32() {
+    static const int w = [] { const char* e = getenv("DEER_FUSED_W"); return (e && atoi(e) == 4) ? 4 : 8; }();
+    return w;
+}
 
 template <int N>
 hipError_t launch_fused_n(const ScanParams& p, const GruFeed& gf, hipStream_t s) {
@@ -820,6 +859,9 @@ hipError_t launch_fused_n(const ScanParams& p, const GruFeed& gf, hipStream_t s)
                      // per wavefront measured 10 % slower)
         hipLaunchKernelGGL((scan_mfma_kernel<float, N, MfmaShape<float, N>::LW, MfmaShape<float, N>::WAVES, true, true>), grid,
                            dim3(64 * MfmaShape<float, N>::WAVES), 0, s, p, gf);
+    else if (N == 32 && fused_waves32() == 4)
+        hipLaunchKernelGGL((scan_mfma_kernel<float, 32, MfmaFusedShape32Half::LW, MfmaFusedShape32Half::WAVES, false, true>), grid,
+                           dim3(64 * MfmaFusedShape32Half::WAVES), 0, s, p, gf);
     else
         hipLaunchKernelGGL((scan_mfma_kernel<float, N, LW, WAVES, false, true>), grid, dim3(64 * WAVES), 0, s, p, gf);
     return hipGetLastError();
@@ -835,6 +877,7 @@ int scan_mfma_tile(int dtype, int n) {
 }
 
 int scan_mfma_fused_tile(int n) {
+    if (n == 32 && fused_waves32() == 4) return MfmaFusedShape32Half::LW * MfmaFusedShape32Half::WAVES;
     return n == 16 ? MfmaFusedShape<16>::LW * MfmaFusedShape<16>::WAVES : MfmaFusedShape<32>::LW * MfmaFusedShape<32>::WAVES;
 }
 
