@@ -134,7 +134,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     __shared__ S sT[N * LD];          // tile total
     __shared__ S sTv[N];
     __shared__ S sC[WAVES][N];        // carry entering each wavefront
-    constexpr int HOPS = (sizeof(S) == 4) ? (WAVES < 8 ? 4 : 8) : 2;   // predecessor totals staged in LDS per round
+    constexpr int HOPS = (sizeof(S) == 4) ? ((WAVES < 8 && N == 32) ? 4 : 8) : 2;   // predecessor totals staged in LDS per round
     __shared__ int s_k;               // hops between this tile and the nearest known inclusive carry
     __shared__ int s_ok;
     // fused cell: rows of [U_gate | W_gate (16 columns, zero padded)] per gate, and the four bias vectors
@@ -153,7 +153,12 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    // Segment of the tile (in scan order) of each wavefront.  Wavefronts w and w + 4 of a workgroup share a SIMD, and the
+    // rounds of the tree keep the segments 0, 2, 4, 6, then 0 and 4, busy: those go to four different SIMDs, and each SIMD's
+    // second wavefront takes the odd segment that evens out the serial carry steps of step 4 (segment s makes s of them).
+    const int pw = tid >> 6;
+    // (four-wavefront workgroups have a SIMD per wavefront and keep the plain order: measured faster)
+    const int wave = (WAVES < 8) ? pw : ((pw < WAVES / 2) ? 2 * pw : (WAVES - 1) - 2 * (pw - WAVES / 2));
     const int g = lane >> 4;
     const int r = lane & 15;
 
@@ -287,10 +292,16 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
         const S* __restrict__ xb = reinterpret_cast<const S*>(gf.x) + (long long)b * p.T * d;
         const S* __restrict__ y0p = reinterpret_cast<const S*>(p.y0);
         S (*sSw)[LW][N] = sS[wave];
+        // n = 32 with eight positions per wavefront: two neighbouring wavefronts share the work by row block instead of
+        // by position -- each takes one 16-row block of the 16 positions of the pair, so that all 16 columns of every
+        // matrix instruction and all lanes of the elementwise part carry a position -- and exchange the scalars through
+        // their LDS slices (one more barrier).
+        constexpr bool PAIR = NB == 2 && LW == 8 && WAVES % 2 == 0;
+        const long long e0g = PAIR ? (long long)t * TILE + (long long)(wave & ~1) * LW : e0;
 #pragma unroll
-        for (int cb = 0; cb < (LW + 15) / 16; ++cb) {
-        const int c = (16 * cb + r < LW) ? 16 * cb + r : LW - 1;   // position handled as a column (lanes beyond LW repeat the last)
-        const long long ecol = e0 + c;
+        for (int cb = 0; cb < (PAIR ? 1 : (LW + 15) / 16); ++cb) {
+        const int c = PAIR ? r : ((16 * cb + r < LW) ? 16 * cb + r : LW - 1);   // position handled as a column (lanes beyond LW repeat the last)
+        const long long ecol = e0g + c;
         const S* hp;
         long long exl;
         if constexpr (!REV) {
@@ -313,8 +324,11 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
             const int k = 4 * kk + g;
             xB[kk] = xb[exl * d + (k < d ? k : d - 1)];   // weights beyond d are zero
         }
+        S (*sSd)[LW][N] = PAIR ? sS[(wave & ~1) + (c >> 3)] : sSw;
+        const int cl = PAIR ? (c & 7) : c;
 #pragma unroll
-        for (int I = 0; I < NB; ++I) {
+        for (int Iq = 0; Iq < (PAIR ? 1 : NB); ++Iq) {
+            const int I = PAIR ? (wave & 1) : Iq;
             Acc uh[3], wx[3];
 #pragma unroll
             for (int gate = 0; gate < 3; ++gate) {
@@ -355,15 +369,16 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
                 o_rhs[v] = f - (pz * uh[1][v] + (sr * uh[2][v] + (st * uh[0][v] + z * h)));
             }
             (void)o_rhs;
-            if (16 * cb + r < LW) {
-                vstore<S, 4>(&sSw[0][c][16 * I + 4 * g], o_pz);
-                vstore<S, 4>(&sSw[1][c][16 * I + 4 * g], o_sr);
-                vstore<S, 4>(&sSw[2][c][16 * I + 4 * g], o_st);
-                vstore<S, 4>(&sSw[3][c][16 * I + 4 * g], o_z);
-                if constexpr (!DUAL) vstore<S, 4>(&sSw[4][c][16 * I + 4 * g], o_rhs);
+            if (PAIR || 16 * cb + r < LW) {
+                vstore<S, 4>(&sSd[0][cl][16 * I + 4 * g], o_pz);
+                vstore<S, 4>(&sSd[1][cl][16 * I + 4 * g], o_sr);
+                vstore<S, 4>(&sSd[2][cl][16 * I + 4 * g], o_st);
+                vstore<S, 4>(&sSd[3][cl][16 * I + 4 * g], o_z);
+                if constexpr (!DUAL) vstore<S, 4>(&sSd[4][cl][16 * I + 4 * g], o_rhs);
             }
         }
         }   // column batches
+        if constexpr (PAIR) __syncthreads();
         DEER_STAMP(p, slot, 9, tid == 0);
         // dual scan: the transposed Jacobian in A-operand layout, a[i][I][K][v] = J[16K + 4g + v][16I + r]: the
         // row factors come four at a time, the weights are read down a column
@@ -570,6 +585,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
 #pragma unroll
                 for (int J = 0; J < NB; ++J) P[I][J] = Pn[I][J];
         }
+        DEER_STAMP(p, slot, (stride == 1 ? 12 : (stride == 2 ? 13 : 14)), tid == 0);
     }
 
     // ---- 3. look-back (wavefront 0 now holds the tile total) ----
