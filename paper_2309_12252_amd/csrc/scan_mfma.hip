@@ -531,8 +531,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
 #pragma unroll 1
     for (int stride = 1; stride < WAVES; stride <<= 1) {
         if (stride > 1) {
-            // partial totals of the previous round that are a left factor in this round
-            if ((wave % (2 * stride)) == stride) {
+            // partial totals of the previous round that are a left factor in this round; in front of the last round
+            // wavefront 0 also leaves the total of the tile's first half (slot 0 has no other use): the carries of
+            // the second half start from it in step 4
+            if ((wave % (2 * stride)) == stride || (2 * stride == WAVES && wave == 0)) {
 #pragma unroll
                 for (int I = 0; I < NB; ++I) {
 #pragma unroll
@@ -748,7 +750,17 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     if (tid == 0 && s_ok == 0) atomicOr(p.status, 1u);
 
     // ---- 4. carry entering this wavefront, then the second walk over the resident pairs ----
-    for (int w = 0; w < wave; ++w) {
+    const int w0 = (WAVES >= 4 && wave >= WAVES / 2) ? WAVES / 2 : 0;
+    if (w0 > 0) {
+        // second half of the tile: (total of the first half) applied to the tile's carry
+        S s = S(0);
+        if (lane < N) {
+            s = sPv[0][lane];
+            for (int q = 0; q < N; ++q) s += sP[0][lane * LD + q] * sC[0][q];
+        }
+        if (lane < N) sC[wave][lane] = s;
+    }
+    for (int w = w0; w < wave; ++w) {
         // sC[wave] <- M_w * (carry entering w) + v_w, built up in place from sC[0]
         S s = S(0);
         if (lane < N) {
