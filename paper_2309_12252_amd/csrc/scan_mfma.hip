@@ -591,30 +591,37 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     }
 
     // ---- 3. look-back (wavefront 0 now holds the tile total) ----
+    // The tile total goes to LDS (for the inclusive carry); from there the other wavefronts send it to HBM for the
+    // successors (tagged words, consecutive lanes to consecutive words) while wavefront 0 already looks back.
     if (wave == 0) {
-        // tile total -> LDS (for the inclusive carry) and HBM (for successors, as tagged words)
+#pragma unroll
+        for (int I = 0; I < NB; ++I) {
+#pragma unroll
+            for (int J = 0; J < NB; ++J)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sT[(16 * I + Lay<S>::idx(g, v)) * LD + 16 * J + r] = P[I][J][v];
+            if (g == 0) sTv[16 * I + r] = vr[I];
+        }
+    }
+    __syncthreads();
+    if (wave != 0) {
+        if (t > 0) {
+            constexpr int WS = TaggedWords<S>::per_scalar;
+            constexpr int AGG_WORDS = (N * N + N) * WS;
+            const unsigned tagA = (p.epoch << 2) | TILE_AGGREGATE;
+            unsigned long long* mine = p.aggW + slot * AGG_WORDS;
+            for (int e = tid - 64; e < N * N + N; e += 64 * (WAVES - 1)) {
+                const S val = (e < N * N) ? sT[(e / N) * LD + (e % N)] : sTv[e - N * N];
+                TaggedWords<S>::put(mine, e, val, tagA);
+            }
+        }
+    } else {
         constexpr int WS = TaggedWords<S>::per_scalar;
         constexpr int AGG_WORDS = (N * N + N) * WS;
         const unsigned tagA = (p.epoch << 2) | TILE_AGGREGATE;
         const unsigned tagI = (p.epoch << 2) | TILE_INCLUSIVE;
         const unsigned long long* aggSeq = p.aggW + (long long)b * p.tiles * AGG_WORDS;
         const unsigned long long* inclSeq = p.inclW + (long long)b * p.tiles * (N * WS);
-        unsigned long long* mine = p.aggW + slot * AGG_WORDS;
-#pragma unroll
-        for (int I = 0; I < NB; ++I) {
-#pragma unroll
-            for (int J = 0; J < NB; ++J)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    sT[(16 * I + Lay<S>::idx(g, v)) * LD + 16 * J + r] = P[I][J][v];
-                    if (t > 0) TaggedWords<S>::put(mine, (16 * I + Lay<S>::idx(g, v)) * N + 16 * J + r, P[I][J][v], tagA);
-                }
-            if (g == 0) {
-                sTv[16 * I + r] = vr[I];
-                if (t > 0) TaggedWords<S>::put(mine, N * N + 16 * I + r, vr[I], tagA);
-            }
-        }
-
         DEER_STAMP(p, slot, 2, lane == 0);
         // lane j inspects predecessor t-1-j (index -1 is the given initial state): inclusive carry
         // known, total known, or nothing yet, judged by one word of each
