@@ -399,7 +399,9 @@ def main():
         extras = [inputs.mlp_ode_workload("two_body_shape_mlp_n8_w64_L5_softplus_T10k_B16", 4242, B=16, T=10000, n=8, width=64,
                                           nhid=5, t0=0.0, t1=10.0, act=inputs.ACT_SOFTPLUS),
                   inputs.mh_gru_workload("multihead_gru_32x8_strides8_T1024_B64", 4321, B=64, T=1024, n=8, d=8, H=32, K=8),
-                  inputs.lstm_workload("lstm_u8_d4_T50k_B16", 88, B=16, T=50000, units=8, d=4)]
+                  inputs.lstm_workload("lstm_u8_d4_T50k_B16", 88, B=16, T=50000, units=8, d=4),
+                  # the largest state size of the paper's speed table (Table 4: n = 64, 10k steps, batch 16)
+                  inputs.gru_workload("gru_n64_T10k_B16", 6464, B=16, T=10000, n=64, d=8)]
         for wx in extras:
             wx.extra["no_roofline"] = True
             b = Bench(torch, deer, inputs, dev, wx)

@@ -84,8 +84,9 @@ typedef struct {
     int32_t dtype;              /* deer_dtype                                                            */
     int32_t B;                  /* batch: independent sequences                                          */
     int32_t T;                  /* GRU: number of steps; MLP_ODE: number of grid points (>= 2)           */
-    int32_t n;                  /* state size.  GRU: 1..32 (1, 2, 4, 8, 16, 32 have kernels of their own; any other */
-                                /* size runs embedded in the next of those, with identical results);     */
+    int32_t n;                  /* state size.  GRU: 1..64, above 32 in fp32 only (1, 2, 4, 8, 16, 32, 64 have  */
+                                /* kernels of their own; any other size runs embedded in the next of     */
+                                /* those, with identical results);                                       */
                                 /* MLP_ODE: 2, 4 or 8; multi-head GRU: 2, 4 or 8 per head                */
     int32_t d;                  /* GRU input size (1..32); ignored for MLP_ODE                           */
     int32_t mlp_width;          /* MLP_ODE hidden width w: a multiple of 4, 4..64; ignored for GRU       */

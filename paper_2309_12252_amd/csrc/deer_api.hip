@@ -100,7 +100,7 @@ bool validate(const deer_config* c, std::string& why) {
 
 // smallest state size with kernels of its own that holds n channels (0: none)
 int native_n(int n) {
-    for (int v = 1; v <= 32; v <<= 1)
+    for (int v = 1; v <= 64; v <<= 1)
         if (n <= v) return v;
     return 0;
 }
@@ -137,8 +137,9 @@ bool supported(const deer_config* c, std::string& why) {
         return true;
     }
     if (c->cell == DEER_CELL_GRU) {
-        // 1, 2, 4, 8, 16 and 32 have kernels; the sizes in between run embedded in the next one of those
-        if (n > 32) { why = "GRU state size must be at most 32"; return false; }
+        // 1, 2, 4, 8, 16, 32 and (fp32) 64 have kernels; the sizes in between run embedded in the next one of those
+        if (n > 64) { why = "GRU state size must be at most 64"; return false; }
+        if (n > 32 && c->dtype != DEER_F32) { why = "GRU state sizes above 32 run in fp32 only"; return false; }
         if (c->d < 1 || c->d > 32) { why = "GRU input size must be 1..32"; return false; }
     } else {
         if (!(n == 2 || n == 4 || n == 8)) { why = "MLP_ODE state size must be 2, 4 or 8"; return false; }
@@ -1065,7 +1066,7 @@ deer_status deer_linrec_solve_static(int32_t dtype, int32_t B, int32_t T, int32_
     std::string why;
     if (!validate(&cfg, why)) return fail(nullptr, DEER_ERR_INVALID_ARG, why);
     if (!supported(&cfg, why)) return fail(nullptr, DEER_ERR_UNSUPPORTED, why);
-    if (native_n(n) != n) return fail(nullptr, DEER_ERR_UNSUPPORTED, "the scan alone needs a state size of 1, 2, 4, 8, 16 or 32");
+    if (native_n(n) != n) return fail(nullptr, DEER_ERR_UNSUPPORTED, "the scan alone needs a state size of 1, 2, 4, 8, 16, 32 or (fp32) 64");
     if (!d_A || !d_b || !d_y) return fail(nullptr, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
     // the part of the plan the scan uses, re-based to the start of the static array
     Plan plan = make_plan(&cfg);

@@ -431,6 +431,9 @@ hipError_t launch_fe_s(const GruParams& p, hipStream_t s) {
         case 8: return launch_fe<S, 8>(p, s);
         case 16: return launch_fe<S, 16>(p, s);
         case 32: return launch_fe<S, 32>(p, s);
+        case 64:   // fp32 only
+            if constexpr (sizeof(S) == 4) return launch_fe<S, 64>(p, s);
+            return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }
@@ -504,6 +507,9 @@ hipError_t launch_vjp_s(const GruVjpParams& p, hipStream_t s) {
         case 8: return launch_vjp<S, 8>(p, s);
         case 16: return launch_vjp<S, 16>(p, s);
         case 32: return launch_vjp<S, 32>(p, s);
+        case 64:   // fp32 only
+            if constexpr (sizeof(S) == 4) return launch_vjp<S, 64>(p, s);
+            return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }

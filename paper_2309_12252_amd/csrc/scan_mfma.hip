@@ -134,7 +134,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     __shared__ S sT[N * LD];          // tile total
     __shared__ S sTv[N];
     __shared__ S sC[WAVES][N];        // carry entering each wavefront
-    constexpr int HOPS = (sizeof(S) == 4) ? ((WAVES < 8 && N == 32) ? 4 : 8) : 2;   // predecessor totals staged in LDS per round
+    constexpr int HOPS = (sizeof(S) == 4) ? (N == 64 ? 2 : ((WAVES < 8 && N == 32) ? 4 : 8)) : 2;   // predecessor totals staged in LDS per round
     __shared__ int s_k;               // hops between this tile and the nearest known inclusive carry
     __shared__ int s_ok;
     // fused cell: rows of [U_gate | W_gate (16 columns, zero padded)] per gate, and the four bias vectors
@@ -859,6 +859,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
 template <typename S, int N> struct MfmaShape;
 template <> struct MfmaShape<float, 16> { static constexpr int LW = 16, WAVES = 4; };
 template <> struct MfmaShape<float, 32> { static constexpr int LW = 8, WAVES = 8; };
+// n = 64 (fp32 only): 64 registers per matrix, two positions per wavefront; four wavefronts, because the wavefront totals
+// (16.6 KB each) fill the LDS
+template <> struct MfmaShape<float, 64> { static constexpr int LW = 2, WAVES = 4; };
 template <> struct MfmaShape<double, 16> { static constexpr int LW = 8, WAVES = 8; };
 template <> struct MfmaShape<double, 32> { static constexpr int LW = 4, WAVES = 8; };
 
@@ -905,6 +908,7 @@ hipError_t launch_fused_n(const ScanParams& p, const GruFeed& gf, hipStream_t s)
 }  // namespace
 
 int scan_mfma_tile(int dtype, int n) {
+    if (dtype == 0 && n == 64) return MfmaShape<float, 64>::LW * MfmaShape<float, 64>::WAVES;
     if (dtype == 0) return n == 16 ? MfmaShape<float, 16>::LW * MfmaShape<float, 16>::WAVES
                                    : MfmaShape<float, 32>::LW * MfmaShape<float, 32>::WAVES;
     return n == 16 ? MfmaShape<double, 16>::LW * MfmaShape<double, 16>::WAVES
@@ -925,6 +929,7 @@ hipError_t launch_scan_mfma_fused(int n, const ScanParams& p, const void* theta,
 }
 
 hipError_t launch_scan_mfma(int dtype, int n, const ScanParams& p, hipStream_t s) {
+    if (n == 64) return dtype == 0 ? launch_n<float, 64>(p, s) : hipErrorInvalidValue;
     if (n != 16 && n != 32) return hipErrorInvalidValue;
     if (dtype == 0) return n == 16 ? launch_n<float, 16>(p, s) : launch_n<float, 32>(p, s);
     return n == 16 ? launch_n<double, 16>(p, s) : launch_n<double, 32>(p, s);

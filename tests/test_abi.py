@@ -33,8 +33,12 @@ def test_theta_count_and_validation_on_host():
     assert deer.theta_count(mlp) == 32 * 8 + 32 + 32 * 32 + 32 + 8 * 32 + 8
     assert deer.workspace_bytes(mlp) > 2 * 8 * 100000 * 8 * 8 * 4 - 8 * 64 * 4
     with pytest.raises(deer.DeerError) as e:
-        deer.workspace_bytes(deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 1, 10, 33, d=2))
+        deer.workspace_bytes(deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 1, 10, 65, d=2))
     assert e.value.status == deer.DEER_ERR_UNSUPPORTED
+    with pytest.raises(deer.DeerError) as e:   # state sizes above 32 run in fp32 only
+        deer.workspace_bytes(deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F64, 1, 10, 64, d=2))
+    assert e.value.status == deer.DEER_ERR_UNSUPPORTED
+    assert deer.workspace_bytes(deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 1, 10, 64, d=2)) > 0
     with pytest.raises(deer.DeerError) as e:
         deer.workspace_bytes(deer.make_config(deer.DEER_CELL_GRU, deer.DEER_F32, 0, 10, 4, d=2))
     assert e.value.status == deer.DEER_ERR_INVALID_ARG

@@ -42,6 +42,13 @@ def test_dual_scan_matches_serial_solve(n, dtype):
         run_case(n, B, T, dtype, True, 200 * n + k)
 
 
+@pytest.mark.parametrize("reverse", [False, True])
+def test_scan_of_64_by_64_matrices(reverse):
+    # the largest state size of the paper's speed table (Sec. 4.1, Table 4); fp32 only
+    for k, (B, T) in enumerate(SHAPES + [(2, 3000)]):
+        run_case(64, B, T, deer.DEER_F32, reverse, 6400 + k)
+
+
 @pytest.mark.parametrize("n,B,T", [(8, 2, 50000), (2, 1, 300000), (16, 2, 20000), (32, 1, 10000)])
 def test_many_tiles_per_sequence(n, B, T):
     # long chains of tiles: exercises the look-back window and the carry chain

@@ -39,6 +39,15 @@ def test_state_and_input_sizes_outside_the_menu(n, d, dtype):
         forward_and_backward(w, dtype)
 
 
+@pytest.mark.parametrize("n,d", [(64, 8), (40, 3), (64, 32)])
+def test_state_sizes_up_to_64(n, d):
+    # Sec. 4.1, Table 4 lists n = 64; these sizes run in fp32 only (cell kernel, matrix-core scan, vector-ALU VJP)
+    for k, (B, T) in enumerate([(2, 9), (3, 700), (2, 2100)]):
+        w = inputs.gru_workload("shape_n%d_d%d_T%d" % (n, d, T), 60 * n + d + k, B=B, T=T, n=n, d=d)
+        w.y0 = np.random.default_rng(k).standard_normal((B, n)).astype(np.float32)
+        forward_and_backward(w, deer.DEER_F32)
+
+
 def test_output_comparison_shape():
     # Sec. 4.1, Fig. 3: an untrained GRU with 32 hidden and 32 input channels on 10,000 steps, DEER against the
     # sequential evaluation (here: the oracle's sequential fp64 evaluation)
