@@ -17,12 +17,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "deer_oracle.c")
 _LIB = os.path.join(_HERE, "libdeer_oracle.so")
 
-CELL_GRU, CELL_MLP, CELL_AFFINE, CELL_LSTM = 0, 1, 2, 3
+CELL_GRU, CELL_MLP, CELL_AFFINE, CELL_LSTM, CELL_LEM = 0, 1, 2, 3, 4
 
 
 class _Cell(ctypes.Structure):
     _fields_ = [("cell", ctypes.c_int), ("n", ctypes.c_int), ("d", ctypes.c_int),
-                ("width", ctypes.c_int), ("nhid", ctypes.c_int), ("act", ctypes.c_int)]
+                ("width", ctypes.c_int), ("nhid", ctypes.c_int), ("act", ctypes.c_int), ("dt", ctypes.c_double)]
 
 
 def build(force=False):
@@ -61,8 +61,9 @@ def _p(a):
 ACT_TANH, ACT_SOFTPLUS = 0, 1
 
 
-def make_cell(cell, n, d=0, width=0, nhid=0, act=ACT_TANH):
-    return _Cell(int(cell), int(n), int(d), int(width), int(nhid), int(act))
+def make_cell(cell, n, d=0, width=0, nhid=0, act=ACT_TANH, dt=1.0):
+    """n is the state size (LSTM, LEM: twice the units); dt is the LEM cell's step."""
+    return _Cell(int(cell), int(n), int(d), int(width), int(nhid), int(act), float(dt))
 
 
 def theta_count(cell):

@@ -42,6 +42,15 @@
  *         g = tanh(W_g x + U_g h + b_g)  o = sig(W_o x + U_o h + b_o)
  *         c' = f*c + i*g                 h' = o*tanh(c')
  *     theta = W[4u,d], U[4u,u], b[4u].  (The cell torch.nn.LSTMCell computes with its second bias at zero.)
+ *   - LEM cell (the cell of the paper's last experiment, App. B.5 in the arXiv numbering: "long expressive memory";
+ *     the paper prints no equations, the ones of the cited publication are used): u units, state (y | z) of 2u
+ *     entries, step dt, two learned time scales:
+ *         s1 = dt*sig(W_1 x + U_1 y + b_1)       s2 = dt*sig(W_2 x + U_2 y + b_2)
+ *         z' = (1 - s1)*z + s1*tanh(W_z x + U_z y + b_z)
+ *         y' = (1 - s2)*y + s2*tanh(W_y x + U_y z' + b_y)
+ *     theta = W[4u,d], U[4u,u], b[4u], row blocks in the order 1 | 2 | z | y.  PARITY UNPINNED for the cell's
+ *     definition (no library cell to compare with offline); its Jacobian and vector-Jacobian product are pinned to
+ *     finite differences and autograd of the cell function.
  *   - affine RNN cell (a test hook, used to pin "Newton is exact for linear
  *     f"): f(h, x) = A h + Bm x + c, theta = A[n,n], Bm[n,d], c[n].
  *   - one global convergence test over batch, time and state; the returned
@@ -65,6 +74,7 @@
 #define ORACLE_CELL_MLP 1
 #define ORACLE_CELL_AFFINE 2
 #define ORACLE_CELL_LSTM 3
+#define ORACLE_CELL_LEM 4
 
 typedef struct {
     int cell;   /* ORACLE_CELL_* */
@@ -73,6 +83,7 @@ typedef struct {
     int width;  /* MLP hidden width */
     int nhid;   /* MLP number of hidden layers */
     int act;    /* MLP activation: 0 tanh, 1 softplus */
+    double dt;  /* LEM: the step dt */
 } oracle_cell;
 
 static double sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
@@ -81,7 +92,7 @@ long oracle_theta_count(const oracle_cell* c) {
     long n = c->n, d = c->d, w = c->width;
     if (c->cell == ORACLE_CELL_GRU) return 3 * n * d + 3 * n * n + 3 * n + n;
     if (c->cell == ORACLE_CELL_AFFINE) return n * n + n * d + n;
-    if (c->cell == ORACLE_CELL_LSTM) { long u = n / 2; return 4 * u * d + 4 * u * u + 4 * u; }
+    if (c->cell == ORACLE_CELL_LSTM || c->cell == ORACLE_CELL_LEM) { long u = n / 2; return 4 * u * d + 4 * u * u + 4 * u; }
     if (c->nhid == 0) return n * n + n;
     return (w * n + w) + (long)(c->nhid - 1) * (w * w + w) + (n * w + n);
 }
@@ -373,6 +384,135 @@ static void lstm_vjp(int u, int d, const double* th, const double* y, const doub
     free(g);
 }
 
+/* ------------------------------------------------------------------ LEM -- */
+
+/* s1, s2 (time scales, dt included), gz = tanh(.) of the z update, zn = z', gy = tanh(.) of the y update; u entries each */
+static void lem_gates(int u, int d, double dt, const double* th, const double* s, const double* x,
+                      double* s1, double* s2, double* gz, double* zn, double* gy) {
+    const double* W = th;                 /* [4u, d] */
+    const double* U = W + 4 * u * d;      /* [4u, u] */
+    const double* b = U + 4 * u * u;      /* [4u]    */
+    const double* y = s;
+    const double* z = s + u;
+    for (int j = 0; j < u; j++) {
+        double a[3];
+        for (int q = 0; q < 3; q++) {
+            a[q] = b[q * u + j];
+            for (int k = 0; k < d; k++) a[q] += W[(q * u + j) * d + k] * x[k];
+            for (int k = 0; k < u; k++) a[q] += U[(q * u + j) * u + k] * y[k];
+        }
+        s1[j] = dt * sigmoid(a[0]);
+        s2[j] = dt * sigmoid(a[1]);
+        gz[j] = tanh(a[2]);
+        zn[j] = (1.0 - s1[j]) * z[j] + s1[j] * gz[j];
+    }
+    for (int j = 0; j < u; j++) {   /* the y update sees the new z */
+        double a = b[3 * u + j];
+        for (int k = 0; k < d; k++) a += W[(3 * u + j) * d + k] * x[k];
+        for (int k = 0; k < u; k++) a += U[(3 * u + j) * u + k] * zn[k];
+        gy[j] = tanh(a);
+    }
+}
+
+static void lem_f(int u, int d, double dt, const double* th, const double* s, const double* x, double* out) {
+    double* g = malloc(5 * u * sizeof(double));
+    double *s2 = g + u, *zn = g + 3 * u, *gy = g + 4 * u;
+    lem_gates(u, d, dt, th, s, x, g, s2, g + 2 * u, zn, gy);
+    for (int j = 0; j < u; j++) {
+        out[j] = (1.0 - s2[j]) * s[j] + s2[j] * gy[j];
+        out[u + j] = zn[j];
+    }
+    free(g);
+}
+
+/* J = d(y' | z') / d(y | z), 2u x 2u, row-major */
+static void lem_jac(int u, int d, double dt, const double* th, const double* s, const double* x, double* J) {
+    const double* U = th + 4 * u * d;
+    const double* y = s;
+    const double* z = s + u;
+    int n = 2 * u;
+    double* g = malloc(5 * u * sizeof(double));
+    double *s1 = g, *s2 = g + u, *gz = g + 2 * u, *gy = g + 4 * u;
+    lem_gates(u, d, dt, th, s, x, s1, s2, gz, g + 3 * u, gy);
+    memset(J, 0, (size_t)n * n * sizeof(double));
+    /* rows of z': dz'_j/dy_k and dz'_j/dz_j;  d s1_j / d a = s1_j (1 - s1_j / dt) */
+    for (int j = 0; j < u; j++) {
+        double ds1 = s1[j] * (1.0 - s1[j] / dt);
+        for (int k = 0; k < u; k++)
+            J[(u + j) * n + k] = ds1 * (gz[j] - z[j]) * U[(j)*u + k] + s1[j] * (1.0 - gz[j] * gz[j]) * U[(2 * u + j) * u + k];
+        J[(u + j) * n + u + j] = 1.0 - s1[j];
+    }
+    /* rows of y': through s2 (depends on y), the direct term, and tanh(. U_y z') */
+    for (int j = 0; j < u; j++) {
+        double ds2 = s2[j] * (1.0 - s2[j] / dt);
+        double dgy = s2[j] * (1.0 - gy[j] * gy[j]);
+        for (int k = 0; k < n; k++) {
+            double acc = 0.0;
+            for (int m = 0; m < u; m++) acc += U[(3 * u + j) * u + m] * J[(u + m) * n + k];
+            J[j * n + k] = dgy * acc;
+        }
+        for (int k = 0; k < u; k++) J[j * n + k] += ds2 * (gy[j] - y[j]) * U[(u + j) * u + k];
+        J[j * n + j] += 1.0 - s2[j];
+    }
+    free(g);
+}
+
+/* vector-Jacobian products for an output cotangent lam = (lam_y | lam_z): dtheta += ..., dx, ds overwritten */
+static void lem_vjp(int u, int d, double dt, const double* th, const double* s, const double* x,
+                    const double* lam, double* dtheta, double* dx, double* ds) {
+    const double* W = th;
+    const double* U = W + 4 * u * d;
+    double* dW = dtheta;
+    double* dU = dW + 4 * u * d;
+    double* db = dU + 4 * u * u;
+    const double* y = s;
+    const double* z = s + u;
+    double* g = malloc(6 * u * sizeof(double));
+    double *s1 = g, *s2 = g + u, *gz = g + 2 * u, *zn = g + 3 * u, *gy = g + 4 * u, *dzn = g + 5 * u;
+    lem_gates(u, d, dt, th, s, x, s1, s2, gz, zn, gy);
+    for (int k = 0; k < d; k++) dx[k] = 0.0;
+    for (int k = 0; k < 2 * u; k++) ds[k] = 0.0;
+    for (int m = 0; m < u; m++) dzn[m] = lam[u + m];
+    /* the y update: pre-activations of s2 (block 1) and of tanh(W_y x + U_y z' + b_y) (block 3) */
+    for (int j = 0; j < u; j++) {
+        double da2 = lam[j] * (gy[j] - y[j]) * s2[j] * (1.0 - s2[j] / dt);
+        double day = lam[j] * s2[j] * (1.0 - gy[j] * gy[j]);
+        ds[j] += lam[j] * (1.0 - s2[j]);
+        for (int k = 0; k < d; k++) {
+            dW[(u + j) * d + k] += da2 * x[k];
+            dW[(3 * u + j) * d + k] += day * x[k];
+            dx[k] += W[(u + j) * d + k] * da2 + W[(3 * u + j) * d + k] * day;
+        }
+        for (int k = 0; k < u; k++) {
+            dU[(u + j) * u + k] += da2 * y[k];
+            dU[(3 * u + j) * u + k] += day * zn[k];
+            ds[k] += U[(u + j) * u + k] * da2;
+            dzn[k] += U[(3 * u + j) * u + k] * day;
+        }
+        db[u + j] += da2;
+        db[3 * u + j] += day;
+    }
+    /* the z update: pre-activations of s1 (block 0) and of tanh(W_z x + U_z y + b_z) (block 2) */
+    for (int j = 0; j < u; j++) {
+        double da1 = dzn[j] * (gz[j] - z[j]) * s1[j] * (1.0 - s1[j] / dt);
+        double daz = dzn[j] * s1[j] * (1.0 - gz[j] * gz[j]);
+        ds[u + j] += dzn[j] * (1.0 - s1[j]);
+        for (int k = 0; k < d; k++) {
+            dW[(j)*d + k] += da1 * x[k];
+            dW[(2 * u + j) * d + k] += daz * x[k];
+            dx[k] += W[(j)*d + k] * da1 + W[(2 * u + j) * d + k] * daz;
+        }
+        for (int k = 0; k < u; k++) {
+            dU[(j)*u + k] += da1 * y[k];
+            dU[(2 * u + j) * u + k] += daz * y[k];
+            ds[k] += U[(j)*u + k] * da1 + U[(2 * u + j) * u + k] * daz;
+        }
+        db[j] += da1;
+        db[2 * u + j] += daz;
+    }
+    free(g);
+}
+
 /* --------------------------------------------------------------- affine -- */
 
 static void affine_f(int n, int d, const double* th, const double* h, const double* x, double* out) {
@@ -392,6 +532,7 @@ static void affine_f(int n, int d, const double* th, const double* h, const doub
 void oracle_cell_f(const oracle_cell* c, const double* th, const double* h, const double* x, double* out) {
     if (c->cell == ORACLE_CELL_GRU) gru_f(c->n, c->d, th, h, x, out);
     else if (c->cell == ORACLE_CELL_LSTM) lstm_f(c->n / 2, c->d, th, h, x, out);
+    else if (c->cell == ORACLE_CELL_LEM) lem_f(c->n / 2, c->d, c->dt, th, h, x, out);
     else if (c->cell == ORACLE_CELL_MLP) mlp_f(c, th, h, out);
     else affine_f(c->n, c->d, th, h, x, out);
 }
@@ -399,6 +540,7 @@ void oracle_cell_f(const oracle_cell* c, const double* th, const double* h, cons
 void oracle_cell_jac(const oracle_cell* c, const double* th, const double* h, const double* x, double* J) {
     if (c->cell == ORACLE_CELL_GRU) gru_jac(c->n, c->d, th, h, x, J);
     else if (c->cell == ORACLE_CELL_LSTM) lstm_jac(c->n / 2, c->d, th, h, x, J);
+    else if (c->cell == ORACLE_CELL_LEM) lem_jac(c->n / 2, c->d, c->dt, th, h, x, J);
     else if (c->cell == ORACLE_CELL_MLP) mlp_jac(c, th, h, J);
     else memcpy(J, th, (size_t)c->n * c->n * sizeof(double));
 }
@@ -409,10 +551,11 @@ void oracle_gru_vjp(int n, int d, const double* th, const double* h, const doubl
     gru_vjp(n, d, th, h, x, lam, dtheta, dx, dh);
 }
 
-/* GRU and LSTM: vector-Jacobian products of the cell; dtheta is accumulated into, dx and dh overwritten */
+/* GRU, LSTM and LEM: vector-Jacobian products of the cell; dtheta is accumulated into, dx and dh overwritten */
 void oracle_cell_vjp(const oracle_cell* c, const double* th, const double* h, const double* x,
                      const double* lam, double* dtheta, double* dx, double* dh) {
     if (c->cell == ORACLE_CELL_GRU) gru_vjp(c->n, c->d, th, h, x, lam, dtheta, dx, dh);
+    else if (c->cell == ORACLE_CELL_LEM) lem_vjp(c->n / 2, c->d, c->dt, th, h, x, lam, dtheta, dx, dh);
     else lstm_vjp(c->n / 2, c->d, th, h, x, lam, dtheta, dx, dh);
 }
 

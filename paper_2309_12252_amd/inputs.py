@@ -15,6 +15,7 @@ import numpy as np
 CELL_GRU = 0
 CELL_MLP_ODE = 1
 CELL_LSTM = 2
+CELL_LEM = 3
 
 
 @dataclass
@@ -90,6 +91,17 @@ def lstm_workload(name, seed, B, T, units, d, tol=1e-4, max_iter=50):
     x = _normal(rng, (B, T, d), 1.0)
     y0 = np.zeros((B, 2 * units), dtype=np.float32)
     return Workload(name=name, cell=CELL_LSTM, B=B, T=T, n=units, d=d, tol=tol, max_iter=max_iter, theta=theta, x=x, y0=y0)
+
+
+def lem_workload(name, seed, B, T, units, d, dt=1.0, tol=1e-4, max_iter=50):
+    """LEM cell with `units` units (state (y | z) of 2 units entries; Workload.n holds the units, Workload.t1 the
+    cell's step dt): weights and biases ~ N(0, 1/units), x ~ N(0,1), y0 = 0."""
+    rng = np.random.default_rng(seed)
+    theta = _normal(rng, lstm_theta_count(units, d), 1.0 / np.sqrt(units))
+    x = _normal(rng, (B, T, d), 1.0)
+    y0 = np.zeros((B, 2 * units), dtype=np.float32)
+    return Workload(name=name, cell=CELL_LEM, B=B, T=T, n=units, d=d, t1=float(dt), tol=tol, max_iter=max_iter, theta=theta,
+                    x=x, y0=y0)
 
 
 def mh_gru_workload(name, seed, B, T, n, d, H, K, tol=1e-4, max_iter=50):
