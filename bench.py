@@ -395,11 +395,13 @@ def main():
                 del b
                 torch.cuda.empty_cache()
         # shapes of the paper's other experiments that the library also runs (random weights stand in for trained
-        # ones): the two-body network's field (App. B.2), the multi-head GRU with strides (App. B.4), an LSTM (Sec. 3.4)
+        # ones): the two-body network's field (App. B.2), the multi-head GRU with strides (App. B.4), an LSTM (Sec. 3.4), the LEM cell
         extras = [inputs.mlp_ode_workload("two_body_shape_mlp_n8_w64_L5_softplus_T10k_B16", 4242, B=16, T=10000, n=8, width=64,
                                           nhid=5, t0=0.0, t1=10.0, act=inputs.ACT_SOFTPLUS),
                   inputs.mh_gru_workload("multihead_gru_32x8_strides8_T1024_B64", 4321, B=64, T=1024, n=8, d=8, H=32, K=8),
                   inputs.lstm_workload("lstm_u8_d4_T50k_B16", 88, B=16, T=50000, units=8, d=4),
+                  # the LEM cell on the length and channels of the series the paper trains it on (App. B.3 shapes)
+                  inputs.lem_workload("lem_u16_d6_T17984_B32", 89, B=32, T=17984, units=16, d=6, dt=1.0),
                   # the largest state size of the paper's speed table (Table 4: n = 64, 10k steps, batch 16)
                   inputs.gru_workload("gru_n64_T10k_B16", 6464, B=16, T=10000, n=64, d=8)]
         for wx in extras:

@@ -41,6 +41,13 @@
  *       c' = f * c + i * g                 h' = o * tanh(c')
  *     theta (flat): W[4u,d], U[4u,u], b[4u].  An iteration is a Jacobian kernel followed by the scan over the 2u x 2u
  *     Jacobians (embedded in the next state size with a scan kernel).
+ *   LEM cell (the cell of the paper's last experiment, which trains it with DEER; the paper prints no equations, the
+ *   ones of the publication it cites are used; cell = DEER_CELL_LEM, n = number of units u, 1..16, d = 1..8, t1 = the
+ *   cell's step dt > 0).  The state is (y | z) with 2u entries, laid out like the LSTM's; two learned time scales:
+ *       s1 = dt * sigmoid(W_1 x + U_1 y + b_1)   s2 = dt * sigmoid(W_2 x + U_2 y + b_2)
+ *       z' = (1 - s1) * z + s1 * tanh(W_z x + U_z y + b_z)
+ *       y' = (1 - s2) * y + s2 * tanh(W_y x + U_y z' + b_y)
+ *     theta (flat): W[4u,d], U[4u,u], b[4u], row blocks in the order 1 | 2 | z | y.  Kernels as for the LSTM.
  *   Multi-head GRU with strides (Sec. 4.4, App. B.4; heads > 1 or stride_levels > 1): the state is H heads of n
  *   channels, every head a GRU cell of its own on its own d input channels, and head h looks back
  *   s_h = 2^(h mod K) steps instead of one (the K stride levels are dealt out to the heads in turn):
@@ -75,7 +82,7 @@ typedef enum {
     DEER_ERR_NONFINITE = 5     /* the iteration produced a NaN/Inf; outputs hold the last iterate        */
 } deer_status;
 
-typedef enum { DEER_CELL_GRU = 0, DEER_CELL_MLP_ODE = 1, DEER_CELL_LSTM = 2 } deer_cell;
+typedef enum { DEER_CELL_GRU = 0, DEER_CELL_MLP_ODE = 1, DEER_CELL_LSTM = 2, DEER_CELL_LEM = 3 } deer_cell;
 typedef enum { DEER_F32 = 0, DEER_F64 = 1 } deer_dtype;
 typedef enum { DEER_ACT_TANH = 0, DEER_ACT_SOFTPLUS = 1 } deer_activation;
 
@@ -91,7 +98,7 @@ typedef struct {
     int32_t d;                  /* GRU input size (1..32); ignored for MLP_ODE                           */
     int32_t mlp_width;          /* MLP_ODE hidden width w: a multiple of 4, 4..64; ignored for GRU       */
     int32_t mlp_hidden_layers;  /* MLP_ODE: hidden layers L, 1..5 (L + 1 linear layers)                  */
-    double t0, t1;              /* MLP_ODE: uniform grid t_j = t0 + j (t1 - t0)/(T - 1)                  */
+    double t0, t1;              /* MLP_ODE: uniform grid t_j = t0 + j (t1 - t0)/(T - 1); LEM: t1 = step dt */
     int32_t mlp_activation;     /* MLP_ODE: deer_activation of the hidden layers (0 = tanh)              */
     int32_t heads;              /* GRU: number of heads H (0 or 1: the plain cell); see "multi-head GRU"  */
     int32_t stride_levels;      /* GRU: stride levels K (0 or 1: every head has stride 1)                */

@@ -62,10 +62,13 @@ struct Plan {
     size_t off_J, off_rhs, off_ybuf, off_Gbar, off_zbar, off_aggW, off_inclW, off_barrier, off_ctl, off_partial, off_timing, total;
 };
 
+// cells whose state is two halves of n units each (n of the configuration = units): LSTM (h | c), LEM (y | z)
+bool two_part_cell(int cell) { return cell == DEER_CELL_LSTM || cell == DEER_CELL_LEM; }
+
 size_t theta_count(const deer_config* c) {
     const size_t n = (size_t)c->n;
     if (c->cell == DEER_CELL_GRU) return (size_t)(c->heads > 1 ? c->heads : 1) * (3 * n * (size_t)c->d + 3 * n * n + 4 * n);
-    if (c->cell == DEER_CELL_LSTM) {
+    if (two_part_cell(c->cell)) {
         const size_t u = c->reserved > 0 ? (size_t)c->reserved : n;   // (the configuration the kernels run keeps the units there)
         return 4 * u * (size_t)c->d + 4 * u * u + 4 * u;
     }
@@ -89,7 +92,7 @@ int env_int(const char* name, int dflt) {
 
 bool validate(const deer_config* c, std::string& why) {
     if (!c) { why = "config is NULL"; return false; }
-    if (c->cell != DEER_CELL_GRU && c->cell != DEER_CELL_MLP_ODE && c->cell != DEER_CELL_LSTM) { why = "unknown cell"; return false; }
+    if (c->cell != DEER_CELL_GRU && c->cell != DEER_CELL_MLP_ODE && !two_part_cell(c->cell)) { why = "unknown cell"; return false; }
     if (c->dtype != DEER_F32 && c->dtype != DEER_F64) { why = "unknown dtype"; return false; }
     if (c->B < 1 || c->T < 1 || c->n < 1) { why = "B, T and n must be positive"; return false; }
     if ((long long)c->B * c->T > (1LL << 31) - 1) { why = "B*T must fit 31 bits"; return false; }
@@ -113,7 +116,7 @@ bool is_multihead(const deer_config* c);
 deer_config internal_config(const deer_config* user) {
     deer_config c = *user;
     if (c.cell == DEER_CELL_GRU && !is_multihead(user) && native_n(c.n) > 0) c.n = native_n(c.n);
-    if (c.cell == DEER_CELL_LSTM) {   // state (h | c) of 2 units entries in the next state size with a scan kernel
+    if (two_part_cell(c.cell)) {   // state (h | c) or (y | z) of 2 units entries in the next state size with a scan kernel
         c.reserved = user->n;
         c.n = native_n(2 * user->n);
     }
@@ -132,8 +135,9 @@ bool supported(const deer_config* c, std::string& why) {
         if (env_int("DEER_FUSED", 1) == 0 || env_int("DEER_GRAD_FUSED", 1) == 0) { why = "multi-head GRU runs only with the cell inside the scans"; return false; }
         return true;
     }
-    if (c->cell == DEER_CELL_LSTM) {
-        if (!lstm_supported(n, c->d)) { why = "LSTM: 1..16 units and input size 1..8"; return false; }
+    if (two_part_cell(c->cell)) {
+        if (!lstm_supported(n, c->d)) { why = "LSTM and LEM: 1..16 units and input size 1..8"; return false; }
+        if (c->cell == DEER_CELL_LEM && !(c->t1 > 0.0)) { why = "LEM: t1 holds the cell's step and must be positive"; return false; }
         return true;
     }
     if (c->cell == DEER_CELL_GRU) {
@@ -308,7 +312,7 @@ Plan make_plan(const deer_config* c) {
         if (p.fused_tiles < 1) p.fused_tiles = 1;
     }
     p.vjp_blocks = c->cell == DEER_CELL_GRU    ? gru_vjp_blocks(c->n, (long long)B * T)
-                   : c->cell == DEER_CELL_LSTM ? lstm_vjp_blocks(c->reserved, (long long)B * T)
+                   : two_part_cell(c->cell) ? lstm_vjp_blocks(c->reserved, (long long)B * T)
                    : mlp_fast_path(c)       ? mlp_vjp_blocks(c->dtype, c->n, c->mlp_width, (long long)B * T)
                                             : mlp_general_vjp_blocks(c->dtype, c->n, c->mlp_width, c->mlp_hidden_layers, (long long)B * T);
 
@@ -352,7 +356,7 @@ struct PadPlan {
 
 static PadPlan make_pad_plan(const deer_config* user, const deer_config* in, size_t base) {
     PadPlan q{};
-    const int user_state = user->cell == DEER_CELL_LSTM ? 2 * user->n : user->n;
+    const int user_state = two_part_cell(user->cell) ? 2 * user->n : user->n;
     q.on = in->n != user_state;
     q.total = base;
     if (!q.on) return q;
@@ -718,7 +722,7 @@ deer_status deer_eval(deer_ctx* c, const void* d_theta, const void* d_x, const v
     // channels of the result come out
     if (!d_theta || !d_y0 || !d_y || !d_x) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
     const deer_config& g = c->cfg;
-    const bool lstm = g.cell == DEER_CELL_LSTM;   // its kernels take the parameters as they are
+    const bool lstm = two_part_cell(g.cell);   // its kernels take the parameters as they are
     const int n = lstm ? 2 * c->user.n : c->user.n, np = g.n;
     const long long rows = (long long)g.B * g.T;
     char* pth = c->ws + c->pad.off_theta;
@@ -812,9 +816,11 @@ static deer_status eval_impl(deer_ctx* c, const void* d_theta, const void* d_x, 
                 HIPCHK(c, run_scan(c, nullptr, nullptr, d_y0, dst, src, 0, 0, (long long)(T * n), 0, slot, true, 0, gate,
                                    k, d_theta, d_x));
             } else if (!ode) {
-                GruParams gp{d_theta, d_x, d_y0, src, J, rhs, g.B, g.T, g.n, g.d, gate, g.cell == DEER_CELL_LSTM ? g.reserved : 0};
+                GruParams gp{d_theta, d_x, d_y0, src, J, rhs, g.B, g.T, g.n, g.d, gate, two_part_cell(g.cell) ? g.reserved : 0, g.t1};
                 prof_begin(c, KIND_FUNCEVAL, k);
-                HIPCHK(c, g.cell == DEER_CELL_LSTM ? launch_lstm_funceval(g.dtype, gp, c->stream) : launch_gru_funceval(g.dtype, gp, c->stream));
+                HIPCHK(c, g.cell == DEER_CELL_LSTM  ? launch_lstm_funceval(g.dtype, gp, c->stream)
+                          : g.cell == DEER_CELL_LEM ? launch_lem_funceval(g.dtype, gp, c->stream)
+                                                    : launch_gru_funceval(g.dtype, gp, c->stream));
                 prof_end(c);
                 HIPCHK(c, run_scan(c, J, rhs, d_y0, dst, src, (long long)(T * n * n), (long long)(T * n),
                                    (long long)(T * n), 0, slot, true, 0, gate, k));
@@ -952,7 +958,7 @@ deer_status deer_grad(deer_ctx* c, const void* d_theta, const void* d_x, const v
     // channels is zero and stays zero through the dual recurrence)
     if (!d_theta || !d_x || !d_y0 || !d_y || !d_dLdy || !d_dLdtheta) return fail(c, DEER_ERR_INVALID_ARG, "a required pointer is NULL");
     const deer_config& g = c->cfg;
-    const bool lstm = g.cell == DEER_CELL_LSTM;
+    const bool lstm = two_part_cell(g.cell);
     const int n = lstm ? 2 * c->user.n : c->user.n, np = g.n;
     const long long rows = (long long)g.B * g.T;
     char* pth = c->ws + c->pad.off_theta;
@@ -993,9 +999,11 @@ static deer_status grad_impl(deer_ctx* c, const void* d_theta, const void* d_x, 
                            Gate{nullptr, 0.0}, -1, d_theta, d_x));
     } else {
         // Jacobians at the given trajectory (the right-hand side output is not used)
-        GruParams gp{d_theta, d_x, d_y0, d_y, J, rhs, g.B, g.T, g.n, g.d, Gate{nullptr, 0.0}, g.cell == DEER_CELL_LSTM ? g.reserved : 0};
+        GruParams gp{d_theta, d_x, d_y0, d_y, J, rhs, g.B, g.T, g.n, g.d, Gate{nullptr, 0.0}, two_part_cell(g.cell) ? g.reserved : 0, g.t1};
         prof_begin(c, KIND_FUNCEVAL);
-        HIPCHK(c, g.cell == DEER_CELL_LSTM ? launch_lstm_funceval(g.dtype, gp, c->stream) : launch_gru_funceval(g.dtype, gp, c->stream));
+        HIPCHK(c, g.cell == DEER_CELL_LSTM  ? launch_lstm_funceval(g.dtype, gp, c->stream)
+                  : g.cell == DEER_CELL_LEM ? launch_lem_funceval(g.dtype, gp, c->stream)
+                                            : launch_gru_funceval(g.dtype, gp, c->stream));
         prof_end(c);
         // lam = (dL/dy) L_G^{-1}: reverse scan with transposed Jacobians
         HIPCHK(c, run_scan(c, J, d_dLdy, nullptr, lam, nullptr, (long long)(T * n * n), (long long)(T * n),
@@ -1003,10 +1011,12 @@ static deer_status grad_impl(deer_ctx* c, const void* d_theta, const void* d_x, 
     }
     GruVjpParams vp{d_theta, d_x, d_y0, d_y, lam, d_dLdx, d_dLdy0, c->ws + c->plan.off_partial, d_dLdtheta,
                     g.B, g.T, g.n, g.d, c->plan.vjp_blocks, c->plan.mh ? c->plan.mh_H : 0, c->plan.mh ? c->plan.mh_K : 0,
-                    c->plan.mh ? c->ws + c->plan.off_dy0parts : nullptr, g.cell == DEER_CELL_LSTM ? g.reserved : 0};
+                    c->plan.mh ? c->ws + c->plan.off_dy0parts : nullptr, two_part_cell(g.cell) ? g.reserved : 0, g.t1};
     prof_begin(c, KIND_VJP);
     if (g.cell == DEER_CELL_LSTM) {
         HIPCHK(c, launch_lstm_vjp(g.dtype, vp, c->stream));
+    } else if (g.cell == DEER_CELL_LEM) {
+        HIPCHK(c, launch_lem_vjp(g.dtype, vp, c->stream));
     } else if (!c->plan.mh && gru_vjp_mfma_supported(g.dtype, g.n, g.d) && env_int("DEER_VJP_MFMA", 1) != 0) {
         HIPCHK(c, launch_gru_vjp_mfma(vp, c->stream));
         HIPCHK(c, launch_partial_reduce(g.dtype, vp.partial, d_dLdtheta, (long long)theta_count(&g), vp.blocks * 4, c->stream));

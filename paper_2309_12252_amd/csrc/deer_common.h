@@ -240,7 +240,8 @@ struct GruParams {
     void* J; void* rhs;                                               // outputs [B,T,n,n], [B,T,n]
     int B, T, n, d;
     Gate gate;
-    int units;         // LSTM kernels: units of the cell (n is then the scan's state size, >= 2 units); 0 otherwise
+    int units;         // LSTM and LEM kernels: units of the cell (n is then the scan's state size, >= 2 units); 0 otherwise
+    double dt;         // LEM kernels: the cell's step
 };
 
 struct GruVjpParams {
@@ -254,7 +255,8 @@ struct GruVjpParams {
     int H, K;          // multi-head GRU with strides: heads and stride levels (0 or 1: the plain GRU); arrays are then
                        // [B][T][H][.], theta and dtheta [H][theta_count], partial [H][blocks * 4][theta_count]
     void* dy0_parts;   // multi-head: [B][H][2^(K-1)][n] scratch for the terms of dL/dy0
-    int units;         // LSTM kernels: units of the cell (n: the scan's state size); 0 otherwise
+    int units;         // LSTM and LEM kernels: units of the cell (n: the scan's state size); 0 otherwise
+    double dt;         // LEM kernels: the cell's step
 };
 
 struct MlpParams {
@@ -331,6 +333,9 @@ bool lstm_supported(int units, int d);
 int lstm_vjp_blocks(int units, long long steps);
 hipError_t launch_lstm_funceval(int dtype, const GruParams& p, hipStream_t s);
 hipError_t launch_lstm_vjp(int dtype, const GruVjpParams& p, hipStream_t s);
+// LEM cell (same shapes and parameter layout as the LSTM: units 1..16, d 1..8; p.dt is the step)
+hipError_t launch_lem_funceval(int dtype, const GruParams& p, hipStream_t s);
+hipError_t launch_lem_vjp(int dtype, const GruVjpParams& p, hipStream_t s);
 hipError_t launch_mlp_funceval(int dtype, const MlpParams& p, hipStream_t s);
 hipError_t launch_ode_discretise(int dtype, const OdeDiscParams& p, hipStream_t s);
 hipError_t launch_ode_dual(int dtype, const OdeDualParams& p, hipStream_t s);

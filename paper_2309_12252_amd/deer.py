@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdeer_hip.so")
 
 DEER_OK, DEER_ERR_INVALID_ARG, DEER_ERR_UNSUPPORTED, DEER_ERR_WORKSPACE, DEER_ERR_HIP, DEER_ERR_NONFINITE = range(6)
-DEER_CELL_GRU, DEER_CELL_MLP_ODE, DEER_CELL_LSTM = 0, 1, 2
+DEER_CELL_GRU, DEER_CELL_MLP_ODE, DEER_CELL_LSTM, DEER_CELL_LEM = 0, 1, 2, 3
 DEER_F32, DEER_F64 = 0, 1
 
 EXPORTS = ["deer_theta_count", "deer_workspace_bytes", "deer_create", "deer_eval", "deer_grad",
@@ -150,7 +150,7 @@ class DeerContext:
         if c.cell == DEER_CELL_GRU and (c.heads > 1 or c.stride_levels > 1):
             H = max(1, c.heads)
             return (c.B, c.T, H, c.n), (c.B, c.T, H, c.d), (c.B, H, c.n)
-        if c.cell == DEER_CELL_LSTM:   # n units, state (h | c)
+        if c.cell in (DEER_CELL_LSTM, DEER_CELL_LEM):   # n units, state (h | c) or (y | z)
             return (c.B, c.T, 2 * c.n), (c.B, c.T, c.d), (c.B, 2 * c.n)
         return (c.B, c.T, c.n), (c.B, c.T, c.d), (c.B, c.n)
 
