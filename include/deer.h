@@ -234,7 +234,7 @@ void deer_destroy(deer_ctx* ctx);
 
 /* Environment.  Every variable the library reads; all are meant for tests and measurements, none changes a
  * result beyond rounding.  Read by deer_workspace_bytes() and deer_create() (the plan and the workspace size
- * depend on them), except DEER_VJP_MFMA, which deer_grad() reads at each call.
+ * depend on them), except DEER_VJP_MFMA and DEER_MLP_MFMA, which deer_grad() / deer_eval() read at each call.
  *   DEER_FUSED=0        GRU: run the cell kernel and the plain scan as two launches per iteration (needs the
  *                       Jacobian stream in the workspace) instead of the scan with the cell inside
  *   DEER_GRAD_FUSED=0   GRU deer_grad(): Jacobian kernel + plain reverse scan instead of the reverse scan with the
@@ -245,6 +245,9 @@ void deer_destroy(deer_ctx* ctx);
  *                       the plain n = 4 scan) and wavefronts per tile (4 or 8); ignored when no such variant exists
  *   DEER_BATCH          Newton iterations enqueued per host round trip on a fresh context (1..8, default 4)
  *   DEER_VJP_MFMA=0     vector-ALU kernels for the vector-Jacobian products instead of the matrix-core ones
+ *   DEER_MLP_MFMA=0     MLP fields outside the two-layer tanh shapes (fp32, n = 8, width 32 or 64): vector-ALU field
+ *                       kernel instead of the matrix-core one
+ *   DEER_FUSED_W=4      GRU n = 32: four-wavefront tiles of the scan with the cell inside (two workgroups per CU)
  * Test hooks (exercise paths that ordinary runs reach rarely; never set them in production):
  *   DEER_EPOCH0         first launch epoch of the context (default 1), to reach the wrap-around of the 30-bit
  *                       epoch that tags published words

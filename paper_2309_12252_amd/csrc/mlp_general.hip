@@ -68,6 +68,241 @@ __host__ __device__ inline long long layer_offset(int n, int w, int l) {
 __host__ __device__ inline long long gen_theta_len(int n, int w, int L) { return layer_offset(n, w, L) + (long long)n * w + n; }
 
 // ---------------------------------------------------------------------------------------------------------
+// field + Jacobian on the matrix cores (fp32, n = 8, hidden width 16 * WB, L hidden layers)
+// ---------------------------------------------------------------------------------------------------------
+// The two-hidden-layer kernel's scheme for any depth: a wavefront handles 16 grid points as the columns of
+// 16 x 16 x 4 products whose results stay in accumulator layout (a valid B operand of the next product):
+//   values      A_1 = s(W_1 Y + b_1), A_l = s(W_l A_{l-1} + b_l), f = W_out A_L + b_out
+//   J y         Q_1 = D_1 (W_1 Y), Q_l = D_l (W_l Q_{l-1}), J y = W_out Q_L            (z = f - J y)
+//   Jacobians   16 columns (two points x 8 state entries) at a time: U_1 = D_1 W_1, U_l = D_l (W_l U_{l-1}),
+//               J = W_out U_L; the derivative factors D_l of a column's point come from that point's lane by
+//               one shuffle each.
+// The derivative factors of all layers stay in registers (L * WB * 4); the weights are A operands read from
+// LDS (rows padded to W + 4 words: 16-byte reads, lanes of a row group on different banks).
+typedef float gacc __attribute__((ext_vector_type(4)));
+
+// softplus and its derivative (the logistic function) from one exp2, one log2 and one reciprocal of the hardware:
+// absolute errors below 3e-7
+__device__ __forceinline__ void fast_act(int kind, float pre, float& a, float& da) {
+    if (kind == 0) {
+        a = feed_tanh(pre);
+        da = 1.0f - a * a;
+    } else {
+        const float e = __builtin_amdgcn_exp2f(-1.44269504088896341f * fabsf(pre));   // exp(-|pre|) in (0, 1]
+        const float r = __builtin_amdgcn_rcpf(1.0f + e);
+        a = fmaxf(pre, 0.0f) + 0.693147180559945309f * __builtin_amdgcn_logf(1.0f + e);
+        da = pre >= 0.0f ? r : e * r;
+    }
+}
+
+template <int WB, int L>
+__global__ __launch_bounds__(kThreads) void mlp_gen_funceval_mfma_kernel(MlpParams p) {
+    if (gate_closed<float>(p.gate)) return;
+    constexpr int W = 16 * WB, N = 8, WS = W + 4, W1S = 12;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    float* sW1 = reinterpret_cast<float*>(smem_raw);   // [W][W1S]: W_1, 8 columns used
+    float* sWh = sW1 + W * W1S;                        // [L - 1][W][WS]
+    float* sWo = sWh + (L - 1) * W * WS;               // [16][WS]: W_out, rows 8..15 zero
+    float* sb = sWo + 16 * WS;                         // [L][W] hidden biases, then [16] output bias (entries 8..15 zero)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int g = lane >> 4, c = lane & 15;
+    const float* __restrict__ th = reinterpret_cast<const float*>(p.theta);
+    const int kind = p.act;
+    for (int q = tid; q < W * N; q += kThreads) sW1[(q / N) * W1S + (q % N)] = th[q];
+    for (int q = tid; q < W; q += kThreads) sb[q] = th[W * N + q];
+    for (int l = 1; l < L; ++l) {
+        const float* src = th + layer_offset(N, W, l);
+        for (int q = tid; q < W * W; q += kThreads) sWh[((l - 1) * W + q / W) * WS + (q % W)] = src[q];
+        for (int q = tid; q < W; q += kThreads) sb[l * W + q] = src[W * W + q];
+    }
+    {
+        const float* src = th + layer_offset(N, W, L);
+        for (int q = tid; q < 16 * W; q += kThreads) sWo[(q / W) * WS + (q % W)] = (q / W < N) ? src[q] : 0.0f;
+        if (tid < 16) sb[L * W + tid] = (tid < N) ? src[N * W + tid] : 0.0f;
+    }
+    __syncthreads();
+
+    const float* __restrict__ y = reinterpret_cast<const float*>(p.y);
+    float* __restrict__ G = reinterpret_cast<float*>(p.G);
+    float* __restrict__ z = reinterpret_cast<float*>(p.z);
+    float w1b[WB][4];   // W_1[16K + 4g + v][c & 7]: the column factor of D_1 W_1
+#pragma unroll
+    for (int K = 0; K < WB; ++K)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) w1b[K][v] = sW1[(16 * K + 4 * g + v) * W1S + (c & 7)];
+
+    const long long total = (long long)p.B * p.T;
+    const long long nblk = (total + 15) / 16;
+    const long long wave0 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
+    for (long long blk = wave0; blk < nblk; blk += nwaves) {
+        const long long s0 = blk * 16;
+        const long long sc = (s0 + c < total) ? s0 + c : total - 1;
+        float yb[2];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) yb[kk] = y[sc * N + 4 * kk + g];
+
+        gacc a[WB], q[WB], d[L][WB];
+        // layer 1
+#pragma unroll
+        for (int I = 0; I < WB; ++I) {
+            gacc bias, acc;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) bias[v] = sb[16 * I + 4 * g + v];
+            acc = bias;
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(sW1[(16 * I + c) * W1S + 4 * kk + g], yb[kk], acc, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float av, dv;
+                fast_act(kind, acc[v], av, dv);
+                a[I][v] = av;
+                d[0][I][v] = dv;
+                q[I][v] = dv * (acc[v] - bias[v]);
+            }
+        }
+        // hidden layers 2..L
+#pragma unroll
+        for (int l = 1; l < L; ++l) {
+            gacc an[WB], qn[WB];
+#pragma unroll
+            for (int I = 0; I < WB; ++I) {
+                gacc acc, accq = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[v] = sb[l * W + 16 * I + 4 * g + v];
+#pragma unroll
+                for (int K = 0; K < WB; ++K) {
+                    float wa[4];
+                    vload<float, 4>(wa, &sWh[((l - 1) * W + 16 * I + c) * WS + 16 * K + 4 * g]);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[v], a[K][v], acc, 0, 0, 0);
+                        if (!p.jac_only) accq = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[v], q[K][v], accq, 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float av, dv;
+                    fast_act(kind, acc[v], av, dv);
+                    an[I][v] = av;
+                    d[l][I][v] = dv;
+                    qn[I][v] = dv * accq[v];
+                }
+            }
+#pragma unroll
+            for (int I = 0; I < WB; ++I) { a[I] = an[I]; q[I] = qn[I]; }
+        }
+        // output layer: z = f - J y at point s0 + c, rows 4g + v < 8
+        {
+            gacc f = {0.f, 0.f, 0.f, 0.f}, jy = {0.f, 0.f, 0.f, 0.f};
+            if (!p.jac_only) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) f[v] = sb[L * W + 4 * g + v];
+#pragma unroll
+                for (int K = 0; K < WB; ++K) {
+                    float wa[4];
+                    vload<float, 4>(wa, &sWo[c * WS + 16 * K + 4 * g]);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        f = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[v], a[K][v], f, 0, 0, 0);
+                        jy = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[v], q[K][v], jy, 0, 0, 0);
+                    }
+                }
+            }
+            if (g < 2 && s0 + c < total) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) z[(s0 + c) * N + 4 * g + v] = f[v] - jy[v];
+            }
+        }
+        // Jacobians, two points (16 columns) per round
+#pragma unroll 1
+        for (int cb = 0; cb < 8; ++cb) {
+            const int src = (lane & 48) + 2 * cb + ((lane >> 3) & 1);   // lane holding the factors of this column's point
+            // (an offset the compiler cannot see through: the weight reads of a round stay in the round instead of being
+            // hoisted into hundreds of registers in front of the loop)
+            int zoff = 0;
+            asm volatile("" : "+v"(zoff));
+            float u[WB][4];
+#pragma unroll
+            for (int K = 0; K < WB; ++K)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) u[K][v] = __shfl(d[0][K][v], src) * w1b[K][v];
+#pragma unroll
+            for (int l = 1; l < L; ++l) {
+                float un[WB][4];
+#pragma unroll
+                for (int I = 0; I < WB; ++I) {
+                    gacc t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int K = 0; K < WB; ++K) {
+                        float wa[4];
+                        vload<float, 4>(wa, &sWh[((l - 1) * W + 16 * I + c) * WS + 16 * K + 4 * g + zoff]);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) t = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[v], u[K][v], t, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) un[I][v] = __shfl(d[l][I][v], src) * t[v];
+                }
+#pragma unroll
+                for (int I = 0; I < WB; ++I)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) u[I][v] = un[I][v];
+            }
+            gacc jb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int K = 0; K < WB; ++K) {
+                float wa[4];
+                vload<float, 4>(wa, &sWo[c * WS + 16 * K + 4 * g + zoff]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) jb = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[v], u[K][v], jb, 0, 0, 0);
+            }
+            const long long sp = s0 + 2 * cb + (c >> 3);
+            if (g < 2 && sp < total) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) G[(sp * N + 4 * g + v) * N + (c & 7)] = -jb[v];
+            }
+        }
+    }
+}
+
+size_t fe_mfma_smem(int W, int L) { return ((size_t)W * 12 + (size_t)(L - 1) * W * (W + 4) + 16 * (size_t)(W + 4) + (size_t)L * W + 16) * 4; }
+
+template <int WB, int L>
+hipError_t launch_fe_mfma_wl(const MlpParams& p, hipStream_t s) {
+    const size_t shmem = fe_mfma_smem(16 * WB, L);
+    static bool attr_set = false;   // more than 64 KB of dynamic LDS needs the attribute (set once per instantiation)
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_gen_funceval_mfma_kernel<WB, L>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long long nblk = ((long long)p.B * p.T + 15) / 16;
+    long long blocks = (nblk + 3) / 4;
+    if (blocks > 512) blocks = 512;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((mlp_gen_funceval_mfma_kernel<WB, L>), dim3((unsigned)blocks), dim3(kThreads), shmem, s, p);
+    return hipGetLastError();
+}
+
+template <int WB>
+hipError_t launch_fe_mfma_w(const MlpParams& p, hipStream_t s) {
+    switch (p.nhid) {
+        case 1: return launch_fe_mfma_wl<WB, 1>(p, s);
+        case 2: return launch_fe_mfma_wl<WB, 2>(p, s);
+        case 3: return launch_fe_mfma_wl<WB, 3>(p, s);
+        case 4: return launch_fe_mfma_wl<WB, 4>(p, s);
+        case 5: return launch_fe_mfma_wl<WB, 5>(p, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+bool fe_mfma_supported(int dtype, int n, int width, int nhid) {
+    return dtype == 0 && n == 8 && (width == 32 || width == 64) && nhid >= 1 && nhid <= 5;
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // field + Jacobian
 // ---------------------------------------------------------------------------------------------------------
 struct FeRow {
@@ -474,6 +709,10 @@ int mlp_general_vjp_blocks(int dtype, int n, int width, int nhid, long long poin
 
 hipError_t launch_mlp_general_funceval(int dtype, const MlpParams& p, hipStream_t s) {
     if (!mlp_general_supported(p.n, p.width, p.nhid, p.act)) return hipErrorInvalidValue;
+    // fp32, n = 8, width 32 or 64: on the matrix cores (DEER_MLP_MFMA=0 keeps the vector-ALU kernel)
+    const char* e = getenv("DEER_MLP_MFMA");   // (read per call: the tests run both kernels in one process)
+    const bool mfma = !(e && *e && atoi(e) == 0);
+    if (mfma && fe_mfma_supported(dtype, p.n, p.width, p.nhid)) return p.width == 32 ? launch_fe_mfma_w<2>(p, s) : launch_fe_mfma_w<4>(p, s);
     return dtype == 0 ? launch_fe<float>(p, s) : launch_fe<double>(p, s);
 }
 

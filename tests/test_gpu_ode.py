@@ -58,6 +58,19 @@ def test_fields_of_other_depths_and_activations(n, width, nhid, act, dtype):
         check(w, dtype)
 
 
+@pytest.mark.parametrize("width,nhid,act", [(64, 5, inputs.ACT_SOFTPLUS), (32, 3, inputs.ACT_TANH), (32, 1, inputs.ACT_SOFTPLUS),
+                                            (64, 2, inputs.ACT_SOFTPLUS), (32, 4, inputs.ACT_TANH)])
+def test_general_field_on_both_kernels(width, nhid, act, monkeypatch):
+    # fp32, n = 8, width 32 / 64 run the field on the matrix cores by default; the knob selects the vector-ALU kernel
+    for knob in ("1", "0"):
+        monkeypatch.setenv("DEER_MLP_MFMA", knob)
+        for k, (B, T, t1) in enumerate([(1, 2, 0.1), (2, 37, 1.0), (3, 1300, 2.0)]):
+            w = inputs.mlp_ode_workload("both_w%d_L%d_T%d" % (width, nhid, T), 950 + width + nhid + k, B=B, T=T, n=8,
+                                        width=width, nhid=nhid, t0=0.0, t1=t1, tol=1e-4, act=act)
+            check(w, deer.DEER_F32)
+            check_grad(w, deer.DEER_F32)
+
+
 def two_body_shaped(B, T):
     # the shape of the paper's two-body network (Sec. 4.2, App. B.2): state 8, six linear layers (five hidden
     # ones of width 64), softplus, 10,000 grid points on [0, 10]; random weights stand in for the trained ones
