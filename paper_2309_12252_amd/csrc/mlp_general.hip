@@ -14,6 +14,9 @@
 // (cotangent) x (layer input) over the points in registers; one partial row per block, added by the
 // fixed-order reduction.
 //
+// fp32 with n = 8 and width 32 or 64 runs both on the matrix cores (mlp_gen_funceval_mfma_kernel,
+// mlp_gen_vjp_mfma_kernel, described where they are defined); the kernels described here serve every other shape.
+//
 // Both kernels take the shape at run time.  A block of 256 threads handles `pts` grid points at a time with
 // 256 / pts threads per point, which share the hidden units of a layer; a point's state is a row in LDS
 // (row length = 4 mod 32 words, so that the 16-byte reads of consecutive points fall on different banks).
@@ -300,6 +303,259 @@ hipError_t launch_fe_mfma_w(const MlpParams& p, hipStream_t s) {
 
 bool fe_mfma_supported(int dtype, int n, int width, int nhid) {
     return dtype == 0 && n == 8 && (width == 32 || width == 64) && nhid >= 1 && nhid <= 5;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// vector-Jacobian product on the matrix cores (fp32, n = 8, hidden width 16 * WB, L hidden layers)
+// ---------------------------------------------------------------------------------------------------------
+// dL/dtheta = sum over grid points j of (df/dtheta)(y_j)^T w_j, w_j = (u_j + u_{j-1}) / 2 (Sec. 3.1.1 eq. 7, outer
+// bracket, ODE form).  The accumulators of all layers do not fit the registers of a wavefront (width 64: 64 per
+// hidden layer), so blockIdx.y names the layer a block accumulates: 0 = (W_1, b_1), l = (W_{l+1}, b_{l+1}),
+// L = (W_out, b_out).  Every block runs the forward pass of its 16-point tiles (it needs the derivative factors
+// of the layers above its own) and the reverse pass down to its layer, all as 16 x 16 x 4 products in accumulator
+// layout as in the field kernel (weights from LDS; for the reverse products they are read down a column, row
+// stride = 4 mod 64 words: no bank conflicts); its layer's cotangent and input then cross a wavefront-private LDS
+// tile so that the grid points land on the contraction index of the outer-product sum.  One partial row per
+// wavefront (each block fills its layer's slice of the row), the fixed-order reduction adds the rows.
+template <int WB, int L>
+__global__ __launch_bounds__(kThreads) void mlp_gen_vjp_mfma_kernel(MlpVjpParams p) {
+    constexpr int W = 16 * WB, N = 8, WS = W + 4, W1S = 12, LD = 17, kWaves = kThreads / 64;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    float* sW1 = reinterpret_cast<float*>(smem_raw);   // [W][W1S]
+    float* sWh = sW1 + W * W1S;                        // [L - 1][W][WS]
+    float* sWo = sWh + (L - 1) * W * WS;               // [16][WS], rows 8..15 zero
+    float* sb = sWo + 16 * WS;                         // [L][W] (+ 16 unused)
+    float* sD = sb + L * W + 16;                       // [kWaves][2 W][LD]: cotangent rows | input rows of the block's layer
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 4, c = lane & 15;
+    const int grp = blockIdx.y;
+    const int kind = p.act;
+    const float* __restrict__ th = reinterpret_cast<const float*>(p.theta);
+    for (int q = tid; q < W * N; q += kThreads) sW1[(q / N) * W1S + (q % N)] = th[q];
+    for (int q = tid; q < W; q += kThreads) sb[q] = th[W * N + q];
+    for (int l = 1; l < L; ++l) {
+        const float* src = th + layer_offset(N, W, l);
+        for (int q = tid; q < W * W; q += kThreads) sWh[((l - 1) * W + q / W) * WS + (q % W)] = src[q];
+        for (int q = tid; q < W; q += kThreads) sb[l * W + q] = src[W * W + q];
+    }
+    {
+        const float* src = th + layer_offset(N, W, L);
+        for (int q = tid; q < 16 * W; q += kThreads) sWo[(q / W) * WS + (q % W)] = (q / W < N) ? src[q] : 0.0f;
+    }
+    float* myD = sD + (size_t)wave * 2 * W * LD;
+    for (int q = lane; q < 2 * W * LD; q += 64) myD[q] = 0.0f;   // (rows that a layer does not use stay zero)
+    __syncthreads();
+
+    const float* __restrict__ yg = reinterpret_cast<const float*>(p.y);
+    const float* __restrict__ ug = reinterpret_cast<const float*>(p.u);
+    gacc acc[WB][WB], accB[WB];
+#pragma unroll
+    for (int I = 0; I < WB; ++I) {
+        accB[I] = gacc{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int J = 0; J < WB; ++J) acc[I][J] = gacc{0.f, 0.f, 0.f, 0.f};
+    }
+    const long long total = (long long)p.B * p.T;
+    const long long tiles = (total + 15) / 16;
+    const long long tstride = (long long)gridDim.x * kWaves;
+    for (long long tile = (long long)blockIdx.x * kWaves + wave; tile < tiles; tile += tstride) {
+        const long long s0 = tile * 16;
+        const long long sc = s0 + c;
+        const bool live = sc < total;
+        const long long scl = live ? sc : 0;
+        float yB[2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m) yB[m] = live ? yg[scl * N + 4 * m + g] : 0.0f;
+        // w in accumulator layout: entries 4g .. 4g+3 of point c (zero for g >= 2 and past the end)
+        gacc wA = {0.f, 0.f, 0.f, 0.f};
+        if (live && g < 2) {
+            const long long b = sc / p.T, j = sc - b * p.T;
+            float4 ua = {0.f, 0.f, 0.f, 0.f}, ub = {0.f, 0.f, 0.f, 0.f};
+            if (j + 1 < p.T) ua = *reinterpret_cast<const float4*>(ug + (b * (p.T - 1) + j) * N + 4 * g);
+            if (j > 0) ub = *reinterpret_cast<const float4*>(ug + (b * (p.T - 1) + j - 1) * N + 4 * g);
+            wA = gacc{0.5f * (ua.x + ub.x), 0.5f * (ua.y + ub.y), 0.5f * (ua.z + ub.z), 0.5f * (ua.w + ub.w)};
+        }
+
+        // ---- forward: activations (the one entering the block's layer is kept) and derivative factors ----
+        gacc a[WB], ain[WB], dact[L][WB];
+#pragma unroll
+        for (int I = 0; I < WB; ++I) {
+            gacc z;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) z[v] = sb[16 * I + 4 * g + v];
+#pragma unroll
+            for (int m = 0; m < 2; ++m) z = __builtin_amdgcn_mfma_f32_16x16x4f32(sW1[(16 * I + c) * W1S + 4 * m + g], yB[m], z, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float av, dv;
+                fast_act(kind, z[v], av, dv);
+                a[I][v] = live ? av : 0.0f;
+                dact[0][I][v] = dv;
+            }
+            ain[I] = a[I];
+        }
+#pragma unroll
+        for (int l = 1; l < L; ++l) {
+            gacc an[WB];
+#pragma unroll
+            for (int I = 0; I < WB; ++I) {
+                gacc z;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) z[v] = sb[l * W + 16 * I + 4 * g + v];
+#pragma unroll
+                for (int K = 0; K < WB; ++K) {
+                    float wa[4];
+                    vload<float, 4>(wa, &sWh[((l - 1) * W + 16 * I + c) * WS + 16 * K + 4 * g]);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) z = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[v], a[K][v], z, 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float av, dv;
+                    fast_act(kind, z[v], av, dv);
+                    an[I][v] = live ? av : 0.0f;
+                    dact[l][I][v] = dv;
+                }
+            }
+#pragma unroll
+            for (int I = 0; I < WB; ++I) {
+                a[I] = an[I];
+                if (l < grp) ain[I] = an[I];   // ain = output of hidden layer min(grp, L) - 1 (grp >= 1)
+            }
+        }
+
+        // ---- reverse, down to the block's layer: dcur = cotangent of the pre-activation of hidden layer l ----
+        gacc dcur[WB];
+        if (grp < L) {
+#pragma unroll
+            for (int I = 0; I < WB; ++I) {
+                gacc z = {0.f, 0.f, 0.f, 0.f};
+                // k-step v: lane group g supplies entry 4g + v of w (zero from g = 2 on); A[i = c][k = g] = W_out[4g + v][16 I + c]
+#pragma unroll
+                for (int v = 0; v < 4; ++v) z = __builtin_amdgcn_mfma_f32_16x16x4f32(sWo[(4 * g + v) * WS + 16 * I + c], wA[v], z, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) dcur[I][v] = z[v] * dact[L - 1][I][v];
+            }
+#pragma unroll
+            for (int l = L - 2; l >= 0; --l) {
+                if (l >= grp) {   // (uniform)
+                    gacc dn[WB];
+#pragma unroll
+                    for (int I = 0; I < WB; ++I) {
+                        gacc z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int K = 0; K < WB; ++K)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                z = __builtin_amdgcn_mfma_f32_16x16x4f32(sWh[(l * W + 16 * K + 4 * g + v) * WS + 16 * I + c], dcur[K][v], z, 0, 0, 0);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) dn[I][v] = z[v] * dact[l][I][v];
+                    }
+#pragma unroll
+                    for (int I = 0; I < WB; ++I) dcur[I] = dn[I];
+                }
+            }
+        }
+
+        // ---- the layer's cotangent (rows 0 .. W-1 of the tile) and input (rows W .. 2W-1) with the points as columns ----
+        if (grp == L) {
+            if (g < 2) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) myD[(4 * g + v) * LD + c] = wA[v];
+            }
+            accB[0] += wA;
+        } else {
+#pragma unroll
+            for (int I = 0; I < WB; ++I) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) myD[(16 * I + 4 * g + v) * LD + c] = dcur[I][v];
+                accB[I] += dcur[I];
+            }
+        }
+        if (grp > 0) {
+#pragma unroll
+            for (int I = 0; I < WB; ++I)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) myD[(W + 16 * I + 4 * g + v) * LD + c] = ain[I][v];
+        }
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            // A[i = c][k = g -> point 4m + g] from the cotangent rows, B[k = g -> point 4m + g][j = c] from the input rows
+            const int at = c * LD + 4 * m + g;
+            float td[WB], tin[WB];
+#pragma unroll
+            for (int I = 0; I < WB; ++I) {
+                td[I] = myD[(16 * I) * LD + at];
+                tin[I] = myD[(W + 16 * I) * LD + at];
+            }
+            if (grp == 0) {
+                const long long sp = s0 + 4 * m + g;
+                const float yK = (c < N && sp < total) ? yg[sp * N + c] : 0.0f;   // entry c of point 4m + g
+#pragma unroll
+                for (int I = 0; I < WB; ++I) acc[I][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(td[I], yK, acc[I][0], 0, 0, 0);
+            } else if (grp == L) {
+#pragma unroll
+                for (int J = 0; J < WB; ++J) acc[0][J] = __builtin_amdgcn_mfma_f32_16x16x4f32(td[0], tin[J], acc[0][J], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int I = 0; I < WB; ++I)
+#pragma unroll
+                    for (int J = 0; J < WB; ++J) acc[I][J] = __builtin_amdgcn_mfma_f32_16x16x4f32(td[I], tin[J], acc[I][J], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- this layer's slice of the wavefront's partial row ----
+    const long long P = gen_theta_len(N, W, L);
+    float* __restrict__ prow = reinterpret_cast<float*>(p.partial) + ((long long)blockIdx.x * kWaves + wave) * P;
+    const long long base = layer_offset(N, W, grp);
+#pragma unroll
+    for (int I = 0; I < WB; ++I)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = 16 * I + 4 * g + v;
+            float sbias = accB[I][v];
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) sbias += __shfl_xor(sbias, o);
+            if (grp == 0) {
+                if (c < N) prow[base + row * N + c] = acc[I][0][v];
+                if (c == 0) prow[base + W * N + row] = sbias;
+            } else if (grp == L) {
+                if (I == 0 && g < 2) {
+#pragma unroll
+                    for (int J = 0; J < WB; ++J) prow[base + (4 * g + v) * W + 16 * J + c] = acc[0][J][v];
+                    if (c == 0) prow[base + N * W + 4 * g + v] = sbias;
+                }
+            } else {
+#pragma unroll
+                for (int J = 0; J < WB; ++J) prow[base + row * W + 16 * J + c] = acc[I][J][v];
+                if (c == 0) prow[base + W * W + row] = sbias;
+            }
+        }
+}
+
+size_t vj_mfma_smem(int W, int L) { return ((size_t)W * 12 + (size_t)(L - 1) * W * (W + 4) + 16 * (size_t)(W + 4) + (size_t)L * W + 16 + 4 * 2 * (size_t)W * 17) * 4; }
+
+template <int WB, int L>
+hipError_t launch_vj_mfma_wl(const MlpVjpParams& p, int blocks, hipStream_t s) {
+    const size_t shmem = vj_mfma_smem(16 * WB, L);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_gen_vjp_mfma_kernel<WB, L>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((mlp_gen_vjp_mfma_kernel<WB, L>), dim3((unsigned)blocks, (unsigned)(L + 1)), dim3(kThreads), shmem, s, p);
+    return hipGetLastError();
+}
+
+template <int WB>
+hipError_t launch_vj_mfma_w(const MlpVjpParams& p, int blocks, hipStream_t s) {
+    switch (p.nhid) {
+        case 1: return launch_vj_mfma_wl<WB, 1>(p, blocks, s);
+        case 2: return launch_vj_mfma_wl<WB, 2>(p, blocks, s);
+        case 3: return launch_vj_mfma_wl<WB, 3>(p, blocks, s);
+        case 4: return launch_vj_mfma_wl<WB, 4>(p, blocks, s);
+        case 5: return launch_vj_mfma_wl<WB, 5>(p, blocks, s);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -718,6 +974,14 @@ hipError_t launch_mlp_general_funceval(int dtype, const MlpParams& p, hipStream_
 
 hipError_t launch_mlp_general_vjp(int dtype, const MlpVjpParams& p, hipStream_t s) {
     if (!mlp_general_supported(p.n, p.width, p.nhid, p.act) || p.T < 2) return hipErrorInvalidValue;
+    const char* e = getenv("DEER_MLP_MFMA");
+    if (!(e && *e && atoi(e) == 0) && fe_mfma_supported(dtype, p.n, p.width, p.nhid) && p.blocks >= 1) {
+        // the partial region holds p.blocks * 4 rows: that many wavefront rows at most, and one block per CU by its LDS
+        const int blocks = p.blocks < 256 ? p.blocks : 256;
+        hipError_t err = p.width == 32 ? launch_vj_mfma_w<2>(p, blocks, s) : launch_vj_mfma_w<4>(p, blocks, s);
+        if (err != hipSuccess) return err;
+        return launch_partial_reduce(0, p.partial, p.dtheta, gen_theta_len(p.n, p.width, p.nhid), blocks * 4, s);
+    }
     return dtype == 0 ? launch_vj<float>(p, s) : launch_vj<double>(p, s);
 }
 
