@@ -88,6 +88,20 @@ __device__ __forceinline__ LstmGates<S> lstm_gates(const LstmShared<S>& w, int u
     return g;
 }
 
+// a row of np <= 32 scalars (np a power of two) from registers to memory
+template <typename S>
+__device__ __forceinline__ void store_row(S* dst, const S* row, int np) {
+    if (np < 4) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            if (k < np) dst[k] = row[k];
+        return;
+    }
+#pragma unroll
+    for (int k4 = 0; k4 < 2 * kMaxU / 4; ++k4)
+        if (4 * k4 < np) vstore<S, 4>(dst + 4 * k4, row + 4 * k4);
+}
+
 template <typename S>
 __global__ __launch_bounds__(kThreads) void lstm_funceval_kernel(GruParams p) {
     if (gate_closed<S>(p.gate)) return;
@@ -124,6 +138,14 @@ __global__ __launch_bounds__(kThreads) void lstm_funceval_kernel(GruParams p) {
         S* Jh = J + (s * np + j) * np;         // row of h'_j
         S* Jc = J + (s * np + u + j) * np;     // row of c'_j
         S acch = g.o * g.tc, accc = g.cn;      // rhs = f - J y
+        // the two rows are put together in registers and leave as 16-byte stores (a row is np scalars, np = 4, 8, 16 or 32;
+        // np = 2 takes scalar stores)
+        S rowh[2 * kMaxU], rowc[2 * kMaxU];
+#pragma unroll
+        for (int k = 0; k < 2 * kMaxU; ++k) {
+            rowc[k] = (k == u + j) ? g.f : S(0);
+            rowh[k] = (k == u + j) ? hc * g.f : S(0);
+        }
 #pragma unroll
         for (int k = 0; k < kMaxU; ++k)
             if (k < u) {
@@ -131,13 +153,11 @@ __global__ __launch_bounds__(kThreads) void lstm_funceval_kernel(GruParams p) {
                 const S vh = ho * w.U[(3 * u + j) * us + k] + hc * vc;
                 accc -= vc * h[k];
                 acch -= vh * h[k];
-                Jc[k] = vc;
-                Jh[k] = vh;
+                rowc[k] = vc;
+                rowh[k] = vh;
             }
-        for (int k = u; k < np; ++k) {
-            Jc[k] = (k == u + j) ? g.f : S(0);
-            Jh[k] = (k == u + j) ? hc * g.f : S(0);
-        }
+        store_row<S>(Jh, rowh, np);
+        store_row<S>(Jc, rowc, np);
         accc -= g.f * cj;
         acch -= hc * g.f * cj;
         rhs[s * np + j] = acch;
@@ -318,14 +338,17 @@ __device__ __forceinline__ LemGates<S> lem_gates(const LstmShared<S>& w, int u, 
     return g;
 }
 
-template <typename S>
+// UC: the number of units when it is 2, 4, 8 or 16 and the scan's state size is exactly 2 UC (the rows of the Jacobian are
+// then put together in registers and leave as 16-byte stores); 0: any shape, scalar stores
+template <typename S, int UC>
 __global__ __launch_bounds__(kThreads) void lem_funceval_kernel(GruParams p) {
     if (gate_closed<S>(p.gate)) return;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int u = p.units, d = p.d, np = p.n, us = u | 1;
+    const int u = UC > 0 ? UC : p.units, d = p.d, np = UC > 0 ? 2 * UC : p.n, us = u | 1;
     const S dt = (S)p.dt;
     const LstmShared<S> w = stage_weights<S>(reinterpret_cast<const S*>(p.theta), u, d, reinterpret_cast<S*>(smem_raw), tid);
+    S* sMw = reinterpret_cast<S*>(smem_raw) + ((lstm_smem_scalars(u, d) + 3) & ~(size_t)3) + (size_t)wave * 64 * us;   // [64 lanes][us]
     __syncthreads();
     const int PW = 64 / u;
     const int pg = lane / u, j = lane % u;
@@ -360,33 +383,67 @@ __global__ __launch_bounds__(kThreads) void lem_funceval_kernel(GruParams p) {
         const S c1 = ds1 * (g.gz - zj), c2 = g.s1 * (S(1) - g.gz * g.gz);
         const S dgy = g.s2 * (S(1) - g.gy * g.gy);
         const S c3 = ds2 * (g.gy - yj);
-        S c1v[kMaxU], c2v[kMaxU], s1v[kMaxU];
+        // row j of dz'/dy goes to the wavefront's LDS slice: the rows of dy'/dy need all of them (U_y times that matrix)
+        S mrow[kMaxU], s1v[kMaxU];
 #pragma unroll
         for (int k = 0; k < kMaxU; ++k) {
-            const int src = base + (k < u ? k : 0);
-            c1v[k] = __shfl(c1, src);
-            c2v[k] = __shfl(c2, src);
-            s1v[k] = __shfl(g.s1, src);
+            mrow[k] = (k < u) ? c1 * w.U[(j)*us + k] + c2 * w.U[(2 * u + j) * us + k] : S(0);
+            if (k < u) sMw[lane * us + k] = mrow[k];
+            s1v[k] = __shfl(g.s1, base + (k < u ? k : 0));
         }
+        __builtin_amdgcn_wave_barrier();
+        S chain[kMaxU];   // chain[k] = sum over m of U_y[j][m] dz'_m/dy_k
+#pragma unroll
+        for (int k = 0; k < kMaxU; ++k) chain[k] = S(0);
+#pragma unroll
+        for (int m = 0; m < kMaxU; ++m)
+            if (m < u) {
+                const S uym = w.U[(3 * u + j) * us + m];
+#pragma unroll
+                for (int k = 0; k < kMaxU; ++k)
+                    if (k < u) chain[k] += uym * sMw[(base + m) * us + k];
+            }
+        __builtin_amdgcn_wave_barrier();
         if (live) {
             S* Jy = J + (s * np + j) * np;        // row of y'_j
             S* Jz = J + (s * np + u + j) * np;    // row of z'_j
             S accy = (S(1) - g.s2) * yj + g.s2 * g.gy, accz = g.zn;   // rhs = f - J (y | z)
-            for (int k = 0; k < u; ++k) {
-                const S vz = c1 * w.U[(j)*us + k] + c2 * w.U[(2 * u + j) * us + k];
-                S chain = S(0);   // sum over m of U_y[j][m] dz'_m/dy_k
-                for (int m = 0; m < u; ++m)
-                    chain += w.U[(3 * u + j) * us + m] * (c1v[m] * w.U[(m)*us + k] + c2v[m] * w.U[(2 * u + m) * us + k]);
-                S vy = dgy * chain + c3 * w.U[(u + j) * us + k];
-                if (k == j) vy += S(1) - g.s2;
-                const S vyz = dgy * w.U[(3 * u + j) * us + k] * (S(1) - s1v[k]);
-                accz -= vz * yv[k];
-                accy -= vy * yv[k] + vyz * zv[k];
-                Jz[k] = vz;
-                Jy[k] = vy;
-                Jy[u + k] = vyz;
-                Jz[u + k] = (k == j) ? S(1) - g.s1 : S(0);
+            if constexpr (UC > 0) {
+                S rowy[2 * UC], rowz[2 * UC];
+#pragma unroll
+                for (int k = 0; k < UC; ++k) {
+                    const S vz = mrow[k];
+                    S vy = dgy * chain[k] + c3 * w.U[(u + j) * us + k];
+                    if (k == j) vy += S(1) - g.s2;
+                    const S vyz = dgy * w.U[(3 * u + j) * us + k] * (S(1) - s1v[k]);
+                    accz -= vz * yv[k];
+                    accy -= vy * yv[k] + vyz * zv[k];
+                    rowz[k] = vz;
+                    rowy[k] = vy;
+                    rowy[UC + k] = vyz;
+                    rowz[UC + k] = (k == j) ? S(1) - g.s1 : S(0);
+                }
+                accz -= (S(1) - g.s1) * zj;
+                vstore<S, 2 * UC>(Jy, rowy);
+                vstore<S, 2 * UC>(Jz, rowz);
+                rhs[s * np + j] = accy;
+                rhs[s * np + u + j] = accz;
+                continue;
             }
+#pragma unroll
+            for (int k = 0; k < kMaxU; ++k)
+                if (k < u) {
+                    const S vz = mrow[k];
+                    S vy = dgy * chain[k] + c3 * w.U[(u + j) * us + k];
+                    if (k == j) vy += S(1) - g.s2;
+                    const S vyz = dgy * w.U[(3 * u + j) * us + k] * (S(1) - s1v[k]);
+                    accz -= vz * yv[k];
+                    accy -= vy * yv[k] + vyz * zv[k];
+                    Jz[k] = vz;
+                    Jy[k] = vy;
+                    Jy[u + k] = vyz;
+                    Jz[u + k] = (k == j) ? S(1) - g.s1 : S(0);
+                }
             accz -= (S(1) - g.s1) * zj;
             for (int k = 2 * u; k < np; ++k) { Jy[k] = S(0); Jz[k] = S(0); }
             rhs[s * np + j] = accy;
@@ -527,8 +584,15 @@ hipError_t launch_lem_fe(const GruParams& p, hipStream_t s) {
     long long blocks = (total + 4 * PW - 1) / (4 * PW);
     if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
-    const size_t shmem = lstm_smem_scalars(p.units, p.d) * sizeof(S);
-    hipLaunchKernelGGL((lem_funceval_kernel<S>), dim3((unsigned)blocks), dim3(kThreads), shmem, s, p);
+    const size_t shmem = (((lstm_smem_scalars(p.units, p.d) + 3) & ~(size_t)3) + (size_t)4 * 64 * (p.units | 1)) * sizeof(S);
+    const dim3 grid((unsigned)blocks), blk(kThreads);
+    int uc = (p.n == 2 * p.units) ? p.units : 0;
+    if (sizeof(S) == 8 && uc == 16) uc = 0;   // (64 fp64 row entries in registers spill)
+    if (uc == 16) hipLaunchKernelGGL((lem_funceval_kernel<S, 16>), grid, blk, shmem, s, p);
+    else if (uc == 8) hipLaunchKernelGGL((lem_funceval_kernel<S, 8>), grid, blk, shmem, s, p);
+    else if (uc == 4) hipLaunchKernelGGL((lem_funceval_kernel<S, 4>), grid, blk, shmem, s, p);
+    else if (uc == 2) hipLaunchKernelGGL((lem_funceval_kernel<S, 2>), grid, blk, shmem, s, p);
+    else hipLaunchKernelGGL((lem_funceval_kernel<S, 0>), grid, blk, shmem, s, p);
     return hipGetLastError();
 }
 
