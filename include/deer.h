@@ -247,7 +247,6 @@ void deer_destroy(deer_ctx* ctx);
  *   DEER_VJP_MFMA=0     vector-ALU kernels for the vector-Jacobian products instead of the matrix-core ones
  *   DEER_MLP_MFMA=0     MLP fields outside the two-layer tanh shapes (fp32, n = 8, width 32 or 64): vector-ALU field
  *                       kernel instead of the matrix-core one
- *   DEER_FUSED_W=4      GRU n = 32: four-wavefront tiles of the scan with the cell inside (two workgroups per CU)
  * Test hooks (exercise paths that ordinary runs reach rarely; never set them in production):
  *   DEER_EPOCH0         first launch epoch of the context (default 1), to reach the wrap-around of the 30-bit
  *                       epoch that tags published words

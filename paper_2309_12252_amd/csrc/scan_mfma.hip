@@ -134,7 +134,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void scan_mfma_kernel(ScanParams p, 
     __shared__ S sT[N * LD];          // tile total
     __shared__ S sTv[N];
     __shared__ S sC[WAVES][N];        // carry entering each wavefront
-    constexpr int HOPS = (sizeof(S) == 4) ? (N == 64 ? 2 : ((WAVES < 8 && N == 32) ? 4 : 8)) : 2;   // predecessor totals staged in LDS per round
+    constexpr int HOPS = (sizeof(S) == 4) ? (N == 64 ? 2 : 8) : 2;   // predecessor totals staged in LDS per round
     __shared__ int s_k;               // hops between this tile and the nearest known inclusive carry
     __shared__ int s_ok;
     // fused cell: rows of [U_gate | W_gate (16 columns, zero padded)] per gate, and the four bias vectors
@@ -881,14 +881,6 @@ hipError_t launch_n(const ScanParams& p, hipStream_t s) {
 template <int N> struct MfmaFusedShape;
 template <> struct MfmaFusedShape<16> { static constexpr int LW = 24, WAVES = 4; };
 template <> struct MfmaFusedShape<32> { static constexpr int LW = 8, WAVES = 8; };
-// n = 32 on four wavefronts: two workgroups share a compute unit, each one's serial phases (tree, look-back, fold)
-// run under the other's compositions
-struct MfmaFusedShape32Half { static constexpr int LW = 8, WAVES = 4; };
-static int fused_waves32() {
-    static const int w = [] { const char* e = getenv("DEER_FUSED_W"); return (e && atoi(e) == 4) ? 4 : 8; }();
-    return w;
-}
-
 template <int N>
 hipError_t launch_fused_n(const ScanParams& p, const GruFeed& gf, hipStream_t s) {
     constexpr int LW = MfmaFusedShape<N>::LW, WAVES = MfmaFusedShape<N>::WAVES;
@@ -897,9 +889,6 @@ hipError_t launch_fused_n(const ScanParams& p, const GruFeed& gf, hipStream_t s)
                      // per wavefront measured 10 % slower)
         hipLaunchKernelGGL((scan_mfma_kernel<float, N, MfmaShape<float, N>::LW, MfmaShape<float, N>::WAVES, true, true>), grid,
                            dim3(64 * MfmaShape<float, N>::WAVES), 0, s, p, gf);
-    else if (N == 32 && fused_waves32() == 4)
-        hipLaunchKernelGGL((scan_mfma_kernel<float, 32, MfmaFusedShape32Half::LW, MfmaFusedShape32Half::WAVES, false, true>), grid,
-                           dim3(64 * MfmaFusedShape32Half::WAVES), 0, s, p, gf);
     else
         hipLaunchKernelGGL((scan_mfma_kernel<float, N, LW, WAVES, false, true>), grid, dim3(64 * WAVES), 0, s, p, gf);
     return hipGetLastError();
@@ -916,7 +905,6 @@ int scan_mfma_tile(int dtype, int n) {
 }
 
 int scan_mfma_fused_tile(int n) {
-    if (n == 32 && fused_waves32() == 4) return MfmaFusedShape32Half::LW * MfmaFusedShape32Half::WAVES;
     return n == 16 ? MfmaFusedShape<16>::LW * MfmaFusedShape<16>::WAVES : MfmaFusedShape<32>::LW * MfmaFusedShape<32>::WAVES;
 }
 
