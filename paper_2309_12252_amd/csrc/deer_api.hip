@@ -132,6 +132,7 @@ bool supported(const deer_config* c, std::string& why) {
         if (!(n == 2 || n == 4 || n == 8) || c->d < 1 || c->d > 8) { why = "multi-head GRU: state size per head must be 2, 4 or 8 and input size per head 1..8"; return false; }
         if (H > 64 || K > 8) { why = "multi-head GRU: at most 64 heads and 8 stride levels"; return false; }
         if ((long long)c->B * c->T * H > (1LL << 31) - 1) { why = "B*T*heads must fit 31 bits"; return false; }
+        if (c->T > (1 << 22)) { why = "multi-head GRU: at most 4,194,304 steps (17 bits of tile index per recurrence)"; return false; }
         if (env_int("DEER_FUSED", 1) == 0 || env_int("DEER_GRAD_FUSED", 1) == 0) { why = "multi-head GRU runs only with the cell inside the scans"; return false; }
         return true;
     }
@@ -162,13 +163,22 @@ bool supported(const deer_config* c, std::string& why) {
 }
 
 // Multi-head GRU: the tiles of one batch entry, head by head, recurrence by recurrence (first time index r < stride),
-// tile by tile: head << 26 | r << 19 | tile.  The kernels read this list instead of decoding a ticket.
+// tile by tile: head << 26 | r << 19 | pack << 17 | tile.  The kernels read this list instead of decoding a ticket.
+// Recurrences of at most half a tile share one: 2^pack of them (first time indices r .. r + 2^pack - 1), each on
+// an eighth, a quarter or half of the tile's eight wavefronts.
 std::vector<unsigned> mh_table(const deer_config* c, int tile) {
     const int H = c->heads > 1 ? c->heads : 1, K = c->stride_levels > 1 ? c->stride_levels : 1;
     std::vector<unsigned> v;
     for (int h = 0; h < H; ++h) {
         const long long s = 1LL << (h % K);
-        for (long long r = 0; r < s && r < (long long)c->T; ++r) {
+        const long long nrec = s < (long long)c->T ? s : (long long)c->T;   // recurrences that have a position
+        const long long len0 = ((long long)c->T + s - 1) / s;              // the longest of them (r = 0)
+        int pack = 0;
+        while (pack < 3 && len0 * (2LL << pack) <= tile && (2LL << pack) <= nrec) ++pack;
+        long long r = 0;
+        for (; pack > 0 && r + (1LL << pack) <= nrec; r += 1LL << pack)
+            v.push_back((unsigned)h << 26 | (unsigned)r << 19 | (unsigned)pack << 17);
+        for (; r < nrec; ++r) {
             const long long len = ((long long)c->T - r + s - 1) / s;
             for (long long t = 0; t * tile < len; ++t) v.push_back((unsigned)h << 26 | (unsigned)r << 19 | (unsigned)t);
         }

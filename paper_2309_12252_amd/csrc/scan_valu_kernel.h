@@ -522,12 +522,14 @@ __device__ __forceinline__ void gru_pairs_dual(const GruFeed& gf, const S* __res
 
 // Inclusive log-step scan over the groups of a wavefront.  (M | v): this group's pair, lane i holds
 // row i.  Afterwards group g holds pair_g o ... o pair_0.
+// seg (a power of two): the groups fall into aligned runs of seg groups that are scanned separately (64 / N or more:
+// one run).
 template <typename S, int N>
-__device__ __forceinline__ void scan_groups(S* M, S& v, int group, int i, int ngroups_active) {
+__device__ __forceinline__ void scan_groups(S* M, S& v, int group, int i, int ngroups_active, int seg = 64 / N) {
     constexpr int NG = 64 / N;
 #pragma unroll
     for (int d = 1; d < NG; d <<= 1) {
-        if (d >= ngroups_active) break;   // uniform
+        if (d >= ngroups_active || d >= seg) break;   // uniform
         S Mo[N], vo;
 #pragma unroll
         for (int c = 0; c < N; ++c) Mo[c] = __shfl_up(M[c], d * N);
@@ -539,7 +541,7 @@ __device__ __forceinline__ void scan_groups(S* M, S& v, int group, int i, int ng
         for (int c = 0; c < N; ++c) keepM[c] = M[c];
         swizzle_row<S, N>(keepM, leftM, i);
         group_apply<S, N>(leftM, keepv, Mo, vo);
-        const bool upd = group >= d;
+        const bool upd = (group & (seg - 1)) >= d;
 #pragma unroll
         for (int c = 0; c < N; ++c) M[c] = upd ? Mo[c] : keepM[c];
         v = upd ? vo : keepv;
@@ -562,8 +564,10 @@ struct TileShared {
 // barrier).  Out: (Pex | pex) the prefix of this group inside its wavefront (row i, swizzled); sh.EM/Ev the
 // prefixes in front of the wavefronts; in wavefront 0, group W-1: (Mt | vt) the tile total (natural order).
 template <typename S, int N, int L, int W>
+// seg: wavefronts per sequence when the tile holds W / seg independent short sequences, one per aligned run of seg
+// wavefronts (W: the tile belongs to one sequence); the prefixes then restart at every run.
 __device__ __forceinline__ void tile_local(const ScanParams& p, TileShared<S, N, W>& sh, const S (*Ar)[N], const S* be,
-                                           long long seq0, int t, S* Pex, S& pex, S* Mt, S& vt) {
+                                           long long seq0, int t, S* Pex, S& pex, S* Mt, S& vt, int seg = W) {
     constexpr int NG = 64 / N;
     static_assert(NG >= W, "wavefront 0 scans one wavefront total per group");
     const int tid = threadIdx.x;
@@ -615,12 +619,14 @@ __device__ __forceinline__ void tile_local(const ScanParams& p, TileShared<S, N,
             const S u = sh.v[gw][i];
             vt = has ? u : S(0);
         }
-        scan_groups<S, N>(Mt, vt, group, i, W);
-        // group g now holds the prefix through wavefront g: it is the prefix in front of wavefront g+1
+        scan_groups<S, N>(Mt, vt, group, i, W, seg);
+        // group g now holds the prefix through wavefront g: it is the prefix in front of wavefront g+1 (the identity
+        // where a new sequence starts)
         if (group < W - 1) {
+            const bool fresh = ((group + 1) & (seg - 1)) == 0;
 #pragma unroll
-            for (int c = 0; c < N; ++c) sh.EM[group + 1][i * N + c] = Mt[c];
-            sh.Ev[group + 1][i] = vt;
+            for (int c = 0; c < N; ++c) sh.EM[group + 1][i * N + c] = fresh ? ((c == i) ? S(1) : S(0)) : Mt[c];
+            sh.Ev[group + 1][i] = fresh ? S(0) : vt;
         }
     }
 }
@@ -908,11 +914,11 @@ __device__ __forceinline__ void tile_lookback_split(const ScanParams& p, TileSha
 // Steps 1b-4 in one go (see tile_local, tile_lookback and tile_lookback_split).
 template <typename S, int N, int L, int W, bool SPLIT = false>
 __device__ __forceinline__ void tile_carry(const ScanParams& p, TileShared<S, N, W>& sh, const S (*Ar)[N], const S* be,
-                                           long long seq0, int t, unsigned epoch, S* Pex, S& pex, const S* y0row) {
+                                           long long seq0, int t, unsigned epoch, S* Pex, S& pex, const S* y0row, int seg = W) {
     S Mt[N], vt = S(0);
 #pragma unroll
     for (int c = 0; c < N; ++c) Mt[c] = S(0);
-    tile_local<S, N, L, W>(p, sh, Ar, be, seq0, t, Pex, pex, Mt, vt);
+    tile_local<S, N, L, W>(p, sh, Ar, be, seq0, t, Pex, pex, Mt, vt, seg);
     if constexpr (SPLIT) tile_lookback_split<S, N, W>(p, sh, seq0, t, epoch, Mt, vt, y0row);
     else tile_lookback<S, N, W>(p, sh, seq0, t, epoch, Mt, vt, y0row);
 }
@@ -975,6 +981,7 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     const S* __restrict__ oldb =
         p.yold ? reinterpret_cast<const S*>(p.yold) + (long long)b * p.strideOld : nullptr;
     long long T = p.T;
+    int seg = W, wv = wave;          // wavefronts per sequence in this tile and this wavefront's index among them (multi-head)
     long long psy = N, psx = gf.d;   // scalars between consecutive positions of the trajectory and of the inputs
     const S* __restrict__ xb = nullptr;
     const S* __restrict__ y0row = nullptr;
@@ -984,13 +991,19 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     }
     if constexpr (MH) {
         // p.tiles counts the tiles of one batch entry over all its recurrences; the table lists them head by head,
-        // recurrence by recurrence, tile by tile: head (6 bits) | first time index r (7 bits) | tile (19 bits).  The
-        // tiles of a recurrence are consecutive entries, so its published words are consecutive slots.
+        // recurrence by recurrence, tile by tile: head (6 bits) | first time index r (7 bits) | log2 of the recurrences
+        // packed into the tile (2 bits) | tile (17 bits).  The tiles of a recurrence are consecutive entries, so its
+        // published words are consecutive slots.  Short recurrences share a tile: 2^pack of them (same head, first time
+        // indices r, r + 1, ...), each on an aligned run of W >> pack wavefronts, each starting from the head's y0.
         const int H = p.mh_H;
         const int entry = t;
         const unsigned ent = p.mh_table[entry];
-        const int h = (int)(ent >> 26), r = (int)((ent >> 19) & 127u);
-        t = (int)(ent & 0x7ffffu);
+        const int h = (int)(ent >> 26);
+        const int lp = (int)((ent >> 17) & 3u);
+        seg = W >> lp;
+        const int r = (int)((ent >> 19) & 127u) + wave / seg;
+        wv = wave & (seg - 1);
+        t = (int)(ent & 0x1ffffu);
         seq0 = (long long)b * p.tiles + entry - t;
         const long long bi = b;
         const long long s = 1LL << (h % p.mh_K);
@@ -1006,14 +1019,16 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
         if (p.y0) y0row = reinterpret_cast<const S*>(p.y0) + (bi * H + h) * N;
         gf.theta = reinterpret_cast<const S*>(gf.theta) + (long long)h * p.mh_P;
     }
-    const long long e0 = (long long)t * TILE + (long long)(wave * NG + group) * L;
+    const long long e0 = (long long)t * TILE + (long long)(wv * NG + group) * L;
     const long long slot = seq0 + t;
     DEER_STAMP(p, slot, 0, tid == 0);
 
     // ---- 1. this group's pairs (kept for the second walk), then their composition ----
     // A tile that lies completely inside the sequence takes the FULL variants: one base address with
     // constant offsets and no end-of-sequence handling.
-    const bool full = (long long)(t + 1) * TILE <= T && (!REV || t > 0);
+    // (per wavefront where short sequences share the tile)
+    const bool full = (MH && seg < W) ? (!REV && (long long)(wv + 1) * (NG * L) <= T)
+                                      : ((long long)(t + 1) * TILE <= T && (!REV || t > 0));
     S Ar[L][N], be[L], yo[L];
     if (full) {
         if constexpr (STAGED) {
@@ -1052,7 +1067,7 @@ __global__ __launch_bounds__(64 * W) void scan_valu_kernel(ScanParams p, GruFeed
     S Pex[N], pex;
     // plain scans of n <= 4 look back on wavefront 1 while wavefront 0 scans the wavefront totals (measured on
     // chip-filling streams: +5 % at n = 4, +12 % at n = 2; at n = 8 the extra registers cost more than it gains)
-    tile_carry<S, N, L, W, DP == 0 && N <= 4>(p, sh, Ar, be, seq0, t, p.epoch, Pex, pex, y0row);
+    tile_carry<S, N, L, W, DP == 0 && N <= 4>(p, sh, Ar, be, seq0, t, p.epoch, Pex, pex, y0row, seg);
 
     // ---- 5. starting state of this group, then the second walk over the resident pairs ----
     S y = tile_start_state<S, N, W>(sh, Pex, pex, wave, i);

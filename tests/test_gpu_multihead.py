@@ -43,6 +43,19 @@ def run(w, dtype, check_grad=True):
 @pytest.mark.parametrize("n,d,H,K,B,T", [(8, 4, 4, 3, 2, 300), (4, 3, 5, 2, 3, 77), (2, 2, 3, 3, 2, 1000), (8, 8, 8, 8, 1, 700),
                                          (8, 5, 2, 1, 2, 600), (4, 1, 1, 4, 2, 129), (8, 4, 6, 4, 2, 5), (8, 4, 3, 2, 1, 1)])
 def test_small_multihead_shapes(n, d, H, K, B, T, dtype):
+    _small(n, d, H, K, B, T, dtype)
+
+
+# short recurrences share a tile (two, four or eight of them on a half, a quarter or an eighth of its wavefronts):
+# fewer steps than the largest stride, recurrence counts that leave a remainder, every state size
+@pytest.mark.parametrize("dtype", [deer.DEER_F32, deer.DEER_F64])
+@pytest.mark.parametrize("n,d,H,K,B,T", [(8, 4, 8, 8, 2, 100), (8, 8, 8, 8, 2, 1030), (2, 2, 8, 8, 2, 333), (4, 3, 8, 7, 3, 50),
+                                         (8, 4, 8, 8, 1, 131), (4, 2, 16, 6, 2, 2050), (8, 3, 5, 8, 2, 515)])
+def test_short_recurrences_that_share_tiles(n, d, H, K, B, T, dtype):
+    _small(n, d, H, K, B, T, dtype)
+
+
+def _small(n, d, H, K, B, T, dtype):
     w = inputs.mh_gru_workload("mh_n%d_H%d_K%d_T%d" % (n, H, K, T), 40 * n + H + K, B=B, T=T, n=n, d=d, H=H, K=K)
     w.y0 = np.random.default_rng(3).standard_normal((B, H, n)).astype(np.float32)
     run(w, dtype)
