@@ -94,8 +94,9 @@ typedef struct {
     int32_t n;                  /* state size.  GRU: 1..64, above 32 in fp32 only (1, 2, 4, 8, 16, 32, 64 have  */
                                 /* kernels of their own; any other size runs embedded in the next of     */
                                 /* those, with identical results);                                       */
-                                /* MLP_ODE: 2, 4 or 8; multi-head GRU: 2, 4 or 8 per head                */
-    int32_t d;                  /* GRU input size (1..32); ignored for MLP_ODE                           */
+                                /* MLP_ODE: 2, 4 or 8; multi-head GRU: 2, 4 or 8 per head; LSTM and LEM: */
+                                /* the number of units u, 1..16 (the state has 2u entries)               */
+    int32_t d;                  /* GRU input size (1..32); LSTM and LEM: 1..8; ignored for MLP_ODE       */
     int32_t mlp_width;          /* MLP_ODE hidden width w: a multiple of 4, 4..64; ignored for GRU       */
     int32_t mlp_hidden_layers;  /* MLP_ODE: hidden layers L, 1..5 (L + 1 linear layers)                  */
     double t0, t1;              /* MLP_ODE: uniform grid t_j = t0 + j (t1 - t0)/(T - 1); LEM: t1 = step dt */
